@@ -1,0 +1,55 @@
+"""Pins of the host-side cost model against the two closed-form tables the paper prints."""
+import os
+
+import pytest
+
+from paper_2601_13155_amd import costmodel as cm
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                yield line.split()
+
+
+def test_proxy_flops_table():
+    D, Dff = 4096, 14336
+    n_ok = 0
+    for dlow, r, printed, consistent in _rows("proxy_flops_table.txt"):
+        dl = None if dlow == "/" else int(dlow)
+        rr = None if r == "/" else int(r)
+        macs = cm.proxy_macs_per_token_per_projection(D, Dff, dl, rr)
+        if consistent == "1":
+            assert round(macs / 1000.0) == int(printed), (dlow, r, macs)
+            n_ok += 1
+        else:
+            assert round(macs / 1000.0) != int(printed)
+    assert n_ok == 5
+    assert cm.proxy_macs_per_token_per_projection(D, Dff, 512, 192) == 884736
+
+
+def test_kv_cache_memory_table():
+    K = 1024
+    for ctx, full, with_pap, saving in _rows("kv_cache_memory_table.txt"):
+        N = int(ctx) * K
+        # 10 dense layers, then stages of 4/5/5/5 layers with budgets 9/7/4/2 K; the three layers after
+        # the last stage end run at the inferred next budget of 1 K.
+        cached = cm.kv_cached_tokens(N, dense_layers=10, stage_layers=(4, 5, 5, 5, 3),
+                                     budgets=(9 * K, 7 * K, 4 * K, 2 * K, 1 * K), prune_per_stage=K)
+        ratio = cached / (32.0 * N)
+        assert abs(ratio * float(full) - float(with_pap)) < 0.006, (ctx, ratio * float(full))
+        assert abs((1.0 - ratio) * 100.0 - float(saving)) < 0.06
+
+
+def test_layer_flops_matches_hand_count():
+    # 8B-shaped layer at N = 8192, keep 0.4, P = 64, r = 256, Dlow = Dff
+    f = cm.layer_flops(4096, 32, 8, 128, 14336, 8192, 64, 3276, 3276, 256, 14336)
+    assert f["k_proj"] == 2.0 * 8192 * 4096 * 1024
+    assert f["ffn"] == 2.0 * 3276 * 3 * 4096 * 14336
+    assert abs(sum(f.values()) / 1e12 - 1.80) < 0.02
+    dense = cm.layer_flops(4096, 32, 8, 128, 14336, 8192, 64, 8192, 8192, 256, 14336, skip=False)
+    assert abs(sum(dense.values()) / 1e12 - 4.12) < 0.02
