@@ -1,0 +1,158 @@
+/*
+ * spts.h -- C ABI of the SPTS token-skipped decoder-layer prefill for AMD MI355X (gfx950).
+ *
+ * SPTS ("Probe and Skip: Self-Predictive Token Skipping") runs each decoder layer of a
+ * prefill on a subset of the candidate tokens:
+ *   PAP  (Sec. 3.2, Eq. (mha_importance), Alg. 1 "Partial Attention Probing" block): keys of all
+ *        candidates + queries of the trailing probe window give a score S^MHA per candidate; the
+ *        top M_a candidates take Q/V projection, causal attention and the output projection, the
+ *        others keep their residual (Eq. (skip));
+ *   LTP  (Sec. 3.3, Eq. (proxy_ffn), (ffn_transformation), (ffn_importance), (ffn_selection)): a
+ *        rank-r proxy of the SwiGLU FFN predicts each token's update norm C^FFN; the top M_f
+ *        candidates by C^FFN * S^MHA take the full FFN (Eq. (ffn_function));
+ *   MSDP (Sec. 3.4, Eq. (stage_prune)): at a stage end the candidate set itself is cut down to the
+ *        top N_{s+1} candidates by the last S^MHA and the hidden states are compacted.
+ *
+ * Conventions
+ *  - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned, valid until the
+ *    stream work queued by the call has finished.  The library keeps no caller pointer after a call
+ *    returns except the workspace and stream given to spts_create.
+ *  - All calls are asynchronous on the context's HIP stream and never synchronise with the host.
+ *    All counts (N, budgets) are host integers.
+ *  - Element type of hidden states, weights, K/V: spts_model_desc.dtype (fp32, or bf16 with fp32
+ *    accumulation).  Scores are fp32, indices and positions int32.
+ *  - Matrices are row-major.  Every weight/factor matrix is stored [d_out, d_in] so that a
+ *    projection is y = x * W^T (the layout checkpoints use for linear layers).  In the paper's
+ *    notation (y = x W): Wq = W_Q^T [H*d, D], Wk = W_K^T [Hkv*d, D], Wv = W_V^T [Hkv*d, D],
+ *    Wo = W_O^T [D, H*d], Wgate = W_gate^T [Dff, D], Wup = W_up^T [Dff, D], Wdown = W_down [D, Dff]
+ *    (the paper applies W_down transposed), Ug = U_gate^T [r, D], Vg = V_gate^T [Dlow, r],
+ *    Uu = U_up^T [r, D], Vu = V_up^T [Dlow, r], Ud = U_down [D, r], Vd = V_down [r, Dlow].
+ *  - Candidates are rows 0..N-1 of x with strictly ascending absolute positions pos[]; rotary
+ *    embedding (pairing (j, j+d/2), theta_j = rope_base^(-2j/d)) and the causal mask use pos[].
+ *    RMSNorm precedes attention and FFN (pre-norm block).
+ *  - Selected index lists are ascending; TopK is the k largest under (score descending, index
+ *    ascending), -0.0 == +0.0; NaN scores are a caller error.  With protect_last != 0 and k >= 1 the
+ *    last candidate is always selected.
+ *  - Return value: SPTS_OK or a negative spts_status.  Arguments are validated before any launch;
+ *    after an error the outputs are unspecified.  Nothing throws across this boundary.
+ */
+#ifndef SPTS_H
+#define SPTS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPTS_OK = 0,
+    SPTS_EINVAL = -1,     /* null pointer, negative size, k > N, probe_len > N or < 1 ...          */
+    SPTS_ESHAPE = -2,     /* unsupported dimensions (H % Hkv, odd d, d > 256, sizes beyond create) */
+    SPTS_EALIGN = -3,     /* a data pointer is not 16-byte aligned                                 */
+    SPTS_EWORKSPACE = -4, /* workspace given to spts_create is too small for this call            */
+    SPTS_EDTYPE = -5,     /* dtype is neither SPTS_F32 nor SPTS_BF16                               */
+    SPTS_EHIP = -6        /* a HIP call failed; see spts_last_hip_error                            */
+} spts_status;
+
+typedef enum { SPTS_F32 = 0, SPTS_BF16 = 1 } spts_dtype;
+
+/* Layer dimensions in the paper's notation: D hidden, H query heads, Hkv key/value heads,
+ * d head dimension, Dff FFN inner dimension (Sec. 3.2, 3.3). */
+typedef struct {
+    int32_t D, H, Hkv, d, Dff;
+    float rms_eps;
+    float rope_base;
+    int32_t dtype; /* spts_dtype */
+} spts_model_desc;
+
+/* Device pointers to one layer's parameters, layouts as listed above.  gamma1/gamma2 are the
+ * RMSNorm gains [D] in the model dtype.  The proxy factors may be NULL for a layer that is only
+ * ever run with skip = 0. */
+typedef struct {
+    const void *Wq, *Wk, *Wv, *Wo, *gamma1;
+    const void *Wgate, *Wup, *Wdown, *gamma2;
+    const void *Ug, *Vg, *Uu, *Vu, *Ud, *Vd;
+    int32_t r;    /* proxy rank                         */
+    int32_t Dlow; /* proxy inner dimension (<= Dff)     */
+} spts_layer_weights;
+
+/* Per-layer control (Alg. 1: skip flag, budgets M_fixed; Sec. 3.4). */
+typedef struct {
+    int32_t skip;         /* 0: dense layer (the else-branches of Alg. 1); 1: PAP + LTP          */
+    int32_t probe_len;    /* P >= 1 trailing candidates used as probe queries (P = 1 in Sec. 3.2)  */
+    int64_t m_attn;       /* M_fixed for attention; the library applies min(N, m)                  */
+    int64_t m_ffn;        /* M_fixed for the FFN                                                   */
+    int32_t protect_last; /* != 0: the last candidate is always active                             */
+    int32_t kv_mode;      /* 0: keys/values of the active set only (Alg. 1); 1: of all candidates  */
+} spts_layer_cfg;
+
+/* Optional KV-cache output of a layer (Sec. 3.2 last paragraph: only active pairs are cached).
+ * k, v: [capacity, Hkv, d] model dtype, post-rotary keys; pos: [capacity] int32.
+ * count is written by the library on the host: number of rows filled. */
+typedef struct {
+    void *k, *v;
+    int32_t *pos;
+    int64_t capacity;
+    int64_t count;
+} spts_kv_out;
+
+typedef struct spts_ctx spts_ctx;
+
+/* Bytes of device workspace a context needs to serve calls with N <= max_tokens,
+ * probe_len <= max_probe, r <= max_r, Dlow <= max_dlow.  0 on invalid arguments. */
+size_t spts_workspace_bytes(const spts_model_desc *model, int64_t max_tokens, int32_t max_probe,
+                            int32_t max_r, int32_t max_dlow);
+
+/* Creates a context bound to a HIP stream (hipStream_t passed as void*; NULL = default stream)
+ * and to a caller-owned device workspace of at least spts_workspace_bytes(...) bytes, which must
+ * stay allocated until spts_destroy.  The limits must be the ones the workspace was sized for.
+ * Calls on one context must not overlap. */
+int spts_create(spts_ctx **ctx, const spts_model_desc *model, void *hip_stream, void *workspace,
+                size_t workspace_bytes, int64_t max_tokens, int32_t max_probe, int32_t max_r,
+                int32_t max_dlow);
+void spts_destroy(spts_ctx *ctx);
+const char *spts_strerror(int status);
+/* Last hipError_t seen by this context (0 if none), as an int. */
+int spts_last_hip_error(const spts_ctx *ctx);
+/* 1 if the matrix-core (MFMA bf16) kernels serve this context's shapes, 0 if the generic kernels do. */
+int spts_uses_mfma(const spts_ctx *ctx);
+
+/* PAP probe (Sec. 3.2, Eq. (mha_importance); Alg. 1 PAP block, first two lines).
+ * x [N, D]: hidden states before the layer.  Computes the post-rotary keys of all candidates
+ * k_out [N, Hkv, d] and s_mha[n] = mean over the P*H probe rows of softmax(q k^T / sqrt(d))[n],
+ * where probe row p is candidate N-P+p and sees candidates 0..N-P+p.  Needs 1 <= probe_len <= N. */
+int spts_probe_attn(spts_ctx *ctx, const void *x, const int32_t *pos, int64_t N,
+                    const spts_layer_weights *w, int32_t probe_len, void *k_out, float *s_mha);
+
+/* LTP probe (Sec. 3.3, Eq. (proxy_ffn), (ffn_transformation), (ffn_importance)).
+ * x [N, D]: residual stream after the attention update.  c_ffn[n] = || f(rmsnorm(x_n)) ||_2,
+ * s_ffn[n] = c_ffn[n] * s_mha[n].  s_mha may be NULL (then s_ffn = c_ffn); c_ffn may be NULL. */
+int spts_probe_ffn(spts_ctx *ctx, const void *x, int64_t N, const spts_layer_weights *w,
+                   const float *s_mha, float *c_ffn, float *s_ffn);
+
+/* TopK (Sec. 3.2; Eq. (ffn_selection)).  idx_out [k] ascending.  0 <= k <= N; k == 0 writes nothing. */
+int spts_select_topk(spts_ctx *ctx, const float *scores, int64_t N, int64_t k, int32_t protect_last,
+                     int32_t *idx_out);
+
+/* One decoder layer of Alg. 1 in place on x [N, D] (PAP block then LTP block, or the dense
+ * branches when cfg->skip == 0).  Optional outputs (NULL = not wanted): kv, s_mha [N],
+ * idx_attn [min(N, m_attn)], idx_ffn [min(N, m_ffn)].  With skip == 0 the optional score/index
+ * outputs are not written and kv receives all N rows. */
+int spts_layer_prefill(spts_ctx *ctx, void *x, const int32_t *pos, int64_t N,
+                       const spts_layer_weights *w, const spts_layer_cfg *cfg, spts_kv_out *kv,
+                       float *s_mha, int32_t *idx_attn, int32_t *idx_ffn);
+
+/* Stage-end pruning (Sec. 3.4, Eq. (stage_prune); Alg. 1 last block): keeps the
+ * N' = min(N, N_next) candidates with the largest s_mha.  Out of place: x_out [N', D],
+ * pos_out [N'], map_new2old [N'] (ascending), map_old2new [N] (-1 for dropped rows; may be NULL).
+ * x_out must not overlap x_in. */
+int spts_msdp_compact(spts_ctx *ctx, const void *x_in, const int32_t *pos_in, const float *s_mha,
+                      int64_t N, int64_t N_next, int32_t protect_last, void *x_out, int32_t *pos_out,
+                      int32_t *map_new2old, int32_t *map_old2new);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPTS_H */

@@ -1,0 +1,185 @@
+"""ctypes binding of libspts (include/spts.h): argument marshalling only.
+
+Every function has the name and argument order of its C entry point and takes
+torch tensors that live on the GPU (PyTorch is used for device memory and
+streams only).  No step of the method is computed here, and there is no CPU
+fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspts.so")
+
+SPTS_OK = 0
+SPTS_EINVAL, SPTS_ESHAPE, SPTS_EALIGN, SPTS_EWORKSPACE, SPTS_EDTYPE, SPTS_EHIP = -1, -2, -3, -4, -5, -6
+SPTS_F32, SPTS_BF16 = 0, 1
+
+EXPORTS = (
+    "spts_workspace_bytes", "spts_create", "spts_destroy", "spts_strerror", "spts_last_hip_error", "spts_uses_mfma",
+    "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_layer_prefill", "spts_msdp_compact",
+)
+
+
+class spts_model_desc(C.Structure):
+    _fields_ = [("D", C.c_int32), ("H", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("Dff", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32)]
+
+
+class spts_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("Wq", "Wk", "Wv", "Wo", "gamma1", "Wgate", "Wup", "Wdown", "gamma2",
+                                           "Ug", "Vg", "Uu", "Vu", "Ud", "Vd")] + [("r", C.c_int32), ("Dlow", C.c_int32)]
+
+
+class spts_layer_cfg(C.Structure):
+    _fields_ = [("skip", C.c_int32), ("probe_len", C.c_int32), ("m_attn", C.c_int64), ("m_ffn", C.c_int64),
+                ("protect_last", C.c_int32), ("kv_mode", C.c_int32)]
+
+
+class spts_kv_out(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("pos", C.c_void_p), ("capacity", C.c_int64), ("count", C.c_int64)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Loads libspts.so built in-tree; raises if it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.spts_workspace_bytes.restype = C.c_size_t
+    lib.spts_workspace_bytes.argtypes = [C.POINTER(spts_model_desc), i64, i32, i32, i32]
+    lib.spts_create.restype = C.c_int
+    lib.spts_create.argtypes = [C.POINTER(vp), C.POINTER(spts_model_desc), vp, vp, C.c_size_t, i64, i32, i32, i32]
+    lib.spts_destroy.restype = None
+    lib.spts_destroy.argtypes = [vp]
+    lib.spts_strerror.restype = C.c_char_p
+    lib.spts_strerror.argtypes = [C.c_int]
+    lib.spts_last_hip_error.restype = C.c_int
+    lib.spts_last_hip_error.argtypes = [vp]
+    lib.spts_uses_mfma.restype = C.c_int
+    lib.spts_uses_mfma.argtypes = [vp]
+    lib.spts_probe_attn.restype = C.c_int
+    lib.spts_probe_attn.argtypes = [vp, vp, vp, i64, C.POINTER(spts_layer_weights), i32, vp, vp]
+    lib.spts_probe_ffn.restype = C.c_int
+    lib.spts_probe_ffn.argtypes = [vp, vp, i64, C.POINTER(spts_layer_weights), vp, vp, vp]
+    lib.spts_select_topk.restype = C.c_int
+    lib.spts_select_topk.argtypes = [vp, vp, i64, i64, i32, vp]
+    lib.spts_layer_prefill.restype = C.c_int
+    lib.spts_layer_prefill.argtypes = [vp, vp, vp, i64, C.POINTER(spts_layer_weights), C.POINTER(spts_layer_cfg),
+                                       C.POINTER(spts_kv_out), vp, vp, vp]
+    lib.spts_msdp_compact.restype = C.c_int
+    lib.spts_msdp_compact.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+class SptsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {load().spts_strerror(status).decode()} ({status})")
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _check(status: int, where: str):
+    if status != SPTS_OK:
+        raise SptsError(status, where)
+
+
+def model_desc(shape) -> spts_model_desc:
+    """shape: any object with D, H, Hkv, d, Dff, rms_eps, rope_base, dtype ('f32' | 'bf16')."""
+    return spts_model_desc(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, shape.rms_eps, shape.rope_base,
+                           SPTS_BF16 if shape.dtype == "bf16" else SPTS_F32)
+
+
+def layer_weights(tensors: dict, r: int = 0, Dlow: int = 0) -> spts_layer_weights:
+    """tensors: name -> device tensor in the ABI layout ([d_out, d_in]); missing names become NULL."""
+    w = spts_layer_weights()
+    for name, _ in spts_layer_weights._fields_[:15]:
+        t = tensors.get(name)
+        setattr(w, name, _ptr(t))
+    w.r, w.Dlow = int(r), int(Dlow)
+    w._keepalive = tensors  # keep the device tensors referenced as long as the struct lives
+    return w
+
+
+def spts_workspace_bytes(model: spts_model_desc, max_tokens: int, max_probe: int, max_r: int, max_dlow: int) -> int:
+    return int(load().spts_workspace_bytes(C.byref(model), max_tokens, max_probe, max_r, max_dlow))
+
+
+class Context:
+    """Owns an spts_ctx and its workspace tensor (allocated through torch on the current device)."""
+
+    def __init__(self, shape, max_tokens: int, max_probe: int, max_r: int, max_dlow: int, stream=None):
+        import torch
+        lib = load()
+        if not torch.cuda.is_available():
+            raise RuntimeError("libspts needs a GPU: no device is visible (there is no CPU fallback)")
+        self.shape = shape
+        self.model = model_desc(shape)
+        nbytes = spts_workspace_bytes(self.model, max_tokens, max_probe, max_r, max_dlow)
+        if nbytes == 0:
+            raise SptsError(SPTS_EINVAL, "spts_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        h = C.c_void_p()
+        _check(lib.spts_create(C.byref(h), C.byref(self.model), self.stream.cuda_stream, self.workspace.data_ptr(),
+                               nbytes, max_tokens, max_probe, max_r, max_dlow), "spts_create")
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load().spts_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def uses_mfma(self) -> bool:
+        return bool(load().spts_uses_mfma(self.handle))
+
+    # ---- the five calls; each returns the status raised as SptsError when non-zero -------------
+    def spts_probe_attn(self, x, pos, N, w: spts_layer_weights, probe_len, k_out, s_mha):
+        _check(load().spts_probe_attn(self.handle, _ptr(x), _ptr(pos), N, C.byref(w), probe_len, _ptr(k_out), _ptr(s_mha)),
+               "spts_probe_attn")
+
+    def spts_probe_ffn(self, x, N, w: spts_layer_weights, s_mha, c_ffn, s_ffn):
+        _check(load().spts_probe_ffn(self.handle, _ptr(x), N, C.byref(w), _ptr(s_mha), _ptr(c_ffn), _ptr(s_ffn)),
+               "spts_probe_ffn")
+
+    def spts_select_topk(self, scores, N, k, protect_last, idx_out):
+        _check(load().spts_select_topk(self.handle, _ptr(scores), N, k, protect_last, _ptr(idx_out)), "spts_select_topk")
+
+    def spts_layer_prefill(self, x, pos, N, w: spts_layer_weights, cfg: spts_layer_cfg, kv: Optional[spts_kv_out] = None,
+                           s_mha=None, idx_attn=None, idx_ffn=None):
+        _check(load().spts_layer_prefill(self.handle, _ptr(x), _ptr(pos), N, C.byref(w), C.byref(cfg),
+                                         C.byref(kv) if kv is not None else None, _ptr(s_mha), _ptr(idx_attn),
+                                         _ptr(idx_ffn)), "spts_layer_prefill")
+
+    def spts_msdp_compact(self, x_in, pos_in, s_mha, N, N_next, protect_last, x_out, pos_out, map_new2old,
+                          map_old2new=None):
+        _check(load().spts_msdp_compact(self.handle, _ptr(x_in), _ptr(pos_in), _ptr(s_mha), N, N_next, protect_last,
+                                        _ptr(x_out), _ptr(pos_out), _ptr(map_new2old), _ptr(map_old2new)),
+               "spts_msdp_compact")
+
+    # raw status (for error-path tests)
+    def raw(self, name, *args):
+        return getattr(load(), name)(self.handle, *args)

@@ -1,0 +1,420 @@
+// C ABI of libspts: argument validation, workspace carving and the launch sequence of each call.
+// No arithmetic of the method lives here; every step runs in the kernels of this library.
+#include "../../include/spts.h"
+#include "spts_internal.h"
+
+#include <new>
+
+using namespace spts;
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct Workspace {
+    size_t rope, xn, kall, tmp32, qp, probe, S, C, SF, part, idxA, idxF, posA, q, khat, vhat, vt, att, t, z, big, misc;
+    size_t total;
+};
+
+struct Limits { int64_t max_tokens; int32_t max_probe, max_r, max_dlow; };
+
+Workspace carve(const spts_model_desc& m, const Limits& L) {
+    Workspace w{};
+    const size_t b = m.dtype == SPTS_BF16 ? 2 : 4;
+    const size_t Nm = (size_t)L.max_tokens;
+    const size_t Np = (Nm + 255) / 256 * 256;  // row padding for tile-granular kernels
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    w.rope = take(Np * (size_t)(m.d / 2) * sizeof(float2));
+    w.xn = take(Np * m.D * b);
+    w.kall = take(Np * (size_t)m.Hkv * m.d * b);
+    w.tmp32 = take(Np * (size_t)m.H * m.d * 4);
+    w.qp = take((size_t)(L.max_probe + 256) * m.H * m.d * b);
+    w.probe = take(probe_scratch_floats(L.max_tokens, L.max_probe, m.H, m.Hkv) * 4);
+    w.S = take(Np * 4);
+    w.C = take(Np * 4);
+    w.SF = take(Np * 4);
+    w.part = take(Np * (size_t)((m.D + 63) / 64) * 4);
+    w.idxA = take(Np * 4);
+    w.idxF = take(Np * 4);
+    w.posA = take(Np * 4);
+    w.q = take(Np * (size_t)m.H * m.d * b);
+    w.khat = take(Np * (size_t)m.Hkv * m.d * b);
+    w.vhat = take(Np * (size_t)m.Hkv * m.d * b);
+    w.vt = take((size_t)m.Hkv * m.d * (Np + 256) * b);
+    w.att = take(Np * (size_t)m.H * m.d * b);
+    w.t = take(Np * (size_t)(2 * L.max_r) * b);
+    w.z = take(Np * (size_t)L.max_r * b);
+    size_t inner = (size_t)(m.Dff > L.max_dlow ? m.Dff : L.max_dlow);
+    w.big = take(Np * inner * b);
+    w.misc = take(4096);
+    w.total = off;
+    return w;
+}
+
+bool model_ok(const spts_model_desc* m, int* status) {
+    if (!m) { *status = SPTS_EINVAL; return false; }
+    if (m->dtype != SPTS_F32 && m->dtype != SPTS_BF16) { *status = SPTS_EDTYPE; return false; }
+    if (m->D <= 0 || m->H <= 0 || m->Hkv <= 0 || m->d <= 0 || m->Dff <= 0) { *status = SPTS_EINVAL; return false; }
+    if (m->H % m->Hkv != 0 || (m->d & 1) || m->d > 256) { *status = SPTS_ESHAPE; return false; }
+    if (!(m->rms_eps >= 0.f) || !(m->rope_base > 0.f)) { *status = SPTS_EINVAL; return false; }
+    *status = SPTS_OK;
+    return true;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+struct spts_ctx {
+    spts_model_desc m;
+    Limits lim;
+    hipStream_t stream;
+    char* ws;
+    Workspace off;
+    bool bf16;
+    int last_hip;
+    template <typename T> T* p(size_t o) const { return reinterpret_cast<T*>(ws + o); }
+};
+
+#define SPTS_HIP(ctx, expr)                                                   \
+    do {                                                                      \
+        hipError_t e__ = (expr);                                              \
+        if (e__ != hipSuccess) { (ctx)->last_hip = (int)e__; return SPTS_EHIP; } \
+    } while (0)
+#define SPTS_TRY(expr)                       \
+    do {                                     \
+        int s__ = (expr);                    \
+        if (s__ != SPTS_OK) return s__;      \
+    } while (0)
+
+namespace {
+
+// ---- dispatch helpers -------------------------------------------------------------------------
+int run_gemm(spts_ctx* c, const GemmArgs& a) {
+    if (c->bf16 && gemm_mfma_supported(a)) SPTS_HIP(c, launch_gemm_mfma(a, c->stream));
+    else SPTS_HIP(c, launch_gemm_generic(a, c->bf16, c->stream));
+    return SPTS_OK;
+}
+
+GemmArgs gemm_args(const void* A, int64_t lda, const int32_t* a_idx, const void* B, int64_t ldb, void* C, int64_t ldc,
+                   int64_t M, int32_t N, int32_t K, int epi = EPI_STORE) {
+    GemmArgs g{};
+    g.A = A; g.lda = lda; g.a_idx = a_idx; g.B0 = B; g.B1 = nullptr; g.ldb = ldb; g.C = C; g.ldc = ldc;
+    g.M = M; g.N = N; g.K = K; g.epi = epi;
+    return g;
+}
+
+// out[rows, heads*d] = rotary(A * B^T); table row of output row i is (tidx ? tidx[i] : i + row0)
+int run_gemm_rope(spts_ctx* c, GemmArgs g, int heads, const int32_t* tidx, int64_t row0, void* out) {
+    const float2* table = c->p<float2>(c->off.rope);
+    GemmArgs f = g;
+    f.epi = EPI_ROPE; f.C = out; f.rope = table + row0 * (c->m.d / 2); f.rope_idx = tidx; f.head_dim = c->m.d;
+    if (c->bf16 && gemm_mfma_supported(f)) { SPTS_HIP(c, launch_gemm_mfma(f, c->stream)); return SPTS_OK; }
+    g.C = c->p<float>(c->off.tmp32); g.c_is_f32 = 1; g.epi = EPI_STORE;
+    SPTS_TRY(run_gemm(c, g));
+    SPTS_HIP(c, launch_rope_apply(c->p<float>(c->off.tmp32), table, tidx, row0, out, g.M, heads, c->m.d, c->bf16, c->stream));
+    return SPTS_OK;
+}
+
+int check_weights_attn(const spts_layer_weights* w) {
+    if (!w || !w->Wq || !w->Wk || !w->gamma1) return SPTS_EINVAL;
+    if (!aligned16(w->Wq) || !aligned16(w->Wk) || !aligned16(w->gamma1)) return SPTS_EALIGN;
+    return SPTS_OK;
+}
+int check_weights_proxy(const spts_ctx* c, const spts_layer_weights* w) {
+    if (!w || !w->gamma2 || !w->Ug || !w->Vg || !w->Uu || !w->Vu || !w->Ud || !w->Vd) return SPTS_EINVAL;
+    if (w->r <= 0 || w->Dlow <= 0) return SPTS_EINVAL;
+    if (w->r > c->lim.max_r || w->Dlow > c->lim.max_dlow) return SPTS_EWORKSPACE;
+    const void* ps[] = {w->gamma2, w->Ug, w->Vg, w->Uu, w->Vu, w->Ud, w->Vd};
+    for (const void* p : ps) if (!aligned16(p)) return SPTS_EALIGN;
+    return SPTS_OK;
+}
+int check_weights_full(const spts_ctx* c, const spts_layer_weights* w, bool need_proxy) {
+    SPTS_TRY(check_weights_attn(w));
+    if (!w->Wv || !w->Wo || !w->Wgate || !w->Wup || !w->Wdown || !w->gamma2) return SPTS_EINVAL;
+    const void* ps[] = {w->Wv, w->Wo, w->Wgate, w->Wup, w->Wdown, w->gamma2};
+    for (const void* p : ps) if (!aligned16(p)) return SPTS_EALIGN;
+    if (need_proxy) SPTS_TRY(check_weights_proxy(c, w));
+    return SPTS_OK;
+}
+
+// ---- PAP probe: norm, keys, probe queries, scores ----------------------------------------------
+// leaves xn (normalised x) and the rotary table in the workspace for the caller
+int probe_attn_impl(spts_ctx* c, const void* x, const int32_t* pos, int64_t N, const spts_layer_weights* w, int P,
+                    bool want_scores, void* k_out, float* s_out) {
+    const auto& m = c->m;
+    SPTS_HIP(c, launch_rope_table(pos, N, m.d, m.rope_base, c->p<float2>(c->off.rope), c->stream));
+    SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, c->p<void>(c->off.xn), N, m.D, c->bf16, c->stream));
+    const int KV = m.Hkv * m.d, QD = m.H * m.d;
+    GemmArgs gk = gemm_args(c->p<void>(c->off.xn), m.D, nullptr, w->Wk, m.D, nullptr, KV, N, KV, m.D);
+    SPTS_TRY(run_gemm_rope(c, gk, m.Hkv, nullptr, 0, k_out));
+    if (!want_scores) return SPTS_OK;
+    const size_t eb = c->bf16 ? 2 : 4;
+    const char* xn_probe = c->p<char>(c->off.xn) + (size_t)(N - P) * m.D * eb;
+    GemmArgs gq = gemm_args(xn_probe, m.D, nullptr, w->Wq, m.D, nullptr, QD, P, QD, m.D);
+    SPTS_TRY(run_gemm_rope(c, gq, m.H, nullptr, N - P, c->p<void>(c->off.qp)));
+    ProbeArgs pa{};
+    pa.qp = c->p<void>(c->off.qp); pa.k = k_out; pa.S = s_out;
+    pa.stats = c->p<float>(c->off.probe);
+    pa.partial = c->p<float>(c->off.probe) + (2 * (size_t)P * m.H + 64);
+    pa.N = N; pa.P = P; pa.H = m.H; pa.Hkv = m.Hkv; pa.d = m.d;
+    if (c->bf16 && probe_mfma_supported(pa)) SPTS_HIP(c, launch_probe_mfma(pa, c->stream));
+    else SPTS_HIP(c, launch_probe_generic(pa, c->bf16, c->stream));
+    return SPTS_OK;
+}
+
+// ---- LTP probe on an already normalised xn2 [N, D] ---------------------------------------------
+int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_weights* w, const float* s_mha,
+                      float* c_ffn, float* s_ffn) {
+    const auto& m = c->m;
+    const int r = w->r, Dlow = w->Dlow;
+    const size_t eb = c->bf16 ? 2 : 4;
+    char* t = c->p<char>(c->off.t);  // [N, 2r]: columns [0,r) = x Ug, [r,2r) = x Uu
+    GemmArgs g1 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, r, m.D);
+    SPTS_TRY(run_gemm(c, g1));
+    GemmArgs g2 = gemm_args(xn2, m.D, nullptr, w->Uu, m.D, t + (size_t)r * eb, 2 * r, N, r, m.D);
+    SPTS_TRY(run_gemm(c, g2));
+    // hp = silu(tg Vg) * (tu Vu)   [N, Dlow]
+    GemmArgs g3 = gemm_args(t, 2 * r, nullptr, w->Vg, r, c->p<void>(c->off.big), Dlow, N, Dlow, r, EPI_SILU_MUL);
+    g3.B1 = w->Vu; g3.A1 = t + (size_t)r * eb;
+    SPTS_TRY(run_gemm(c, g3));
+    // z = hp Vd^T   [N, r]
+    GemmArgs g4 = gemm_args(c->p<void>(c->off.big), Dlow, nullptr, w->Vd, Dlow, c->p<void>(c->off.z), r, N, r, Dlow);
+    SPTS_TRY(run_gemm(c, g4));
+    // o = z Ud^T [N, D] is never stored: per-block sums of squares, then the square root
+    GemmArgs g5 = gemm_args(c->p<void>(c->off.z), r, nullptr, w->Ud, r, nullptr, 0, N, m.D, r, EPI_SUMSQ);
+    bool mf = c->bf16 && gemm_mfma_supported(g5);
+    int nb = gemm_sumsq_blocks(m.D, mf);
+    g5.part = c->p<float>(c->off.part); g5.part_ld = nb;
+    SPTS_TRY(run_gemm(c, g5));
+    SPTS_HIP(c, launch_finish_ffn_scores(c->p<float>(c->off.part), nb, s_mha, c_ffn, s_ffn, N, c->stream));
+    return SPTS_OK;
+}
+
+int common_call_checks(const spts_ctx* c, int64_t N) {
+    if (!c) return SPTS_EINVAL;
+    if (N < 0) return SPTS_EINVAL;
+    if (N > c->lim.max_tokens) return SPTS_EWORKSPACE;
+    if (N > 0x7fffffff) return SPTS_ESHAPE;
+    return SPTS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* spts_strerror(int status) {
+    switch (status) {
+        case SPTS_OK: return "ok";
+        case SPTS_EINVAL: return "invalid argument";
+        case SPTS_ESHAPE: return "unsupported shape";
+        case SPTS_EALIGN: return "pointer not 16-byte aligned";
+        case SPTS_EWORKSPACE: return "workspace too small for this call";
+        case SPTS_EDTYPE: return "unsupported dtype";
+        case SPTS_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+size_t spts_workspace_bytes(const spts_model_desc* model, int64_t max_tokens, int32_t max_probe, int32_t max_r,
+                            int32_t max_dlow) {
+    int st;
+    if (!model_ok(model, &st)) return 0;
+    if (max_tokens <= 0 || max_probe <= 0 || max_r <= 0 || max_dlow <= 0) return 0;
+    Limits L{max_tokens, max_probe, max_r, max_dlow};
+    return carve(*model, L).total;
+}
+
+int spts_create(spts_ctx** ctx, const spts_model_desc* model, void* hip_stream, void* workspace, size_t workspace_bytes,
+                int64_t max_tokens, int32_t max_probe, int32_t max_r, int32_t max_dlow) {
+    if (!ctx) return SPTS_EINVAL;
+    *ctx = nullptr;
+    int st;
+    if (!model_ok(model, &st)) return st;
+    if (max_tokens <= 0 || max_probe <= 0 || max_r <= 0 || max_dlow <= 0 || !workspace) return SPTS_EINVAL;
+    if (!aligned16(workspace)) return SPTS_EALIGN;
+    Limits L{max_tokens, max_probe, max_r, max_dlow};
+    Workspace w = carve(*model, L);
+    if (workspace_bytes < w.total) return SPTS_EWORKSPACE;
+    spts_ctx* c = new (std::nothrow) spts_ctx();
+    if (!c) return SPTS_EINVAL;
+    c->m = *model; c->lim = L; c->stream = (hipStream_t)hip_stream; c->ws = (char*)workspace; c->off = w;
+    c->bf16 = model->dtype == SPTS_BF16; c->last_hip = 0;
+    *ctx = c;
+    return SPTS_OK;
+}
+
+void spts_destroy(spts_ctx* ctx) { delete ctx; }
+
+int spts_last_hip_error(const spts_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+int spts_uses_mfma(const spts_ctx* ctx) {
+    if (!ctx || !ctx->bf16) return 0;
+    const auto& m = ctx->m;
+    GemmArgs g = gemm_args((const void*)16, m.D, nullptr, (const void*)16, m.D, (void*)16, m.Dff, 256, m.Dff, m.D);
+    return gemm_mfma_supported(g) ? 1 : 0;
+}
+
+int spts_probe_attn(spts_ctx* c, const void* x, const int32_t* pos, int64_t N, const spts_layer_weights* w,
+                    int32_t probe_len, void* k_out, float* s_mha) {
+    SPTS_TRY(common_call_checks(c, N));
+    if (N == 0) return SPTS_OK;
+    if (!x || !pos || !k_out || !s_mha) return SPTS_EINVAL;
+    if (!aligned16(x) || !aligned16(pos) || !aligned16(k_out) || !aligned16(s_mha)) return SPTS_EALIGN;
+    SPTS_TRY(check_weights_attn(w));
+    if (probe_len < 1 || probe_len > N) return SPTS_EINVAL;
+    if (probe_len > c->lim.max_probe) return SPTS_EWORKSPACE;
+    return probe_attn_impl(c, x, pos, N, w, probe_len, true, k_out, s_mha);
+}
+
+int spts_probe_ffn(spts_ctx* c, const void* x, int64_t N, const spts_layer_weights* w, const float* s_mha, float* c_ffn,
+                   float* s_ffn) {
+    SPTS_TRY(common_call_checks(c, N));
+    if (N == 0) return SPTS_OK;
+    if (!x || !s_ffn) return SPTS_EINVAL;
+    if (!aligned16(x) || !aligned16(s_ffn) || (s_mha && !aligned16(s_mha)) || (c_ffn && !aligned16(c_ffn))) return SPTS_EALIGN;
+    SPTS_TRY(check_weights_proxy(c, w));
+    SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, c->m.rms_eps, c->p<void>(c->off.xn), N, c->m.D, c->bf16, c->stream));
+    return proxy_scores_impl(c, c->p<void>(c->off.xn), N, w, s_mha, c_ffn, s_ffn);
+}
+
+int spts_select_topk(spts_ctx* c, const float* scores, int64_t N, int64_t k, int32_t protect_last, int32_t* idx_out) {
+    SPTS_TRY(common_call_checks(c, N));
+    if (k < 0 || k > N) return SPTS_EINVAL;
+    if (k == 0) return SPTS_OK;
+    if (!scores || !idx_out) return SPTS_EINVAL;
+    if (!aligned16(scores) || !aligned16(idx_out)) return SPTS_EALIGN;
+    SPTS_HIP(c, launch_topk(scores, N, k, protect_last, idx_out, c->p<int32_t>(c->off.misc), c->stream));
+    return SPTS_OK;
+}
+
+int spts_msdp_compact(spts_ctx* c, const void* x_in, const int32_t* pos_in, const float* s_mha, int64_t N, int64_t N_next,
+                      int32_t protect_last, void* x_out, int32_t* pos_out, int32_t* map_new2old, int32_t* map_old2new) {
+    SPTS_TRY(common_call_checks(c, N));
+    if (N_next < 0) return SPTS_EINVAL;
+    const int64_t keep = N_next < N ? N_next : N;
+    if (N == 0) return SPTS_OK;
+    if (map_old2new) {
+        if (!aligned16(map_old2new)) return SPTS_EALIGN;
+    }
+    if (keep > 0) {
+        if (!x_in || !pos_in || !s_mha || !x_out || !pos_out || !map_new2old) return SPTS_EINVAL;
+        if (!aligned16(x_in) || !aligned16(pos_in) || !aligned16(s_mha) || !aligned16(x_out) || !aligned16(pos_out) ||
+            !aligned16(map_new2old))
+            return SPTS_EALIGN;
+        const size_t row_bytes = (size_t)c->m.D * (c->bf16 ? 2 : 4);
+        const char* a = (const char*)x_in; const char* b = (const char*)x_out;
+        if (a < b + (size_t)keep * row_bytes && b < a + (size_t)N * row_bytes) return SPTS_EINVAL;  // overlap
+    }
+    if (map_old2new) SPTS_HIP(c, launch_fill_i32(map_old2new, -1, N, c->stream));
+    if (keep == 0) return SPTS_OK;
+    SPTS_HIP(c, launch_topk(s_mha, N, keep, protect_last, map_new2old, c->p<int32_t>(c->off.misc), c->stream));
+    const int64_t row_bytes = (int64_t)c->m.D * (c->bf16 ? 2 : 4);
+    SPTS_HIP(c, launch_gather_rows(x_in, map_new2old, x_out, keep, row_bytes, c->stream));
+    SPTS_HIP(c, launch_gather_i32(pos_in, map_new2old, pos_out, keep, c->stream));
+    if (map_old2new) SPTS_HIP(c, launch_scatter_iota(map_new2old, map_old2new, keep, c->stream));
+    return SPTS_OK;
+}
+
+int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, const spts_layer_weights* w,
+                       const spts_layer_cfg* cfg, spts_kv_out* kv, float* s_mha, int32_t* idx_attn, int32_t* idx_ffn) {
+    SPTS_TRY(common_call_checks(c, N));
+    if (!cfg) return SPTS_EINVAL;
+    if (cfg->m_attn < 0 || cfg->m_ffn < 0) return SPTS_EINVAL;
+    if (kv) kv->count = 0;
+    if (N == 0) return SPTS_OK;
+    if (!x || !pos) return SPTS_EINVAL;
+    if (!aligned16(x) || !aligned16(pos)) return SPTS_EALIGN;
+    const bool skip = cfg->skip != 0;
+    SPTS_TRY(check_weights_full(c, w, skip));
+    if (skip) {
+        if (cfg->probe_len < 1 || cfg->probe_len > N) return SPTS_EINVAL;
+        if (cfg->probe_len > c->lim.max_probe) return SPTS_EWORKSPACE;
+        if ((s_mha && !aligned16(s_mha)) || (idx_attn && !aligned16(idx_attn)) || (idx_ffn && !aligned16(idx_ffn)))
+            return SPTS_EALIGN;
+    }
+    const auto& m = c->m;
+    const int64_t Ma = skip ? (cfg->m_attn < N ? cfg->m_attn : N) : N;
+    const int64_t Mf = skip ? (cfg->m_ffn < N ? cfg->m_ffn : N) : N;
+    const bool full_kv = !skip || cfg->kv_mode == 1;
+    const int64_t Mk = full_kv ? N : Ma;
+    if (kv) {
+        if (Ma > 0) {
+            if (!kv->k || !kv->v || !kv->pos) return SPTS_EINVAL;
+            if (!aligned16(kv->k) || !aligned16(kv->v) || !aligned16(kv->pos)) return SPTS_EALIGN;
+            if (kv->capacity < Mk) return SPTS_EINVAL;
+        }
+    }
+    const int KV = m.Hkv * m.d, QD = m.H * m.d;
+    const size_t eb = c->bf16 ? 2 : 4;
+    hipStream_t st = c->stream;
+    void* xn = c->p<void>(c->off.xn);
+
+    // ------------------------------------------------ attention block (Alg. 1, PAP block / dense branch)
+    float* S = s_mha ? s_mha : c->p<float>(c->off.S);
+    int32_t* idxA = nullptr;
+    void* kall = (kv && full_kv && Ma > 0) ? kv->k : c->p<void>(c->off.kall);
+    SPTS_TRY(probe_attn_impl(c, x, pos, N, w, skip ? cfg->probe_len : 0, skip, kall, S));
+    if (skip) {
+        idxA = idx_attn ? idx_attn : c->p<int32_t>(c->off.idxA);
+        SPTS_HIP(c, launch_topk(S, N, Ma, cfg->protect_last, idxA, c->p<int32_t>(c->off.misc), st));
+    }
+    if (Ma > 0) {
+        // queries of the active rows (rows gathered through idxA inside the GEMM's A loads)
+        GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, Ma, QD, m.D);
+        SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q)));
+        const int32_t* qpos = pos;
+        const int32_t* kpos = pos;
+        void* kk = kall;
+        void* vv;
+        if (skip) {
+            int32_t* posA = (kv && !full_kv) ? kv->pos : c->p<int32_t>(c->off.posA);
+            SPTS_HIP(c, launch_gather_i32(pos, idxA, posA, Ma, st));
+            qpos = posA;
+        }
+        if (!full_kv) {
+            kk = kv ? kv->k : c->p<void>(c->off.khat);
+            SPTS_HIP(c, launch_gather_rows(kall, idxA, kk, Ma, (int64_t)KV * eb, st));
+            kpos = qpos;
+        } else if (kv) {
+            SPTS_HIP(c, launch_copy_bytes(pos, kv->pos, N * 4, st));
+        }
+        vv = kv ? kv->v : c->p<void>(c->off.vhat);
+        AttnArgs aa{};
+        aa.q = c->p<void>(c->off.q); aa.k = kk; aa.v = vv; aa.qpos = qpos; aa.kpos = kpos; aa.out = c->p<void>(c->off.att);
+        aa.Mq = Ma; aa.Mk = Mk; aa.H = m.H; aa.Hkv = m.Hkv; aa.d = m.d;
+        aa.ldvt = (Mk + 255) / 256 * 256; aa.vt = c->p<void>(c->off.vt);
+        const bool amf = c->bf16 && attention_mfma_supported(aa);
+        GemmArgs gv = gemm_args(xn, m.D, full_kv ? nullptr : idxA, w->Wv, m.D, vv, KV, Mk, KV, m.D);
+        if (amf) { gv.Ct = c->p<void>(c->off.vt); gv.ldct = aa.ldvt; }
+        SPTS_TRY(run_gemm(c, gv));
+        if (kv) kv->count = Mk;
+        if (amf) SPTS_HIP(c, launch_attention_mfma(aa, st));
+        else SPTS_HIP(c, launch_attention_generic(aa, c->bf16, st));
+        // x[T_a] += att * Wo^T
+        GemmArgs go = gemm_args(c->p<void>(c->off.att), QD, nullptr, w->Wo, QD, x, m.D, Ma, m.D, QD, EPI_RESIDUAL);
+        go.c_idx = idxA;
+        SPTS_TRY(run_gemm(c, go));
+    }
+
+    // ------------------------------------------------ FFN block (Alg. 1, LTP block / dense branch)
+    if (Mf == 0) return SPTS_OK;
+    SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, m.rms_eps, xn, N, m.D, c->bf16, st));
+    int32_t* idxF = nullptr;
+    if (skip) {
+        float* SF = c->p<float>(c->off.SF);
+        SPTS_TRY(proxy_scores_impl(c, xn, N, w, S, nullptr, SF));
+        idxF = idx_ffn ? idx_ffn : c->p<int32_t>(c->off.idxF);
+        SPTS_HIP(c, launch_topk(SF, N, Mf, cfg->protect_last, idxF, c->p<int32_t>(c->off.misc), st));
+    }
+    GemmArgs gh = gemm_args(xn, m.D, idxF, w->Wgate, m.D, c->p<void>(c->off.big), m.Dff, Mf, m.Dff, m.D, EPI_SILU_MUL);
+    gh.B1 = w->Wup;
+    SPTS_TRY(run_gemm(c, gh));
+    GemmArgs gd = gemm_args(c->p<void>(c->off.big), m.Dff, nullptr, w->Wdown, m.Dff, x, m.D, Mf, m.D, m.Dff, EPI_RESIDUAL);
+    gd.c_idx = idxF;
+    SPTS_TRY(run_gemm(c, gd));
+    return SPTS_OK;
+}
+
+}  // extern "C"

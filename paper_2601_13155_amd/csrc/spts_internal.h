@@ -1,0 +1,109 @@
+// Internal declarations shared by the HIP translation units of libspts (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spts {
+
+// ------------------------------------------------------------------ element types
+struct bf16_t { uint16_t v; };
+
+__host__ __device__ inline float bf16_to_f32(bf16_t h) {
+    union { uint32_t u; float f; } c; c.u = ((uint32_t)h.v) << 16; return c.f;
+}
+// round-to-nearest-even; NaN stays NaN
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+    union { uint32_t u; float f; } c; c.f = f;
+    uint32_t u = c.u;
+    bf16_t r;
+    if ((u & 0x7fffffffu) > 0x7f800000u) { r.v = (uint16_t)((u >> 16) | 0x40); return r; }
+    u += 0x7fffu + ((u >> 16) & 1u);
+    r.v = (uint16_t)(u >> 16);
+    return r;
+}
+__device__ inline float to_f32(float v) { return v; }
+__device__ inline float to_f32(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ inline T from_f32(float v);
+template <> __device__ inline float from_f32<float>(float v) { return v; }
+template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+// ------------------------------------------------------------------ GEMM (C = A * B^T)
+enum GemmEpilogue : int {
+    EPI_STORE = 0,      // C[row, col] = acc          (T, or fp32 when c_is_f32)
+    EPI_SILU_MUL = 1,   // C[row, col] = silu(acc0) * acc1     (two B operands)
+    EPI_RESIDUAL = 2,   // C[crow, col] = C[crow, col] + acc   (crow = c_idx ? c_idx[row] : row)
+    EPI_SUMSQ = 3,      // part[row, col_block] = sum over the block's columns of acc^2
+    EPI_ROPE = 4,       // C[row, col] = rotary(acc) with table row (a_idx ? a_idx[row] : row); MFMA path only
+};
+
+struct GemmArgs {
+    const void* A; int64_t lda; const int32_t* a_idx;   // A [*, K] rows optionally gathered
+    const void* A1;                                     // EPI_SILU_MUL: A operand of the second product (null = A)
+    const void* B0; const void* B1; int64_t ldb;        // B [N, K]
+    void* C; int64_t ldc; const int32_t* c_idx;         // output rows optionally scattered
+    void* Ct; int64_t ldct;                             // optional transposed copy Ct[col, row]
+    float* part; int32_t part_ld;                       // EPI_SUMSQ partial sums [M, part_ld]
+    const float2* rope; int32_t head_dim;               // EPI_ROPE: cos/sin table [rows, head_dim/2]
+    const int32_t* rope_idx;                            // table row = rope_idx ? rope_idx[row] : row
+    int64_t M; int32_t N; int32_t K;
+    int32_t epi; int32_t c_is_f32;
+};
+
+hipError_t launch_gemm_generic(const GemmArgs& a, bool bf16, hipStream_t s);
+// true when the matrix-core kernel can serve these arguments (alignment / divisibility)
+bool gemm_mfma_supported(const GemmArgs& a);
+hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s);
+// number of column blocks a EPI_SUMSQ launch writes per row
+int gemm_sumsq_blocks(int32_t N, bool mfma);
+
+// ------------------------------------------------------------------ elementwise / data movement
+hipError_t launch_rope_table(const int32_t* pos, int64_t N, int d, float base, float2* table, hipStream_t s);
+hipError_t launch_rmsnorm(const void* x, const void* gamma, float eps, void* out, int64_t N, int D, bool bf16, hipStream_t s);
+// out[n, h, :] = rotary(in_f32[n, h, :]) with table row (idx ? idx[n] : n + row0)
+hipError_t launch_rope_apply(const float* in, const float2* table, const int32_t* idx, int64_t row0, void* out,
+                             int64_t n, int heads, int d, bool bf16, hipStream_t s);
+// out[i, :] = in[idx[i], :]   (row_bytes multiple of 4)
+hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n, int64_t row_bytes, hipStream_t s);
+hipError_t launch_gather_i32(const int32_t* in, const int32_t* idx, int32_t* out, int64_t n, hipStream_t s);
+hipError_t launch_copy_bytes(const void* in, void* out, int64_t bytes, hipStream_t s);
+hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
+hipError_t launch_iota_i32(int32_t* p, int64_t n, hipStream_t s);
+// old2new[idx[i]] = i
+hipError_t launch_scatter_iota(const int32_t* idx, int32_t* old2new, int64_t n, hipStream_t s);
+// c = sqrt(sum_j part[n, j]); s_ffn = c * (s_mha ? s_mha[n] : 1)
+hipError_t launch_finish_ffn_scores(const float* part, int nparts, const float* s_mha, float* c_ffn, float* s_ffn,
+                                    int64_t N, hipStream_t s);
+// vt[c, i] = v[i, c]  (v [M, C] -> vt [C, ldvt]); columns i in [M, ldvt) are zero-filled
+hipError_t launch_transpose_pad(const void* v, void* vt, int64_t M, int C, int64_t ldvt, bool bf16, hipStream_t s);
+
+// ------------------------------------------------------------------ TopK
+// idx_out[0..k) ascending.  scratch: >= 64 int32.
+hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out,
+                       int32_t* scratch, hipStream_t s);
+
+// ------------------------------------------------------------------ attention
+struct AttnArgs {
+    const void* q;  // [Mq, H, d]
+    const void* k;  // [Mk, Hkv, d]
+    const void* v;  // [Mk, Hkv, d]
+    const void* vt; // [Hkv*d, ldvt] transposed values (MFMA path), may be null for the generic path
+    int64_t ldvt;
+    const int32_t* qpos; const int32_t* kpos;  // ascending absolute positions
+    void* out;      // [Mq, H, d]
+    int64_t Mq, Mk; int H, Hkv, d;
+};
+hipError_t launch_attention_generic(const AttnArgs& a, bool bf16, hipStream_t s);
+bool attention_mfma_supported(const AttnArgs& a);
+hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t s);
+
+// probe: qp [P, H, d], k [N, Hkv, d] -> S[N]; scratch floats: 2*P*H (+ Hkv*N for the MFMA path)
+struct ProbeArgs {
+    const void* qp; const void* k; float* S; float* stats; float* partial;
+    int64_t N; int P, H, Hkv, d;
+};
+hipError_t launch_probe_generic(const ProbeArgs& a, bool bf16, hipStream_t s);
+bool probe_mfma_supported(const ProbeArgs& a);
+hipError_t launch_probe_mfma(const ProbeArgs& a, hipStream_t s);
+size_t probe_scratch_floats(int64_t N, int P, int H, int Hkv);
+
+}  // namespace spts

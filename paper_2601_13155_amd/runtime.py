@@ -1,0 +1,130 @@
+"""Host-side conveniences around the C-ABI binding: uploads, context creation, layer/stack drivers.
+
+Marshalling and sequencing only: every arithmetic step of the path runs inside libspts kernels.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import numpy as np
+
+from . import binding, synth
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def to_device(a: np.ndarray, dtype: str):
+    """fp32 numpy array (already rounded to the storage dtype) -> device tensor of that dtype."""
+    torch = _torch()
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def to_host(t) -> np.ndarray:
+    torch = _torch()
+    if t.dtype == torch.bfloat16:
+        return t.to(torch.float32).cpu().numpy()
+    return t.cpu().numpy()
+
+
+def make_context(shape, max_tokens: int, max_probe: int, max_r: int, max_dlow: int) -> binding.Context:
+    return binding.Context(shape, max_tokens, max_probe, max_r, max_dlow)
+
+
+def upload_layer(w: Dict[str, np.ndarray], shape, r: int) -> binding.spts_layer_weights:
+    """Weights in the paper's orientation (synth.make_layer) -> device struct in the ABI layout."""
+    abi = synth.to_abi_layout(w)
+    dev = {k: to_device(v, shape.dtype) for k, v in abi.items()}
+    dlow = int(abi["Vd"].shape[1]) if "Vd" in abi else 0
+    return binding.layer_weights(dev, r=r if "Ug" in abi else 0, Dlow=dlow)
+
+
+def run_layer(ctx: binding.Context, x: np.ndarray, pos: np.ndarray, dw: binding.spts_layer_weights, shape, *, skip: int,
+              probe_len: int, m_attn: int, m_ffn: int, protect_last: int = 1, kv_mode: int = 0, want_kv: bool = False):
+    """One spts_layer_prefill call on host arrays; returns host arrays (tests and smoke use this)."""
+    torch = _torch()
+    N = int(x.shape[0])
+    xd = to_device(x, shape.dtype)
+    posd = torch.from_numpy(np.ascontiguousarray(pos, dtype=np.int32)).cuda()
+    Ma = min(N, m_attn) if skip else N
+    Mf = min(N, m_ffn) if skip else N
+    s = torch.zeros(max(N, 1), dtype=torch.float32, device="cuda")
+    ia = torch.full((max(Ma, 1),), -1, dtype=torch.int32, device="cuda")
+    iff = torch.full((max(Mf, 1),), -1, dtype=torch.int32, device="cuda")
+    cfg = binding.spts_layer_cfg(skip, probe_len, m_attn, m_ffn, protect_last, kv_mode)
+    kv = None
+    if want_kv:
+        cap = N if (not skip or kv_mode == 1) else Ma
+        tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        kk = torch.zeros((max(cap, 1), shape.Hkv, shape.d), dtype=tdt, device="cuda")
+        vv = torch.zeros_like(kk)
+        pp = torch.zeros(max(cap, 1), dtype=torch.int32, device="cuda")
+        kv = binding.spts_kv_out(kk.data_ptr(), vv.data_ptr(), pp.data_ptr(), cap, 0)
+    ctx.spts_layer_prefill(xd, posd, N, dw, cfg, kv, s, ia, iff)
+    torch.cuda.synchronize()
+    out = dict(x=to_host(xd).astype(np.float64), s_mha=s[:N].cpu().numpy(), idx_attn=ia[:Ma].cpu().numpy(),
+               idx_ffn=iff[:Mf].cpu().numpy())
+    if want_kv:
+        cnt = int(kv.count)
+        out.update(kv_count=cnt, k_cache=to_host(kk[:cnt]).astype(np.float64), v_cache=to_host(vv[:cnt]).astype(np.float64),
+                   pos_cache=pp[:cnt].cpu().numpy())
+    return out
+
+
+class StackRunner:
+    """Runs Alg. 1's outer loop on the GPU: per layer one spts_layer_prefill, at stage ends one
+    spts_msdp_compact.  Buffers are allocated once; run() only enqueues work (no host sync)."""
+
+    def __init__(self, ctx: binding.Context, shape, layers: List[binding.spts_layer_weights], plan: List[dict],
+                 probe_len: int, protect_last: int = 1, skip: int = 1, keep_trace: bool = False):
+        torch = _torch()
+        self.ctx, self.shape, self.layers, self.plan = ctx, shape, layers, plan
+        self.probe_len, self.protect_last, self.skip = probe_len, protect_last, skip
+        N0 = plan[0]["N"]
+        tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        self.xa = torch.empty((N0, shape.D), dtype=tdt, device="cuda")
+        self.xb = torch.empty((N0, shape.D), dtype=tdt, device="cuda")
+        self.posa = torch.empty(N0, dtype=torch.int32, device="cuda")
+        self.posb = torch.empty(N0, dtype=torch.int32, device="cuda")
+        self.s = torch.empty(N0, dtype=torch.float32, device="cuda")
+        self.new2old = torch.empty(N0, dtype=torch.int32, device="cuda")
+        self.keep_trace = keep_trace
+        self.trace = []
+        self.cfgs = []
+        for item in plan:
+            self.cfgs.append(binding.spts_layer_cfg(skip, probe_len, item["m_attn"], item["m_ffn"], protect_last, 0))
+
+    def run(self, x0, pos0):
+        """x0 [N0, D] device tensor (copied, not modified), pos0 [N0] int32 device tensor.
+        Returns (x, pos, N_final) as views into the runner's buffers."""
+        torch = _torch()
+        xa, xb, pa, pb = self.xa, self.xb, self.posa, self.posb
+        N = self.plan[0]["N"]
+        xa[:N].copy_(x0)
+        pa[:N].copy_(pos0)
+        self.trace = []
+        for li, (w, item, cfg) in enumerate(zip(self.layers, self.plan, self.cfgs)):
+            tr = None
+            if self.keep_trace:
+                tr = dict(N=N, x_in=xa[:N].clone(), pos_in=pa[:N].clone(),
+                          idx_attn=torch.empty(max(min(N, item["m_attn"]), 1), dtype=torch.int32, device="cuda"),
+                          idx_ffn=torch.empty(max(min(N, item["m_ffn"]), 1), dtype=torch.int32, device="cuda"))
+            self.ctx.spts_layer_prefill(xa, pa, N, w, cfg, None, self.s,
+                                        tr["idx_attn"] if tr else None, tr["idx_ffn"] if tr else None)
+            if tr is not None:
+                tr["x_out"] = xa[:N].clone()
+                tr["s_mha"] = self.s[:N].clone()
+            if self.skip and item.get("N_next") is not None:
+                n_next = min(N, item["N_next"])
+                self.ctx.spts_msdp_compact(xa, pa, self.s, N, n_next, self.protect_last, xb, pb, self.new2old, None)
+                if tr is not None:
+                    tr["map_new2old"] = self.new2old[:n_next].clone()
+                xa, xb = xb, xa
+                pa, pb = pb, pa
+                N = n_next
+            if tr is not None:
+                self.trace.append(tr)
+        return xa[:N], pa[:N], N

@@ -14,3 +14,72 @@ def small_shape(dtype="f32", **kw) -> synth.ModelShape:
     base = dict(D=64, H=4, Hkv=2, d=16, Dff=96, rms_eps=1e-5, rope_base=10000.0, dtype=dtype)
     base.update(kw)
     return synth.ModelShape(**base)
+
+
+# ---------------------------------------------------------------------------
+# parity protocol helpers (GPU tests)
+# ---------------------------------------------------------------------------
+TOL = {"f32": dict(score=1e-4, hidden=1e-4), "bf16": dict(score=2e-2, hidden=2e-2)}
+
+
+def rnd_for(dtype):
+    return orc.bf16_round if dtype == "bf16" else orc.identity
+
+
+def row_rel_err(got, ref):
+    """max over rows of max|got-ref| / max|ref| of that row."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    den = np.maximum(np.max(np.abs(ref), axis=-1), 1e-30)
+    return float(np.max(np.max(np.abs(got - ref), axis=-1) / den))
+
+
+def score_rel_err(got, ref, floor_frac=1e-6):
+    """elementwise relative error of non-negative scores, with a floor at floor_frac * max(ref)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.maximum(np.abs(ref), floor_frac * np.max(np.abs(ref)))
+    return float(np.max(np.abs(got - ref) / den))
+
+
+def count_swaps(idx_gpu, idx_ref, scores_ref, band, protect_last=1):
+    """Compares two selected sets.  Returns the number of near-tie swaps; raises if an index differs
+    whose oracle score is not within `band` (relative) of the oracle's k-th largest score."""
+    a, b = set(np.asarray(idx_gpu).tolist()), set(np.asarray(idx_ref).tolist())
+    assert len(a) == len(idx_gpu) == len(idx_ref), "selected set has duplicates or wrong size"
+    assert np.all(np.diff(np.asarray(idx_gpu)) > 0), "selected indices are not ascending"
+    if a == b:
+        return 0
+    s = np.asarray(scores_ref, dtype=np.float64).copy()
+    if protect_last and len(idx_ref) >= 1:
+        s[-1] = np.inf
+    kth = np.sort(s)[::-1][len(idx_ref) - 1]
+    diff = sorted(a ^ b)
+    for i in diff:
+        assert abs(s[i] - kth) <= band * abs(kth), f"index {i}: score {s[i]} vs k-th {kth} is not a near tie"
+    return len(diff) // 2
+
+
+def lockstep_layer(gpu, x, pos, w, mdl, cfg, dtype):
+    """Lock-step parity of one layer: selections equal up to counted near-tie swaps (the oracle then
+    adopts the GPU's set), hidden states within tolerance.  Returns dict(swaps_attn, swaps_ffn, err)."""
+    rnd = rnd_for(dtype)
+    tol = TOL[dtype]
+    ref = orc.layer_prefill(x, pos, w, mdl, cfg, rnd=rnd, score_cast=orc.f32_round)
+    sw_a = sw_f = 0
+    if cfg.skip:
+        assert score_rel_err(gpu["s_mha"], ref.s_mha) <= tol["score"], "S^MHA out of tolerance"
+        sw_a = count_swaps(gpu["idx_attn"], ref.idx_attn, ref.s_mha, tol["score"], cfg.protect_last)
+        if sw_a:
+            ref = orc.layer_prefill(x, pos, w, mdl, cfg, rnd=rnd, score_cast=orc.f32_round,
+                                    force_idx_attn=gpu["idx_attn"])
+        if min(x.shape[0], cfg.m_ffn) > 0:
+            sw_f = count_swaps(gpu["idx_ffn"], ref.idx_ffn, ref.s_ffn, tol["score"], cfg.protect_last)
+            if sw_f:
+                ref = orc.layer_prefill(x, pos, w, mdl, cfg, rnd=rnd, score_cast=orc.f32_round,
+                                        force_idx_attn=gpu["idx_attn"], force_idx_ffn=gpu["idx_ffn"])
+    err = row_rel_err(gpu["x"], ref.x)
+    assert err <= tol["hidden"], f"hidden states: row-relative error {err}"
+    return dict(swaps_attn=sw_a, swaps_ffn=sw_f, err=err, ref=ref)

@@ -1,0 +1,270 @@
+"""GPU parity tests: every call goes through the C ABI and is compared with the CPU oracle.
+
+Bar: index sets / compaction maps bit-exact (on identical fp32 scores); scores and hidden states
+within the tolerance of tests/helpers.TOL (fp32 1e-4, bf16 2e-2, relative).
+"""
+import numpy as np
+import pytest
+
+from oracle import spts_oracle as orc
+from paper_2601_13155_amd import binding, runtime, synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+_CTX = {}
+
+
+def ctx_for(shape, max_tokens, max_probe=128, max_r=256, max_dlow=None):
+    key = (shape, max_tokens, max_probe, max_r, max_dlow or shape.Dff)
+    if key not in _CTX:
+        _CTX[key] = runtime.make_context(shape, max_tokens, max_probe, max_r, max_dlow or shape.Dff)
+    return _CTX[key]
+
+
+# ------------------------------------------------------------------------------------------ TopK
+def _topk_cases(rng):
+    for n in (1, 2, 63, 64, 65, 1000, 1024, 1025, 5000, 32768, 40000, 131072):
+        yield "uniform", rng.random(n).astype(np.float32)
+        yield "all_equal", np.full(n, 0.5, dtype=np.float32)
+        z = rng.random(n).astype(np.float32); z[rng.random(n) < 0.7] = 0.0
+        yield "many_zeros", z
+        yield "duplicates", rng.integers(0, 5, n).astype(np.float32)
+        e = np.exp(-rng.random(n) * 100).astype(np.float32); e[::7] = -0.0
+        yield "softmax_like_signed_zero", e
+        yield "tiny_denormal", (rng.random(n) * 1e-44).astype(np.float32)
+
+
+def test_select_topk_bit_exact(torch):
+    rng = np.random.default_rng(0)
+    ctx = ctx_for(synth.TINY, 131072)
+    for name, s in _topk_cases(rng):
+        n = len(s)
+        sd = torch.from_numpy(s).cuda()
+        ks = sorted({0, 1, 2, n // 3, int(0.4 * n), n - 1, n})
+        for k in ks:
+            if k < 0 or k > n:
+                continue
+            for protect in (0, 1):
+                out = torch.full((max(k, 1),), -7, dtype=torch.int32, device="cuda")
+                ctx.spts_select_topk(sd, n, k, protect, out)
+                got = out[:k].cpu().numpy()
+                ref = orc.topk_select(s, k, protect)
+                assert np.array_equal(got, ref), (name, n, k, protect)
+                if k == 0:
+                    assert int(out[0]) == -7
+
+
+def test_select_topk_deterministic_and_nested(torch):
+    rng = np.random.default_rng(1)
+    ctx = ctx_for(synth.TINY, 131072)
+    s = rng.random(100000).astype(np.float32)
+    sd = torch.from_numpy(s).cuda()
+    prev = None
+    for k in (10, 1000, 40000, 99999):
+        a = torch.empty(k, dtype=torch.int32, device="cuda")
+        b = torch.empty(k, dtype=torch.int32, device="cuda")
+        ctx.spts_select_topk(sd, len(s), k, 1, a)
+        ctx.spts_select_topk(sd, len(s), k, 1, b)
+        assert torch.equal(a, b)
+        cur = set(a.cpu().numpy().tolist())
+        if prev is not None:
+            assert prev <= cur
+        prev = cur
+
+
+# ------------------------------------------------------------------------------------------ MSDP
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_msdp_compact_bit_exact(torch, dtype):
+    shape = H.small_shape(dtype=dtype, D=72)   # row bytes 144 (bf16): exercises the non-16-byte-multiple? no: 144 = 9*16
+    ctx = ctx_for(shape, 4096)
+    rng = np.random.default_rng(3)
+    for N in (1, 7, 300, 4096):
+        x = synth.storage_round(rng.standard_normal((N, shape.D)).astype(np.float32), dtype)
+        pos = (np.arange(N) * 3 + 2).astype(np.int32)
+        s = rng.random(N).astype(np.float32)
+        s[rng.random(N) < 0.3] = 0.0
+        xd = runtime.to_device(x, dtype)
+        pd, sd = torch.from_numpy(pos).cuda(), torch.from_numpy(s).cuda()
+        for n_next in sorted({0, 1, N // 2, int(0.7 * N), N, N + 5}):
+            keep = min(N, n_next)
+            xo = torch.zeros((max(keep, 1), shape.D), dtype=xd.dtype, device="cuda")
+            po = torch.zeros(max(keep, 1), dtype=torch.int32, device="cuda")
+            n2o = torch.zeros(max(keep, 1), dtype=torch.int32, device="cuda")
+            o2n = torch.zeros(N, dtype=torch.int32, device="cuda")
+            ctx.spts_msdp_compact(xd, pd, sd, N, n_next, 1, xo, po, n2o, o2n)
+            rx, rp, rn2o, ro2n = orc.msdp_compact(x, pos, s, n_next, 1)
+            assert np.array_equal(n2o[:keep].cpu().numpy(), rn2o)
+            assert np.array_equal(o2n.cpu().numpy(), ro2n)
+            assert np.array_equal(po[:keep].cpu().numpy(), rp)
+            assert np.array_equal(runtime.to_host(xo[:keep]), rx.astype(np.float32))   # bitwise row copies
+
+
+# ------------------------------------------------------------------------------------------ probes
+def _mk(shape, N, r, seed):
+    w = synth.make_layer(seed, 0, shape, r)
+    x = synth.hidden_states(seed, N, shape.D, shape.dtype)
+    pos = (synth.positions(N) * 2 + 1).astype(np.int32)
+    return w, x, pos
+
+
+PROBE_CASES = [
+    ("c0", synth.TINY, 512, 32, 16),
+    ("c0_ragged", synth.TINY, 333, 7, 16),
+    ("c0_p1", synth.TINY, 200, 1, 16),
+    ("small_bf16", H.small_shape(dtype="bf16"), 150, 5, 8),
+    ("bf16_d128", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 700, 64, 64),
+    ("bf16_d128_ragged", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 1111, 33, 64),
+]
+
+
+@pytest.mark.parametrize("name,shape,N,P,r", PROBE_CASES, ids=[c[0] for c in PROBE_CASES])
+def test_probe_attn_and_ffn(torch, name, shape, N, P, r):
+    ctx = ctx_for(shape, 2048)
+    w, x, pos = _mk(shape, N, r, seed=5)
+    dw = runtime.upload_layer(w, shape, r)
+    mdl = H.oracle_model(shape)
+    rnd = H.rnd_for(shape.dtype)
+    tol = H.TOL[shape.dtype]
+    xd = runtime.to_device(x, shape.dtype)
+    pd = torch.from_numpy(pos).cuda()
+    kd = torch.zeros((N, shape.Hkv, shape.d), dtype=xd.dtype, device="cuda")
+    sd = torch.zeros(N, dtype=torch.float32, device="cuda")
+    ctx.spts_probe_attn(xd, pd, N, dw, P, kd, sd)
+    K, S = orc.probe_attn(x, pos, w, mdl, P, rnd)
+    assert H.row_rel_err(runtime.to_host(kd).reshape(N, -1), K.reshape(N, -1)) <= tol["hidden"]
+    s_gpu = sd.cpu().numpy()
+    assert H.score_rel_err(s_gpu, S) <= tol["score"]
+    assert abs(float(s_gpu.astype(np.float64).sum()) - 1.0) < 1e-3
+    # LTP probe on the same x, conditioned on the GPU's own S (identical inputs on both sides)
+    cd = torch.zeros(N, dtype=torch.float32, device="cuda")
+    fd = torch.zeros(N, dtype=torch.float32, device="cuda")
+    ctx.spts_probe_ffn(xd, N, dw, sd, cd, fd)
+    c_ref, sf_ref = orc.probe_ffn(x, w, mdl, s_gpu, rnd)
+    assert H.score_rel_err(cd.cpu().numpy(), c_ref) <= tol["score"]
+    assert H.score_rel_err(fd.cpu().numpy(), sf_ref) <= tol["score"]
+    # s_mha = NULL -> s_ffn = c_ffn ; c_ffn = NULL allowed
+    f2 = torch.zeros(N, dtype=torch.float32, device="cuda")
+    ctx.spts_probe_ffn(xd, N, dw, None, None, f2)
+    assert torch.equal(f2, cd)
+
+
+# ------------------------------------------------------------------------------------------ layer
+LAYER_CASES = [
+    # name, shape, N, P, r, keep_attn, keep_ffn
+    ("c0", synth.TINY, 512, 32, 16, 0.5, 0.5),
+    ("c0_ragged", synth.TINY, 301, 32, 16, 0.37, 0.61),
+    ("small_bf16", H.small_shape(dtype="bf16"), 130, 4, 8, 0.4, 0.4),
+    ("bf16_d128", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 900, 64, 64, 0.4, 0.4),
+    ("bf16_d128_ragged", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 1237, 64, 64, 0.4, 0.3),
+]
+
+
+@pytest.mark.parametrize("name,shape,N,P,r,ka,kf", LAYER_CASES, ids=[c[0] for c in LAYER_CASES])
+def test_layer_prefill_lockstep(torch, name, shape, N, P, r, ka, kf):
+    ctx = ctx_for(shape, 2048)
+    w, x, pos = _mk(shape, N, r, seed=0 if name.startswith("c0") else 6)
+    dw = runtime.upload_layer(w, shape, r)
+    mdl = H.oracle_model(shape)
+    m_attn, m_ffn = int(ka * N), int(kf * N)
+    gpu = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=m_attn, m_ffn=m_ffn, protect_last=1,
+                            want_kv=True)
+    cfg = orc.LayerCfg(1, P, m_attn, m_ffn, 1, 0)
+    res = H.lockstep_layer(gpu, x, pos, w, mdl, cfg, shape.dtype)
+    if shape.dtype == "f32":
+        assert res["swaps_attn"] == 0 and res["swaps_ffn"] == 0
+    # Level A: the GPU's TopK on the GPU's own scores is the oracle's TopK on those scores
+    assert np.array_equal(gpu["idx_attn"], orc.topk_select(gpu["s_mha"], m_attn, 1))
+    # rows outside both active sets are bitwise untouched (Eq. (skip))
+    touched = np.zeros(N, bool); touched[gpu["idx_attn"]] = True; touched[gpu["idx_ffn"]] = True
+    assert np.array_equal(gpu["x"][~touched], x[~touched].astype(np.float64))
+    # KV cache holds the active pairs
+    ref = res["ref"]
+    assert gpu["kv_count"] == m_attn
+    assert np.array_equal(gpu["pos_cache"], pos[gpu["idx_attn"]])
+    tol = H.TOL[shape.dtype]["hidden"]
+    assert H.row_rel_err(gpu["k_cache"].reshape(m_attn, -1), ref.k_cache.reshape(m_attn, -1)) <= tol
+    assert H.row_rel_err(gpu["v_cache"].reshape(m_attn, -1), ref.v_cache.reshape(m_attn, -1)) <= tol
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layer_dense_keepall_keepzero_and_modes(torch, dtype):
+    shape = synth.TINY if dtype == "f32" else synth.ModelShape(D=256, H=4, Hkv=2, d=64, Dff=688, dtype="bf16")
+    N, P, r = 200, 8, 16
+    ctx = ctx_for(shape, 2048)
+    w, x, pos = _mk(shape, N, r, seed=9)
+    dw = runtime.upload_layer(w, shape, r)
+    mdl = H.oracle_model(shape)
+    # dense branch of Alg. 1
+    dense = runtime.run_layer(ctx, x, pos, dw, shape, skip=0, probe_len=P, m_attn=0, m_ffn=0, want_kv=True)
+    H.lockstep_layer(dense, x, pos, w, mdl, orc.LayerCfg(skip=0), dtype)
+    assert dense["kv_count"] == N
+    # keep everything == dense (same kernels, same rows: bitwise)
+    full = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=N, m_ffn=10 * N)
+    assert np.array_equal(full["idx_attn"], np.arange(N)) and np.array_equal(full["idx_ffn"], np.arange(N))
+    assert np.array_equal(full["x"], dense["x"])
+    # keep nothing == identity, bitwise
+    none = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=0, m_ffn=0)
+    assert np.array_equal(none["x"], x.astype(np.float64))
+    # literal mode (protect_last = 0) and kv_mode = 1
+    lit = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=60, m_ffn=70, protect_last=0)
+    H.lockstep_layer(lit, x, pos, w, mdl, orc.LayerCfg(1, P, 60, 70, 0, 0), dtype)
+    kv1 = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=60, m_ffn=70, kv_mode=1, want_kv=True)
+    H.lockstep_layer(kv1, x, pos, w, mdl, orc.LayerCfg(1, P, 60, 70, 1, 1), dtype)
+    assert kv1["kv_count"] == N
+    # tiny inputs: N = 1 and N = P
+    for n_small in (1, P):
+        ws, xs, ps = w, x[:n_small], pos[:n_small]
+        g = runtime.run_layer(ctx, xs, ps, dw, shape, skip=1, probe_len=min(P, n_small), m_attn=max(n_small // 2, 1),
+                              m_ffn=max(n_small // 2, 1))
+        H.lockstep_layer(g, xs, ps, ws, mdl, orc.LayerCfg(1, min(P, n_small), max(n_small // 2, 1), max(n_small // 2, 1), 1, 0), dtype)
+
+
+def test_layer_prefill_is_deterministic(torch):
+    shape = synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16")
+    ctx = ctx_for(shape, 2048)
+    w, x, pos = _mk(shape, 777, 64, seed=2)
+    dw = runtime.upload_layer(w, shape, 64)
+    a = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=64, m_attn=300, m_ffn=300)
+    b = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=64, m_attn=300, m_ffn=300)
+    for k in ("x", "s_mha", "idx_attn", "idx_ffn"):
+        assert np.array_equal(a[k], b[k]), k
+
+
+# ------------------------------------------------------------------------------------------ stack
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stack_with_msdp_lockstep(torch, dtype):
+    """Alg. 1 outer loop with stage-end pruning: every layer is re-computed by the oracle from the
+    GPU's own layer input (lock-step), every compaction map is compared bit-exactly."""
+    shape = synth.TINY if dtype == "f32" else synth.ModelShape(D=256, H=4, Hkv=2, d=64, Dff=688, dtype="bf16")
+    wl = synth.scaled(synth.WORKLOADS["c2"], shape=shape, N=400, layers=4, stage_end_layers=(1, 2, 3), probe_len=16, r=16)
+    plan = wl.layer_plan()
+    ws = [synth.make_layer(wl.seed, l, shape, wl.r) for l in range(wl.layers)]
+    dws = [runtime.upload_layer(w, shape, wl.r) for w in ws]
+    ctx = ctx_for(shape, 2048)
+    runner = runtime.StackRunner(ctx, shape, dws, plan, wl.probe_len, keep_trace=True)
+    x0 = synth.hidden_states(wl.seed, wl.N, shape.D, dtype)
+    pos0 = synth.positions(wl.N)
+    xo, po, n_final = runner.run(runtime.to_device(x0, dtype), torch.from_numpy(pos0).cuda())
+    torch.cuda.synchronize()
+    assert n_final == plan[-1]["N"] == 140
+    mdl = H.oracle_model(shape)
+    for tr, item, w in zip(runner.trace, plan, ws):
+        N = tr["N"]
+        x_in = runtime.to_host(tr["x_in"]); pos_in = tr["pos_in"].cpu().numpy()
+        gpu = dict(x=runtime.to_host(tr["x_out"]).astype(np.float64), s_mha=tr["s_mha"].cpu().numpy(),
+                   idx_attn=tr["idx_attn"][:min(N, item["m_attn"])].cpu().numpy(),
+                   idx_ffn=tr["idx_ffn"][:min(N, item["m_ffn"])].cpu().numpy())
+        H.lockstep_layer(gpu, x_in, pos_in, w, mdl, orc.LayerCfg(1, wl.probe_len, item["m_attn"], item["m_ffn"], 1, 0), dtype)
+        if item["N_next"] is not None:
+            _, rp, rn2o, _ = orc.msdp_compact(gpu["x"], pos_in, gpu["s_mha"], item["N_next"], 1)
+            assert np.array_equal(tr["map_new2old"].cpu().numpy(), rn2o)
+    assert po[-1].item() == wl.N - 1
