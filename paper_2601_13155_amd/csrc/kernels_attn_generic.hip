@@ -146,12 +146,6 @@ __global__ void __launch_bounds__(256) probe_accum_generic_kernel(ProbeArgs a) {
     a.S[n] = acc / (float)(a.P * a.H);
 }
 
-size_t probe_scratch_floats(int64_t N, int P, int H, int Hkv) {
-    // stats [P*H, 2]  +  per-KV-head partial scores (matrix-core path) [Hkv, N], N rounded up to 256
-    int64_t Np = (N + 255) / 256 * 256;
-    return (size_t)(2 * (int64_t)P * H + 64) + (size_t)((int64_t)Hkv * Np);
-}
-
 hipError_t launch_probe_generic(const ProbeArgs& a, bool bf16, hipStream_t s) {
     if (a.N == 0) return hipSuccess;
     dim3 g1((unsigned)(a.P * a.H)), g2((unsigned)((a.N + 255) / 256)), b(256);

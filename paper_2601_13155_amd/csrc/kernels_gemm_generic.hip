@@ -111,8 +111,6 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(GemmArgs a) {
     }
 }
 
-int gemm_sumsq_blocks(int32_t N, bool mfma) { return mfma ? (N + 255) / 256 : (N + GT - 1) / GT; }
-
 hipError_t launch_gemm_generic(const GemmArgs& a, bool bf16, hipStream_t s) {
     if (a.M == 0 || a.N == 0) return hipSuccess;
     dim3 grid((unsigned)((a.N + GT - 1) / GT), (unsigned)((a.M + GT - 1) / GT)), block(256);

@@ -1,0 +1,346 @@
+// bf16 matrix-core GEMM for gfx950:  C[M,N] = A[M,K] * B[N,K]^T, fp32 accumulation.
+//
+// Serves the dense contractions of the SPTS layer: K / Q / V / O projections, the gathered SwiGLU
+// FFN and the low-rank proxy.  Both operands are K-contiguous, so MFMA fragments are plain 16-byte
+// LDS reads with no transposition.
+//
+//  * 256x256 output tile per workgroup, 4 wavefronts (2x2), each owning 128x128 = 4x4 MFMA
+//    32x32x16 blocks: 256 fp32 accumulators per lane (AGPRs), 16 MFMAs per 8 fragment reads.
+//  * K is consumed in slabs of BK (64, or 32 when a second A operand is staged); global->register
+//    prefetch of slab k+1 overlaps the MFMAs of slab k; two LDS stages, one barrier per slab.
+//  * LDS rows are XOR-swizzled in 16-byte chunks so that both the 16-lane b128 fragment reads and
+//    the staging writes are bank-conflict free without padding.
+//  * Rows of A may be gathered through an index list (the active-token gather of Eq. (skip) is
+//    folded into the A loads: a row is 2*K contiguous bytes, so nothing is lost in coalescing),
+//    rows of C may be scattered through one (the residual update X[T] += ...).
+//  * The MFMA is issued as D^T = B * A^T so that a lane ends up with 4 consecutive output columns
+//    of one row: 8-byte packed stores, lane-local rotary / SiLU-mul pairing, in-lane row sums.
+//  * Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous range
+//    of tiles in groups of 4 row panels: concurrently running tiles share A and B panels in L2.
+//
+// Epilogues: plain store (+ optional transposed copy for V), rotary embedding (pairs (j, j+d/2) sit
+// in the same lane because an N block pair is d/2 apart), SiLU(gate)*up with gate and up columns
+// interleaved per wavefront, residual add into scattered rows, per-row partial sums of squares.
+#include "spts_internal.h"
+
+namespace spts {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 256, BN = 256, NTHREADS = 256;
+
+template <int BK> struct Slab {
+    static constexpr int ROW_BYTES = BK * 2;
+    static constexpr int CPR = BK / 8;              // 16-byte chunks per tile row
+    static constexpr int RP = 256 / ROW_BYTES;      // tile rows per 256 bytes (all 64 banks)
+    static constexpr int TILE_BYTES = 256 * ROW_BYTES;
+    static constexpr int ROWS_PER_PASS = NTHREADS / CPR;
+    __device__ static inline int off(int row, int c) { return row * ROW_BYTES + ((c ^ ((row / RP) % CPR)) << 4); }
+};
+
+__device__ inline uint32_t pack_bf16x2(float a, float b) {
+    return (uint32_t)f32_to_bf16(a).v | ((uint32_t)f32_to_bf16(b).v << 16);
+}
+__device__ inline float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+
+template <int EPI, int BK, bool DUAL_A>
+__global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM, int nN, int total) {
+    using S = Slab<BK>;
+    constexpr bool DUAL = (EPI == EPI_SILU_MUL);
+    constexpr int CPR = S::CPR;
+    constexpr int STAGE = S::TILE_BYTES * (DUAL_A ? 3 : 2);
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    // ---- tile id: XCD-contiguous ranges, grouped raster
+    const int per = (total + 7) / 8;
+    const int id = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
+    if (id >= total) return;
+    constexpr int GM = 4;
+    const int group = id / (GM * nN);
+    const int first_m = group * GM;
+    const int gsz = (nM - first_m) < GM ? (nM - first_m) : GM;
+    const int in_g = id % (GM * nN);
+    const int tm = first_m + in_g % gsz;
+    const int tn = in_g / gsz;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int64_t row0 = (int64_t)tm * BM;
+    constexpr int OUT_COLS = DUAL ? 128 : 256;   // output columns covered by one tile
+    const int col0 = tn * OUT_COLS;
+
+    // ---- global load assignment: thread owns chunk column lc of rows lr + ROWS_PER_PASS * i
+    const int lc = tid % CPR, lr = tid / CPR;
+    const bf16_t* A = (const bf16_t*)a.A;
+    const bf16_t* A1 = (const bf16_t*)a.A1;
+    const bf16_t* pa[CPR];
+    const bf16_t* pa1[DUAL_A ? CPR : 1];
+    const bf16_t* pb[CPR];
+#pragma unroll
+    for (int i = 0; i < CPR; ++i) {
+        int r = lr + S::ROWS_PER_PASS * i;
+        int64_t grow = row0 + r;
+        if (grow >= a.M) grow = a.M - 1;  // clamp: duplicates of the last row are never stored
+        int64_t srow = a.a_idx ? (int64_t)a.a_idx[grow] : grow;
+        pa[i] = A + srow * a.lda + lc * 8;
+        if (DUAL_A) pa1[i] = A1 + srow * a.lda + lc * 8;
+        const bf16_t* bsrc;
+        if (DUAL) bsrc = (r < 128) ? (const bf16_t*)a.B0 + (int64_t)(col0 + r) * a.ldb
+                                   : (const bf16_t*)a.B1 + (int64_t)(col0 + r - 128) * a.ldb;
+        else bsrc = (const bf16_t*)a.B0 + (int64_t)(col0 + r) * a.ldb;
+        pb[i] = bsrc + lc * 8;
+    }
+
+    uint4 ra[CPR], rb[CPR], ra1[DUAL_A ? CPR : 1];
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < CPR; ++i) {
+            ra[i] = *reinterpret_cast<const uint4*>(pa[i] + k0);
+            rb[i] = *reinterpret_cast<const uint4*>(pb[i] + k0);
+            if (DUAL_A) ra1[i] = *reinterpret_cast<const uint4*>(pa1[i] + k0);
+        }
+    };
+    auto store_lds = [&](int stage) {
+        char* sA = smem + stage * STAGE;
+        char* sB = sA + S::TILE_BYTES;
+#pragma unroll
+        for (int i = 0; i < CPR; ++i) {
+            int r = lr + S::ROWS_PER_PASS * i;
+            int o = S::off(r, lc);
+            *reinterpret_cast<uint4*>(sA + o) = ra[i];
+            *reinterpret_cast<uint4*>(sB + o) = rb[i];
+            if (DUAL_A) *reinterpret_cast<uint4*>(sB + S::TILE_BYTES + o) = ra1[i];
+        }
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // B tile row of this wavefront's N block j
+    auto brow = [&](int j) { return DUAL ? (j >> 1) * 128 + wn * 64 + (j & 1) * 32 : wn * 128 + j * 32; };
+
+    const int nk = a.K / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) load_global((kt + 1) * BK);
+        const char* sA = smem + (kt & 1) * STAGE;
+        const char* sB = sA + S::TILE_BYTES;
+        const char* sA1 = sB + S::TILE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 af[4], bfr[4], af1[DUAL_A ? 4 : 1];
+            const int c = ks * 2 + lh;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                af[i] = *reinterpret_cast<const bf16x8*>(sA + S::off(wm * 128 + i * 32 + l32, c));
+                if (DUAL_A) af1[i] = *reinterpret_cast<const bf16x8*>(sA1 + S::off(wm * 128 + i * 32 + l32, c));
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(sB + S::off(brow(j) + l32, c));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (DUAL_A && j >= 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af1[i], acc[i][j], 0, 0, 0);
+                    else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+                }
+        }
+        if (kt + 1 < nk) store_lds((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue.  acc[i][j][r]: row = row0 + wm*128 + i*32 + l32,
+    //      column (inside N block j) = 8*(r/4) + 4*lh + r%4  -> 4 consecutive columns per r/4.
+    bf16_t* Cb = (bf16_t*)a.C;
+    if (EPI == EPI_SUMSQ) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s += acc[i][j][r] * acc[i][j][r];
+            s += __shfl_xor(s, 32);
+            int64_t grow = row0 + wm * 128 + i * 32 + l32;
+            if (lh == 0 && grow < a.M) a.part[grow * a.part_ld + tn * 2 + wn] = s;
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t grow = row0 + wm * 128 + i * 32 + l32;
+        const bool rok = grow < a.M;
+        const int64_t growc = rok ? grow : a.M - 1;
+        const int64_t crow = a.c_idx ? (int64_t)a.c_idx[growc] : growc;
+        if (EPI == EPI_STORE) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int cb = col0 + wn * 128 + j * 32 + 4 * lh;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint2 o;
+                    o.x = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+                    o.y = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                    if (rok) *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q) = o;
+                    if (a.Ct && grow < a.ldct) {
+                        bf16_t* ct = (bf16_t*)a.Ct;
+                        const uint16_t e[4] = {(uint16_t)(o.x & 0xffff), (uint16_t)(o.x >> 16), (uint16_t)(o.y & 0xffff), (uint16_t)(o.y >> 16)};
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) ct[(int64_t)(cb + 8 * q + t) * a.ldct + grow].v = e[t];
+                    }
+                }
+            }
+        } else if (EPI == EPI_RESIDUAL) {
+            if (rok) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int cb = col0 + wn * 128 + j * 32 + 4 * lh;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint2* p = reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q);
+                        uint2 old = *p;
+                        float x0 = __uint_as_float(old.x << 16), x1 = __uint_as_float(old.x & 0xffff0000u);
+                        float x2 = __uint_as_float(old.y << 16), x3 = __uint_as_float(old.y & 0xffff0000u);
+                        uint2 o;
+                        o.x = pack_bf16x2(x0 + acc[i][j][4 * q], x1 + acc[i][j][4 * q + 1]);
+                        o.y = pack_bf16x2(x2 + acc[i][j][4 * q + 2], x3 + acc[i][j][4 * q + 3]);
+                        *p = o;
+                    }
+                }
+            }
+        } else if (EPI == EPI_SILU_MUL) {
+            if (rok) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int cb = col0 + wn * 64 + j * 32 + 4 * lh;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float h0 = silu_f(acc[i][j][4 * q]) * acc[i][j + 2][4 * q];
+                        float h1 = silu_f(acc[i][j][4 * q + 1]) * acc[i][j + 2][4 * q + 1];
+                        float h2 = silu_f(acc[i][j][4 * q + 2]) * acc[i][j + 2][4 * q + 2];
+                        float h3 = silu_f(acc[i][j][4 * q + 3]) * acc[i][j + 2][4 * q + 3];
+                        uint2 o; o.x = pack_bf16x2(h0, h1); o.y = pack_bf16x2(h2, h3);
+                        *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q) = o;
+                    }
+                }
+            }
+        } else if (EPI == EPI_ROPE) {
+            if (rok) {
+                const int64_t trow = a.rope_idx ? (int64_t)a.rope_idx[grow] : grow;
+                const int half = a.head_dim >> 1;
+                const float2* tab = a.rope + trow * half;
+                if (half == 64) {
+                    // wavefront = one head of 128 columns: blocks (0,2) and (1,3) are d/2 apart
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int jj = j * 32 + 4 * lh;
+                        const int cb = col0 + wn * 128 + jj;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            float lo[4], hi[4];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                float2 cs = tab[jj + 8 * q + t];
+                                float x1 = acc[i][j][4 * q + t], x2 = acc[i][j + 2][4 * q + t];
+                                lo[t] = x1 * cs.x - x2 * cs.y;
+                                hi[t] = x2 * cs.x + x1 * cs.y;
+                            }
+                            uint2 o1, o2;
+                            o1.x = pack_bf16x2(lo[0], lo[1]); o1.y = pack_bf16x2(lo[2], lo[3]);
+                            o2.x = pack_bf16x2(hi[0], hi[1]); o2.y = pack_bf16x2(hi[2], hi[3]);
+                            *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q) = o1;
+                            *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 64 + 8 * q) = o2;
+                        }
+                    }
+                } else {
+                    // d = 64: two heads per wavefront; blocks (0,1) and (2,3) are d/2 = 32 apart
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        const int jj = 4 * lh;
+                        const int cb = col0 + wn * 128 + hh * 64 + jj;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            float lo[4], hi[4];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                float2 cs = tab[jj + 8 * q + t];
+                                float x1 = acc[i][2 * hh][4 * q + t], x2 = acc[i][2 * hh + 1][4 * q + t];
+                                lo[t] = x1 * cs.x - x2 * cs.y;
+                                hi[t] = x2 * cs.x + x1 * cs.y;
+                            }
+                            uint2 o1, o2;
+                            o1.x = pack_bf16x2(lo[0], lo[1]); o1.y = pack_bf16x2(lo[2], lo[3]);
+                            o2.x = pack_bf16x2(hi[0], hi[1]); o2.y = pack_bf16x2(hi[2], hi[3]);
+                            *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q) = o1;
+                            *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 32 + 8 * q) = o2;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+int gemm_sumsq_blocks(int32_t N, bool mfma) { return mfma ? (N + 127) / 128 : (N + 63) / 64; }
+
+static inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool gemm_mfma_supported(const GemmArgs& a) {
+    if (a.c_is_f32) return false;
+    const bool dual = a.epi == EPI_SILU_MUL;
+    const int ncols = dual ? 128 : 256;
+    if (a.M <= 0 || a.N <= 0 || a.N % ncols != 0) return false;
+    const int bk = (dual && a.A1) ? 32 : 64;
+    if (a.K < bk || a.K % bk != 0) return false;
+    if (a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
+    if (!al16(a.A) || !al16(a.B0) || (a.A1 && !al16(a.A1)) || (dual && !al16(a.B1))) return false;
+    if (a.epi != EPI_SUMSQ) {
+        if (a.ldc % 4 != 0 || (reinterpret_cast<uintptr_t>(a.C) & 7u)) return false;
+    }
+    if (a.epi == EPI_ROPE && a.head_dim != 128 && a.head_dim != 64) return false;
+    if (a.Ct && a.epi != EPI_STORE) return false;
+    if (a.M > (int64_t)1 << 30) return false;
+    return true;
+}
+
+template <int EPI, int BK, bool DUAL_A>
+static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
+    const int ncols = EPI == EPI_SILU_MUL ? 128 : 256;
+    const int nM = (int)((a.M + BM - 1) / BM), nN = a.N / ncols;
+    const int total = nM * nN;
+    const int grid = (total + 7) / 8 * 8;
+    const size_t lds = (size_t)Slab<BK>::TILE_BYTES * (DUAL_A ? 3 : 2) * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<EPI, BK, DUAL_A>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    gemm_mfma_kernel<EPI, BK, DUAL_A><<<dim3(grid), dim3(NTHREADS), lds, s>>>(a, nM, nN, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
+    switch (a.epi) {
+        case EPI_STORE: return launch_t<EPI_STORE, 64, false>(a, s);
+        case EPI_RESIDUAL: return launch_t<EPI_RESIDUAL, 64, false>(a, s);
+        case EPI_SUMSQ: return launch_t<EPI_SUMSQ, 64, false>(a, s);
+        case EPI_ROPE: return launch_t<EPI_ROPE, 64, false>(a, s);
+        case EPI_SILU_MUL:
+            if (a.A1) return launch_t<EPI_SILU_MUL, 32, true>(a, s);
+            return launch_t<EPI_SILU_MUL, 64, false>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace spts

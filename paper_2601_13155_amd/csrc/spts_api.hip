@@ -387,8 +387,14 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         aa.ldvt = (Mk + 255) / 256 * 256; aa.vt = c->p<void>(c->off.vt);
         const bool amf = c->bf16 && attention_mfma_supported(aa);
         GemmArgs gv = gemm_args(xn, m.D, full_kv ? nullptr : idxA, w->Wv, m.D, vv, KV, Mk, KV, m.D);
-        if (amf) { gv.Ct = c->p<void>(c->off.vt); gv.ldct = aa.ldvt; }
+        bool vt_done = false;
+        if (amf) {
+            // the matrix-core projection writes the transposed copy (keys contiguous) in its epilogue
+            GemmArgs gvt = gv; gvt.Ct = c->p<void>(c->off.vt); gvt.ldct = aa.ldvt;
+            if (gemm_mfma_supported(gvt)) { gv = gvt; vt_done = true; }
+        }
         SPTS_TRY(run_gemm(c, gv));
+        if (amf && !vt_done) SPTS_HIP(c, launch_transpose_pad(vv, c->p<void>(c->off.vt), Mk, KV, aa.ldvt, c->bf16, st));
         if (kv) kv->count = Mk;
         if (amf) SPTS_HIP(c, launch_attention_mfma(aa, st));
         else SPTS_HIP(c, launch_attention_generic(aa, c->bf16, st));

@@ -123,6 +123,8 @@ PROBE_CASES = [
     ("small_bf16", H.small_shape(dtype="bf16"), 150, 5, 8),
     ("bf16_d128", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 700, 64, 64),
     ("bf16_d128_ragged", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 1111, 33, 64),
+    ("bf16_all_mfma", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 64, 256),
+    ("bf16_d64_mfma", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16"), 1100, 16, 256),
 ]
 
 
@@ -165,6 +167,8 @@ LAYER_CASES = [
     ("small_bf16", H.small_shape(dtype="bf16"), 130, 4, 8, 0.4, 0.4),
     ("bf16_d128", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 900, 64, 64, 0.4, 0.4),
     ("bf16_d128_ragged", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 1237, 64, 64, 0.4, 0.3),
+    ("bf16_all_mfma", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 64, 256, 0.4, 0.4),
+    ("bf16_d64_mfma", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16"), 1100, 16, 256, 0.3, 0.5),
 ]
 
 
@@ -175,6 +179,8 @@ def test_layer_prefill_lockstep(torch, name, shape, N, P, r, ka, kf):
     dw = runtime.upload_layer(w, shape, r)
     mdl = H.oracle_model(shape)
     m_attn, m_ffn = int(ka * N), int(kf * N)
+    if name.endswith("mfma"):
+        assert ctx.uses_mfma()
     gpu = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=m_attn, m_ffn=m_ffn, protect_last=1,
                             want_kv=True)
     cfg = orc.LayerCfg(1, P, m_attn, m_ffn, 1, 0)
