@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""SPTS prefill benchmark on one MI355X: tokens/s + TTFT of the token-skipped prefill, with the
+roofline fraction of the dominant kernel, the library's own dense prefill, and the CPU oracle
+timed on the host cores as a reported baseline.
+
+A step is one pass of the whole hot path (every layer of the stack: PAP probe, TopK, reduced
+attention, LTP proxy, reduced FFN, MSDP compaction at stage ends) over one batch of seeded
+synthetic hidden states that already sit in HBM.  TTFT here = stack-in hidden states -> final
+hidden states (no embedding, final norm or LM head).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA (published)
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E (published)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(wl, w_host, sample_tokens, layers_equiv):
+    """Times the oracle (as it stands) on one skip layer over a prefix of the workload's input."""
+    import numpy as np
+    from oracle import spts_oracle as orc
+    from paper_2601_13155_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+    except Exception:
+        threadpool_info = None
+    shape = wl.shape
+    n = min(sample_tokens, wl.N)
+    x = synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype)[:n]
+    pos = synth.positions(n)
+    mdl = orc.Model(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, shape.rms_eps, shape.rope_base)
+    cfg = orc.LayerCfg(1, min(wl.probe_len, n), int(wl.attn_keep * n), int(wl.ffn_keep * n), wl.protect_last, 0)
+    t0 = time.perf_counter()
+    orc.layer_prefill(x, pos, w_host, mdl, cfg, rnd=orc.bf16_round if shape.dtype == "bf16" else orc.identity,
+                      score_cast=orc.f32_round)
+    dt = time.perf_counter() - t0
+    threads = None
+    if threadpool_info is not None:
+        ths = [p.get("num_threads") for p in threadpool_info() if p.get("user_api") == "blas"]
+        threads = max(ths) if ths else None
+    if threads is None:
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {
+        "value": n / (dt * layers_equiv), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"oracle.layer_prefill (numpy fp64, bf16-faithful rounding) on ONE skip layer over the first {n} "
+                   f"tokens of the workload input (keep {wl.attn_keep}/{wl.ffn_keep}, P={min(wl.probe_len, n)}, r={wl.r}): "
+                   f"{dt:.2f} s; tokens/s extrapolated as {n} / ({dt:.2f} s x {layers_equiv} layers), i.e. ignoring "
+                   f"both the MSDP shrink and the growth of attention cost with length"),
+        "seconds_one_layer": dt,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's)")
+    ap.add_argument("--weight-pool", type=int, default=2,
+                    help="distinct synthetic weight sets; layers cycle through them (bounds set-up time)")
+    ap.add_argument("--dense-steps", type=int, default=1, help="timed steps of the dense (skip=0) prefill; 0 = skip it")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096, help="0 = no cpu_baseline leg")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket phases with events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported (nothing here shards).")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2601_13155_amd import costmodel as cm
+    from paper_2601_13155_amd import runtime, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    if args.layers:
+        ends = tuple(e for e in wl.stage_end_layers if e < args.layers)
+        wl = synth.scaled(wl, layers=args.layers, stage_end_layers=ends, stage_cum_keep=wl.stage_cum_keep[:len(ends) + 1])
+    shape = wl.shape
+    plan = wl.layer_plan()
+    Dlow = shape.Dff
+
+    t_setup = time.perf_counter()
+    pool = max(1, min(args.weight_pool, wl.layers))
+    host_sets, dev_sets = [], []
+    for i in range(pool):
+        w = synth.make_layer(wl.seed, i, shape, wl.r)
+        dev_sets.append(runtime.upload_layer(w, shape, wl.r))
+        host_sets.append(w if i == 0 else None)
+        log(f"[setup] weight set {i + 1}/{pool} ready ({time.perf_counter() - t_setup:.1f} s)")
+    layers = [dev_sets[l % pool] for l in range(wl.layers)]
+    x0 = runtime.to_device(synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype), shape.dtype)
+    pos0 = torch.from_numpy(synth.positions(wl.N)).cuda()
+    ctx = runtime.make_context(shape, wl.N, wl.probe_len, wl.r, Dlow)
+    assert ctx.uses_mfma(), "matrix-core kernels are not serving this workload"
+    runner = runtime.StackRunner(ctx, shape, layers, plan, wl.probe_len, wl.protect_last, skip=1)
+    log(f"[setup] done in {time.perf_counter() - t_setup:.1f} s; workload {wl.name}: N={wl.N}, layers={wl.layers}")
+
+    def timed(run, steps, warmup, profile):
+        for _ in range(warmup):
+            run.run(x0, pos0)
+        torch.cuda.synchronize()
+        if profile:
+            ctx.spts_profile_begin()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            run.run(x0, pos0)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        phases = ctx.spts_profile_end() if profile else {}
+        return e0.elapsed_time(e1) / steps, wall / steps, phases
+
+    profile = not args.no_profile
+    ms, wall_ms, phases = timed(runner, args.steps, args.warmup, profile)
+    log(f"[spts] {ms:.2f} ms/step (host wall {wall_ms:.2f} ms)")
+    xo, po, n_final = runner.run(x0, pos0)
+    torch.cuda.synchronize()
+    assert n_final == plan[-1]["N"] if plan[-1]["N_next"] is None else True
+    assert bool(torch.isfinite(xo.float()).all()), "non-finite hidden states"
+
+    # ---- algorithmic work of the timed region
+    flops_by = {}
+    for item in plan:
+        f = cm.layer_flops(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, item["N"], wl.probe_len,
+                           min(item["N"], item["m_attn"]), min(item["N"], item["m_ffn"]), wl.r, Dlow, True)
+        for k, v in f.items():
+            flops_by[k] = flops_by.get(k, 0.0) + v
+    total_flops = sum(flops_by.values())
+    gate_up_flops = flops_by["ffn"] * 2.0 / 3.0   # gate + up projections of the gathered rows
+    roofline = None
+    phase_out = {}
+    if phases:
+        for name, (tot_ms, n) in phases.items():
+            phase_out[name] = {"ms_per_step": tot_ms / args.steps, "launches_per_step": n / args.steps}
+        gu_ms = phases["ffn_gate_up"][0] / args.steps
+        achieved = gate_up_flops / (gu_ms * 1e-3) / 1e12
+        roofline = {"kernel": "gemm_mfma_kernel<EPI_SILU_MUL> (ffn_gate_up)", "bound": "mfma", "achieved": achieved,
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                    "flops_per_step": gate_up_flops, "ms_per_step": gu_ms,
+                    "launches_per_step": phases["ffn_gate_up"][1] / args.steps}
+        # add derived rates for the other phases
+        phase_flops = {"k_proj": flops_by["k_proj"], "probe_q": flops_by["probe_q"], "probe_attn": flops_by["probe_attn"],
+                       "attention": flops_by["attention"], "o_proj": flops_by["o_proj"],
+                       "ffn_gate_up": gate_up_flops, "ffn_down": flops_by["ffn"] / 3.0,
+                       "q_proj": flops_by["qv_proj"] * shape.H / (shape.H + shape.Hkv),
+                       "v_proj": flops_by["qv_proj"] * shape.Hkv / (shape.H + shape.Hkv)}
+        proxy_ms = sum(phase_out[k]["ms_per_step"] for k in ("proxy_in", "proxy_mid", "proxy_z", "proxy_out") if k in phase_out)
+        for k, fl in phase_flops.items():
+            if k in phase_out and phase_out[k]["ms_per_step"] > 0:
+                phase_out[k]["tflops"] = fl / (phase_out[k]["ms_per_step"] * 1e-3) / 1e12
+        if proxy_ms > 0:
+            phase_out["proxy_total"] = {"ms_per_step": proxy_ms, "tflops": flops_by["proxy"] / (proxy_ms * 1e-3) / 1e12}
+        b = 2 if shape.dtype == "bf16" else 4
+        norm_bytes = sum(2 * 2.0 * item["N"] * shape.D * b for item in plan)
+        if "rmsnorm" in phase_out:
+            phase_out["rmsnorm"]["gbs"] = norm_bytes / (phase_out["rmsnorm"]["ms_per_step"] * 1e-3) / 1e9
+        probe_bytes = sum(item["N"] * shape.Hkv * shape.d * b + 4.0 * item["N"] for item in plan)
+        if "probe_attn" in phase_out:
+            phase_out["probe_attn"]["gbs"] = probe_bytes / (phase_out["probe_attn"]["ms_per_step"] * 1e-3) / 1e9
+
+    # ---- dense prefill of the same stack through the same library (skip = 0 on every layer)
+    dense = None
+    if args.dense_steps > 0:
+        drunner = runtime.StackRunner(ctx, shape, layers, plan, wl.probe_len, wl.protect_last, skip=0)
+        dms, _, _ = timed(drunner, args.dense_steps, 0, False)
+        dflops = wl.layers * sum(cm.layer_flops(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, wl.N, wl.probe_len,
+                                                wl.N, wl.N, wl.r, Dlow, False).values())
+        dense = {"ms_per_step": dms, "tokens_per_s": wl.N / (dms * 1e-3), "speedup_spts_over_dense": dms / ms,
+                 "tflops": dflops / (dms * 1e-3) / 1e12, "steps": args.dense_steps}
+        log(f"[dense] {dms:.2f} ms/step -> SPTS speedup {dms / ms:.2f}x")
+
+    cpu = None
+    if args.cpu_sample_tokens > 0:
+        cpu = cpu_baseline(wl, host_sets[0], args.cpu_sample_tokens, wl.layers)
+        log(f"[cpu] oracle layer on {min(args.cpu_sample_tokens, wl.N)} tokens: {cpu['seconds_one_layer']:.2f} s")
+
+    out = {
+        "metric": "SPTS prefill tokens/s (TTFT = ms_per_step) at %dK, %s-shaped, 1 GPU" % (wl.N // 1024,
+                  "LLaMA-3.1-8B" if shape.D == 4096 else "Qwen2.5-7B"),
+        "value": wl.N / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "ttft_ms": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "seq_len": wl.N, "layers": wl.layers, "probe_len": wl.probe_len,
+                   "attn_keep": wl.attn_keep, "ffn_keep": wl.ffn_keep, "proxy_rank": wl.r, "proxy_dlow": Dlow,
+                   "stage_end_layers": list(wl.stage_end_layers), "stage_cum_keep": list(wl.stage_cum_keep),
+                   "weight_pool": pool, "batch": 1},
+        "algorithmic_tflop_per_step": total_flops / 1e12,
+        "achieved_tflops_whole_step": total_flops / (ms * 1e-3) / 1e12,
+        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -152,6 +152,16 @@ int spts_msdp_compact(spts_ctx *ctx, const void *x_in, const int32_t *pos_in, co
                       int64_t N, int64_t N_next, int32_t protect_last, void *x_out, int32_t *pos_out,
                       int32_t *map_new2old, int32_t *map_old2new);
 
+/* Per-phase timing for benchmarks.  Between spts_profile_begin and spts_profile_end every phase of
+ * every call on this context (k_proj, probe_attn, topk, attention, ffn_gate_up, ...) is bracketed
+ * by two HIP events on the context's stream.  spts_profile_end synchronises the stream (the only
+ * call of this library that does) and accumulates the elapsed milliseconds and the number of
+ * bracketed launches per phase; spts_profile_get reads phase i in [0, spts_profile_count). */
+int spts_profile_begin(spts_ctx *ctx);
+int spts_profile_end(spts_ctx *ctx);
+int spts_profile_count(const spts_ctx *ctx);
+int spts_profile_get(const spts_ctx *ctx, int i, const char **name, double *total_ms, int64_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

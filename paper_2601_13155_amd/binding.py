@@ -21,6 +21,7 @@ SPTS_F32, SPTS_BF16 = 0, 1
 EXPORTS = (
     "spts_workspace_bytes", "spts_create", "spts_destroy", "spts_strerror", "spts_last_hip_error", "spts_uses_mfma",
     "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_layer_prefill", "spts_msdp_compact",
+    "spts_profile_begin", "spts_profile_end", "spts_profile_count", "spts_profile_get",
 )
 
 
@@ -78,6 +79,14 @@ def load() -> C.CDLL:
                                        C.POINTER(spts_kv_out), vp, vp, vp]
     lib.spts_msdp_compact.restype = C.c_int
     lib.spts_msdp_compact.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.spts_profile_begin.restype = C.c_int
+    lib.spts_profile_begin.argtypes = [vp]
+    lib.spts_profile_end.restype = C.c_int
+    lib.spts_profile_end.argtypes = [vp]
+    lib.spts_profile_count.restype = C.c_int
+    lib.spts_profile_count.argtypes = [vp]
+    lib.spts_profile_get.restype = C.c_int
+    lib.spts_profile_get.argtypes = [vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_double), C.POINTER(i64)]
     _lib = lib
     return lib
 
@@ -179,6 +188,21 @@ class Context:
         _check(load().spts_msdp_compact(self.handle, _ptr(x_in), _ptr(pos_in), _ptr(s_mha), N, N_next, protect_last,
                                         _ptr(x_out), _ptr(pos_out), _ptr(map_new2old), _ptr(map_old2new)),
                "spts_msdp_compact")
+
+    def spts_profile_begin(self):
+        _check(load().spts_profile_begin(self.handle), "spts_profile_begin")
+
+    def spts_profile_end(self) -> dict:
+        """Ends profiling; returns {phase: (total_ms, launches)} for the phases that ran."""
+        lib = load()
+        _check(lib.spts_profile_end(self.handle), "spts_profile_end")
+        out = {}
+        for i in range(lib.spts_profile_count(self.handle)):
+            name, ms, n = C.c_char_p(), C.c_double(), C.c_int64()
+            _check(lib.spts_profile_get(self.handle, i, C.byref(name), C.byref(ms), C.byref(n)), "spts_profile_get")
+            if n.value:
+                out[name.value.decode()] = (ms.value, n.value)
+        return out
 
     # raw status (for error-path tests)
     def raw(self, name, *args):

@@ -102,7 +102,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
     const int vc = tid % 8, vr = tid / 8;
     const bf16_t* Kg = (const bf16_t*)a.k;
     const bf16_t* Vt = (const bf16_t*)a.vt;
-    uint4 rk[KCH], rv[VCH];
+    u32x4 rk[KCH], rv[VCH];
     int rpos = 0;
     auto load_tile = [&](int t) {
         const int64_t key0 = (int64_t)t * BKV;
@@ -110,12 +110,12 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
         for (int i = 0; i < KCH; ++i) {
             int64_t key = key0 + kr + (256 / L::CPRK) * i;
             if (key >= a.Mk) key = a.Mk - 1;
-            rk[i] = *reinterpret_cast<const uint4*>(Kg + (key * a.Hkv + g) * (int64_t)D + kc * 8);
+            rk[i] = *reinterpret_cast<const u32x4*>(Kg + (key * a.Hkv + g) * (int64_t)D + kc * 8);
         }
 #pragma unroll
         for (int i = 0; i < VCH; ++i) {
             int row = vr + 32 * i;
-            rv[i] = *reinterpret_cast<const uint4*>(Vt + ((int64_t)g * D + row) * a.ldvt + key0 + vc * 8);
+            rv[i] = *reinterpret_cast<const u32x4*>(Vt + ((int64_t)g * D + row) * a.ldvt + key0 + vc * 8);
         }
         if (tid < BKV) { int64_t key = key0 + tid; rpos = key < a.Mk ? a.kpos[key] : 0x7fffffff; }
     };
@@ -124,12 +124,12 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
         char* sV = sK + L::K_BYTES;
         int* sP = reinterpret_cast<int*>(sV + L::V_BYTES);
 #pragma unroll
-        for (int i = 0; i < KCH; ++i) *reinterpret_cast<uint4*>(sK + L::koff(kr + (256 / L::CPRK) * i, kc)) = rk[i];
+        for (int i = 0; i < KCH; ++i) *reinterpret_cast<u32x4*>(sK + L::koff(kr + (256 / L::CPRK) * i, kc)) = rk[i];
 #pragma unroll
         for (int i = 0; i < VCH; ++i) {
             int row = vr + 32 * i;
-            *reinterpret_cast<uint2*>(sV + L::voff(row, 2 * vc)) = make_uint2(rv[i].x, rv[i].y);
-            *reinterpret_cast<uint2*>(sV + L::voff(row, 2 * vc + 1)) = make_uint2(rv[i].z, rv[i].w);
+            *reinterpret_cast<u32x2*>(sV + L::voff(row, 2 * vc)) = u32x2{rv[i].x, rv[i].y};
+            *reinterpret_cast<u32x2*>(sV + L::voff(row, 2 * vc + 1)) = u32x2{rv[i].z, rv[i].w};
         }
         if (tid < BKV) sP[tid] = rpos;
     };
@@ -216,9 +216,8 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
                         float p[8];
 #pragma unroll
                         for (int e = 0; e < 8; ++e) { p[e] = __builtin_amdgcn_exp2f(s[kb][qb][8 * hf + e] - m_use); sum += p[e]; }
-                        uint4 packed;
-                        packed.x = pk2(p[0], p[1]); packed.y = pk2(p[2], p[3]); packed.z = pk2(p[4], p[5]); packed.w = pk2(p[6], p[7]);
-                        pf[qb][2 * kb + hf] = *reinterpret_cast<bf16x8*>(&packed);
+                        u32x4 packed = {pk2(p[0], p[1]), pk2(p[2], p[3]), pk2(p[4], p[5]), pk2(p[6], p[7])};
+                        pf[qb][2 * kb + hf] = __builtin_bit_cast(bf16x8, packed);
                     }
                 l_run[qb] = l_run[qb] * alpha + sum;
 #pragma unroll
@@ -231,10 +230,10 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
             for (int st = 0; st < 4; ++st) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    uint2 v0 = *reinterpret_cast<const uint2*>(sV + L::voff(db * 32 + l32, 4 * st + lh));
-                    uint2 v1 = *reinterpret_cast<const uint2*>(sV + L::voff(db * 32 + l32, 4 * st + 2 + lh));
-                    uint4 vv = make_uint4(v0.x, v0.y, v1.x, v1.y);
-                    bf16x8 vf = *reinterpret_cast<bf16x8*>(&vv);
+                    u32x2 v0 = *reinterpret_cast<const u32x2*>(sV + L::voff(db * 32 + l32, 4 * st + lh));
+                    u32x2 v1 = *reinterpret_cast<const u32x2*>(sV + L::voff(db * 32 + l32, 4 * st + 2 + lh));
+                    u32x4 vv = {v0.x, v0.y, v1.x, v1.y};
+                    bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb)
                         o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][st], o[db][qb], 0, 0, 0);

@@ -93,27 +93,24 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
         pb[i] = bsrc + lc * 8;
     }
 
-    uint4 ra[CPR], rb[CPR], ra1[DUAL_A ? CPR : 1];
-    auto load_global = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < CPR; ++i) {
-            ra[i] = *reinterpret_cast<const uint4*>(pa[i] + k0);
-            rb[i] = *reinterpret_cast<const uint4*>(pb[i] + k0);
-            if (DUAL_A) ra1[i] = *reinterpret_cast<const uint4*>(pa1[i] + k0);
-        }
-    };
-    auto store_lds = [&](int stage) {
-        char* sA = smem + stage * STAGE;
-        char* sB = sA + S::TILE_BYTES;
-#pragma unroll
-        for (int i = 0; i < CPR; ++i) {
-            int r = lr + S::ROWS_PER_PASS * i;
-            int o = S::off(r, lc);
-            *reinterpret_cast<uint4*>(sA + o) = ra[i];
-            *reinterpret_cast<uint4*>(sB + o) = rb[i];
-            if (DUAL_A) *reinterpret_cast<uint4*>(sB + S::TILE_BYTES + o) = ra1[i];
-        }
-    };
+    u32x4 ra[CPR], rb[CPR], ra1[DUAL_A ? CPR : 1];
+#define SPTS_LOAD_GLOBAL(k0)                                                            \
+    _Pragma("unroll") for (int i = 0; i < CPR; ++i) {                                   \
+        ra[i] = *reinterpret_cast<const u32x4*>(pa[i] + (k0));                          \
+        rb[i] = *reinterpret_cast<const u32x4*>(pb[i] + (k0));                          \
+        if (DUAL_A) ra1[i] = *reinterpret_cast<const u32x4*>(pa1[i] + (k0));            \
+    }
+#define SPTS_STORE_LDS(stage)                                                           \
+    {                                                                                   \
+        char* sA_ = smem + (stage) * STAGE;                                             \
+        char* sB_ = sA_ + S::TILE_BYTES;                                                \
+        _Pragma("unroll") for (int i = 0; i < CPR; ++i) {                               \
+            int o_ = S::off(lr + S::ROWS_PER_PASS * i, lc);                             \
+            *reinterpret_cast<u32x4*>(sA_ + o_) = ra[i];                                \
+            *reinterpret_cast<u32x4*>(sB_ + o_) = rb[i];                                \
+            if (DUAL_A) *reinterpret_cast<u32x4*>(sB_ + S::TILE_BYTES + o_) = ra1[i];   \
+        }                                                                               \
+    }
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -127,11 +124,11 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
     auto brow = [&](int j) { return DUAL ? (j >> 1) * 128 + wn * 64 + (j & 1) * 32 : wn * 128 + j * 32; };
 
     const int nk = a.K / BK;
-    load_global(0);
-    store_lds(0);
+    SPTS_LOAD_GLOBAL(0)
+    SPTS_STORE_LDS(0)
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
+        if (kt + 1 < nk) { SPTS_LOAD_GLOBAL((kt + 1) * BK) }
         const char* sA = smem + (kt & 1) * STAGE;
         const char* sB = sA + S::TILE_BYTES;
         const char* sA1 = sB + S::TILE_BYTES;
@@ -154,7 +151,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
                     else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
                 }
         }
-        if (kt + 1 < nk) store_lds((kt + 1) & 1);
+        if (kt + 1 < nk) SPTS_STORE_LDS((kt + 1) & 1)
         __syncthreads();
     }
 

@@ -71,18 +71,18 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
     constexpr int KCH = PKV * L::CPRK / 256;
     const int kc = tid % L::CPRK, kr = tid / L::CPRK;
     const bf16_t* Kg = (const bf16_t*)a.k;
-    uint4 rk[KCH];
+    u32x4 rk[KCH];
     auto load_tile = [&](int t) {
 #pragma unroll
         for (int i = 0; i < KCH; ++i) {
             int64_t key = key_begin + (int64_t)t * PKV + kr + (256 / L::CPRK) * i;
             if (key >= a.N) key = a.N - 1;
-            rk[i] = *reinterpret_cast<const uint4*>(Kg + (key * a.Hkv + g) * (int64_t)D + kc * 8);
+            rk[i] = *reinterpret_cast<const u32x4*>(Kg + (key * a.Hkv + g) * (int64_t)D + kc * 8);
         }
     };
     auto store_tile = [&](int stage) {
 #pragma unroll
-        for (int i = 0; i < KCH; ++i) *reinterpret_cast<uint4*>(sK[stage] + L::koff(kr + (256 / L::CPRK) * i, kc)) = rk[i];
+        for (int i = 0; i < KCH; ++i) *reinterpret_cast<u32x4*>(sK[stage] + L::koff(kr + (256 / L::CPRK) * i, kc)) = rk[i];
     };
 
     float m_run[RB], l_run[RB];

@@ -4,6 +4,7 @@
 #include "spts_internal.h"
 
 #include <new>
+#include <vector>
 
 using namespace spts;
 
@@ -74,8 +75,47 @@ struct spts_ctx {
     Workspace off;
     bool bf16;
     int last_hip;
+    // per-phase timing (spts_profile_*): events recorded around the launches of each phase
+    bool prof_on = false;
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used = 0;
+    struct Rec { int phase; hipEvent_t a, b; };
+    std::vector<Rec> recs;
+    double phase_ms[32] = {};
+    int64_t phase_n[32] = {};
     template <typename T> T* p(size_t o) const { return reinterpret_cast<T*>(ws + o); }
 };
+
+enum PhaseId {
+    PH_ROPE_TABLE = 0, PH_RMSNORM, PH_K_PROJ, PH_PROBE_Q, PH_PROBE_ATTN, PH_TOPK, PH_GATHER, PH_Q_PROJ, PH_V_PROJ,
+    PH_ATTENTION, PH_O_PROJ, PH_PROXY_IN, PH_PROXY_MID, PH_PROXY_Z, PH_PROXY_OUT, PH_FFN_GATE_UP, PH_FFN_DOWN,
+    PH_COMPACT, PH_COUNT
+};
+static const char* const kPhaseNames[PH_COUNT] = {
+    "rope_table", "rmsnorm", "k_proj", "probe_q", "probe_attn", "topk", "gather", "q_proj", "v_proj",
+    "attention", "o_proj", "proxy_in", "proxy_mid", "proxy_z", "proxy_out", "ffn_gate_up", "ffn_down", "compact"};
+
+// Brackets the launches issued during its lifetime with two events when profiling is on.
+struct PhaseScope {
+    spts_ctx* c; int rec = -1;
+    PhaseScope(spts_ctx* ctx, int phase) : c(ctx) {
+        if (!c->prof_on) return;
+        hipEvent_t e[2];
+        for (int i = 0; i < 2; ++i) {
+            if (c->ev_used == c->ev_pool.size()) {
+                hipEvent_t n;
+                if (hipEventCreate(&n) != hipSuccess) return;
+                c->ev_pool.push_back(n);
+            }
+            e[i] = c->ev_pool[c->ev_used++];
+        }
+        if (hipEventRecord(e[0], c->stream) != hipSuccess) return;
+        c->recs.push_back({phase, e[0], e[1]});
+        rec = (int)c->recs.size() - 1;
+    }
+    ~PhaseScope() { if (rec >= 0) (void)hipEventRecord(c->recs[rec].b, c->stream); }
+};
+#define PHASE(ctx, id) PhaseScope phase_scope__(ctx, id)
 
 #define SPTS_HIP(ctx, expr)                                                   \
     do {                                                                      \
@@ -144,21 +184,22 @@ int check_weights_full(const spts_ctx* c, const spts_layer_weights* w, bool need
 int probe_attn_impl(spts_ctx* c, const void* x, const int32_t* pos, int64_t N, const spts_layer_weights* w, int P,
                     bool want_scores, void* k_out, float* s_out) {
     const auto& m = c->m;
-    SPTS_HIP(c, launch_rope_table(pos, N, m.d, m.rope_base, c->p<float2>(c->off.rope), c->stream));
-    SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, c->p<void>(c->off.xn), N, m.D, c->bf16, c->stream));
+    { PHASE(c, PH_ROPE_TABLE); SPTS_HIP(c, launch_rope_table(pos, N, m.d, m.rope_base, c->p<float2>(c->off.rope), c->stream)); }
+    { PHASE(c, PH_RMSNORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, c->p<void>(c->off.xn), N, m.D, c->bf16, c->stream)); }
     const int KV = m.Hkv * m.d, QD = m.H * m.d;
     GemmArgs gk = gemm_args(c->p<void>(c->off.xn), m.D, nullptr, w->Wk, m.D, nullptr, KV, N, KV, m.D);
-    SPTS_TRY(run_gemm_rope(c, gk, m.Hkv, nullptr, 0, k_out));
+    { PHASE(c, PH_K_PROJ); SPTS_TRY(run_gemm_rope(c, gk, m.Hkv, nullptr, 0, k_out)); }
     if (!want_scores) return SPTS_OK;
     const size_t eb = c->bf16 ? 2 : 4;
     const char* xn_probe = c->p<char>(c->off.xn) + (size_t)(N - P) * m.D * eb;
     GemmArgs gq = gemm_args(xn_probe, m.D, nullptr, w->Wq, m.D, nullptr, QD, P, QD, m.D);
-    SPTS_TRY(run_gemm_rope(c, gq, m.H, nullptr, N - P, c->p<void>(c->off.qp)));
+    { PHASE(c, PH_PROBE_Q); SPTS_TRY(run_gemm_rope(c, gq, m.H, nullptr, N - P, c->p<void>(c->off.qp))); }
     ProbeArgs pa{};
     pa.qp = c->p<void>(c->off.qp); pa.k = k_out; pa.S = s_out;
     pa.stats = c->p<float>(c->off.probe);
     pa.partial = c->p<float>(c->off.probe) + (2 * (size_t)P * m.H + 64);
     pa.N = N; pa.P = P; pa.H = m.H; pa.Hkv = m.Hkv; pa.d = m.d;
+    PHASE(c, PH_PROBE_ATTN);
     if (c->bf16 && probe_mfma_supported(pa)) SPTS_HIP(c, launch_probe_mfma(pa, c->stream));
     else SPTS_HIP(c, launch_probe_generic(pa, c->bf16, c->stream));
     return SPTS_OK;
@@ -172,21 +213,22 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
     const size_t eb = c->bf16 ? 2 : 4;
     char* t = c->p<char>(c->off.t);  // [N, 2r]: columns [0,r) = x Ug, [r,2r) = x Uu
     GemmArgs g1 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, r, m.D);
-    SPTS_TRY(run_gemm(c, g1));
+    { PHASE(c, PH_PROXY_IN); SPTS_TRY(run_gemm(c, g1)); }
     GemmArgs g2 = gemm_args(xn2, m.D, nullptr, w->Uu, m.D, t + (size_t)r * eb, 2 * r, N, r, m.D);
-    SPTS_TRY(run_gemm(c, g2));
+    { PHASE(c, PH_PROXY_IN); SPTS_TRY(run_gemm(c, g2)); }
     // hp = silu(tg Vg) * (tu Vu)   [N, Dlow]
     GemmArgs g3 = gemm_args(t, 2 * r, nullptr, w->Vg, r, c->p<void>(c->off.big), Dlow, N, Dlow, r, EPI_SILU_MUL);
     g3.B1 = w->Vu; g3.A1 = t + (size_t)r * eb;
-    SPTS_TRY(run_gemm(c, g3));
+    { PHASE(c, PH_PROXY_MID); SPTS_TRY(run_gemm(c, g3)); }
     // z = hp Vd^T   [N, r]
     GemmArgs g4 = gemm_args(c->p<void>(c->off.big), Dlow, nullptr, w->Vd, Dlow, c->p<void>(c->off.z), r, N, r, Dlow);
-    SPTS_TRY(run_gemm(c, g4));
+    { PHASE(c, PH_PROXY_Z); SPTS_TRY(run_gemm(c, g4)); }
     // o = z Ud^T [N, D] is never stored: per-block sums of squares, then the square root
     GemmArgs g5 = gemm_args(c->p<void>(c->off.z), r, nullptr, w->Ud, r, nullptr, 0, N, m.D, r, EPI_SUMSQ);
     bool mf = c->bf16 && gemm_mfma_supported(g5);
     int nb = gemm_sumsq_blocks(m.D, mf);
     g5.part = c->p<float>(c->off.part); g5.part_ld = nb;
+    PHASE(c, PH_PROXY_OUT);
     SPTS_TRY(run_gemm(c, g5));
     SPTS_HIP(c, launch_finish_ffn_scores(c->p<float>(c->off.part), nb, s_mha, c_ffn, s_ffn, N, c->stream));
     return SPTS_OK;
@@ -245,7 +287,45 @@ int spts_create(spts_ctx** ctx, const spts_model_desc* model, void* hip_stream, 
     return SPTS_OK;
 }
 
-void spts_destroy(spts_ctx* ctx) { delete ctx; }
+void spts_destroy(spts_ctx* ctx) {
+    if (!ctx) return;
+    for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+int spts_profile_begin(spts_ctx* c) {
+    if (!c) return SPTS_EINVAL;
+    c->recs.clear();
+    c->ev_used = 0;
+    for (int i = 0; i < PH_COUNT; ++i) { c->phase_ms[i] = 0.0; c->phase_n[i] = 0; }
+    c->prof_on = true;
+    return SPTS_OK;
+}
+
+int spts_profile_end(spts_ctx* c) {
+    if (!c) return SPTS_EINVAL;
+    c->prof_on = false;
+    SPTS_HIP(c, hipStreamSynchronize(c->stream));
+    for (const auto& r : c->recs) {
+        float ms = 0.f;
+        SPTS_HIP(c, hipEventElapsedTime(&ms, r.a, r.b));
+        c->phase_ms[r.phase] += ms;
+        c->phase_n[r.phase] += 1;
+    }
+    c->recs.clear();
+    c->ev_used = 0;
+    return SPTS_OK;
+}
+
+int spts_profile_count(const spts_ctx* c) { return c ? (int)PH_COUNT : 0; }
+
+int spts_profile_get(const spts_ctx* c, int i, const char** name, double* total_ms, int64_t* launches) {
+    if (!c || i < 0 || i >= PH_COUNT) return SPTS_EINVAL;
+    if (name) *name = kPhaseNames[i];
+    if (total_ms) *total_ms = c->phase_ms[i];
+    if (launches) *launches = c->phase_n[i];
+    return SPTS_OK;
+}
 
 int spts_last_hip_error(const spts_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
 
@@ -275,7 +355,7 @@ int spts_probe_ffn(spts_ctx* c, const void* x, int64_t N, const spts_layer_weigh
     if (!x || !s_ffn) return SPTS_EINVAL;
     if (!aligned16(x) || !aligned16(s_ffn) || (s_mha && !aligned16(s_mha)) || (c_ffn && !aligned16(c_ffn))) return SPTS_EALIGN;
     SPTS_TRY(check_weights_proxy(c, w));
-    SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, c->m.rms_eps, c->p<void>(c->off.xn), N, c->m.D, c->bf16, c->stream));
+    { PHASE(c, PH_RMSNORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, c->m.rms_eps, c->p<void>(c->off.xn), N, c->m.D, c->bf16, c->stream)); }
     return proxy_scores_impl(c, c->p<void>(c->off.xn), N, w, s_mha, c_ffn, s_ffn);
 }
 
@@ -285,6 +365,7 @@ int spts_select_topk(spts_ctx* c, const float* scores, int64_t N, int64_t k, int
     if (k == 0) return SPTS_OK;
     if (!scores || !idx_out) return SPTS_EINVAL;
     if (!aligned16(scores) || !aligned16(idx_out)) return SPTS_EALIGN;
+    PHASE(c, PH_TOPK);
     SPTS_HIP(c, launch_topk(scores, N, k, protect_last, idx_out, c->p<int32_t>(c->off.misc), c->stream));
     return SPTS_OK;
 }
@@ -307,6 +388,7 @@ int spts_msdp_compact(spts_ctx* c, const void* x_in, const int32_t* pos_in, cons
         const char* a = (const char*)x_in; const char* b = (const char*)x_out;
         if (a < b + (size_t)keep * row_bytes && b < a + (size_t)N * row_bytes) return SPTS_EINVAL;  // overlap
     }
+    PHASE(c, PH_COMPACT);
     if (map_old2new) SPTS_HIP(c, launch_fill_i32(map_old2new, -1, N, c->stream));
     if (keep == 0) return SPTS_OK;
     SPTS_HIP(c, launch_topk(s_mha, N, keep, protect_last, map_new2old, c->p<int32_t>(c->off.misc), c->stream));
@@ -358,23 +440,26 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
     SPTS_TRY(probe_attn_impl(c, x, pos, N, w, skip ? cfg->probe_len : 0, skip, kall, S));
     if (skip) {
         idxA = idx_attn ? idx_attn : c->p<int32_t>(c->off.idxA);
+        PHASE(c, PH_TOPK);
         SPTS_HIP(c, launch_topk(S, N, Ma, cfg->protect_last, idxA, c->p<int32_t>(c->off.misc), st));
     }
     if (Ma > 0) {
         // queries of the active rows (rows gathered through idxA inside the GEMM's A loads)
         GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, Ma, QD, m.D);
-        SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q)));
+        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q))); }
         const int32_t* qpos = pos;
         const int32_t* kpos = pos;
         void* kk = kall;
         void* vv;
         if (skip) {
             int32_t* posA = (kv && !full_kv) ? kv->pos : c->p<int32_t>(c->off.posA);
+            PHASE(c, PH_GATHER);
             SPTS_HIP(c, launch_gather_i32(pos, idxA, posA, Ma, st));
             qpos = posA;
         }
         if (!full_kv) {
             kk = kv ? kv->k : c->p<void>(c->off.khat);
+            PHASE(c, PH_GATHER);
             SPTS_HIP(c, launch_gather_rows(kall, idxA, kk, Ma, (int64_t)KV * eb, st));
             kpos = qpos;
         } else if (kv) {
@@ -393,33 +478,40 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
             GemmArgs gvt = gv; gvt.Ct = c->p<void>(c->off.vt); gvt.ldct = aa.ldvt;
             if (gemm_mfma_supported(gvt)) { gv = gvt; vt_done = true; }
         }
-        SPTS_TRY(run_gemm(c, gv));
-        if (amf && !vt_done) SPTS_HIP(c, launch_transpose_pad(vv, c->p<void>(c->off.vt), Mk, KV, aa.ldvt, c->bf16, st));
+        {
+            PHASE(c, PH_V_PROJ);
+            SPTS_TRY(run_gemm(c, gv));
+            if (amf && !vt_done) SPTS_HIP(c, launch_transpose_pad(vv, c->p<void>(c->off.vt), Mk, KV, aa.ldvt, c->bf16, st));
+        }
         if (kv) kv->count = Mk;
-        if (amf) SPTS_HIP(c, launch_attention_mfma(aa, st));
-        else SPTS_HIP(c, launch_attention_generic(aa, c->bf16, st));
+        {
+            PHASE(c, PH_ATTENTION);
+            if (amf) SPTS_HIP(c, launch_attention_mfma(aa, st));
+            else SPTS_HIP(c, launch_attention_generic(aa, c->bf16, st));
+        }
         // x[T_a] += att * Wo^T
         GemmArgs go = gemm_args(c->p<void>(c->off.att), QD, nullptr, w->Wo, QD, x, m.D, Ma, m.D, QD, EPI_RESIDUAL);
         go.c_idx = idxA;
-        SPTS_TRY(run_gemm(c, go));
+        { PHASE(c, PH_O_PROJ); SPTS_TRY(run_gemm(c, go)); }
     }
 
     // ------------------------------------------------ FFN block (Alg. 1, LTP block / dense branch)
     if (Mf == 0) return SPTS_OK;
-    SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, m.rms_eps, xn, N, m.D, c->bf16, st));
+    { PHASE(c, PH_RMSNORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, m.rms_eps, xn, N, m.D, c->bf16, st)); }
     int32_t* idxF = nullptr;
     if (skip) {
         float* SF = c->p<float>(c->off.SF);
         SPTS_TRY(proxy_scores_impl(c, xn, N, w, S, nullptr, SF));
         idxF = idx_ffn ? idx_ffn : c->p<int32_t>(c->off.idxF);
+        PHASE(c, PH_TOPK);
         SPTS_HIP(c, launch_topk(SF, N, Mf, cfg->protect_last, idxF, c->p<int32_t>(c->off.misc), st));
     }
     GemmArgs gh = gemm_args(xn, m.D, idxF, w->Wgate, m.D, c->p<void>(c->off.big), m.Dff, Mf, m.Dff, m.D, EPI_SILU_MUL);
     gh.B1 = w->Wup;
-    SPTS_TRY(run_gemm(c, gh));
+    { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
     GemmArgs gd = gemm_args(c->p<void>(c->off.big), m.Dff, nullptr, w->Wdown, m.Dff, x, m.D, Mf, m.D, m.Dff, EPI_RESIDUAL);
     gd.c_idx = idxF;
-    SPTS_TRY(run_gemm(c, gd));
+    { PHASE(c, PH_FFN_DOWN); SPTS_TRY(run_gemm(c, gd)); }
     return SPTS_OK;
 }
 

@@ -5,6 +5,11 @@
 
 namespace spts {
 
+// Native vector types for register staging (arrays of HIP's uint4 struct are not scalarised by the
+// compiler and end up in scratch memory).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
 // ------------------------------------------------------------------ element types
 struct bf16_t { uint16_t v; };
 

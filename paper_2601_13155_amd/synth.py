@@ -118,9 +118,11 @@ def _gen(seed: int, tid: int) -> np.random.Generator:
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """fp32 array -> nearest-even bfloat16 value, returned as fp32 (data formatting only)."""
     a = np.ascontiguousarray(a, dtype=np.float32)
-    u = a.view(np.uint32).astype(np.uint64)
-    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+    u = a.view(np.uint32)
+    r = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)   # finite inputs: no wrap-around
+    r += u
+    r &= np.uint32(0xFFFF0000)
+    return r.view(np.float32).reshape(a.shape)
 
 
 def bf16_bits(a: np.ndarray) -> np.ndarray:
@@ -166,14 +168,19 @@ def layer_weights(seed: int, layer: int, shape: ModelShape) -> Dict[str, np.ndar
         "Wgate": (D, Dff), "Wup": (D, Dff),
         "Wdown": (D, Dff),  # applied transposed: d_in = Dff
     }
-    out: Dict[str, np.ndarray] = {}
-    for i, name in enumerate(_MATS):
+    def one(item):
+        i, name = item
         rows, cols = dims[name]
         d_in = cols if name == "Wdown" else rows
         g = _gen(seed, _TID_WEIGHT0 + 16 * layer + i)
         w = g.standard_normal((rows, cols), dtype=np.float32)
         w *= np.float32(1.0 / math.sqrt(d_in))
-        out[name] = storage_round(w, shape.dtype)
+        return name, storage_round(w, shape.dtype)
+
+    # every matrix has its own generator key, so the threads below do not change any value
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        out: Dict[str, np.ndarray] = dict(ex.map(one, enumerate(_MATS)))
     out["gamma1"] = np.ones(D, dtype=np.float32)
     out["gamma2"] = np.ones(D, dtype=np.float32)
     return out
