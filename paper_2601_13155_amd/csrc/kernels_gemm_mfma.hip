@@ -6,10 +6,18 @@
 //
 //  * 256x256 output tile per workgroup, 4 wavefronts (2x2), each owning 128x128 = 4x4 MFMA
 //    32x32x16 blocks: 256 fp32 accumulators per lane (AGPRs), 16 MFMAs per 8 fragment reads.
-//  * K is consumed in slabs of BK (64, or 32 when a second A operand is staged); global->register
-//    prefetch of slab k+1 overlaps the MFMAs of slab k; two LDS stages, one barrier per slab.
-//  * LDS rows are XOR-swizzled in 16-byte chunks so that both the 16-lane b128 fragment reads and
-//    the staging writes are bank-conflict free without padding.
+//  * K is consumed in slabs of 32.  Slabs travel global memory -> LDS directly
+//    (global_load_lds_dwordx4: no VGPR staging, no ds_write instructions) into a ring of 4 LDS
+//    stages (3 when a second A operand is staged), so the loads of slab k+3 are in flight while
+//    slab k is multiplied: ~1.3 us of memory latency are covered at full MFMA rate.  The wavefront
+//    counts its own outstanding slab loads with s_waitcnt vmcnt(n) and one workgroup barrier per
+//    slab publishes a landed slab and frees the stage consumed before it.
+//  * A direct-to-LDS load puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that makes the
+//    16-lane b128 fragment reads bank-conflict free is applied on the global side: lane i fetches
+//    the chunk that belongs at position i.
+//  * Fragment reads of the next k-step are issued between the MFMAs of the current one
+//    (sched_group_barrier pins the interleaving); the barrier sits a few MFMAs into the second
+//    k-step so that the matrix pipe stays fed while wavefronts meet.
 //  * Rows of A may be gathered through an index list (the active-token gather of Eq. (skip) is
 //    folded into the A loads: a row is 2*K contiguous bytes, so nothing is lost in coalescing),
 //    rows of C may be scattered through one (the residual update X[T] += ...).
@@ -29,27 +37,34 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 256, BN = 256, NTHREADS = 256;
+constexpr int BK = 32;                       // K slab
+constexpr int ROW_BYTES = BK * 2;            // 64 bytes per tile row
+constexpr int TILE_BYTES = 256 * ROW_BYTES;  // 16 KB per operand tile
 
-template <int BK> struct Slab {
-    static constexpr int ROW_BYTES = BK * 2;
-    static constexpr int CPR = BK / 8;              // 16-byte chunks per tile row
-    static constexpr int RP = 256 / ROW_BYTES;      // tile rows per 256 bytes (all 64 banks)
-    static constexpr int TILE_BYTES = 256 * ROW_BYTES;
-    static constexpr int ROWS_PER_PASS = NTHREADS / CPR;
-    __device__ static inline int off(int row, int c) { return row * ROW_BYTES + ((c ^ ((row / RP) % CPR)) << 4); }
-};
+// byte offset of 16-byte chunk c (0..3) of tile row `row`: chunk index XOR-ed with (row/4)%4, so the
+// 16 lanes of a b128 read (16 consecutive rows, same chunk) cover all 64 banks exactly once
+__device__ inline int tile_off(int row, int c) { return row * ROW_BYTES + ((c ^ ((row >> 2) & 3)) << 4); }
 
 __device__ inline uint32_t pack_bf16x2(float a, float b) {
     return (uint32_t)f32_to_bf16(a).v | ((uint32_t)f32_to_bf16(b).v << 16);
 }
 __device__ inline float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
-template <int EPI, int BK, bool DUAL_A>
+// One direct-to-LDS load: every lane fetches 16 bytes from its own global address; the wavefront's
+// 1 KB lands at lds_base + 16 * lane.  lds_base must be wavefront-uniform.
+__device__ inline void dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\t" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
+#define SPTS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 0xF) | (((n) >> 4) << 14))
+
+template <int EPI, bool DUAL_A>
 __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM, int nN, int total) {
-    using S = Slab<BK>;
     constexpr bool DUAL = (EPI == EPI_SILU_MUL);
-    constexpr int CPR = S::CPR;
-    constexpr int STAGE = S::TILE_BYTES * (DUAL_A ? 3 : 2);
+    constexpr int NOPS = DUAL_A ? 3 : 2;          // operand tiles per stage (A, B[, A1])
+    constexpr int NST = DUAL_A ? 3 : 4;           // LDS ring stages
+    constexpr int STAGE = TILE_BYTES * NOPS;
+    constexpr int PER = 4 * NOPS;                 // direct-to-LDS loads per wavefront per slab
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     // ---- tile id: XCD-contiguous ranges, grouped raster
@@ -64,53 +79,48 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
     const int tm = first_m + in_g % gsz;
     const int tn = in_g / gsz;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
     const int64_t row0 = (int64_t)tm * BM;
     constexpr int OUT_COLS = DUAL ? 128 : 256;   // output columns covered by one tile
     const int col0 = tn * OUT_COLS;
 
-    // ---- global load assignment: thread owns chunk column lc of rows lr + ROWS_PER_PASS * i
-    const int lc = tid % CPR, lr = tid / CPR;
-    const bf16_t* A = (const bf16_t*)a.A;
-    const bf16_t* A1 = (const bf16_t*)a.A1;
-    const bf16_t* pa[CPR];
-    const bf16_t* pa1[DUAL_A ? CPR : 1];
-    const bf16_t* pb[CPR];
+    // ---- direct-to-LDS assignment: wavefront w moves tile rows [64w, 64w+64) of every operand, 16
+    //      rows (1 KB) per load; lane -> (row = 64w + 16q + lane/4, LDS chunk = lane%4), and fetches
+    //      the global chunk that the swizzle maps to that LDS position.
+    const bf16_t* ga[4];
+    const bf16_t* ga1[DUAL_A ? 4 : 1];
+    const bf16_t* gb[4];
 #pragma unroll
-    for (int i = 0; i < CPR; ++i) {
-        int r = lr + S::ROWS_PER_PASS * i;
+    for (int q = 0; q < 4; ++q) {
+        const int r = wave * 64 + q * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 2) & 3);
         int64_t grow = row0 + r;
         if (grow >= a.M) grow = a.M - 1;  // clamp: duplicates of the last row are never stored
-        int64_t srow = a.a_idx ? (int64_t)a.a_idx[grow] : grow;
-        pa[i] = A + srow * a.lda + lc * 8;
-        if (DUAL_A) pa1[i] = A1 + srow * a.lda + lc * 8;
+        const int64_t srow = a.a_idx ? (int64_t)a.a_idx[grow] : grow;
+        ga[q] = (const bf16_t*)a.A + srow * a.lda + c * 8;
+        if (DUAL_A) ga1[q] = (const bf16_t*)a.A1 + srow * a.lda + c * 8;
         const bf16_t* bsrc;
         if (DUAL) bsrc = (r < 128) ? (const bf16_t*)a.B0 + (int64_t)(col0 + r) * a.ldb
                                    : (const bf16_t*)a.B1 + (int64_t)(col0 + r - 128) * a.ldb;
         else bsrc = (const bf16_t*)a.B0 + (int64_t)(col0 + r) * a.ldb;
-        pb[i] = bsrc + lc * 8;
+        gb[q] = bsrc + c * 8;
     }
-
-    u32x4 ra[CPR], rb[CPR], ra1[DUAL_A ? CPR : 1];
-#define SPTS_LOAD_GLOBAL(k0)                                                            \
-    _Pragma("unroll") for (int i = 0; i < CPR; ++i) {                                   \
-        ra[i] = *reinterpret_cast<const u32x4*>(pa[i] + (k0));                          \
-        rb[i] = *reinterpret_cast<const u32x4*>(pb[i] + (k0));                          \
-        if (DUAL_A) ra1[i] = *reinterpret_cast<const u32x4*>(pa1[i] + (k0));            \
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    const uint32_t lds_w = lds0 + wave * 4096;   // this wavefront's 64 rows inside an operand tile
+    // load number u (0 .. PER-1) of slab kt_: operand u % NOPS, 16-row group u / NOPS
+#define SPTS_DMA_ONE(kt_, u)                                                                   \
+    {                                                                                          \
+        const uint32_t sb_ = lds_w + ((kt_) % NST) * STAGE + ((u) / NOPS) * 1024;              \
+        const int ko_ = (kt_) * BK;                                                            \
+        if ((u) % NOPS == 0) dma16(ga[(u) / NOPS] + ko_, sb_);                                 \
+        else if ((u) % NOPS == 1) dma16(gb[(u) / NOPS] + ko_, sb_ + TILE_BYTES);               \
+        else dma16(ga1[DUAL_A ? (u) / NOPS : 0] + ko_, sb_ + 2 * TILE_BYTES);                  \
     }
-#define SPTS_STORE_LDS(stage)                                                           \
-    {                                                                                   \
-        char* sA_ = smem + (stage) * STAGE;                                             \
-        char* sB_ = sA_ + S::TILE_BYTES;                                                \
-        _Pragma("unroll") for (int i = 0; i < CPR; ++i) {                               \
-            int o_ = S::off(lr + S::ROWS_PER_PASS * i, lc);                             \
-            *reinterpret_cast<u32x4*>(sA_ + o_) = ra[i];                                \
-            *reinterpret_cast<u32x4*>(sB_ + o_) = rb[i];                                \
-            if (DUAL_A) *reinterpret_cast<u32x4*>(sB_ + S::TILE_BYTES + o_) = ra1[i];   \
-        }                                                                               \
-    }
+#define SPTS_DMA_SLAB(kt_)                                                                     \
+    { _Pragma("unroll") for (int u_ = 0; u_ < PER; ++u_) SPTS_DMA_ONE(kt_, u_) }
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -123,37 +133,92 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
     // B tile row of this wavefront's N block j
     auto brow = [&](int j) { return DUAL ? (j >> 1) * 128 + wn * 64 + (j & 1) * 32 : wn * 128 + j * 32; };
 
-    const int nk = a.K / BK;
-    SPTS_LOAD_GLOBAL(0)
-    SPTS_STORE_LDS(0)
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) { SPTS_LOAD_GLOBAL((kt + 1) * BK) }
-        const char* sA = smem + (kt & 1) * STAGE;
-        const char* sB = sA + S::TILE_BYTES;
-        const char* sA1 = sB + S::TILE_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[4], bfr[4], af1[DUAL_A ? 4 : 1];
-            const int c = ks * 2 + lh;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                af[i] = *reinterpret_cast<const bf16x8*>(sA + S::off(wm * 128 + i * 32 + l32, c));
-                if (DUAL_A) af1[i] = *reinterpret_cast<const bf16x8*>(sA1 + S::off(wm * 128 + i * 32 + l32, c));
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(sB + S::off(brow(j) + l32, c));
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (DUAL_A && j >= 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af1[i], acc[i][j], 0, 0, 0);
-                    else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-                }
-        }
-        if (kt + 1 < nk) SPTS_STORE_LDS((kt + 1) & 1)
-        __syncthreads();
+    bf16x8 af[2][4], bfr[2][4], af1[2][DUAL_A ? 4 : 1];
+#define SPTS_LOAD_FRAGS(buf, stage, ks)                                                                      \
+    {                                                                                                        \
+        const char* sA_ = smem + (stage) * STAGE;                                                            \
+        const char* sB_ = sA_ + TILE_BYTES;                                                                  \
+        const int c_ = (ks) * 2 + lh;                                                                        \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                      \
+            af[buf][i] = *reinterpret_cast<const bf16x8*>(sA_ + tile_off(wm * 128 + i * 32 + l32, c_));      \
+            if (DUAL_A)                                                                                      \
+                af1[buf][i] = *reinterpret_cast<const bf16x8*>(sB_ + TILE_BYTES + tile_off(wm * 128 + i * 32 + l32, c_)); \
+        }                                                                                                    \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                        \
+            bfr[buf][j] = *reinterpret_cast<const bf16x8*>(sB_ + tile_off(brow(j) + l32, c_));               \
     }
+#define SPTS_MFMA(buf, i, j)                                                                                 \
+    {                                                                                                        \
+        if (DUAL_A && (j) >= 2)                                                                              \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][j], af1[buf][i], acc[i][j], 0, 0, 0); \
+        else                                                                                                 \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][j], af[buf][i], acc[i][j], 0, 0, 0);  \
+    }
+    constexpr int NREADS = DUAL_A ? 12 : 8;   // fragment reads per k-step
+
+    const int nk = a.K / BK;
+    // ---- prologue: slabs 0 .. NST-2 are put in flight, slab 0 must have landed
+    {
+        const int npre = nk < NST - 1 ? nk : NST - 1;
+        for (int t = 0; t < npre; ++t) SPTS_DMA_SLAB(t)
+        if (npre == NST - 1) { SPTS_WAIT_VMCNT((NST - 2) * PER); } else { SPTS_WAIT_VMCNT(0); }
+    }
+    __syncthreads();
+    SPTS_LOAD_FRAGS(0, 0, 0)
+
+    // One K slab = 32 MFMAs per wavefront.  Every memory instruction sits in the shadow of an MFMA
+    // (an MFMA occupies the matrix pipe for 32 cycles while the wavefront may issue other work):
+    //   MFMA  1- 8 (k-step 0): one fragment read of k-step 1 after each
+    //   MFMA  9-16 (k-step 0): one direct-to-LDS load of slab kt+NST-1 after each (ISSUE)
+    //   MFMA 17-20 (k-step 1), then wait for this wavefront's share of slab kt+1 and meet the
+    //               workgroup: slab kt+1 is published, stage kt%NST is free for the next iteration
+    //   MFMA 21-32 (k-step 1): one fragment read of slab kt+1, k-step 0, after each of the first 8
+    // ISSUE / NEXT are literal constants at every expansion.
+    // 8 MFMA slots, one fragment read after each (two after the first NREADS-8 when 12 are due)
+#define SPTS_INTERLEAVE_READS                                                                                \
+    _Pragma("unroll") for (int g_ = 0; g_ < NREADS - 8; ++g_) {                                              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                   \
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                                   \
+    }                                                                                                        \
+    _Pragma("unroll") for (int g_ = NREADS - 8; g_ < 8; ++g_) {                                              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                   \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                   \
+    }
+#define SPTS_SLAB(kt_, ISSUE, NEXT, WAITN)                                                                   \
+    {                                                                                                        \
+        const int st_ = (kt_) % NST;                                                                         \
+        SPTS_LOAD_FRAGS(1, st_, 1)                                                                           \
+        _Pragma("unroll") for (int m_ = 0; m_ < 8; ++m_) SPTS_MFMA(0, m_ / 4, m_ % 4)                        \
+        SPTS_INTERLEAVE_READS                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                                   \
+        _Pragma("unroll") for (int m_ = 8; m_ < 16; ++m_) {                                                  \
+            SPTS_MFMA(0, m_ / 4, m_ % 4)                                                                     \
+            if (ISSUE) {                                                                                     \
+                __builtin_amdgcn_sched_barrier(0);                                                           \
+                SPTS_DMA_ONE((kt_) + NST - 1, m_ - 8)                                                        \
+                if (m_ < PER) SPTS_DMA_ONE((kt_) + NST - 1, (m_ < PER ? m_ : 0))                             \
+                __builtin_amdgcn_sched_barrier(0);                                                           \
+            }                                                                                                \
+        }                                                                                                    \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) SPTS_MFMA(1, 0, j)                                     \
+        if (NEXT) { SPTS_WAIT_VMCNT(WAITN); }                                                                \
+        __syncthreads();                                                                                     \
+        if (NEXT) { SPTS_LOAD_FRAGS(0, ((kt_) + 1) % NST, 0) }                                               \
+        _Pragma("unroll") for (int i = 1; i < 4; ++i)                                                        \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) SPTS_MFMA(1, i, j)                                 \
+        if (NEXT) {                                                                                          \
+            SPTS_INTERLEAVE_READS                                                                            \
+        }                                                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                                   \
+    }
+
+    int kt = 0;
+    // steady state: slab kt+NST-1 exists; after its loads are issued the slabs behind kt+1 in flight
+    // are kt+2 .. kt+NST-1
+    for (; kt + NST - 1 < nk; ++kt) SPTS_SLAB(kt, true, true, (NST - 2) * PER)
+    // drain: nothing left to issue; wait for everything that is still in flight
+    for (; kt + 1 < nk; ++kt) SPTS_SLAB(kt, false, true, 0)
+    SPTS_SLAB(kt, false, false, 0)
 
     // ---- epilogue.  acc[i][j][r]: row = row0 + wm*128 + i*32 + l32,
     //      column (inside N block j) = 8*(r/4) + 4*lh + r%4  -> 4 consecutive columns per r/4.
@@ -296,8 +361,7 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     const bool dual = a.epi == EPI_SILU_MUL;
     const int ncols = dual ? 128 : 256;
     if (a.M <= 0 || a.N <= 0 || a.N % ncols != 0) return false;
-    const int bk = (dual && a.A1) ? 32 : 64;
-    if (a.K < bk || a.K % bk != 0) return false;
+    if (a.K < BK || a.K % BK != 0) return false;
     if (a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
     if (!al16(a.A) || !al16(a.B0) || (a.A1 && !al16(a.A1)) || (dual && !al16(a.B1))) return false;
     if (a.epi != EPI_SUMSQ) {
@@ -309,33 +373,33 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     return true;
 }
 
-template <int EPI, int BK, bool DUAL_A>
+template <int EPI, bool DUAL_A>
 static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     const int ncols = EPI == EPI_SILU_MUL ? 128 : 256;
     const int nM = (int)((a.M + BM - 1) / BM), nN = a.N / ncols;
     const int total = nM * nN;
     const int grid = (total + 7) / 8 * 8;
-    const size_t lds = (size_t)Slab<BK>::TILE_BYTES * (DUAL_A ? 3 : 2) * 2;
+    const size_t lds = (size_t)TILE_BYTES * (DUAL_A ? 3 * 3 : 2 * 4);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<EPI, BK, DUAL_A>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<EPI, DUAL_A>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_mfma_kernel<EPI, BK, DUAL_A><<<dim3(grid), dim3(NTHREADS), lds, s>>>(a, nM, nN, total);
+    gemm_mfma_kernel<EPI, DUAL_A><<<dim3(grid), dim3(NTHREADS), lds, s>>>(a, nM, nN, total);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
     switch (a.epi) {
-        case EPI_STORE: return launch_t<EPI_STORE, 64, false>(a, s);
-        case EPI_RESIDUAL: return launch_t<EPI_RESIDUAL, 64, false>(a, s);
-        case EPI_SUMSQ: return launch_t<EPI_SUMSQ, 64, false>(a, s);
-        case EPI_ROPE: return launch_t<EPI_ROPE, 64, false>(a, s);
+        case EPI_STORE: return launch_t<EPI_STORE, false>(a, s);
+        case EPI_RESIDUAL: return launch_t<EPI_RESIDUAL, false>(a, s);
+        case EPI_SUMSQ: return launch_t<EPI_SUMSQ, false>(a, s);
+        case EPI_ROPE: return launch_t<EPI_ROPE, false>(a, s);
         case EPI_SILU_MUL:
-            if (a.A1) return launch_t<EPI_SILU_MUL, 32, true>(a, s);
-            return launch_t<EPI_SILU_MUL, 64, false>(a, s);
+            if (a.A1) return launch_t<EPI_SILU_MUL, true>(a, s);
+            return launch_t<EPI_SILU_MUL, false>(a, s);
         default: return hipErrorInvalidValue;
     }
 }
