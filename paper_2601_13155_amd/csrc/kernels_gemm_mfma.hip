@@ -37,13 +37,19 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 256, BN = 256, NTHREADS = 256;
-constexpr int BK = 32;                       // K slab
-constexpr int ROW_BYTES = BK * 2;            // 64 bytes per tile row
-constexpr int TILE_BYTES = 256 * ROW_BYTES;  // 16 KB per operand tile
 
-// byte offset of 16-byte chunk c (0..3) of tile row `row`: chunk index XOR-ed with (row/4)%4, so the
-// 16 lanes of a b128 read (16 consecutive rows, same chunk) cover all 64 banks exactly once
-__device__ inline int tile_off(int row, int c) { return row * ROW_BYTES + ((c ^ ((row >> 2) & 3)) << 4); }
+// K slab geometry.  A tile row holds BK bf16 = CPR 16-byte chunks; chunk c of row `row` is stored at
+// chunk position c ^ ((row / RP) % CPR) (RP = rows per 256 bytes), so the 16 lanes of a b128
+// fragment read (16 consecutive rows, same chunk) cover all 64 LDS banks exactly once.
+template <int BK> struct Slab {
+    static constexpr int ROW_BYTES = BK * 2;
+    static constexpr int CPR = BK / 8;
+    static constexpr int RP = 256 / ROW_BYTES;
+    static constexpr int TILE_BYTES = 256 * ROW_BYTES;
+    static constexpr int ROWS_PER_LOAD = 64 / CPR;   // tile rows moved by one direct-to-LDS load
+    __device__ static inline int swz(int row) { return (row / RP) % CPR; }
+    __device__ static inline int off(int row, int c) { return row * ROW_BYTES + ((c ^ swz(row)) << 4); }
+};
 
 __device__ inline uint32_t pack_bf16x2(float a, float b) {
     return (uint32_t)f32_to_bf16(a).v | ((uint32_t)f32_to_bf16(b).v << 16);
@@ -58,13 +64,17 @@ __device__ inline void dma16(const void* gptr, uint32_t lds_base) {
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
 #define SPTS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 0xF) | (((n) >> 4) << 14))
 
-template <int EPI, bool DUAL_A>
+template <int EPI, int BK, bool DUAL_A>
 __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM, int nN, int total) {
+    using S = Slab<BK>;
     constexpr bool DUAL = (EPI == EPI_SILU_MUL);
+    constexpr int TILE_BYTES = S::TILE_BYTES;
     constexpr int NOPS = DUAL_A ? 3 : 2;          // operand tiles per stage (A, B[, A1])
-    constexpr int NST = DUAL_A ? 3 : 4;           // LDS ring stages
+    constexpr int NST = BK == 64 ? 2 : (DUAL_A ? 3 : 4);   // LDS ring stages
     constexpr int STAGE = TILE_BYTES * NOPS;
-    constexpr int PER = 4 * NOPS;                 // direct-to-LDS loads per wavefront per slab
+    constexpr int LPO = 64 / S::ROWS_PER_LOAD;    // loads per wavefront per operand tile
+    constexpr int PER = LPO * NOPS;               // direct-to-LDS loads per wavefront per slab
+    constexpr int KSTEPS = BK / 16;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     // ---- tile id: XCD-contiguous ranges, grouped raster
@@ -88,15 +98,15 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
     const int col0 = tn * OUT_COLS;
 
     // ---- direct-to-LDS assignment: wavefront w moves tile rows [64w, 64w+64) of every operand, 16
-    //      rows (1 KB) per load; lane -> (row = 64w + 16q + lane/4, LDS chunk = lane%4), and fetches
+    //      (BK=32) or 8 (BK=64) rows = 1 KB per load; lane -> (row, LDS chunk position), and fetches
     //      the global chunk that the swizzle maps to that LDS position.
-    const bf16_t* ga[4];
-    const bf16_t* ga1[DUAL_A ? 4 : 1];
-    const bf16_t* gb[4];
+    const bf16_t* ga[LPO];
+    const bf16_t* ga1[DUAL_A ? LPO : 1];
+    const bf16_t* gb[LPO];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int r = wave * 64 + q * 16 + (lane >> 2);
-        const int c = (lane & 3) ^ ((r >> 2) & 3);
+    for (int q = 0; q < LPO; ++q) {
+        const int r = wave * 64 + q * S::ROWS_PER_LOAD + lane / S::CPR;
+        const int c = (lane % S::CPR) ^ S::swz(r);
         int64_t grow = row0 + r;
         if (grow >= a.M) grow = a.M - 1;  // clamp: duplicates of the last row are never stored
         const int64_t srow = a.a_idx ? (int64_t)a.a_idx[grow] : grow;
@@ -109,7 +119,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
         gb[q] = bsrc + c * 8;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-    const uint32_t lds_w = lds0 + wave * 4096;   // this wavefront's 64 rows inside an operand tile
+    const uint32_t lds_w = lds0 + wave * (64 * S::ROW_BYTES);   // this wavefront's 64 rows inside an operand tile
     // load number u (0 .. PER-1) of slab kt_: operand u % NOPS, 16-row group u / NOPS
 #define SPTS_DMA_ONE(kt_, u)                                                                   \
     {                                                                                          \
@@ -140,12 +150,12 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
         const char* sB_ = sA_ + TILE_BYTES;                                                                  \
         const int c_ = (ks) * 2 + lh;                                                                        \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                      \
-            af[buf][i] = *reinterpret_cast<const bf16x8*>(sA_ + tile_off(wm * 128 + i * 32 + l32, c_));      \
+            af[buf][i] = *reinterpret_cast<const bf16x8*>(sA_ + S::off(wm * 128 + i * 32 + l32, c_));      \
             if (DUAL_A)                                                                                      \
-                af1[buf][i] = *reinterpret_cast<const bf16x8*>(sB_ + TILE_BYTES + tile_off(wm * 128 + i * 32 + l32, c_)); \
+                af1[buf][i] = *reinterpret_cast<const bf16x8*>(sB_ + TILE_BYTES + S::off(wm * 128 + i * 32 + l32, c_)); \
         }                                                                                                    \
         _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                        \
-            bfr[buf][j] = *reinterpret_cast<const bf16x8*>(sB_ + tile_off(brow(j) + l32, c_));               \
+            bfr[buf][j] = *reinterpret_cast<const bf16x8*>(sB_ + S::off(brow(j) + l32, c_));               \
     }
 #define SPTS_MFMA(buf, i, j)                                                                                 \
     {                                                                                                        \
@@ -161,18 +171,19 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
     {
         const int npre = nk < NST - 1 ? nk : NST - 1;
         for (int t = 0; t < npre; ++t) SPTS_DMA_SLAB(t)
-        if (npre == NST - 1) { SPTS_WAIT_VMCNT((NST - 2) * PER); } else { SPTS_WAIT_VMCNT(0); }
+        if (npre == NST - 1) { SPTS_WAIT_VMCNT((NST - 2) * PER); } else { SPTS_WAIT_VMCNT(0); }   // slab 0 landed
     }
     __syncthreads();
     SPTS_LOAD_FRAGS(0, 0, 0)
 
-    // One K slab = 32 MFMAs per wavefront.  Every memory instruction sits in the shadow of an MFMA
-    // (an MFMA occupies the matrix pipe for 32 cycles while the wavefront may issue other work):
-    //   MFMA  1- 8 (k-step 0): one fragment read of k-step 1 after each
-    //   MFMA  9-16 (k-step 0): one direct-to-LDS load of slab kt+NST-1 after each (ISSUE)
-    //   MFMA 17-20 (k-step 1), then wait for this wavefront's share of slab kt+1 and meet the
-    //               workgroup: slab kt+1 is published, stage kt%NST is free for the next iteration
-    //   MFMA 21-32 (k-step 1): one fragment read of slab kt+1, k-step 0, after each of the first 8
+    // One K slab = KSTEPS k-steps of 16 MFMAs per wavefront.  Every memory instruction sits in the
+    // shadow of an MFMA (an MFMA occupies the matrix pipe for 32 cycles while the wavefront may
+    // issue other work):
+    //   k-step s < KSTEPS-1: MFMA 1-8 are each followed by one fragment read of k-step s+1,
+    //                        MFMA 9-16 by one direct-to-LDS load of slab kt+NST-1 (ISSUE);
+    //   last k-step: 4 MFMAs, then wait for this wavefront's share of slab kt+1 and meet the
+    //                workgroup (slab kt+1 is published, stage kt%NST is free for the next iteration),
+    //                then 12 MFMAs, the first 8 each followed by a fragment read of slab kt+1.
     // ISSUE / NEXT are literal constants at every expansion.
     // 8 MFMA slots, one fragment read after each (two after the first NREADS-8 when 12 are due)
 #define SPTS_INTERLEAVE_READS                                                                                \
@@ -187,29 +198,34 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
 #define SPTS_SLAB(kt_, ISSUE, NEXT, WAITN)                                                                   \
     {                                                                                                        \
         const int st_ = (kt_) % NST;                                                                         \
-        SPTS_LOAD_FRAGS(1, st_, 1)                                                                           \
-        _Pragma("unroll") for (int m_ = 0; m_ < 8; ++m_) SPTS_MFMA(0, m_ / 4, m_ % 4)                        \
-        SPTS_INTERLEAVE_READS                                                                                \
-        __builtin_amdgcn_sched_barrier(0);                                                                   \
-        _Pragma("unroll") for (int m_ = 8; m_ < 16; ++m_) {                                                  \
-            SPTS_MFMA(0, m_ / 4, m_ % 4)                                                                     \
-            if (ISSUE) {                                                                                     \
-                __builtin_amdgcn_sched_barrier(0);                                                           \
-                SPTS_DMA_ONE((kt_) + NST - 1, m_ - 8)                                                        \
-                if (m_ < PER) SPTS_DMA_ONE((kt_) + NST - 1, (m_ < PER ? m_ : 0))                             \
-                __builtin_amdgcn_sched_barrier(0);                                                           \
+        _Pragma("unroll") for (int ks = 0; ks + 1 < KSTEPS; ++ks) {                                          \
+            const int fb = ks & 1;                                                                           \
+            SPTS_LOAD_FRAGS(fb ^ 1, st_, ks + 1)                                                             \
+            _Pragma("unroll") for (int m_ = 0; m_ < 8; ++m_) SPTS_MFMA(fb, m_ / 4, m_ % 4)                   \
+            SPTS_INTERLEAVE_READS                                                                            \
+            __builtin_amdgcn_sched_barrier(0);                                                               \
+            _Pragma("unroll") for (int m_ = 8; m_ < 16; ++m_) {                                              \
+                SPTS_MFMA(fb, m_ / 4, m_ % 4)                                                                \
+                if (ISSUE) {                                                                                 \
+                    const int u_ = ks * 8 + m_ - 8;                                                          \
+                    __builtin_amdgcn_sched_barrier(0);                                                       \
+                    if (u_ < PER) SPTS_DMA_ONE((kt_) + NST - 1, (u_ < PER ? u_ : 0))                         \
+                    if (KSTEPS == 2 && u_ + 8 < PER) SPTS_DMA_ONE((kt_) + NST - 1, (u_ + 8 < PER ? u_ + 8 : 0)) \
+                    __builtin_amdgcn_sched_barrier(0);                                                       \
+                }                                                                                            \
             }                                                                                                \
         }                                                                                                    \
-        _Pragma("unroll") for (int j = 0; j < 4; ++j) SPTS_MFMA(1, 0, j)                                     \
-        if (NEXT) { SPTS_WAIT_VMCNT(WAITN); }                                                                \
-        __syncthreads();                                                                                     \
-        if (NEXT) { SPTS_LOAD_FRAGS(0, ((kt_) + 1) % NST, 0) }                                               \
-        _Pragma("unroll") for (int i = 1; i < 4; ++i)                                                        \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) SPTS_MFMA(1, i, j)                                 \
-        if (NEXT) {                                                                                          \
-            SPTS_INTERLEAVE_READS                                                                            \
+        {                                                                                                    \
+            constexpr int fb = (KSTEPS - 1) & 1;                                                             \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) SPTS_MFMA(fb, 0, j)                                \
+            if (NEXT) { SPTS_WAIT_VMCNT(WAITN); }                                                            \
+            __syncthreads();                                                                                 \
+            if (NEXT) { SPTS_LOAD_FRAGS(fb ^ 1, ((kt_) + 1) % NST, 0) }                                      \
+            _Pragma("unroll") for (int i = 1; i < 4; ++i)                                                    \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j) SPTS_MFMA(fb, i, j)                            \
+            if (NEXT) { SPTS_INTERLEAVE_READS }                                                              \
+            __builtin_amdgcn_sched_barrier(0);                                                               \
         }                                                                                                    \
-        __builtin_amdgcn_sched_barrier(0);                                                                   \
     }
 
     int kt = 0;
@@ -361,7 +377,7 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     const bool dual = a.epi == EPI_SILU_MUL;
     const int ncols = dual ? 128 : 256;
     if (a.M <= 0 || a.N <= 0 || a.N % ncols != 0) return false;
-    if (a.K < BK || a.K % BK != 0) return false;
+    if (a.K < 32 || a.K % 32 != 0) return false;
     if (a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
     if (!al16(a.A) || !al16(a.B0) || (a.A1 && !al16(a.A1)) || (dual && !al16(a.B1))) return false;
     if (a.epi != EPI_SUMSQ) {
@@ -373,33 +389,33 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     return true;
 }
 
-template <int EPI, bool DUAL_A>
+template <int EPI, int BK, bool DUAL_A>
 static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     const int ncols = EPI == EPI_SILU_MUL ? 128 : 256;
     const int nM = (int)((a.M + BM - 1) / BM), nN = a.N / ncols;
     const int total = nM * nN;
     const int grid = (total + 7) / 8 * 8;
-    const size_t lds = (size_t)TILE_BYTES * (DUAL_A ? 3 * 3 : 2 * 4);
+    const size_t lds = (size_t)Slab<BK>::TILE_BYTES * (DUAL_A ? 3 : 2) * (BK == 64 ? 2 : (DUAL_A ? 3 : 4));
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<EPI, DUAL_A>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<EPI, BK, DUAL_A>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_mfma_kernel<EPI, DUAL_A><<<dim3(grid), dim3(NTHREADS), lds, s>>>(a, nM, nN, total);
+    gemm_mfma_kernel<EPI, BK, DUAL_A><<<dim3(grid), dim3(NTHREADS), lds, s>>>(a, nM, nN, total);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
     switch (a.epi) {
-        case EPI_STORE: return launch_t<EPI_STORE, false>(a, s);
-        case EPI_RESIDUAL: return launch_t<EPI_RESIDUAL, false>(a, s);
-        case EPI_SUMSQ: return launch_t<EPI_SUMSQ, false>(a, s);
-        case EPI_ROPE: return launch_t<EPI_ROPE, false>(a, s);
+        case EPI_STORE: return (a.K % 64 == 0 ? launch_t<EPI_STORE, 64, false>(a, s) : launch_t<EPI_STORE, 32, false>(a, s));
+        case EPI_RESIDUAL: return (a.K % 64 == 0 ? launch_t<EPI_RESIDUAL, 64, false>(a, s) : launch_t<EPI_RESIDUAL, 32, false>(a, s));
+        case EPI_SUMSQ: return (a.K % 64 == 0 ? launch_t<EPI_SUMSQ, 64, false>(a, s) : launch_t<EPI_SUMSQ, 32, false>(a, s));
+        case EPI_ROPE: return (a.K % 64 == 0 ? launch_t<EPI_ROPE, 64, false>(a, s) : launch_t<EPI_ROPE, 32, false>(a, s));
         case EPI_SILU_MUL:
-            if (a.A1) return launch_t<EPI_SILU_MUL, true>(a, s);
-            return launch_t<EPI_SILU_MUL, false>(a, s);
+            if (a.A1) return launch_t<EPI_SILU_MUL, 32, true>(a, s);
+            return a.K % 64 == 0 ? launch_t<EPI_SILU_MUL, 64, false>(a, s) : launch_t<EPI_SILU_MUL, 32, false>(a, s);
         default: return hipErrorInvalidValue;
     }
 }
