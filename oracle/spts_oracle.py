@@ -280,7 +280,9 @@ def layer_prefill(x: Array, pos: Array, w: Dict[str, Array], mdl: Model, cfg: La
     ``score_cast`` is applied to scores before a TopK takes its decision, so
     that the decision is taken in the precision the scores are stored in.
     ``force_idx_*`` replace the oracle's own selected sets (used by lock-step
-    parity after near-tie swaps have been counted).
+    parity after near-tie swaps have been counted): either an index array, or a
+    callable ``f(scores, own_idx) -> idx`` that sees the oracle's scores and its
+    own selection and returns the set to continue with.
     """
     x = rnd(np.array(x, dtype=np.float64, copy=True))
     pos = np.asarray(pos)
@@ -299,7 +301,11 @@ def layer_prefill(x: Array, pos: Array, w: Dict[str, Array], mdl: Model, cfg: La
         S = score_cast(probe_scores(qp, k_all, mdl))
         out.s_mha = S
         Ma = min(N, int(cfg.m_attn))
-        Ta = topk_select(S, Ma, cfg.protect_last) if force_idx_attn is None else np.asarray(force_idx_attn, dtype=np.int32)
+        Ta = topk_select(S, Ma, cfg.protect_last)
+        if callable(force_idx_attn):
+            Ta = np.asarray(force_idx_attn(S, Ta), dtype=np.int32)
+        elif force_idx_attn is not None:
+            Ta = np.asarray(force_idx_attn, dtype=np.int32)
     else:
         S = None
         Ta = np.arange(N, dtype=np.int32)
@@ -328,7 +334,11 @@ def layer_prefill(x: Array, pos: Array, w: Dict[str, Array], mdl: Model, cfg: La
         SF = score_cast(out.c_ffn * S)
         out.s_ffn = SF
         Mf = min(N, int(cfg.m_ffn))
-        Tf = topk_select(SF, Mf, cfg.protect_last) if force_idx_ffn is None else np.asarray(force_idx_ffn, dtype=np.int32)
+        Tf = topk_select(SF, Mf, cfg.protect_last)
+        if callable(force_idx_ffn):
+            Tf = np.asarray(force_idx_ffn(SF, Tf), dtype=np.int32)
+        elif force_idx_ffn is not None:
+            Tf = np.asarray(force_idx_ffn, dtype=np.int32)
     else:
         Tf = np.arange(N, dtype=np.int32)
     out.idx_ffn = Tf

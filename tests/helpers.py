@@ -63,23 +63,26 @@ def count_swaps(idx_gpu, idx_ref, scores_ref, band, protect_last=1):
 
 
 def lockstep_layer(gpu, x, pos, w, mdl, cfg, dtype):
-    """Lock-step parity of one layer: selections equal up to counted near-tie swaps (the oracle then
-    adopts the GPU's set), hidden states within tolerance.  Returns dict(swaps_attn, swaps_ffn, err)."""
+    """Lock-step parity of one layer in a single oracle pass: at each selection point the oracle's own
+    set is compared with the GPU's (near-tie swaps counted, anything else fails), then the oracle
+    adopts the GPU's set so that the hidden states stay like-for-like.
+    Returns dict(swaps_attn, swaps_ffn, err, ref)."""
     rnd = rnd_for(dtype)
     tol = TOL[dtype]
-    ref = orc.layer_prefill(x, pos, w, mdl, cfg, rnd=rnd, score_cast=orc.f32_round)
-    sw_a = sw_f = 0
+    swaps = {"attn": 0, "ffn": 0}
+
+    def adopt(which, gpu_idx):
+        def hook(scores, own):
+            swaps[which] = count_swaps(gpu_idx, own, scores, tol["score"], cfg.protect_last)
+            return gpu_idx
+        return hook
+
+    kw = {}
+    if cfg.skip:
+        kw = dict(force_idx_attn=adopt("attn", gpu["idx_attn"]), force_idx_ffn=adopt("ffn", gpu["idx_ffn"]))
+    ref = orc.layer_prefill(x, pos, w, mdl, cfg, rnd=rnd, score_cast=orc.f32_round, **kw)
     if cfg.skip:
         assert score_rel_err(gpu["s_mha"], ref.s_mha) <= tol["score"], "S^MHA out of tolerance"
-        sw_a = count_swaps(gpu["idx_attn"], ref.idx_attn, ref.s_mha, tol["score"], cfg.protect_last)
-        if sw_a:
-            ref = orc.layer_prefill(x, pos, w, mdl, cfg, rnd=rnd, score_cast=orc.f32_round,
-                                    force_idx_attn=gpu["idx_attn"])
-        if min(x.shape[0], cfg.m_ffn) > 0:
-            sw_f = count_swaps(gpu["idx_ffn"], ref.idx_ffn, ref.s_ffn, tol["score"], cfg.protect_last)
-            if sw_f:
-                ref = orc.layer_prefill(x, pos, w, mdl, cfg, rnd=rnd, score_cast=orc.f32_round,
-                                        force_idx_attn=gpu["idx_attn"], force_idx_ffn=gpu["idx_ffn"])
     err = row_rel_err(gpu["x"], ref.x)
     assert err <= tol["hidden"], f"hidden states: row-relative error {err}"
-    return dict(swaps_attn=sw_a, swaps_ffn=sw_f, err=err, ref=ref)
+    return dict(swaps_attn=swaps["attn"], swaps_ffn=swaps["ffn"], err=err, ref=ref)

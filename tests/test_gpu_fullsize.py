@@ -1,0 +1,186 @@
+"""GPU parity at the full sizes of the benchmark's configurations, in the launch configuration that
+bench.py times (matrix-core kernels, 8B-shaped bf16 layer).
+
+* c1 (N = 8192): the whole layer against the oracle, lock-step.
+* c2 (N = 32768): the first layer of the stack on sampled rows the oracle computes one by one from the
+  GPU's own layer input, plus properties that hold at any size (selection = oracle TopK of the
+  GPU's scores, untouched rows, compaction maps, score sum).
+* c3 (N = 131072): properties of the probe / TopK / skip rule at long length.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import spts_oracle as orc
+from paper_2601_13155_amd import runtime, synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+_CACHE = {}
+
+
+def llama_layer():
+    if "w" not in _CACHE:
+        wl = synth.WORKLOADS["c1"]
+        _CACHE["w"] = synth.make_layer(wl.seed, 0, wl.shape, wl.r)
+        _CACHE["dw"] = runtime.upload_layer(_CACHE["w"], wl.shape, wl.r)
+    return _CACHE["w"], _CACHE["dw"]
+
+
+def ctx_for(max_tokens):
+    key = ("ctx", max_tokens)
+    if key not in _CACHE:
+        shape = synth.LLAMA8B
+        _CACHE[key] = runtime.make_context(shape, max_tokens, 128, 256, shape.Dff)
+    return _CACHE[key]
+
+
+def test_c1_full_layer_lockstep():
+    import torch
+    wl = synth.WORKLOADS["c1"]
+    shape = wl.shape
+    w, dw = llama_layer()
+    ctx = ctx_for(32768)
+    assert ctx.uses_mfma()
+    x = synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype)
+    pos = synth.positions(wl.N)
+    item = wl.layer_plan()[0]
+    gpu = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=wl.probe_len, m_attn=item["m_attn"],
+                            m_ffn=item["m_ffn"], protect_last=1)
+    cfg = orc.LayerCfg(1, wl.probe_len, item["m_attn"], item["m_ffn"], 1, 0)
+    res = H.lockstep_layer(gpu, x, pos, w, H.oracle_model(shape), cfg, shape.dtype)
+    print(f"c1: swaps attn={res['swaps_attn']} ffn={res['swaps_ffn']} hidden err={res['err']:.3e}")
+    assert res["swaps_attn"] <= item["m_attn"] // 50 and res["swaps_ffn"] <= item["m_ffn"] // 50
+    assert np.array_equal(gpu["idx_attn"], orc.topk_select(gpu["s_mha"], item["m_attn"], 1))
+    torch.cuda.empty_cache()
+
+
+def _sampled_layer_check(x_in, pos, w, shape, cfg, gpu, n_samples, seed):
+    """Oracle on sampled rows of one skip layer (kv_mode 0), from the GPU's own layer input.
+    Checks S^MHA everywhere, the selections (swap-counted), and the output hidden state of sampled
+    rows (active in attention and/or FFN) one by one."""
+    mdl = H.oracle_model(shape)
+    rnd = orc.bf16_round
+    tol = H.TOL["bf16"]
+    N = x_in.shape[0]
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    xn = rnd(orc.rmsnorm(x_in, w["gamma1"], mdl.rms_eps))
+    K = orc.project_keys(xn, pos, w["Wk"], mdl, rnd)
+    P = cfg.probe_len
+    qp = orc.project_queries(xn[N - P:], pos[N - P:], w["Wq"], mdl, rnd)
+    S = orc.f32_round(orc.probe_scores(qp, K, mdl))
+    assert H.score_rel_err(gpu["s_mha"], S) <= tol["score"]
+    Ma = min(N, cfg.m_attn)
+    swaps_a = H.count_swaps(gpu["idx_attn"], orc.topk_select(S, Ma, 1), S, tol["score"], 1)
+    Ta = gpu["idx_attn"]
+    rng = np.random.default_rng(seed)
+    # sampled active rows (always include the first, the last and a few early ones)
+    pick = np.unique(np.concatenate([[0, 1, Ma - 1], rng.choice(Ma, size=n_samples, replace=False)]))
+    Vh = rnd((xn[Ta] @ f64(w["Wv"])).reshape(Ma, mdl.Hkv, mdl.d))
+    Kh = K[Ta]
+    x_new = {}
+    for i in pick:
+        row = int(Ta[i])
+        q = orc.project_queries(xn[row:row + 1], pos[row:row + 1], w["Wq"], mdl, rnd)
+        att = rnd(orc.causal_attention(q, Kh[: i + 1], Vh[: i + 1], pos[row:row + 1], pos[Ta[: i + 1]], mdl))
+        o = att.reshape(1, -1) @ f64(w["Wo"])
+        x_new[row] = rnd(f64(x_in[row]) + o[0])
+    # FFN half on sampled rows: rows whose post-attention state is known = sampled active rows, and
+    # inactive rows (unchanged by attention)
+    inactive = np.setdiff1d(np.arange(N), Ta)
+    extra = rng.choice(inactive, size=min(n_samples, inactive.size), replace=False)
+    rows = np.concatenate([np.array(sorted(x_new.keys()), dtype=np.int64), extra])
+    x_mid = np.stack([x_new[r] if r in x_new else f64(x_in[r]) for r in rows])
+    xn2 = rnd(orc.rmsnorm(x_mid, w["gamma2"], mdl.rms_eps))
+    in_f = np.isin(rows, gpu["idx_ffn"])
+    upd = orc.ffn(xn2[in_f], w["Wgate"], w["Wup"], w["Wdown"], rnd)
+    x_out = x_mid.copy()
+    x_out[in_f] = rnd(x_mid[in_f] + upd)
+    err = H.row_rel_err(gpu["x"][rows], x_out)
+    assert err <= tol["hidden"], f"sampled rows: {err}"
+    assert in_f.any() and (~in_f).any()
+    return swaps_a, err, len(rows)
+
+
+def test_c2_first_layer_sampled_and_stack_properties():
+    import torch
+    wl = synth.WORKLOADS["c2"]
+    shape = wl.shape
+    w, dw = llama_layer()
+    ctx = ctx_for(32768)
+    plan = wl.layer_plan()
+    x0 = synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype)
+    pos0 = synth.positions(wl.N)
+    # stack of 10 layers (crosses the first stage end after layer 8) with the bench's runner
+    n_layers = 10
+    runner = runtime.StackRunner(ctx, shape, [dw] * n_layers, plan[:n_layers], wl.probe_len, keep_trace=True)
+    xo, po, n_final = runner.run(runtime.to_device(x0, shape.dtype), torch.from_numpy(pos0).cuda())
+    torch.cuda.synchronize()
+    assert n_final == 22937
+    for li, (tr, item) in enumerate(zip(runner.trace, plan[:n_layers])):
+        N = tr["N"]
+        s = tr["s_mha"].cpu().numpy()
+        ia = tr["idx_attn"][: item["m_attn"]].cpu().numpy()
+        iff = tr["idx_ffn"][: item["m_ffn"]].cpu().numpy()
+        assert abs(float(s.astype(np.float64).sum()) - 1.0) < 2e-3 and s.min() >= 0.0
+        # level A: the selection is the oracle's TopK of the scores the GPU stored
+        assert np.array_equal(ia, orc.topk_select(s, item["m_attn"], 1)), li
+        assert np.all(np.diff(iff) > 0) and iff[-1] == N - 1 and iff.size == item["m_ffn"]
+        # Eq. (skip): rows outside both active sets are bitwise untouched
+        touched = torch.zeros(N, dtype=torch.bool, device="cuda")
+        touched[tr["idx_attn"][: item["m_attn"]].long()] = True
+        touched[tr["idx_ffn"][: item["m_ffn"]].long()] = True
+        assert torch.equal(tr["x_in"][~touched], tr["x_out"][~touched]), li
+        changed = (tr["x_in"][touched] != tr["x_out"][touched]).any(dim=1).float().mean().item()
+        assert changed > 0.99, (li, changed)
+        if item["N_next"] is not None:
+            n2o = tr["map_new2old"].cpu().numpy()
+            assert np.array_equal(n2o, orc.topk_select(s, item["N_next"], 1))
+            nxt = runner.trace[li + 1]
+            assert torch.equal(nxt["x_in"], tr["x_out"][tr["map_new2old"].long()])          # bitwise row copies
+            assert torch.equal(nxt["pos_in"], tr["pos_in"][tr["map_new2old"].long()])
+    assert bool(torch.isfinite(xo.float()).all())
+    # first layer: sampled rows against the oracle
+    tr = runner.trace[0]
+    item = plan[0]
+    gpu = dict(x=runtime.to_host(tr["x_out"]).astype(np.float64), s_mha=tr["s_mha"].cpu().numpy(),
+               idx_attn=tr["idx_attn"][: item["m_attn"]].cpu().numpy(), idx_ffn=tr["idx_ffn"][: item["m_ffn"]].cpu().numpy())
+    cfg = orc.LayerCfg(1, wl.probe_len, item["m_attn"], item["m_ffn"], 1, 0)
+    swaps, err, n_rows = _sampled_layer_check(x0, pos0, w, shape, cfg, gpu, n_samples=24, seed=7)
+    print(f"c2 layer 1: attention-set swaps={swaps} sampled rows={n_rows} err={err:.3e}")
+    assert swaps <= item["m_attn"] // 50
+    del runner
+    torch.cuda.empty_cache()
+
+
+def test_c3_long_sequence_properties():
+    import torch
+    wl = synth.WORKLOADS["c3"]
+    shape = wl.shape
+    w, dw = llama_layer()
+    ctx = ctx_for(131072)
+    item = wl.layer_plan()[0]
+    N = wl.N
+    x = synth.hidden_states(wl.seed, N, shape.D, shape.dtype)
+    pos = synth.positions(N)
+    gpu = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=wl.probe_len, m_attn=item["m_attn"],
+                            m_ffn=item["m_ffn"], protect_last=1, want_kv=True)
+    s = gpu["s_mha"]
+    assert abs(float(s.astype(np.float64).sum()) - 1.0) < 2e-3 and s.min() >= 0.0
+    assert np.array_equal(gpu["idx_attn"], orc.topk_select(s, item["m_attn"], 1))
+    assert gpu["idx_ffn"].size == item["m_ffn"] and np.all(np.diff(gpu["idx_ffn"]) > 0) and gpu["idx_ffn"][-1] == N - 1
+    touched = np.zeros(N, bool); touched[gpu["idx_attn"]] = True; touched[gpu["idx_ffn"]] = True
+    assert np.array_equal(gpu["x"][~touched], x[~touched].astype(np.float64))
+    assert np.all(np.isfinite(gpu["x"]))
+    # cached keys of sampled active rows against the oracle (rotary at positions up to 131071)
+    mdl = H.oracle_model(shape)
+    rng = np.random.default_rng(3)
+    sel = np.unique(np.concatenate([[0, item["m_attn"] - 1], rng.choice(item["m_attn"], 64, replace=False)]))
+    rows = gpu["idx_attn"][sel]
+    xn = orc.bf16_round(orc.rmsnorm(x[rows], w["gamma1"], mdl.rms_eps))
+    k_ref = orc.project_keys(xn, pos[rows], w["Wk"], mdl, orc.bf16_round)
+    assert H.row_rel_err(gpu["k_cache"][sel].reshape(len(sel), -1), k_ref.reshape(len(sel), -1)) <= H.TOL["bf16"]["hidden"]
+    assert np.array_equal(gpu["pos_cache"], pos[gpu["idx_attn"]]) and gpu["kv_count"] == item["m_attn"]
+    torch.cuda.empty_cache()
