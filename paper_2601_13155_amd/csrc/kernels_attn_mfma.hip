@@ -41,9 +41,7 @@ template <int D> struct AttnLds {
     __device__ static inline int voff(int row, int c8) { return row * (BKV * 2) + ((c8 ^ ((row >> 1) & 15)) << 3); }
 };
 
-__device__ inline uint32_t pk2(float a, float b) {
-    return (uint32_t)f32_to_bf16(a).v | ((uint32_t)f32_to_bf16(b).v << 16);
-}
+__device__ inline uint32_t pk2(float a, float b) { return cvt_pk_bf16(a, b); }
 
 template <int D, int QB>
 __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int total, float scale_log2e) {
@@ -172,28 +170,25 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
                         s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], s[kb][qb], 0, 0, 0);
                 }
             }
-            // ---- scale, mask (only on tiles that are not entirely visible to this wavefront)
+            // ---- mask (only on tiles that are not entirely visible to this wavefront); logits stay
+            //      unscaled: the softmax scale is folded into the exponent's FMA
             const bool need_mask = klast > qmin_w;
+            if (need_mask) {
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    int4 kp = make_int4(0, 0, 0, 0);
-                    if (need_mask) kp = *reinterpret_cast<const int4*>(sP + kb * 32 + 8 * q4 + 4 * lh);
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const int4 kp = *reinterpret_cast<const int4*>(sP + kb * 32 + 8 * q4 + 4 * lh);
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) {
-                        float v0 = s[kb][qb][4 * q4] * scale_log2e, v1 = s[kb][qb][4 * q4 + 1] * scale_log2e;
-                        float v2 = s[kb][qb][4 * q4 + 2] * scale_log2e, v3 = s[kb][qb][4 * q4 + 3] * scale_log2e;
-                        if (need_mask) {
+                        for (int qb = 0; qb < QB; ++qb) {
                             const int qp = qpos_l[qb];
-                            if (kp.x > qp) v0 = -INFINITY;
-                            if (kp.y > qp) v1 = -INFINITY;
-                            if (kp.z > qp) v2 = -INFINITY;
-                            if (kp.w > qp) v3 = -INFINITY;
+                            if (kp.x > qp) s[kb][qb][4 * q4] = -INFINITY;
+                            if (kp.y > qp) s[kb][qb][4 * q4 + 1] = -INFINITY;
+                            if (kp.z > qp) s[kb][qb][4 * q4 + 2] = -INFINITY;
+                            if (kp.w > qp) s[kb][qb][4 * q4 + 3] = -INFINITY;
                         }
-                        s[kb][qb][4 * q4] = v0; s[kb][qb][4 * q4 + 1] = v1; s[kb][qb][4 * q4 + 2] = v2; s[kb][qb][4 * q4 + 3] = v3;
                     }
-                }
+            }
             // ---- online softmax per query (lane column; lanes l and l^32 share a query)
             bf16x8 pf[QB][4];
 #pragma unroll
@@ -204,9 +199,10 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
 #pragma unroll
                     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][qb][r]);
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[qb], mx);
+                const float m_old = m_run[qb];
+                const float m_new = fmaxf(m_old, mx);
                 const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-                const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_use);
+                const float msc = m_use * scale_log2e;
                 m_run[qb] = m_new;
                 float sum = 0.f;
 #pragma unroll
@@ -215,15 +211,23 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
                     for (int hf = 0; hf < 2; ++hf) {
                         float p[8];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) { p[e] = __builtin_amdgcn_exp2f(s[kb][qb][8 * hf + e] - m_use); sum += p[e]; }
+                        for (int e = 0; e < 8; ++e) {
+                            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][qb][8 * hf + e], scale_log2e, -msc));
+                            sum += p[e];
+                        }
                         u32x4 packed = {pk2(p[0], p[1]), pk2(p[2], p[3]), pk2(p[4], p[5]), pk2(p[6], p[7])};
                         pf[qb][2 * kb + hf] = __builtin_bit_cast(bf16x8, packed);
                     }
-                l_run[qb] = l_run[qb] * alpha + sum;
+                // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
+                if (__ballot(m_new != m_old) != 0) {
+                    const float alpha = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
+                    l_run[qb] *= alpha;
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+                    for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) o[db][qb][r] *= alpha;
+                        for (int r = 0; r < 16; ++r) o[db][qb][r] *= alpha;
+                }
+                l_run[qb] += sum;
             }
             // ---- O^T += V^T P^T
 #pragma unroll

@@ -51,9 +51,7 @@ template <int BK> struct Slab {
     __device__ static inline int off(int row, int c) { return row * ROW_BYTES + ((c ^ swz(row)) << 4); }
 };
 
-__device__ inline uint32_t pack_bf16x2(float a, float b) {
-    return (uint32_t)f32_to_bf16(a).v | ((uint32_t)f32_to_bf16(b).v << 16);
-}
+__device__ inline uint32_t pack_bf16x2(float a, float b) { return cvt_pk_bf16(a, b); }
 __device__ inline float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
 // One direct-to-LDS load: every lane fetches 16 bytes from its own global address; the wavefront's

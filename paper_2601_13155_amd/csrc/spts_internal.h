@@ -28,6 +28,13 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
 }
 __device__ inline float to_f32(float v) { return v; }
 __device__ inline float to_f32(bf16_t v) { return bf16_to_f32(v); }
+// two floats -> packed bf16x2 with the hardware converter (v_cvt_pk_bf16_f32, round to nearest even)
+typedef __bf16 hw_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float hw_f32x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t cvt_pk_bf16(float a, float b) {
+    hw_f32x2 f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, hw_bf16x2));
+}
 template <typename T> __device__ inline T from_f32(float v);
 template <> __device__ inline float from_f32<float>(float v) { return v; }
 template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
