@@ -9,15 +9,19 @@
 //  * S^T = K Q^T is computed instead of S: the MFMA result then has one query per lane column, so
 //    the row maximum / row sum of the online softmax are in-lane reductions plus one exchange with
 //    lane^32, and the probabilities already sit in the operand layout of the second product.
-//  * O^T += V^T P^T takes V^T tiles (keys contiguous) as the A operand: the value projection writes
-//    that transposed copy, so no transposition happens here.  The key index permutation implied by
-//    the accumulator layout is applied to the V^T fragment addresses (a sum over keys is order-free).
-//  * One workgroup = 4 wavefronts x (QB*32) queries of one head; K / V^T tiles of 64 keys are shared
-//    through LDS (XOR-swizzled, conflict-free fragment reads), global->register prefetch of the next
-//    tile overlaps the MFMAs, two LDS stages, one barrier per tile.
-//  * Key tiles beyond the last visible position are never visited (binary search on kpos); tiles
-//    that are entirely visible skip the mask; a wavefront whose queries see nothing of a tile skips
-//    its MFMAs.
+//  * O^T += V^T P^T takes V^T tiles (keys contiguous) as the A operand.  The value projection
+//    writes that transposed copy with the keys of every 16-group in the order the probability
+//    fragments come out of the matrix core (vt_key_slot), so a value fragment is one 16-byte read.
+//  * One workgroup = 4 wavefronts x 64 queries of one head.  K / V^T tiles of 64 keys travel global
+//    memory -> LDS directly (global_load_lds_dwordx4, swizzle applied on the global side) into a ring
+//    of 4 stages: tile t+3 is in flight while tile t is consumed; one barrier per tile.
+//  * Software pipeline inside the wavefront at 32-key block granularity: the QK^T MFMAs of block
+//    b+1 are issued in the same region as the softmax arithmetic of block b (independent
+//    registers), then the PV MFMAs of block b.
+//    The softmax scale is folded into the exponent's FMA, probabilities are packed with the hardware
+//    bf16 converter, the accumulator is rescaled only when some lane's running maximum moved.
+//  * Key tiles beyond the last visible position are never visited; tiles that are entirely visible
+//    to a wavefront skip the mask; a wavefront whose queries see nothing of a tile skips its work.
 //  * Work ids are laid out (kv head, query tile descending, head in group) and split contiguously
 //    over the 8 XCDs: the heads that share a KV head run on the same XCD's L2, longest tiles first.
 #include "spts_internal.h"
@@ -25,20 +29,26 @@
 namespace spts {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BKV = 64;
+constexpr int ATT_NST = 4;
 
 template <int D> struct AttnLds {
     static constexpr int K_BYTES = BKV * D * 2;
     static constexpr int V_BYTES = D * BKV * 2;
-    static constexpr int STAGE = K_BYTES + V_BYTES + BKV * 4;
+    static constexpr int STAGE = K_BYTES + V_BYTES;
     static constexpr int CPRK = D / 8;            // 16-byte chunks per K row
     static constexpr int RPK = 256 / (2 * D);     // K rows per 256 bytes
-    __device__ static inline int koff(int row, int c) { return row * (2 * D) + ((c ^ ((row / RPK) % CPRK)) << 4); }
-    // V^T tile: row = value column, 16 chunks of 8 bytes (4 keys)
-    __device__ static inline int voff(int row, int c8) { return row * (BKV * 2) + ((c8 ^ ((row >> 1) & 15)) << 3); }
+    static constexpr int K_ROWS_PER_LOAD = 64 / CPRK;
+    static constexpr int K_LOADS = (BKV / 4) / K_ROWS_PER_LOAD;   // per wavefront (16 K rows each)
+    static constexpr int V_LOADS = (D / 4) / 8;                   // per wavefront (D/4 V^T rows each, 8 rows per load)
+    static constexpr int PER = K_LOADS + V_LOADS;
+    __device__ static inline int kswz(int row) { return (row / RPK) % CPRK; }
+    __device__ static inline int koff(int row, int c) { return row * (2 * D) + ((c ^ kswz(row)) << 4); }
+    // V^T tile: row = value column (128 bytes = 8 chunks of 16 bytes = 8 keys each)
+    __device__ static inline int vswz(int row) { return (row >> 1) & 7; }
+    __device__ static inline int voff(int row, int c) { return row * (BKV * 2) + ((c ^ vswz(row)) << 4); }
 };
 
 __device__ inline uint32_t pk2(float a, float b) { return cvt_pk_bf16(a, b); }
@@ -49,6 +59,7 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
     constexpr int BQ = 4 * QB * 32;
     constexpr int KS = D / 16;   // k-steps of the QK^T product
     constexpr int DB = D / 32;   // 32-column blocks of the output
+    constexpr int PER = L::PER;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int per = (total + 7) / 8;
@@ -60,24 +71,32 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
     const int g = id / (grp * nQ);
     const int h = g * grp + hg;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lh = lane >> 5;
     const int64_t q0 = (int64_t)qtile * BQ;
     const int64_t q0w = q0 + wave * (QB * 32);
 
-    // ---- visible key range of this workgroup / wavefront
+    // ---- visible key ranges.  Positions are strictly ascending, so "keys visible to position p" is a
+    //      prefix; its length is an upper bound search (or the index itself when both sets coincide).
+    const bool same_set = a.qpos == a.kpos;
+    auto visible_count = [&](int64_t qi) -> int64_t {
+        if (same_set) return qi + 1;
+        const int p = a.qpos[qi];
+        int64_t lo = 0, hi = a.Mk;
+        while (lo < hi) {
+            int64_t mid = (lo + hi) >> 1;
+            if (a.kpos[mid] <= p) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+    };
     const int64_t q_last = (q0 + BQ < a.Mq ? q0 + BQ : a.Mq) - 1;
-    const int qpos_max = a.qpos[q_last];
-    int64_t lo = 0, hi = a.Mk;  // first index with kpos > qpos_max
-    while (lo < hi) {
-        int64_t mid = (lo + hi) >> 1;
-        if (a.kpos[mid] <= qpos_max) lo = mid + 1; else hi = mid;
-    }
-    const int n_tiles = (int)((lo + BKV - 1) / BKV);
+    const int n_tiles = (int)((visible_count(q_last) + BKV - 1) / BKV);            // workgroup
     const int64_t qw_first = q0w < a.Mq ? q0w : a.Mq - 1;
-    const int64_t qw_last = (q0w + QB * 32 < a.Mq ? q0w + QB * 32 : a.Mq) - 1;
-    const int qmin_w = a.qpos[qw_first];
-    const int qmax_w = a.qpos[qw_last > qw_first ? qw_last : qw_first];
+    int64_t qw_last = (q0w + QB * 32 < a.Mq ? q0w + QB * 32 : a.Mq) - 1;
+    if (qw_last < qw_first) qw_last = qw_first;
+    const int nbw = (int)((visible_count(qw_last) + 31) / 32);     // 32-key blocks this wavefront works on
+    const int nbfull = (int)(visible_count(qw_first) / 32);        // blocks it sees entirely (no mask)
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[query = l32][16*ks + 8*lh .. +7]
     bf16x8 qf[QB][KS];
@@ -93,44 +112,37 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
         for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
     }
 
-    // ---- global -> register staging of one K tile and one V^T tile
-    constexpr int KCH = BKV * L::CPRK / 256;   // 16-byte chunks per thread (K)
-    constexpr int VCH = D * 8 / 256;           // 16-byte chunks per thread (V^T)
-    const int kc = tid % L::CPRK, kr = tid / L::CPRK;
-    const int vc = tid % 8, vr = tid / 8;
+    // ---- direct-to-LDS tile loads.  Wavefront w moves K rows [16w, 16w+16) and V^T rows
+    //      [D/4*w, D/4*(w+1)); a lane fetches the chunk that the swizzle maps to its LDS position.
     const bf16_t* Kg = (const bf16_t*)a.k;
     const bf16_t* Vt = (const bf16_t*)a.vt;
-    u32x4 rk[KCH], rv[VCH];
-    int rpos = 0;
-    auto load_tile = [&](int t) {
-        const int64_t key0 = (int64_t)t * BKV;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    int krow[L::K_LOADS], kchunk[L::K_LOADS];
+    const bf16_t* vptr[L::V_LOADS];
 #pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            int64_t key = key0 + kr + (256 / L::CPRK) * i;
-            if (key >= a.Mk) key = a.Mk - 1;
-            rk[i] = *reinterpret_cast<const u32x4*>(Kg + (key * a.Hkv + g) * (int64_t)D + kc * 8);
-        }
+    for (int q = 0; q < L::K_LOADS; ++q) {
+        krow[q] = wave * 16 + q * L::K_ROWS_PER_LOAD + lane / L::CPRK;
+        kchunk[q] = (lane % L::CPRK) ^ L::kswz(krow[q]);
+    }
 #pragma unroll
-        for (int i = 0; i < VCH; ++i) {
-            int row = vr + 32 * i;
-            rv[i] = *reinterpret_cast<const u32x4*>(Vt + ((int64_t)g * D + row) * a.ldvt + key0 + vc * 8);
-        }
-        if (tid < BKV) { int64_t key = key0 + tid; rpos = key < a.Mk ? a.kpos[key] : 0x7fffffff; }
-    };
-    auto store_tile = [&](int stage) {
-        char* sK = smem + stage * L::STAGE;
-        char* sV = sK + L::K_BYTES;
-        int* sP = reinterpret_cast<int*>(sV + L::V_BYTES);
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) *reinterpret_cast<u32x4*>(sK + L::koff(kr + (256 / L::CPRK) * i, kc)) = rk[i];
-#pragma unroll
-        for (int i = 0; i < VCH; ++i) {
-            int row = vr + 32 * i;
-            *reinterpret_cast<u32x2*>(sV + L::voff(row, 2 * vc)) = u32x2{rv[i].x, rv[i].y};
-            *reinterpret_cast<u32x2*>(sV + L::voff(row, 2 * vc + 1)) = u32x2{rv[i].z, rv[i].w};
-        }
-        if (tid < BKV) sP[tid] = rpos;
-    };
+    for (int q = 0; q < L::V_LOADS; ++q) {
+        const int row = wave * (D / 4) + q * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ L::vswz(row);
+        vptr[q] = Vt + ((int64_t)g * D + row) * a.ldvt + c * 8;
+    }
+#define SPTS_ATT_DMA(t_)                                                                                   \
+    {                                                                                                      \
+        const int64_t key0_ = (int64_t)(t_) * BKV;                                                         \
+        const uint32_t sb_ = lds0 + ((t_) % ATT_NST) * L::STAGE;                                           \
+        _Pragma("unroll") for (int q = 0; q < L::K_LOADS; ++q) {                                           \
+            int64_t key_ = key0_ + krow[q];                                                                \
+            if (key_ >= a.Mk) key_ = a.Mk - 1;                                                             \
+            dma16(Kg + (key_ * a.Hkv + g) * (int64_t)D + kchunk[q] * 8,                                    \
+                  sb_ + wave * (16 * 2 * D) + q * 1024);                                                   \
+        }                                                                                                  \
+        _Pragma("unroll") for (int q = 0; q < L::V_LOADS; ++q)                                             \
+            dma16(vptr[q] + key0_, sb_ + L::K_BYTES + wave * (D / 4 * BKV * 2) + q * 1024);                \
+    }
 
     f32x16 o[DB][QB];
 #pragma unroll
@@ -142,110 +154,109 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
     float m_run[QB], l_run[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+    f32x16 sa[QB], sb[QB];   // S^T of two consecutive 32-key blocks (one being produced, one in the softmax)
+    bf16x8 pf[QB][2];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    if (n_tiles > 0) { load_tile(0); store_tile(0); }
+    // S^T block: 32 keys (block kb_ of the tile in `stage_`) x QB*32 queries
+#define SPTS_ATT_QK(SDST, stage_, kb_)                                                                     \
+    {                                                                                                      \
+        const char* sK_ = smem + (stage_) * L::STAGE;                                                      \
+        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                                \
+            const bf16x8 kf_ = *reinterpret_cast<const bf16x8*>(sK_ + L::koff((kb_) * 32 + l32, 2 * ks + lh)); \
+            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                              \
+                SDST[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf_, qf[qb][ks], ks == 0 ? zero16 : SDST[qb], 0, 0, 0); \
+        }                                                                                                  \
+    }
+    // mask of a block that this wavefront does not see entirely (diagonal blocks, tail block)
+#define SPTS_ATT_MASK(SSRC, b_)                                                                            \
+    {                                                                                                      \
+        const int64_t key0_ = (int64_t)(b_) * 32;                                                          \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                   \
+            const int64_t key_ = key0_ + 8 * (r >> 2) + 4 * lh + (r & 3);                                  \
+            const int kpl_ = a.kpos[key_ < a.Mk ? key_ : a.Mk - 1];   /* unconditional, in-bounds load */  \
+            const int kp_ = key_ < a.Mk ? kpl_ : 0x7fffffff;                                               \
+            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                              \
+                SSRC[qb][r] = kp_ > qpos_l[qb] ? -INFINITY : SSRC[qb][r];                                  \
+        }                                                                                                  \
+    }
+    // online softmax of one S^T block: probabilities -> pf (bf16 fragments), new running maximum
+#define SPTS_ATT_SOFTMAX(SSRC)                                                                             \
+    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                                    \
+        float mx_ = -INFINITY;                                                                             \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) mx_ = fmaxf(mx_, SSRC[qb][r]);                      \
+        mx_ = fmaxf(mx_, __shfl_xor(mx_, 32));                                                             \
+        m_old[qb] = m_run[qb];                                                                             \
+        const float m_new_ = fmaxf(m_old[qb], mx_);                                                        \
+        m_use[qb] = (m_new_ == -INFINITY) ? 0.f : m_new_;                                                  \
+        const float msc_ = m_use[qb] * scale_log2e;                                                        \
+        m_run[qb] = m_new_;                                                                                \
+        float sum_ = 0.f;                                                                                  \
+        _Pragma("unroll") for (int hf = 0; hf < 2; ++hf) {                                                 \
+            float p_[8];                                                                                   \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                                \
+                p_[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(SSRC[qb][8 * hf + e], scale_log2e, -msc_));  \
+                sum_ += p_[e];                                                                             \
+            }                                                                                              \
+            const u32x4 pk_ = {pk2(p_[0], p_[1]), pk2(p_[2], p_[3]), pk2(p_[4], p_[5]), pk2(p_[6], p_[7])}; \
+            pf[qb][hf] = __builtin_bit_cast(bf16x8, pk_);                                                  \
+        }                                                                                                  \
+        psum[qb] = sum_;                                                                                   \
+    }
+    // rescale (only when some lane's maximum moved) and accumulate the row sums
+#define SPTS_ATT_RESCALE                                                                                   \
+    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                                    \
+        if (__ballot(m_run[qb] != m_old[qb]) != 0) {                                                       \
+            const float alpha_ = __builtin_amdgcn_exp2f((m_old[qb] - m_use[qb]) * scale_log2e);            \
+            l_run[qb] *= alpha_;                                                                           \
+            _Pragma("unroll") for (int db = 0; db < DB; ++db)                                              \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) o[db][qb][r] *= alpha_;                     \
+        }                                                                                                  \
+        l_run[qb] += psum[qb];                                                                             \
+    }
+    // O^T += V^T P^T for the 32 keys of block kb_ of the V^T tile in `stage_`
+#define SPTS_ATT_PV(stage_, kb_)                                                                           \
+    {                                                                                                      \
+        const char* sV_ = smem + (stage_) * L::STAGE + L::K_BYTES;                                         \
+        _Pragma("unroll") for (int hf = 0; hf < 2; ++hf)                                                   \
+            _Pragma("unroll") for (int db = 0; db < DB; ++db) {                                            \
+                const bf16x8 vf_ = *reinterpret_cast<const bf16x8*>(sV_ + L::voff(db * 32 + l32, 2 * (2 * (kb_) + hf) + lh)); \
+                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                          \
+                    o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pf[qb][hf], o[db][qb], 0, 0, 0); \
+            }                                                                                              \
+    }
+    // One 32-key block b_ = 2*tile + kb: (QK of block b_+1 || softmax of block b_), then PV of block b_.
+#define SPTS_ATT_BLOCK(b_, SC, SN)                                                                         \
+    if ((b_) < nbw) {                                                                                      \
+        float m_old[QB], m_use[QB], psum[QB];                                                              \
+        if ((b_) >= nbfull) SPTS_ATT_MASK(SC, b_)                                                          \
+        if ((b_) + 1 < nbw) {                                                                              \
+            SPTS_ATT_QK(SN, (((b_) + 1) >> 1) % ATT_NST, ((b_) + 1) & 1)                                   \
+            SPTS_ATT_SOFTMAX(SC)                                                                           \
+        } else {                                                                                           \
+            SPTS_ATT_SOFTMAX(SC)                                                                           \
+        }                                                                                                  \
+        SPTS_ATT_RESCALE                                                                                   \
+        SPTS_ATT_PV(((b_) >> 1) % ATT_NST, (b_) & 1)                                                       \
+    }
+
+    // ---- prologue: tiles 0..2 in flight, tile 0 landed, S^T of block 0
+    if (n_tiles > 0) SPTS_ATT_DMA(0)
+    if (n_tiles > 1) SPTS_ATT_DMA(1)
+    if (n_tiles > 2) SPTS_ATT_DMA(2)
+    if (n_tiles > 2) { SPTS_WAIT_VMCNT(2 * PER); } else if (n_tiles > 1) { SPTS_WAIT_VMCNT(PER); } else { SPTS_WAIT_VMCNT(0); }
     __syncthreads();
+    if (nbw > 0) SPTS_ATT_QK(sa, 0, 0)
     for (int t = 0; t < n_tiles; ++t) {
-        if (t + 1 < n_tiles) load_tile(t + 1);
-        const char* sK = smem + (t & 1) * L::STAGE;
-        const char* sV = sK + L::K_BYTES;
-        const int* sP = reinterpret_cast<const int*>(sV + L::V_BYTES);
-        const int kfirst = sP[0], klast = sP[BKV - 1];
-        if (kfirst <= qmax_w) {   // wavefront-uniform: some query of this wavefront sees this tile
-            // ---- S^T = K Q^T   (2 key blocks x QB query blocks)
-            f32x16 s[2][QB];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) s[kb][qb][r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + L::koff(kb * 32 + l32, 2 * ks + lh));
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-                        s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], s[kb][qb], 0, 0, 0);
-                }
-            }
-            // ---- mask (only on tiles that are not entirely visible to this wavefront); logits stay
-            //      unscaled: the softmax scale is folded into the exponent's FMA
-            const bool need_mask = klast > qmin_w;
-            if (need_mask) {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const int4 kp = *reinterpret_cast<const int4*>(sP + kb * 32 + 8 * q4 + 4 * lh);
-#pragma unroll
-                        for (int qb = 0; qb < QB; ++qb) {
-                            const int qp = qpos_l[qb];
-                            if (kp.x > qp) s[kb][qb][4 * q4] = -INFINITY;
-                            if (kp.y > qp) s[kb][qb][4 * q4 + 1] = -INFINITY;
-                            if (kp.z > qp) s[kb][qb][4 * q4 + 2] = -INFINITY;
-                            if (kp.w > qp) s[kb][qb][4 * q4 + 3] = -INFINITY;
-                        }
-                    }
-            }
-            // ---- online softmax per query (lane column; lanes l and l^32 share a query)
-            bf16x8 pf[QB][4];
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                float mx = -INFINITY;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][qb][r]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_old = m_run[qb];
-                const float m_new = fmaxf(m_old, mx);
-                const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-                const float msc = m_use * scale_log2e;
-                m_run[qb] = m_new;
-                float sum = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf) {
-                        float p[8];
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][qb][8 * hf + e], scale_log2e, -msc));
-                            sum += p[e];
-                        }
-                        u32x4 packed = {pk2(p[0], p[1]), pk2(p[2], p[3]), pk2(p[4], p[5]), pk2(p[6], p[7])};
-                        pf[qb][2 * kb + hf] = __builtin_bit_cast(bf16x8, packed);
-                    }
-                // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
-                if (__ballot(m_new != m_old) != 0) {
-                    const float alpha = __builtin_amdgcn_exp2f((m_old - m_use) * scale_log2e);
-                    l_run[qb] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) o[db][qb][r] *= alpha;
-                }
-                l_run[qb] += sum;
-            }
-            // ---- O^T += V^T P^T
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    u32x2 v0 = *reinterpret_cast<const u32x2*>(sV + L::voff(db * 32 + l32, 4 * st + lh));
-                    u32x2 v1 = *reinterpret_cast<const u32x2*>(sV + L::voff(db * 32 + l32, 4 * st + 2 + lh));
-                    u32x4 vv = {v0.x, v0.y, v1.x, v1.y};
-                    bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-                        o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][st], o[db][qb], 0, 0, 0);
-                }
-            }
+        // publish tile t+1 (its blocks are fetched / multiplied during this step), then refill the ring:
+        // stage (t+3)%4 held tile t-1, which nobody reads any more after this barrier
+        if (t + 1 < n_tiles) {
+            if (t + 2 < n_tiles) { SPTS_WAIT_VMCNT(PER); } else { SPTS_WAIT_VMCNT(0); }
         }
-        if (t + 1 < n_tiles) store_tile((t + 1) & 1);
         __syncthreads();
+        if (t + 3 < n_tiles) SPTS_ATT_DMA(t + 3)
+        SPTS_ATT_BLOCK(2 * t, sa, sb)
+        SPTS_ATT_BLOCK(2 * t + 1, sb, sa)
     }
 
     // ---- normalise and store: lane holds 4 consecutive value columns of its query per r/4
@@ -261,10 +272,9 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
-                    uint2 w;
-                    w.x = pk2(o[db][qb][4 * q4] * inv, o[db][qb][4 * q4 + 1] * inv);
-                    w.y = pk2(o[db][qb][4 * q4 + 2] * inv, o[db][qb][4 * q4 + 3] * inv);
-                    *reinterpret_cast<uint2*>(orow + db * 32 + 8 * q4 + 4 * lh) = w;
+                    u32x2 w = {pk2(o[db][qb][4 * q4] * inv, o[db][qb][4 * q4 + 1] * inv),
+                               pk2(o[db][qb][4 * q4 + 2] * inv, o[db][qb][4 * q4 + 3] * inv)};
+                    *reinterpret_cast<u32x2*>(orow + db * 32 + 8 * q4 + 4 * lh) = w;
                 }
         }
     }
@@ -284,7 +294,7 @@ static hipError_t launch_attn_t(const AttnArgs& a, hipStream_t s) {
     const int nQ = (int)((a.Mq + BQ - 1) / BQ);
     const int total = nQ * a.H;
     const int grid = (total + 7) / 8 * 8;
-    const size_t lds = (size_t)AttnLds<D>::STAGE * 2;
+    const size_t lds = (size_t)AttnLds<D>::STAGE * ATT_NST;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<D, QB>),

@@ -252,7 +252,7 @@ hipError_t launch_finish_ffn_scores(const float* part, int nparts, const float* 
 }
 
 // ---------------------------------------------------------------- transpose with zero padding
-// v [M, C] -> vt [C, ldvt]; 32x32 tiles through LDS so both sides are coalesced.
+// v [M, C] -> vt [C, ldvt] (keys in vt_key_slot order); 32x32 tiles through LDS so both sides are coalesced.
 template <typename T>
 __global__ void __launch_bounds__(256) transpose_pad_kernel(const T* __restrict__ v, T* __restrict__ vt, int64_t M, int C, int64_t ldvt) {
     __shared__ T tile[32][33];
@@ -268,7 +268,7 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(const T* __restrict_
     __syncthreads();
     for (int r = ty; r < 32; r += 8) {
         int c = c0 + r; int64_t i = i0 + tx;
-        if (c < C && i < ldvt) vt[(int64_t)c * ldvt + i] = tile[tx][r];
+        if (c < C && i < ldvt) vt[(int64_t)c * ldvt + vt_key_slot(i)] = tile[tx][r];
     }
 }
 hipError_t launch_transpose_pad(const void* v, void* vt, int64_t M, int C, int64_t ldvt, bool bf16, hipStream_t s) {

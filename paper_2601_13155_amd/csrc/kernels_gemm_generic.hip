@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(256) gemm_generic_kernel(GemmArgs a) {
             } else {
                 T o = from_f32<T>(v);
                 ((T*)a.C)[crow * a.ldc + gcol] = o;
-                if (a.Ct) ((T*)a.Ct)[(int64_t)gcol * a.ldct + grow] = o;
+                if (a.Ct) ((T*)a.Ct)[(int64_t)gcol * a.ldct + vt_key_slot(grow)] = o;
             }
         }
     }

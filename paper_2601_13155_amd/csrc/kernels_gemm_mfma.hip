@@ -54,14 +54,6 @@ template <int BK> struct Slab {
 __device__ inline uint32_t pack_bf16x2(float a, float b) { return cvt_pk_bf16(a, b); }
 __device__ inline float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
-// One direct-to-LDS load: every lane fetches 16 bytes from its own global address; the wavefront's
-// 1 KB lands at lds_base + 16 * lane.  lds_base must be wavefront-uniform.
-__device__ inline void dma16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\t" ::"v"(gptr), "s"(lds_base) : "memory");
-}
-// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
-#define SPTS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 0xF) | (((n) >> 4) << 14))
-
 template <int EPI, int BK, bool DUAL_A>
 __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM, int nN, int total) {
     using S = Slab<BK>;
@@ -271,7 +263,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
                         bf16_t* ct = (bf16_t*)a.Ct;
                         const uint16_t e[4] = {(uint16_t)(o.x & 0xffff), (uint16_t)(o.x >> 16), (uint16_t)(o.y & 0xffff), (uint16_t)(o.y >> 16)};
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) ct[(int64_t)(cb + 8 * q + t) * a.ldct + grow].v = e[t];
+                        for (int t = 0; t < 4; ++t) ct[(int64_t)(cb + 8 * q + t) * a.ldct + vt_key_slot(grow)].v = e[t];
                     }
                 }
             }

@@ -39,6 +39,21 @@ template <typename T> __device__ inline T from_f32(float v);
 template <> __device__ inline float from_f32<float>(float v) { return v; }
 template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
 
+// One direct-to-LDS load (gfx950 global_load_lds_dwordx4): every lane fetches 16 bytes from its own
+// global address; the wavefront's 1 KB lands at lds_base + 16 * lane.  lds_base must be
+// wavefront-uniform.  The compiler does not see these loads: the issuing code counts them itself
+// (SPTS_WAIT_VMCNT) and publishes the data with a workgroup barrier.
+__device__ inline void dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\t" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+// s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
+#define SPTS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 0xF) | (((n) >> 4) << 14))
+
+// Key order of the transposed value copy V^T [Hkv*d, ld]: inside every aligned group of 16 keys the
+// two middle quads are swapped (0-3, 8-11, 4-7, 12-15), which is the order the attention kernel's
+// probability fragments come out of the matrix core, so a value fragment is one 16-byte read.
+__host__ __device__ inline int64_t vt_key_slot(int64_t key) { return (key & ~(int64_t)12) | ((key & 4) << 1) | ((key & 8) >> 1); }
+
 // ------------------------------------------------------------------ GEMM (C = A * B^T)
 enum GemmEpilogue : int {
     EPI_STORE = 0,      // C[row, col] = acc          (T, or fp32 when c_is_f32)
@@ -85,7 +100,7 @@ hipError_t launch_scatter_iota(const int32_t* idx, int32_t* old2new, int64_t n, 
 // c = sqrt(sum_j part[n, j]); s_ffn = c * (s_mha ? s_mha[n] : 1)
 hipError_t launch_finish_ffn_scores(const float* part, int nparts, const float* s_mha, float* c_ffn, float* s_ffn,
                                     int64_t N, hipStream_t s);
-// vt[c, i] = v[i, c]  (v [M, C] -> vt [C, ldvt]); columns i in [M, ldvt) are zero-filled
+// vt[c, vt_key_slot(i)] = v[i, c]  (v [M, C] -> vt [C, ldvt]); keys i in [M, ldvt) are zero-filled
 hipError_t launch_transpose_pad(const void* v, void* vt, int64_t M, int C, int64_t ldvt, bool bf16, hipStream_t s);
 
 // ------------------------------------------------------------------ TopK
