@@ -12,9 +12,12 @@
 //  * O^T += V^T P^T takes V^T tiles (keys contiguous) as the A operand.  The value projection
 //    writes that transposed copy with the keys of every 16-group in the order the probability
 //    fragments come out of the matrix core (vt_key_slot), so a value fragment is one 16-byte read.
-//  * One workgroup = 4 wavefronts x 64 queries of one head.  K / V^T tiles of 64 keys travel global
-//    memory -> LDS directly (global_load_lds_dwordx4, swizzle applied on the global side) into a ring
-//    of 4 stages: tile t+3 is in flight while tile t is consumed; one barrier per tile.
+//  * One workgroup = 8 wavefronts x 32 queries of one head (256 queries): two wavefronts per SIMD, so
+//    one wavefront's softmax arithmetic and LDS latencies hide behind the other's MFMAs (4 wavefronts
+//    x 64 queries halve the LDS traffic but leave every LDS round trip exposed: 540 vs 820 TFLOP/s).
+//    K / V^T tiles of 64 keys travel global memory -> LDS directly (global_load_lds_dwordx4, swizzle
+//    applied on the global side) into a ring of 4 stages: tile t+3 is in flight while tile t is
+//    consumed; one barrier per tile.
 //  * Software pipeline inside the wavefront at 32-key block granularity: the QK^T MFMAs of block
 //    b+1 are issued in the same region as the softmax arithmetic of block b (independent
 //    registers), then the PV MFMAs of block b.
@@ -41,9 +44,9 @@ template <int D> struct AttnLds {
     static constexpr int CPRK = D / 8;            // 16-byte chunks per K row
     static constexpr int RPK = 256 / (2 * D);     // K rows per 256 bytes
     static constexpr int K_ROWS_PER_LOAD = 64 / CPRK;
-    static constexpr int K_LOADS = (BKV / 4) / K_ROWS_PER_LOAD;   // per wavefront (16 K rows each)
-    static constexpr int V_LOADS = (D / 4) / 8;                   // per wavefront (D/4 V^T rows each, 8 rows per load)
-    static constexpr int PER = K_LOADS + V_LOADS;
+    // per wavefront, NW wavefronts: BKV/NW K rows and D/NW V^T rows each (8 V^T rows per load)
+    template <int NW> static constexpr int k_loads() { return (BKV / NW) / K_ROWS_PER_LOAD; }
+    template <int NW> static constexpr int v_loads() { return (D / NW) / 8; }
     __device__ static inline int kswz(int row) { return (row / RPK) % CPRK; }
     __device__ static inline int koff(int row, int c) { return row * (2 * D) + ((c ^ kswz(row)) << 4); }
     // V^T tile: row = value column (128 bytes = 8 chunks of 16 bytes = 8 keys each)
@@ -53,13 +56,15 @@ template <int D> struct AttnLds {
 
 __device__ inline uint32_t pk2(float a, float b) { return cvt_pk_bf16(a, b); }
 
-template <int D, int QB>
-__global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int total, float scale_log2e) {
+template <int D, int QB, int NW>
+__global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, int total, float scale_log2e) {
     using L = AttnLds<D>;
-    constexpr int BQ = 4 * QB * 32;
+    constexpr int BQ = NW * QB * 32;
     constexpr int KS = D / 16;   // k-steps of the QK^T product
     constexpr int DB = D / 32;   // 32-column blocks of the output
-    constexpr int PER = L::PER;
+    constexpr int K_LOADS = L::template k_loads<NW>();
+    constexpr int V_LOADS = L::template v_loads<NW>();
+    constexpr int PER = K_LOADS + V_LOADS;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int per = (total + 7) / 8;
@@ -112,21 +117,21 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
         for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
     }
 
-    // ---- direct-to-LDS tile loads.  Wavefront w moves K rows [16w, 16w+16) and V^T rows
-    //      [D/4*w, D/4*(w+1)); a lane fetches the chunk that the swizzle maps to its LDS position.
+    // ---- direct-to-LDS tile loads.  Wavefront w moves K rows [64/NW*w, 64/NW*(w+1)) and V^T rows
+    //      [D/NW*w, D/NW*(w+1)); a lane fetches the chunk that the swizzle maps to its LDS position.
     const bf16_t* Kg = (const bf16_t*)a.k;
     const bf16_t* Vt = (const bf16_t*)a.vt;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-    int krow[L::K_LOADS], kchunk[L::K_LOADS];
-    const bf16_t* vptr[L::V_LOADS];
+    int krow[K_LOADS], kchunk[K_LOADS];
+    const bf16_t* vptr[V_LOADS];
 #pragma unroll
-    for (int q = 0; q < L::K_LOADS; ++q) {
-        krow[q] = wave * 16 + q * L::K_ROWS_PER_LOAD + lane / L::CPRK;
+    for (int q = 0; q < K_LOADS; ++q) {
+        krow[q] = wave * (BKV / NW) + q * L::K_ROWS_PER_LOAD + lane / L::CPRK;
         kchunk[q] = (lane % L::CPRK) ^ L::kswz(krow[q]);
     }
 #pragma unroll
-    for (int q = 0; q < L::V_LOADS; ++q) {
-        const int row = wave * (D / 4) + q * 8 + (lane >> 3);
+    for (int q = 0; q < V_LOADS; ++q) {
+        const int row = wave * (D / NW) + q * 8 + (lane >> 3);
         const int c = (lane & 7) ^ L::vswz(row);
         vptr[q] = Vt + ((int64_t)g * D + row) * a.ldvt + c * 8;
     }
@@ -134,14 +139,14 @@ __global__ void __launch_bounds__(256) attn_mfma_kernel(AttnArgs a, int nQ, int 
     {                                                                                                      \
         const int64_t key0_ = (int64_t)(t_) * BKV;                                                         \
         const uint32_t sb_ = lds0 + ((t_) % ATT_NST) * L::STAGE;                                           \
-        _Pragma("unroll") for (int q = 0; q < L::K_LOADS; ++q) {                                           \
+        _Pragma("unroll") for (int q = 0; q < K_LOADS; ++q) {                                              \
             int64_t key_ = key0_ + krow[q];                                                                \
             if (key_ >= a.Mk) key_ = a.Mk - 1;                                                             \
             dma16(Kg + (key_ * a.Hkv + g) * (int64_t)D + kchunk[q] * 8,                                    \
-                  sb_ + wave * (16 * 2 * D) + q * 1024);                                                   \
+                  sb_ + wave * (BKV / NW * 2 * D) + q * 1024);                                             \
         }                                                                                                  \
-        _Pragma("unroll") for (int q = 0; q < L::V_LOADS; ++q)                                             \
-            dma16(vptr[q] + key0_, sb_ + L::K_BYTES + wave * (D / 4 * BKV * 2) + q * 1024);                \
+        _Pragma("unroll") for (int q = 0; q < V_LOADS; ++q)                                                \
+            dma16(vptr[q] + key0_, sb_ + L::K_BYTES + wave * (D / NW * BKV * 2) + q * 1024);               \
     }
 
     f32x16 o[DB][QB];
@@ -288,28 +293,28 @@ bool attention_mfma_supported(const AttnArgs& a) {
     return al(a.q) && al(a.k) && al(a.vt) && al(a.out);
 }
 
-template <int D, int QB>
+template <int D, int QB, int NW>
 static hipError_t launch_attn_t(const AttnArgs& a, hipStream_t s) {
-    constexpr int BQ = 4 * QB * 32;
+    constexpr int BQ = NW * QB * 32;
     const int nQ = (int)((a.Mq + BQ - 1) / BQ);
     const int total = nQ * a.H;
     const int grid = (total + 7) / 8 * 8;
     const size_t lds = (size_t)AttnLds<D>::STAGE * ATT_NST;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<D, QB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<D, QB, NW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-    attn_mfma_kernel<D, QB><<<dim3(grid), dim3(256), lds, s>>>(a, nQ, total, scale_log2e);
+    attn_mfma_kernel<D, QB, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nQ, total, scale_log2e);
     return hipGetLastError();
 }
 
 hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t s) {
-    if (a.d == 128) return launch_attn_t<128, 2>(a, s);
-    return launch_attn_t<64, 2>(a, s);
+    if (a.d == 128) return launch_attn_t<128, 1, 8>(a, s);
+    return launch_attn_t<64, 1, 8>(a, s);
 }
 
 }  // namespace spts
