@@ -36,7 +36,7 @@ namespace spts {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 256, BN = 256, NTHREADS = 256;
+constexpr int BM = 256, BN = 256;
 
 // K slab geometry.  A tile row holds BK bf16 = CPR 16-byte chunks; chunk c of row `row` is stored at
 // chunk position c ^ ((row / RP) % CPR) (RP = rows per 256 bytes), so the 16 lanes of a b128
@@ -54,15 +54,21 @@ template <int BK> struct Slab {
 __device__ inline uint32_t pack_bf16x2(float a, float b) { return cvt_pk_bf16(a, b); }
 __device__ inline float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
-template <int EPI, int BK, bool DUAL_A>
-__global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM, int nN, int total) {
+// NW wavefronts per workgroup: 4 (2x2 wavefronts of 128x128, one per SIMD) or 8 (4x2 wavefronts of
+// 64x128, two per SIMD: a wavefront's memory instructions, waits and barriers hide behind the other's
+// MFMAs at the price of 50 % more LDS fragment traffic).
+template <int EPI, int BK, bool DUAL_A, int NW>
+__global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, int nN, int total) {
     using S = Slab<BK>;
+    constexpr int MI = 16 / NW;                   // 32-row blocks per wavefront (4 or 2)
+    constexpr int WROWS = 32 * MI;                // output rows per wavefront
+    constexpr int LROWS = 256 / NW;               // operand tile rows each wavefront loads
     constexpr bool DUAL = (EPI == EPI_SILU_MUL);
     constexpr int TILE_BYTES = S::TILE_BYTES;
     constexpr int NOPS = DUAL_A ? 3 : 2;          // operand tiles per stage (A, B[, A1])
     constexpr int NST = BK == 64 ? 2 : (DUAL_A ? 3 : 4);   // LDS ring stages
     constexpr int STAGE = TILE_BYTES * NOPS;
-    constexpr int LPO = 64 / S::ROWS_PER_LOAD;    // loads per wavefront per operand tile
+    constexpr int LPO = LROWS / S::ROWS_PER_LOAD; // loads per wavefront per operand tile
     constexpr int PER = LPO * NOPS;               // direct-to-LDS loads per wavefront per slab
     constexpr int KSTEPS = BK / 16;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -95,7 +101,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
     const bf16_t* gb[LPO];
 #pragma unroll
     for (int q = 0; q < LPO; ++q) {
-        const int r = wave * 64 + q * S::ROWS_PER_LOAD + lane / S::CPR;
+        const int r = wave * LROWS + q * S::ROWS_PER_LOAD + lane / S::CPR;
         const int c = (lane % S::CPR) ^ S::swz(r);
         int64_t grow = row0 + r;
         if (grow >= a.M) grow = a.M - 1;  // clamp: duplicates of the last row are never stored
@@ -109,7 +115,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
         gb[q] = bsrc + c * 8;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-    const uint32_t lds_w = lds0 + wave * (64 * S::ROW_BYTES);   // this wavefront's 64 rows inside an operand tile
+    const uint32_t lds_w = lds0 + wave * (LROWS * S::ROW_BYTES);   // this wavefront's rows inside an operand tile
     // load number u (0 .. PER-1) of slab kt_: operand u % NOPS, 16-row group u / NOPS
 #define SPTS_DMA_ONE(kt_, u)                                                                   \
     {                                                                                          \
@@ -122,9 +128,9 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
 #define SPTS_DMA_SLAB(kt_)                                                                     \
     { _Pragma("unroll") for (int u_ = 0; u_ < PER; ++u_) SPTS_DMA_ONE(kt_, u_) }
 
-    f32x16 acc[4][4];
+    f32x16 acc[MI][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -133,16 +139,16 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
     // B tile row of this wavefront's N block j
     auto brow = [&](int j) { return DUAL ? (j >> 1) * 128 + wn * 64 + (j & 1) * 32 : wn * 128 + j * 32; };
 
-    bf16x8 af[2][4], bfr[2][4], af1[2][DUAL_A ? 4 : 1];
+    bf16x8 af[2][MI], bfr[2][4], af1[2][DUAL_A ? MI : 1];
 #define SPTS_LOAD_FRAGS(buf, stage, ks)                                                                      \
     {                                                                                                        \
         const char* sA_ = smem + (stage) * STAGE;                                                            \
         const char* sB_ = sA_ + TILE_BYTES;                                                                  \
         const int c_ = (ks) * 2 + lh;                                                                        \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                      \
-            af[buf][i] = *reinterpret_cast<const bf16x8*>(sA_ + S::off(wm * 128 + i * 32 + l32, c_));      \
+        _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                     \
+            af[buf][i] = *reinterpret_cast<const bf16x8*>(sA_ + S::off(wm * WROWS + i * 32 + l32, c_));    \
             if (DUAL_A)                                                                                      \
-                af1[buf][i] = *reinterpret_cast<const bf16x8*>(sB_ + TILE_BYTES + S::off(wm * 128 + i * 32 + l32, c_)); \
+                af1[buf][i] = *reinterpret_cast<const bf16x8*>(sB_ + TILE_BYTES + S::off(wm * WROWS + i * 32 + l32, c_)); \
         }                                                                                                    \
         _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                        \
             bfr[buf][j] = *reinterpret_cast<const bf16x8*>(sB_ + S::off(brow(j) + l32, c_));               \
@@ -154,7 +160,9 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
         else                                                                                                 \
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][j], af[buf][i], acc[i][j], 0, 0, 0);  \
     }
-    constexpr int NREADS = DUAL_A ? 12 : 8;   // fragment reads per k-step
+    constexpr int NREADS = (DUAL_A ? 2 * MI : MI) + 4;   // fragment reads per k-step
+    constexpr int NM = 4 * MI;                            // MFMAs per k-step
+    constexpr int HS = NM / 2;                            // MFMA slots per half k-step
 
     const int nk = a.K / BK;
     // ---- prologue: slabs 0 .. NST-2 are put in flight, slab 0 must have landed
@@ -175,13 +183,13 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
     //                workgroup (slab kt+1 is published, stage kt%NST is free for the next iteration),
     //                then 12 MFMAs, the first 8 each followed by a fragment read of slab kt+1.
     // ISSUE / NEXT are literal constants at every expansion.
-    // 8 MFMA slots, one fragment read after each (two after the first NREADS-8 when 12 are due)
+    // HS MFMA slots, one fragment read after each (two after the first NREADS-HS of them)
 #define SPTS_INTERLEAVE_READS                                                                                \
-    _Pragma("unroll") for (int g_ = 0; g_ < NREADS - 8; ++g_) {                                              \
+    _Pragma("unroll") for (int g_ = 0; g_ < NREADS - HS; ++g_) {                                             \
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                   \
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                                   \
     }                                                                                                        \
-    _Pragma("unroll") for (int g_ = NREADS - 8; g_ < 8; ++g_) {                                              \
+    _Pragma("unroll") for (int g_ = NREADS - HS; g_ < HS; ++g_) {                                            \
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                   \
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                   \
     }
@@ -191,16 +199,16 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
         _Pragma("unroll") for (int ks = 0; ks + 1 < KSTEPS; ++ks) {                                          \
             const int fb = ks & 1;                                                                           \
             SPTS_LOAD_FRAGS(fb ^ 1, st_, ks + 1)                                                             \
-            _Pragma("unroll") for (int m_ = 0; m_ < 8; ++m_) SPTS_MFMA(fb, m_ / 4, m_ % 4)                   \
+            _Pragma("unroll") for (int m_ = 0; m_ < HS; ++m_) SPTS_MFMA(fb, m_ / 4, m_ % 4)                  \
             SPTS_INTERLEAVE_READS                                                                            \
             __builtin_amdgcn_sched_barrier(0);                                                               \
-            _Pragma("unroll") for (int m_ = 8; m_ < 16; ++m_) {                                              \
+            _Pragma("unroll") for (int m_ = HS; m_ < NM; ++m_) {                                             \
                 SPTS_MFMA(fb, m_ / 4, m_ % 4)                                                                \
                 if (ISSUE) {                                                                                 \
-                    const int u_ = ks * 8 + m_ - 8;                                                          \
+                    const int u_ = ks * HS + m_ - HS;                                                        \
                     __builtin_amdgcn_sched_barrier(0);                                                       \
                     if (u_ < PER) SPTS_DMA_ONE((kt_) + NST - 1, (u_ < PER ? u_ : 0))                         \
-                    if (KSTEPS == 2 && u_ + 8 < PER) SPTS_DMA_ONE((kt_) + NST - 1, (u_ + 8 < PER ? u_ + 8 : 0)) \
+                    if (KSTEPS == 2 && u_ + HS < PER) SPTS_DMA_ONE((kt_) + NST - 1, (u_ + HS < PER ? u_ + HS : 0)) \
                     __builtin_amdgcn_sched_barrier(0);                                                       \
                 }                                                                                            \
             }                                                                                                \
@@ -211,9 +219,14 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
             if (NEXT) { SPTS_WAIT_VMCNT(WAITN); }                                                            \
             __syncthreads();                                                                                 \
             if (NEXT) { SPTS_LOAD_FRAGS(fb ^ 1, ((kt_) + 1) % NST, 0) }                                      \
-            _Pragma("unroll") for (int i = 1; i < 4; ++i)                                                    \
+            _Pragma("unroll") for (int i = 1; i < MI; ++i)                                                   \
                 _Pragma("unroll") for (int j = 0; j < 4; ++j) SPTS_MFMA(fb, i, j)                            \
-            if (NEXT) { SPTS_INTERLEAVE_READS }                                                              \
+            if (NEXT) {                                                                                      \
+                _Pragma("unroll") for (int g_ = 0; g_ < NM - 4; ++g_) {                                      \
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                       \
+                    __builtin_amdgcn_sched_group_barrier(0x100, (NREADS + NM - 5) / (NM - 4), 0);            \
+                }                                                                                            \
+            }                                                                                                \
             __builtin_amdgcn_sched_barrier(0);                                                               \
         }                                                                                                    \
     }
@@ -226,26 +239,26 @@ __global__ void __launch_bounds__(NTHREADS) gemm_mfma_kernel(GemmArgs a, int nM,
     for (; kt + 1 < nk; ++kt) SPTS_SLAB(kt, false, true, 0)
     SPTS_SLAB(kt, false, false, 0)
 
-    // ---- epilogue.  acc[i][j][r]: row = row0 + wm*128 + i*32 + l32,
+    // ---- epilogue.  acc[i][j][r]: row = row0 + wm*WROWS + i*32 + l32,
     //      column (inside N block j) = 8*(r/4) + 4*lh + r%4  -> 4 consecutive columns per r/4.
     bf16_t* Cb = (bf16_t*)a.C;
     if (EPI == EPI_SUMSQ) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < MI; ++i) {
             float s = 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s += acc[i][j][r] * acc[i][j][r];
             s += __shfl_xor(s, 32);
-            int64_t grow = row0 + wm * 128 + i * 32 + l32;
+            int64_t grow = row0 + wm * WROWS + i * 32 + l32;
             if (lh == 0 && grow < a.M) a.part[grow * a.part_ld + tn * 2 + wn] = s;
         }
         return;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int64_t grow = row0 + wm * 128 + i * 32 + l32;
+    for (int i = 0; i < MI; ++i) {
+        const int64_t grow = row0 + wm * WROWS + i * 32 + l32;
         const bool rok = grow < a.M;
         const int64_t growc = rok ? grow : a.M - 1;
         const int64_t crow = a.c_idx ? (int64_t)a.c_idx[growc] : growc;
@@ -379,7 +392,7 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     return true;
 }
 
-template <int EPI, int BK, bool DUAL_A>
+template <int EPI, int BK, bool DUAL_A, int NW>
 static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     const int ncols = EPI == EPI_SILU_MUL ? 128 : 256;
     const int nM = (int)((a.M + BM - 1) / BM), nN = a.N / ncols;
@@ -388,24 +401,30 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     const size_t lds = (size_t)Slab<BK>::TILE_BYTES * (DUAL_A ? 3 : 2) * (BK == 64 ? 2 : (DUAL_A ? 3 : 4));
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<EPI, BK, DUAL_A>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<EPI, BK, DUAL_A, NW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_mfma_kernel<EPI, BK, DUAL_A><<<dim3(grid), dim3(NTHREADS), lds, s>>>(a, nM, nN, total);
+    gemm_mfma_kernel<EPI, BK, DUAL_A, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nM, nN, total);
     return hipGetLastError();
 }
 
+// wavefronts per workgroup used by launch_gemm_mfma (4 or 8)
+#ifndef SPTS_GEMM_NW
+#define SPTS_GEMM_NW 8
+#endif
+
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
+    constexpr int NW = SPTS_GEMM_NW;
     switch (a.epi) {
-        case EPI_STORE: return (a.K % 64 == 0 ? launch_t<EPI_STORE, 64, false>(a, s) : launch_t<EPI_STORE, 32, false>(a, s));
-        case EPI_RESIDUAL: return (a.K % 64 == 0 ? launch_t<EPI_RESIDUAL, 64, false>(a, s) : launch_t<EPI_RESIDUAL, 32, false>(a, s));
-        case EPI_SUMSQ: return (a.K % 64 == 0 ? launch_t<EPI_SUMSQ, 64, false>(a, s) : launch_t<EPI_SUMSQ, 32, false>(a, s));
-        case EPI_ROPE: return (a.K % 64 == 0 ? launch_t<EPI_ROPE, 64, false>(a, s) : launch_t<EPI_ROPE, 32, false>(a, s));
+        case EPI_STORE: return (a.K % 64 == 0 ? launch_t<EPI_STORE, 64, false, NW>(a, s) : launch_t<EPI_STORE, 32, false, NW>(a, s));
+        case EPI_RESIDUAL: return (a.K % 64 == 0 ? launch_t<EPI_RESIDUAL, 64, false, NW>(a, s) : launch_t<EPI_RESIDUAL, 32, false, NW>(a, s));
+        case EPI_SUMSQ: return (a.K % 64 == 0 ? launch_t<EPI_SUMSQ, 64, false, NW>(a, s) : launch_t<EPI_SUMSQ, 32, false, NW>(a, s));
+        case EPI_ROPE: return (a.K % 64 == 0 ? launch_t<EPI_ROPE, 64, false, NW>(a, s) : launch_t<EPI_ROPE, 32, false, NW>(a, s));
         case EPI_SILU_MUL:
-            if (a.A1) return launch_t<EPI_SILU_MUL, 32, true>(a, s);
-            return a.K % 64 == 0 ? launch_t<EPI_SILU_MUL, 64, false>(a, s) : launch_t<EPI_SILU_MUL, 32, false>(a, s);
+            if (a.A1) return launch_t<EPI_SILU_MUL, 32, true, NW>(a, s);
+            return a.K % 64 == 0 ? launch_t<EPI_SILU_MUL, 64, false, NW>(a, s) : launch_t<EPI_SILU_MUL, 32, false, NW>(a, s);
         default: return hipErrorInvalidValue;
     }
 }
