@@ -155,6 +155,44 @@ def test_c2_first_layer_sampled_and_stack_properties():
     torch.cuda.empty_cache()
 
 
+def test_c4_qwen_shaped_layer_lockstep():
+    """Config c4's layer shape (D = 3584, 28 query / 4 KV heads: 7 query heads per KV head, Dff = 18944) at
+    N = 4096: the whole layer against the oracle, lock-step, plus a stage-end compaction."""
+    import torch
+    wl = synth.WORKLOADS["c4"]
+    shape = wl.shape
+    N = 4096
+    w = synth.make_layer(wl.seed, 0, shape, wl.r)
+    dw = runtime.upload_layer(w, shape, wl.r)
+    ctx = runtime.make_context(shape, N, wl.probe_len, wl.r, shape.Dff)
+    assert ctx.uses_mfma()
+    x = synth.hidden_states(wl.seed, N, shape.D, shape.dtype)
+    pos = synth.positions(N)
+    m_attn, m_ffn = int(wl.attn_keep * N), int(wl.ffn_keep * N)
+    gpu = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=wl.probe_len, m_attn=m_attn, m_ffn=m_ffn,
+                            protect_last=1)
+    cfg = orc.LayerCfg(1, wl.probe_len, m_attn, m_ffn, 1, 0)
+    res = H.lockstep_layer(gpu, x, pos, w, H.oracle_model(shape), cfg, shape.dtype)
+    print(f"c4 layer: swaps attn={res['swaps_attn']} ffn={res['swaps_ffn']} hidden err={res['err']:.3e}")
+    assert res["swaps_attn"] <= m_attn // 50 and res["swaps_ffn"] <= m_ffn // 50
+    # stage-end pruning to 0.7 N with the layer's scores
+    n_next = int(0.7 * N)
+    xd = runtime.to_device(gpu["x"].astype(np.float32), shape.dtype)
+    sd = torch.from_numpy(gpu["s_mha"]).cuda()
+    pd = torch.from_numpy(pos).cuda()
+    xo = torch.empty((n_next, shape.D), dtype=xd.dtype, device="cuda")
+    po = torch.empty(n_next, dtype=torch.int32, device="cuda")
+    n2o = torch.empty(n_next, dtype=torch.int32, device="cuda")
+    o2n = torch.empty(N, dtype=torch.int32, device="cuda")
+    ctx.spts_msdp_compact(xd, pd, sd, N, n_next, 1, xo, po, n2o, o2n)
+    rx, rp, rn2o, ro2n = orc.msdp_compact(gpu["x"], pos, gpu["s_mha"], n_next, 1)
+    assert np.array_equal(n2o.cpu().numpy(), rn2o) and np.array_equal(o2n.cpu().numpy(), ro2n)
+    assert np.array_equal(po.cpu().numpy(), rp)
+    assert torch.equal(xo, xd[n2o.long()])
+    del ctx, dw
+    torch.cuda.empty_cache()
+
+
 def test_c3_long_sequence_properties():
     import torch
     wl = synth.WORKLOADS["c3"]
