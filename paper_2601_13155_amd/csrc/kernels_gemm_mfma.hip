@@ -35,6 +35,7 @@ namespace spts {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256;
 
@@ -75,8 +76,12 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
 
     // ---- tile id: XCD-contiguous ranges, grouped raster
     const int per = (total + 7) / 8;
-    const int id = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
-    if (id >= total) return;
+    const int id_all = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
+    if (id_all >= total) return;
+    // split-K: `total` counts (tile, split) pairs, split fastest
+    const int ksplit = EPI == EPI_PARTIAL ? a.ksplit : 1;
+    const int split = id_all % ksplit;
+    const int id = id_all / ksplit;
     constexpr int GM = 4;
     const int group = id / (GM * nN);
     const int first_m = group * GM;
@@ -111,6 +116,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
         const bf16_t* bsrc;
         if (DUAL) bsrc = (r < 128) ? (const bf16_t*)a.B0 + (int64_t)(col0 + r) * a.ldb
                                    : (const bf16_t*)a.B1 + (int64_t)(col0 + r - 128) * a.ldb;
+        else if (a.B1 && col0 >= a.N / 2) bsrc = (const bf16_t*)a.B1 + (int64_t)(col0 - a.N / 2 + r) * a.ldb;
         else bsrc = (const bf16_t*)a.B0 + (int64_t)(col0 + r) * a.ldb;
         gb[q] = bsrc + c * 8;
     }
@@ -120,7 +126,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
 #define SPTS_DMA_ONE(kt_, u)                                                                   \
     {                                                                                          \
         const uint32_t sb_ = lds_w + ((kt_) % NST) * STAGE + ((u) / NOPS) * 1024;              \
-        const int ko_ = (kt_) * BK;                                                            \
+        const int ko_ = (kbeg + (kt_)) * BK;                                                   \
         if ((u) % NOPS == 0) dma16(ga[(u) / NOPS] + ko_, sb_);                                 \
         else if ((u) % NOPS == 1) dma16(gb[(u) / NOPS] + ko_, sb_ + TILE_BYTES);               \
         else dma16(ga1[DUAL_A ? (u) / NOPS : 0] + ko_, sb_ + 2 * TILE_BYTES);                  \
@@ -164,7 +170,11 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     constexpr int NM = 4 * MI;                            // MFMAs per k-step
     constexpr int HS = NM / 2;                            // MFMA slots per half k-step
 
-    const int nk = a.K / BK;
+    // K slabs of this workgroup: all of them, or the split's share (the first nk_all % ksplit splits
+    // take one slab more)
+    const int nk_all = a.K / BK;
+    const int nk = nk_all / ksplit + (split < nk_all % ksplit ? 1 : 0);
+    const int kbeg = split * (nk_all / ksplit) + (split < nk_all % ksplit ? split : nk_all % ksplit);
     // ---- prologue: slabs 0 .. NST-2 are put in flight, slab 0 must have landed
     {
         const int npre = nk < NST - 1 ? nk : NST - 1;
@@ -242,6 +252,24 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     // ---- epilogue.  acc[i][j][r]: row = row0 + wm*WROWS + i*32 + l32,
     //      column (inside N block j) = 8*(r/4) + 4*lh + r%4  -> 4 consecutive columns per r/4.
     bf16_t* Cb = (bf16_t*)a.C;
+    if (EPI == EPI_PARTIAL) {
+        // raw fp32 accumulators; the buffer has pad256(M) rows per split, so no row guard is needed
+        float* P = a.part32 + (int64_t)split * nM * BM * a.N;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int64_t grow = row0 + wm * WROWS + i * 32 + l32;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int cb = col0 + wn * 128 + j * 32 + 4 * lh;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    *reinterpret_cast<f32x4*>(P + grow * a.N + cb + 8 * q) = v;
+                }
+            }
+        }
+        return;
+    }
     if (EPI == EPI_SUMSQ) {
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
@@ -388,6 +416,8 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     }
     if (a.epi == EPI_ROPE && a.head_dim != 128 && a.head_dim != 64) return false;
     if (a.Ct && a.epi != EPI_STORE) return false;
+    if (a.epi == EPI_STORE && a.B1 && (a.N % 512 != 0 || !al16(a.B1))) return false;
+    if (a.ksplit > 1 && (!a.part32 || (a.epi != EPI_STORE && a.epi != EPI_ROPE) || a.K / 32 < a.ksplit)) return false;
     if (a.M > (int64_t)1 << 30) return false;
     return true;
 }
@@ -396,7 +426,7 @@ template <int EPI, int BK, bool DUAL_A, int NW>
 static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     const int ncols = EPI == EPI_SILU_MUL ? 128 : 256;
     const int nM = (int)((a.M + BM - 1) / BM), nN = a.N / ncols;
-    const int total = nM * nN;
+    const int total = nM * nN * (EPI == EPI_PARTIAL ? a.ksplit : 1);
     const int grid = (total + 7) / 8 * 8;
     const size_t lds = (size_t)Slab<BK>::TILE_BYTES * (DUAL_A ? 3 : 2) * (BK == 64 ? 2 : (DUAL_A ? 3 : 4));
     static bool attr_set = false;
@@ -410,6 +440,71 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
+// ---- split-K second pass: sum the fp32 partial tiles in split order, apply the epilogue
+__global__ void __launch_bounds__(256) splitk_store_kernel(GemmArgs a, int64_t Mpad) {
+    // one thread per (row, 4 consecutive columns)
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int n4 = a.N / 4;
+    if (i >= a.M * n4) return;
+    const int64_t row = i / n4;
+    const int col = (int)(i % n4) * 4;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    for (int sp = 0; sp < a.ksplit; ++sp) v += *reinterpret_cast<const f32x4*>(a.part32 + ((int64_t)sp * Mpad + row) * a.N + col);
+    const int64_t crow = a.c_idx ? (int64_t)a.c_idx[row] : row;
+    u32x2 o = {cvt_pk_bf16(v.x, v.y), cvt_pk_bf16(v.z, v.w)};
+    *reinterpret_cast<u32x2*>((bf16_t*)a.C + crow * a.ldc + col) = o;
+    if (a.Ct) {
+        bf16_t* ct = (bf16_t*)a.Ct;
+        const uint16_t e[4] = {(uint16_t)(o.x & 0xffff), (uint16_t)(o.x >> 16), (uint16_t)(o.y & 0xffff), (uint16_t)(o.y >> 16)};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) ct[(int64_t)(col + t) * a.ldct + vt_key_slot(row)].v = e[t];
+    }
+}
+// transposed copy: key slots in [M, ldct) are zero-filled (the single-pass epilogue writes duplicates of
+// the last row there; either is fine for the attention kernel, which masks those keys)
+__global__ void __launch_bounds__(256) splitk_ct_pad_kernel(GemmArgs a) {
+    const int64_t npad = a.ldct - a.M;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= npad * a.N) return;
+    const int col = (int)(i / npad);
+    const int64_t key = a.M + i % npad;
+    ((bf16_t*)a.Ct)[(int64_t)col * a.ldct + vt_key_slot(key)].v = 0;
+}
+__global__ void __launch_bounds__(256) splitk_rope_kernel(GemmArgs a, int64_t Mpad) {
+    // one thread per (row, head, j < d/2)
+    const int half = a.head_dim >> 1;
+    const int heads = a.N / a.head_dim;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= a.M * heads * half) return;
+    const int j = (int)(i % half);
+    const int64_t t = i / half;
+    const int h = (int)(t % heads);
+    const int64_t row = t / heads;
+    const int col = h * a.head_dim + j;
+    float x1 = 0.f, x2 = 0.f;
+    for (int sp = 0; sp < a.ksplit; ++sp) {
+        const float* p = a.part32 + ((int64_t)sp * Mpad + row) * a.N + col;
+        x1 += p[0];
+        x2 += p[half];
+    }
+    const int64_t trow = a.rope_idx ? (int64_t)a.rope_idx[row] : row;
+    const float2 cs = a.rope[trow * half + j];
+    const int64_t crow = a.c_idx ? (int64_t)a.c_idx[row] : row;
+    bf16_t* c = (bf16_t*)a.C + crow * a.ldc + col;
+    c[0] = f32_to_bf16(x1 * cs.x - x2 * cs.y);
+    c[half] = f32_to_bf16(x2 * cs.x + x1 * cs.y);
+}
+
+int gemm_pick_ksplit(int64_t M, int32_t N, int32_t K, int epi) {
+    if (epi != EPI_STORE && epi != EPI_ROPE) return 1;
+    const int64_t tiles = ((M + BM - 1) / BM) * (N / 256);
+    if (tiles <= 0 || tiles > 160 || K < 1024) return 1;
+    int64_t ks = 256 / tiles;
+    if (ks > 8) ks = 8;
+    if (ks > K / 512) ks = K / 512;
+    return ks < 2 ? 1 : (int)ks;
+}
+
 // wavefronts per workgroup used by launch_gemm_mfma (4 or 8)
 #ifndef SPTS_GEMM_NW
 #define SPTS_GEMM_NW 8
@@ -417,6 +512,25 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
     constexpr int NW = SPTS_GEMM_NW;
+    if (a.ksplit > 1 && (a.epi == EPI_STORE || a.epi == EPI_ROPE)) {
+        GemmArgs p = a;
+        p.epi = EPI_PARTIAL;
+        hipError_t e = a.K % 64 == 0 ? launch_t<EPI_PARTIAL, 64, false, NW>(p, s) : launch_t<EPI_PARTIAL, 32, false, NW>(p, s);
+        if (e != hipSuccess) return e;
+        const int64_t Mpad = (a.M + BM - 1) / BM * BM;
+        if (a.epi == EPI_STORE) {
+            const int64_t n = a.M * (a.N / 4);
+            splitk_store_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(a, Mpad);
+            if (a.Ct && a.ldct > a.M) {
+                const int64_t np = (a.ldct - a.M) * a.N;
+                splitk_ct_pad_kernel<<<dim3((unsigned)((np + 255) / 256)), dim3(256), 0, s>>>(a);
+            }
+        } else {
+            const int64_t n = a.M * (a.N / 2);
+            splitk_rope_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(a, Mpad);
+        }
+        return hipGetLastError();
+    }
     switch (a.epi) {
         case EPI_STORE: return (a.K % 64 == 0 ? launch_t<EPI_STORE, 64, false, NW>(a, s) : launch_t<EPI_STORE, 32, false, NW>(a, s));
         case EPI_RESIDUAL: return (a.K % 64 == 0 ? launch_t<EPI_RESIDUAL, 64, false, NW>(a, s) : launch_t<EPI_RESIDUAL, 32, false, NW>(a, s));

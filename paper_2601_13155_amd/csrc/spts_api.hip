@@ -131,9 +131,21 @@ struct PhaseScope {
 namespace {
 
 // ---- dispatch helpers -------------------------------------------------------------------------
+// matrix-core launch; skinny GEMMs with a long K are split over K through the fp32 staging buffer
+int run_gemm_mfma(spts_ctx* c, GemmArgs a) {
+    const int ks = gemm_pick_ksplit(a.M, a.N, a.K, a.epi);
+    if (ks > 1) {
+        const size_t need = (size_t)ks * (size_t)((a.M + 255) / 256 * 256) * a.N * sizeof(float);
+        const size_t have = (size_t)((c->lim.max_tokens + 255) / 256 * 256) * c->m.H * c->m.d * sizeof(float);
+        if (need <= have) { a.ksplit = ks; a.part32 = c->p<float>(c->off.tmp32); }
+    }
+    SPTS_HIP(c, launch_gemm_mfma(a, c->stream));
+    return SPTS_OK;
+}
+
 int run_gemm(spts_ctx* c, const GemmArgs& a) {
-    if (c->bf16 && gemm_mfma_supported(a)) SPTS_HIP(c, launch_gemm_mfma(a, c->stream));
-    else SPTS_HIP(c, launch_gemm_generic(a, c->bf16, c->stream));
+    if (c->bf16 && gemm_mfma_supported(a)) return run_gemm_mfma(c, a);
+    SPTS_HIP(c, launch_gemm_generic(a, c->bf16, c->stream));
     return SPTS_OK;
 }
 
@@ -150,7 +162,7 @@ int run_gemm_rope(spts_ctx* c, GemmArgs g, int heads, const int32_t* tidx, int64
     const float2* table = c->p<float2>(c->off.rope);
     GemmArgs f = g;
     f.epi = EPI_ROPE; f.C = out; f.rope = table + row0 * (c->m.d / 2); f.rope_idx = tidx; f.head_dim = c->m.d;
-    if (c->bf16 && gemm_mfma_supported(f)) { SPTS_HIP(c, launch_gemm_mfma(f, c->stream)); return SPTS_OK; }
+    if (c->bf16 && gemm_mfma_supported(f)) return run_gemm_mfma(c, f);
     g.C = c->p<float>(c->off.tmp32); g.c_is_f32 = 1; g.epi = EPI_STORE;
     SPTS_TRY(run_gemm(c, g));
     SPTS_HIP(c, launch_rope_apply(c->p<float>(c->off.tmp32), table, tidx, row0, out, g.M, heads, c->m.d, c->bf16, c->stream));
@@ -212,10 +224,20 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
     const int r = w->r, Dlow = w->Dlow;
     const size_t eb = c->bf16 ? 2 : 4;
     char* t = c->p<char>(c->off.t);  // [N, 2r]: columns [0,r) = x Ug, [r,2r) = x Uu
-    GemmArgs g1 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, r, m.D);
-    { PHASE(c, PH_PROXY_IN); SPTS_TRY(run_gemm(c, g1)); }
-    GemmArgs g2 = gemm_args(xn2, m.D, nullptr, w->Uu, m.D, t + (size_t)r * eb, 2 * r, N, r, m.D);
-    { PHASE(c, PH_PROXY_IN); SPTS_TRY(run_gemm(c, g2)); }
+    {
+        PHASE(c, PH_PROXY_IN);
+        // one launch for both factors when the matrix-core kernel takes it (columns [0,r) from Ug, [r,2r) from Uu)
+        GemmArgs g12 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, 2 * r, m.D);
+        g12.B1 = w->Uu;
+        if (c->bf16 && gemm_mfma_supported(g12)) {
+            SPTS_TRY(run_gemm_mfma(c, g12));
+        } else {
+            GemmArgs g1 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, r, m.D);
+            SPTS_TRY(run_gemm(c, g1));
+            GemmArgs g2 = gemm_args(xn2, m.D, nullptr, w->Uu, m.D, t + (size_t)r * eb, 2 * r, N, r, m.D);
+            SPTS_TRY(run_gemm(c, g2));
+        }
+    }
     // hp = silu(tg Vg) * (tu Vu)   [N, Dlow]
     GemmArgs g3 = gemm_args(t, 2 * r, nullptr, w->Vg, r, c->p<void>(c->off.big), Dlow, N, Dlow, r, EPI_SILU_MUL);
     g3.B1 = w->Vu; g3.A1 = t + (size_t)r * eb;

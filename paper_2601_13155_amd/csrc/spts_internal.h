@@ -60,13 +60,14 @@ enum GemmEpilogue : int {
     EPI_SILU_MUL = 1,   // C[row, col] = silu(acc0) * acc1     (two B operands)
     EPI_RESIDUAL = 2,   // C[crow, col] = C[crow, col] + acc   (crow = c_idx ? c_idx[row] : row)
     EPI_SUMSQ = 3,      // part[row, col_block] = sum over the block's columns of acc^2
-    EPI_ROPE = 4,       // C[row, col] = rotary(acc) with table row (a_idx ? a_idx[row] : row); MFMA path only
+    EPI_ROPE = 4,       // C[row, col] = rotary(acc) with table row (rope_idx ? rope_idx[row] : row); MFMA path only
+    EPI_PARTIAL = 5,    // split-K pass (internal): fp32 partial tile -> part32[split][row][col]
 };
 
 struct GemmArgs {
     const void* A; int64_t lda; const int32_t* a_idx;   // A [*, K] rows optionally gathered
     const void* A1;                                     // EPI_SILU_MUL: A operand of the second product (null = A)
-    const void* B0; const void* B1; int64_t ldb;        // B [N, K]
+    const void* B0; const void* B1; int64_t ldb;        // B [N, K]; EPI_STORE with B1: columns [N/2, N) come from B1
     void* C; int64_t ldc; const int32_t* c_idx;         // output rows optionally scattered
     void* Ct; int64_t ldct;                             // optional transposed copy Ct[col, row]
     float* part; int32_t part_ld;                       // EPI_SUMSQ partial sums [M, part_ld]
@@ -74,7 +75,14 @@ struct GemmArgs {
     const int32_t* rope_idx;                            // table row = rope_idx ? rope_idx[row] : row
     int64_t M; int32_t N; int32_t K;
     int32_t epi; int32_t c_is_f32;
+    // split-K (matrix-core path, EPI_STORE / EPI_ROPE only): ksplit > 1 splits the K range over ksplit
+    // workgroups per tile; fp32 partial tiles go to part32 [ksplit][pad256(M)][N] and a second kernel
+    // sums them in a fixed order and applies the epilogue.  Used when a GEMM has too few tiles to fill
+    // the chip (skinny outputs with a long K).
+    int32_t ksplit; float* part32;
 };
+// largest useful split for a GEMM of this shape on 256 CUs (1 = do not split)
+int gemm_pick_ksplit(int64_t M, int32_t N, int32_t K, int epi);
 
 hipError_t launch_gemm_generic(const GemmArgs& a, bool bf16, hipStream_t s);
 // true when the matrix-core kernel can serve these arguments (alignment / divisibility)
