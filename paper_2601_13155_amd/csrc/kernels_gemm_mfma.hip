@@ -55,16 +55,29 @@ template <int BK> struct Slab {
 __device__ inline uint32_t pack_bf16x2(float a, float b) { return cvt_pk_bf16(a, b); }
 __device__ inline float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
+// tile number -> (row tile, column tile): grouped raster, GM row tiles per group, rows fastest inside
+// a group, so that workgroups running together share A and B tiles in L2
+__device__ __forceinline__ void tile_of(int id, int nM, int nN, int& tm, int& tn) {
+    constexpr int GM = 4;
+    const int group = id / (GM * nN);
+    const int first_m = group * GM;
+    const int gsz = (nM - first_m) < GM ? (nM - first_m) : GM;
+    const int in_g = id % (GM * nN);
+    tm = first_m + in_g % gsz;
+    tn = in_g / gsz;
+}
+
 // NW wavefronts per workgroup: 4 (2x2 wavefronts of 128x128, one per SIMD) or 8 (4x2 wavefronts of
 // 64x128, two per SIMD: a wavefront's memory instructions, waits and barriers hide behind the other's
 // MFMAs at the price of 50 % more LDS fragment traffic).
 template <int EPI, int BK, bool DUAL_A, int NW>
-__global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, int nN, int total) {
+__global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, int nN, int nfull, int nunits) {
     using S = Slab<BK>;
     constexpr int MI = 16 / NW;                   // 32-row blocks per wavefront (4 or 2)
     constexpr int WROWS = 32 * MI;                // output rows per wavefront
     constexpr int LROWS = 256 / NW;               // operand tile rows each wavefront loads
     constexpr bool DUAL = (EPI == EPI_SILU_MUL);
+    constexpr bool CAN_SPLIT = (EPI == EPI_STORE || EPI == EPI_RESIDUAL || EPI == EPI_ROPE);
     constexpr int TILE_BYTES = S::TILE_BYTES;
     constexpr int NOPS = DUAL_A ? 3 : 2;          // operand tiles per stage (A, B[, A1])
     constexpr int NST = BK == 64 ? 2 : (DUAL_A ? 3 : 4);   // LDS ring stages
@@ -74,21 +87,27 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     constexpr int KSTEPS = BK / 16;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    // ---- tile id: XCD-contiguous ranges, grouped raster
-    const int per = (total + 7) / 8;
-    const int id_all = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
-    if (id_all >= total) return;
-    // split-K: `total` counts (tile, split) pairs, split fastest
-    const int ksplit = EPI == EPI_PARTIAL ? a.ksplit : 1;
-    const int split = id_all % ksplit;
-    const int id = id_all / ksplit;
-    constexpr int GM = 4;
-    const int group = id / (GM * nN);
-    const int first_m = group * GM;
-    const int gsz = (nM - first_m) < GM ? (nM - first_m) : GM;
-    const int in_g = id % (GM * nN);
-    const int tm = first_m + in_g % gsz;
-    const int tn = in_g / gsz;
+    // ---- work unit.  Workgroup b runs on XCD b % 8 as that XCD's (b / 8)-th workgroup.  Every XCD
+    //      takes a contiguous range of whole tiles first, then a contiguous range of split units
+    //      (a split unit = one K share of one of the tiles behind the first nfull), so that all
+    //      XCDs run out of whole tiles at the same time.
+    const int xcd = (int)(blockIdx.x % 8), pos = (int)(blockIdx.x / 8);
+    const int pf = (nfull + 7) / 8;
+    int id, split = 0, ksplit = 1;
+    if (pos < pf) {
+        id = xcd * pf + pos;
+        if (id >= nfull) return;
+    } else {
+        if (!CAN_SPLIT) return;
+        const int u = xcd * ((nunits + 7) / 8) + (pos - pf);
+        if (u >= nunits) return;
+        ksplit = a.ksplit;
+        id = nfull + u / ksplit;
+        split = u % ksplit;
+    }
+    const bool partial = CAN_SPLIT && ksplit > 1;
+    int tm, tn;
+    tile_of(id, nM, nN, tm, tn);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -252,22 +271,18 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     // ---- epilogue.  acc[i][j][r]: row = row0 + wm*WROWS + i*32 + l32,
     //      column (inside N block j) = 8*(r/4) + 4*lh + r%4  -> 4 consecutive columns per r/4.
     bf16_t* Cb = (bf16_t*)a.C;
-    if (EPI == EPI_PARTIAL) {
-        // raw fp32 accumulators; the buffer has pad256(M) rows per split, so no row guard is needed
-        float* P = a.part32 + (int64_t)split * nM * BM * a.N;
+    if (partial) {
+        // raw fp32 accumulators in fragment order: every store instruction of a wavefront writes 1 KB
+        float* P = a.part32 + ((int64_t)(id - nfull) * ksplit + split) * (BM * 256);
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int64_t grow = row0 + wm * WROWS + i * 32 + l32;
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int cb = col0 + wn * 128 + j * 32 + 4 * lh;
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                    *reinterpret_cast<f32x4*>(P + grow * a.N + cb + 8 * q) = v;
+                    *reinterpret_cast<f32x4*>(P + ((((wave * MI + i) * 4 + j) * 4 + q) * 64 + lane) * 4) = v;
                 }
-            }
-        }
         return;
     }
     if (EPI == EPI_SUMSQ) {
@@ -417,7 +432,10 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     if (a.epi == EPI_ROPE && a.head_dim != 128 && a.head_dim != 64) return false;
     if (a.Ct && a.epi != EPI_STORE) return false;
     if (a.epi == EPI_STORE && a.B1 && (a.N % 512 != 0 || !al16(a.B1))) return false;
-    if (a.ksplit > 1 && (!a.part32 || (a.epi != EPI_STORE && a.epi != EPI_ROPE) || a.K / 32 < a.ksplit)) return false;
+    if (a.ksplit > 1) {
+        if (!a.part32 || !al16(a.part32) || (a.epi != EPI_STORE && a.epi != EPI_RESIDUAL && a.epi != EPI_ROPE)) return false;
+        if (a.K / 64 < a.ksplit || a.nfull < 0 || a.nfull > (a.M + BM - 1) / BM * (a.N / 256)) return false;
+    }
     if (a.M > (int64_t)1 << 30) return false;
     return true;
 }
@@ -426,8 +444,11 @@ template <int EPI, int BK, bool DUAL_A, int NW>
 static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     const int ncols = EPI == EPI_SILU_MUL ? 128 : 256;
     const int nM = (int)((a.M + BM - 1) / BM), nN = a.N / ncols;
-    const int total = nM * nN * (EPI == EPI_PARTIAL ? a.ksplit : 1);
-    const int grid = (total + 7) / 8 * 8;
+    const int tiles = nM * nN;
+    const bool split = a.ksplit > 1;
+    const int nfull = split ? a.nfull : tiles;
+    const int nunits = split ? (tiles - nfull) * a.ksplit : 0;
+    const int grid = 8 * ((nfull + 7) / 8 + (nunits + 7) / 8);
     const size_t lds = (size_t)Slab<BK>::TILE_BYTES * (DUAL_A ? 3 : 2) * (BK == 64 ? 2 : (DUAL_A ? 3 : 4));
     static bool attr_set = false;
     if (!attr_set) {
@@ -436,73 +457,104 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_mfma_kernel<EPI, BK, DUAL_A, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nM, nN, total);
+    gemm_mfma_kernel<EPI, BK, DUAL_A, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nM, nN, nfull, nunits);
     return hipGetLastError();
 }
 
-// ---- split-K second pass: sum the fp32 partial tiles in split order, apply the epilogue
-__global__ void __launch_bounds__(256) splitk_store_kernel(GemmArgs a, int64_t Mpad) {
-    // one thread per (row, 4 consecutive columns)
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int n4 = a.N / 4;
-    if (i >= a.M * n4) return;
-    const int64_t row = i / n4;
-    const int col = (int)(i % n4) * 4;
-    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    for (int sp = 0; sp < a.ksplit; ++sp) v += *reinterpret_cast<const f32x4*>(a.part32 + ((int64_t)sp * Mpad + row) * a.N + col);
-    const int64_t crow = a.c_idx ? (int64_t)a.c_idx[row] : row;
-    u32x2 o = {cvt_pk_bf16(v.x, v.y), cvt_pk_bf16(v.z, v.w)};
-    *reinterpret_cast<u32x2*>((bf16_t*)a.C + crow * a.ldc + col) = o;
-    if (a.Ct) {
-        bf16_t* ct = (bf16_t*)a.Ct;
-        const uint16_t e[4] = {(uint16_t)(o.x & 0xffff), (uint16_t)(o.x >> 16), (uint16_t)(o.y & 0xffff), (uint16_t)(o.y >> 16)};
+// ---- tail split-K second pass: one thread per accumulator-fragment quad (4 consecutive columns of one
+//      row) of a split tile; sums the splits in split order and applies the epilogue exactly as the
+//      single-pass kernel does.  For EPI_ROPE a thread owns the quad and its partner d/2 columns on.
+template <int NW>
+__global__ void __launch_bounds__(256) splitk_finish_kernel(GemmArgs a, int nM, int nN, int nfull) {
+    constexpr int MI = 16 / NW, WROWS = 32 * MI;
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int rt = (int)(g >> 14);                 // split tile (16384 quads per tile)
+    const int v = (int)(g & 16383);
+    const int lane = v & 63, q = (v >> 6) & 3, j = (v >> 8) & 3, wi = v >> 10;
+    const int wave = wi / MI, i = wi % MI;
+    const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, lh = lane >> 5;
+    int tm, tn;
+    tile_of(nfull + rt, nM, nN, tm, tn);
+    const int64_t grow = (int64_t)tm * BM + wm * WROWS + i * 32 + l32;
+    const int col0 = tn * 256;
+    const float* P = a.part32 + (int64_t)rt * a.ksplit * (BM * 256);
+    auto quad = [&](int jj) {
+        const float* p = P + ((((wave * MI + i) * 4 + jj) * 4 + q) * 64 + lane) * 4;
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+        for (int sp = 0; sp < a.ksplit; ++sp) s += *reinterpret_cast<const f32x4*>(p + (int64_t)sp * (BM * 256));
+        return s;
+    };
+    const bool rok = grow < a.M;
+    const int64_t growc = rok ? grow : a.M - 1;
+    const int64_t crow = a.c_idx ? (int64_t)a.c_idx[growc] : growc;
+    bf16_t* Cb = (bf16_t*)a.C;
+    if (a.epi == EPI_STORE) {
+        const f32x4 s = quad(j);
+        const int col = col0 + wn * 128 + j * 32 + 4 * lh + 8 * q;
+        u32x2 o = {pack_bf16x2(s.x, s.y), pack_bf16x2(s.z, s.w)};
+        if (rok) *reinterpret_cast<u32x2*>(Cb + crow * a.ldc + col) = o;
+        if (a.Ct && grow < a.ldct) {
+            bf16_t* ct = (bf16_t*)a.Ct;
+            const uint16_t e[4] = {(uint16_t)(o.x & 0xffff), (uint16_t)(o.x >> 16), (uint16_t)(o.y & 0xffff), (uint16_t)(o.y >> 16)};
 #pragma unroll
-        for (int t = 0; t < 4; ++t) ct[(int64_t)(col + t) * a.ldct + vt_key_slot(row)].v = e[t];
+            for (int t = 0; t < 4; ++t) ct[(int64_t)(col + t) * a.ldct + vt_key_slot(grow)].v = e[t];
+        }
+    } else if (a.epi == EPI_RESIDUAL) {
+        if (!rok) return;
+        const f32x4 s = quad(j);
+        const int col = col0 + wn * 128 + j * 32 + 4 * lh + 8 * q;
+        u32x2* p = reinterpret_cast<u32x2*>(Cb + crow * a.ldc + col);
+        const u32x2 old = *p;
+        u32x2 o;
+        o.x = pack_bf16x2(__uint_as_float(old.x << 16) + s.x, __uint_as_float(old.x & 0xffff0000u) + s.y);
+        o.y = pack_bf16x2(__uint_as_float(old.y << 16) + s.z, __uint_as_float(old.y & 0xffff0000u) + s.w);
+        *p = o;
+    } else {   // EPI_ROPE
+        if (!rok) return;
+        const int half = a.head_dim >> 1;
+        int j1, j2, jj;   // accumulator blocks of the quad and of its partner; column inside the half head
+        if (half == 64) { if (j >= 2) return; j1 = j; j2 = j + 2; jj = j * 32 + 4 * lh + 8 * q; }
+        else { if (j & 1) return; j1 = j; j2 = j + 1; jj = 4 * lh + 8 * q; }
+        const f32x4 x1 = quad(j1), x2 = quad(j2);
+        const int64_t trow = a.rope_idx ? (int64_t)a.rope_idx[grow] : grow;
+        const float2* tab = a.rope + trow * half + jj;
+        float lo[4], hi[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float2 cs = tab[t];
+            lo[t] = x1[t] * cs.x - x2[t] * cs.y;
+            hi[t] = x2[t] * cs.x + x1[t] * cs.y;
+        }
+        const int col = col0 + wn * 128 + (half == 64 ? 0 : (j >> 1) * 64) + jj;
+        u32x2 o1 = {pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3])};
+        u32x2 o2 = {pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])};
+        *reinterpret_cast<u32x2*>(Cb + crow * a.ldc + col) = o1;
+        *reinterpret_cast<u32x2*>(Cb + crow * a.ldc + col + half) = o2;
     }
-}
-// transposed copy: key slots in [M, ldct) are zero-filled (the single-pass epilogue writes duplicates of
-// the last row there; either is fine for the attention kernel, which masks those keys)
-__global__ void __launch_bounds__(256) splitk_ct_pad_kernel(GemmArgs a) {
-    const int64_t npad = a.ldct - a.M;
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= npad * a.N) return;
-    const int col = (int)(i / npad);
-    const int64_t key = a.M + i % npad;
-    ((bf16_t*)a.Ct)[(int64_t)col * a.ldct + vt_key_slot(key)].v = 0;
-}
-__global__ void __launch_bounds__(256) splitk_rope_kernel(GemmArgs a, int64_t Mpad) {
-    // one thread per (row, head, j < d/2)
-    const int half = a.head_dim >> 1;
-    const int heads = a.N / a.head_dim;
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= a.M * heads * half) return;
-    const int j = (int)(i % half);
-    const int64_t t = i / half;
-    const int h = (int)(t % heads);
-    const int64_t row = t / heads;
-    const int col = h * a.head_dim + j;
-    float x1 = 0.f, x2 = 0.f;
-    for (int sp = 0; sp < a.ksplit; ++sp) {
-        const float* p = a.part32 + ((int64_t)sp * Mpad + row) * a.N + col;
-        x1 += p[0];
-        x2 += p[half];
-    }
-    const int64_t trow = a.rope_idx ? (int64_t)a.rope_idx[row] : row;
-    const float2 cs = a.rope[trow * half + j];
-    const int64_t crow = a.c_idx ? (int64_t)a.c_idx[row] : row;
-    bf16_t* c = (bf16_t*)a.C + crow * a.ldc + col;
-    c[0] = f32_to_bf16(x1 * cs.x - x2 * cs.y);
-    c[half] = f32_to_bf16(x2 * cs.x + x1 * cs.y);
 }
 
-int gemm_pick_ksplit(int64_t M, int32_t N, int32_t K, int epi) {
-    if (epi != EPI_STORE && epi != EPI_ROPE) return 1;
+// Cost model behind the split plan (one workgroup per CU, 256 CUs): a whole tile takes
+// t_tile = 2*256*256*K flops at the sustained per-CU rate; the tail of `rem` tiles costs one t_tile
+// unsplit, or ceil(rem*ks/256)/ks of it plus the partial-tile traffic (rem*ks tiles of 256 KB, written
+// and read back) plus one more launch when split ks ways.
+int gemm_pick_split(int64_t M, int32_t N, int32_t K, int epi, int32_t* nfull) {
+    *nfull = 0;
+    if (epi != EPI_STORE && epi != EPI_RESIDUAL && epi != EPI_ROPE) return 1;
+    if (N % 256 != 0 || M <= 0) return 1;
     const int64_t tiles = ((M + BM - 1) / BM) * (N / 256);
-    if (tiles <= 0 || tiles > 160 || K < 1024) return 1;
-    int64_t ks = 256 / tiles;
-    if (ks > 8) ks = 8;
-    if (ks > K / 512) ks = K / 512;
-    return ks < 2 ? 1 : (int)ks;
+    const int rem = (int)(tiles % 256);
+    if (rem == 0) return 1;
+    const double t_tile = 2.0 * 256 * 256 * K / 4.2e12;
+    double best = t_tile;
+    int best_ks = 1;
+    for (int ks = 2; ks <= 8; ++ks) {
+        if (K / ks < 512) break;
+        const int rounds = (rem * ks + 255) / 256;
+        const double t = t_tile * rounds / ks + (double)rem * ks * 262144.0 * 2.0 / 4.0e12 + 6e-6;
+        if (t < best * 0.97) { best = t; best_ks = ks; }
+    }
+    *nfull = (int32_t)(tiles - rem);
+    return best_ks;
 }
 
 // wavefronts per workgroup used by launch_gemm_mfma (4 or 8)
@@ -512,35 +564,24 @@ int gemm_pick_ksplit(int64_t M, int32_t N, int32_t K, int epi) {
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
     constexpr int NW = SPTS_GEMM_NW;
-    if (a.ksplit > 1 && (a.epi == EPI_STORE || a.epi == EPI_ROPE)) {
-        GemmArgs p = a;
-        p.epi = EPI_PARTIAL;
-        hipError_t e = a.K % 64 == 0 ? launch_t<EPI_PARTIAL, 64, false, NW>(p, s) : launch_t<EPI_PARTIAL, 32, false, NW>(p, s);
-        if (e != hipSuccess) return e;
-        const int64_t Mpad = (a.M + BM - 1) / BM * BM;
-        if (a.epi == EPI_STORE) {
-            const int64_t n = a.M * (a.N / 4);
-            splitk_store_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(a, Mpad);
-            if (a.Ct && a.ldct > a.M) {
-                const int64_t np = (a.ldct - a.M) * a.N;
-                splitk_ct_pad_kernel<<<dim3((unsigned)((np + 255) / 256)), dim3(256), 0, s>>>(a);
-            }
-        } else {
-            const int64_t n = a.M * (a.N / 2);
-            splitk_rope_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(a, Mpad);
-        }
-        return hipGetLastError();
-    }
+    hipError_t e;
     switch (a.epi) {
-        case EPI_STORE: return (a.K % 64 == 0 ? launch_t<EPI_STORE, 64, false, NW>(a, s) : launch_t<EPI_STORE, 32, false, NW>(a, s));
-        case EPI_RESIDUAL: return (a.K % 64 == 0 ? launch_t<EPI_RESIDUAL, 64, false, NW>(a, s) : launch_t<EPI_RESIDUAL, 32, false, NW>(a, s));
-        case EPI_SUMSQ: return (a.K % 64 == 0 ? launch_t<EPI_SUMSQ, 64, false, NW>(a, s) : launch_t<EPI_SUMSQ, 32, false, NW>(a, s));
-        case EPI_ROPE: return (a.K % 64 == 0 ? launch_t<EPI_ROPE, 64, false, NW>(a, s) : launch_t<EPI_ROPE, 32, false, NW>(a, s));
+        case EPI_STORE: e = (a.K % 64 == 0 ? launch_t<EPI_STORE, 64, false, NW>(a, s) : launch_t<EPI_STORE, 32, false, NW>(a, s)); break;
+        case EPI_RESIDUAL: e = (a.K % 64 == 0 ? launch_t<EPI_RESIDUAL, 64, false, NW>(a, s) : launch_t<EPI_RESIDUAL, 32, false, NW>(a, s)); break;
+        case EPI_SUMSQ: e = (a.K % 64 == 0 ? launch_t<EPI_SUMSQ, 64, false, NW>(a, s) : launch_t<EPI_SUMSQ, 32, false, NW>(a, s)); break;
+        case EPI_ROPE: e = (a.K % 64 == 0 ? launch_t<EPI_ROPE, 64, false, NW>(a, s) : launch_t<EPI_ROPE, 32, false, NW>(a, s)); break;
         case EPI_SILU_MUL:
-            if (a.A1) return launch_t<EPI_SILU_MUL, 32, true, NW>(a, s);
-            return a.K % 64 == 0 ? launch_t<EPI_SILU_MUL, 64, false, NW>(a, s) : launch_t<EPI_SILU_MUL, 32, false, NW>(a, s);
+            if (a.A1) e = launch_t<EPI_SILU_MUL, 32, true, NW>(a, s);
+            else e = a.K % 64 == 0 ? launch_t<EPI_SILU_MUL, 64, false, NW>(a, s) : launch_t<EPI_SILU_MUL, 32, false, NW>(a, s);
+            break;
         default: return hipErrorInvalidValue;
     }
+    if (e != hipSuccess || a.ksplit <= 1) return e;
+    const int nM = (int)((a.M + BM - 1) / BM), nN = a.N / 256;
+    const int64_t quads = (int64_t)(nM * nN - a.nfull) * 16384;
+    if (quads <= 0) return hipSuccess;
+    splitk_finish_kernel<NW><<<dim3((unsigned)(quads / 256)), dim3(256), 0, s>>>(a, nM, nN, a.nfull);
+    return hipGetLastError();
 }
 
 }  // namespace spts

@@ -131,13 +131,15 @@ struct PhaseScope {
 namespace {
 
 // ---- dispatch helpers -------------------------------------------------------------------------
-// matrix-core launch; skinny GEMMs with a long K are split over K through the fp32 staging buffer
+// matrix-core launch; the partly filled last round of tiles is split over K through the fp32 staging buffer
 int run_gemm_mfma(spts_ctx* c, GemmArgs a) {
-    const int ks = gemm_pick_ksplit(a.M, a.N, a.K, a.epi);
+    int32_t nfull = 0;
+    const int ks = gemm_pick_split(a.M, a.N, a.K, a.epi, &nfull);
     if (ks > 1) {
-        const size_t need = (size_t)ks * (size_t)((a.M + 255) / 256 * 256) * a.N * sizeof(float);
+        const int64_t tiles = (a.M + 255) / 256 * (a.N / 256);
+        const size_t need = (size_t)(tiles - nfull) * ks * 65536 * sizeof(float);
         const size_t have = (size_t)((c->lim.max_tokens + 255) / 256 * 256) * c->m.H * c->m.d * sizeof(float);
-        if (need <= have) { a.ksplit = ks; a.part32 = c->p<float>(c->off.tmp32); }
+        if (need <= have) { a.ksplit = ks; a.nfull = nfull; a.part32 = c->p<float>(c->off.tmp32); }
     }
     SPTS_HIP(c, launch_gemm_mfma(a, c->stream));
     return SPTS_OK;

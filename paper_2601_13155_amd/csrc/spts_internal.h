@@ -61,7 +61,6 @@ enum GemmEpilogue : int {
     EPI_RESIDUAL = 2,   // C[crow, col] = C[crow, col] + acc   (crow = c_idx ? c_idx[row] : row)
     EPI_SUMSQ = 3,      // part[row, col_block] = sum over the block's columns of acc^2
     EPI_ROPE = 4,       // C[row, col] = rotary(acc) with table row (rope_idx ? rope_idx[row] : row); MFMA path only
-    EPI_PARTIAL = 5,    // split-K pass (internal): fp32 partial tile -> part32[split][row][col]
 };
 
 struct GemmArgs {
@@ -75,14 +74,18 @@ struct GemmArgs {
     const int32_t* rope_idx;                            // table row = rope_idx ? rope_idx[row] : row
     int64_t M; int32_t N; int32_t K;
     int32_t epi; int32_t c_is_f32;
-    // split-K (matrix-core path, EPI_STORE / EPI_ROPE only): ksplit > 1 splits the K range over ksplit
-    // workgroups per tile; fp32 partial tiles go to part32 [ksplit][pad256(M)][N] and a second kernel
-    // sums them in a fixed order and applies the epilogue.  Used when a GEMM has too few tiles to fill
-    // the chip (skinny outputs with a long K).
-    int32_t ksplit; float* part32;
+    // tail split-K (matrix-core path; EPI_STORE / EPI_RESIDUAL / EPI_ROPE): the first `nfull` tiles (in
+    // raster order) are computed whole; each of the remaining tiles is shared by `ksplit` workgroups,
+    // every one taking a contiguous share of K and writing its raw fp32 accumulators to part32
+    // (65536 floats per (tile, split), in accumulator-fragment order); a second kernel sums the
+    // splits in split order and applies the epilogue.  With one workgroup resident per CU this turns
+    // the last, partly filled round of tiles into a full round of short work units.
+    // ksplit <= 1 disables it (nfull is then ignored).
+    int32_t ksplit; int32_t nfull; float* part32;
 };
-// largest useful split for a GEMM of this shape on 256 CUs (1 = do not split)
-int gemm_pick_ksplit(int64_t M, int32_t N, int32_t K, int epi);
+// Split plan for a GEMM of this shape on a 256-CU device: returns ksplit (1 = do not split) and
+// sets *nfull; needs (tiles - nfull) * ksplit * 65536 floats of part32.
+int gemm_pick_split(int64_t M, int32_t N, int32_t K, int epi, int32_t* nfull);
 
 hipError_t launch_gemm_generic(const GemmArgs& a, bool bf16, hipStream_t s);
 // true when the matrix-core kernel can serve these arguments (alignment / divisibility)
