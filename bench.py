@@ -22,6 +22,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA (published)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E (published)
+# Bytes per launch that the dominant kernel (ffn_gate_up) moves between L2 and the fabric, from two rocprofv3
+# counter runs (FETCH_SIZE, WRITE_SIZE) of this script scaled by the readings of a plain 1 GiB elementwise
+# kernel (--calibrate-copy); the summary with the commands is profiles/c2_ffn_gate_up_hbm_traffic.txt.
+# Counters cannot be read from inside this process, so workloads without a committed counter run report null.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"c2": 3.3608e9}
 
 
 def log(*a):
@@ -75,6 +80,10 @@ def main():
     ap.add_argument("--dense-steps", type=int, default=1, help="timed steps of the dense (skip=0) prefill; 0 = skip it")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096, help="0 = no cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket phases with events in the timed region")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first launch a plain elementwise kernel (dst = src + 1 over 2^28 floats: reads 1 GiB, writes 1 GiB) "
+                         "three times; under a counter-collecting profiler its FETCH_SIZE / WRITE_SIZE readings give the "
+                         "scale of those counters")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported (nothing here shards).")
@@ -87,6 +96,13 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     wl = synth.WORKLOADS[args.workload]
     if args.layers:
         ends = tuple(e for e in wl.stage_end_layers if e < args.layers)
@@ -154,7 +170,9 @@ def main():
         gu_ms = phases["ffn_gate_up"][0] / args.steps
         achieved = gate_up_flops / (gu_ms * 1e-3) / 1e12
         roofline = {"kernel": "gemm_mfma_kernel<EPI_SILU_MUL> (ffn_gate_up)", "bound": "mfma", "achieved": achieved,
-                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                    "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(wl.name) if not args.layers else None,
+                    "traffic_unit": "bytes per launch (L2 <-> fabric, counter-measured offline)",
                     "flops_per_step": gate_up_flops, "ms_per_step": gu_ms,
                     "launches_per_step": phases["ffn_gate_up"][1] / args.steps}
         # add derived rates for the other phases
