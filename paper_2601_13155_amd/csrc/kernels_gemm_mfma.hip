@@ -4,14 +4,16 @@
 // FFN and the low-rank proxy.  Both operands are K-contiguous, so MFMA fragments are plain 16-byte
 // LDS reads with no transposition.
 //
-//  * 256x256 output tile per workgroup, 4 wavefronts (2x2), each owning 128x128 = 4x4 MFMA
-//    32x32x16 blocks: 256 fp32 accumulators per lane (AGPRs), 16 MFMAs per 8 fragment reads.
-//  * K is consumed in slabs of 32.  Slabs travel global memory -> LDS directly
-//    (global_load_lds_dwordx4: no VGPR staging, no ds_write instructions) into a ring of 4 LDS
-//    stages (3 when a second A operand is staged), so the loads of slab k+3 are in flight while
-//    slab k is multiplied: ~1.3 us of memory latency are covered at full MFMA rate.  The wavefront
-//    counts its own outstanding slab loads with s_waitcnt vmcnt(n) and one workgroup barrier per
-//    slab publishes a landed slab and frees the stage consumed before it.
+//  * 256x256 output tile per workgroup, 8 wavefronts (4x2), each owning 64x128 = 2x4 MFMA
+//    32x32x16 blocks: 128 fp32 accumulators per lane, 8 MFMAs per 6 fragment reads, two wavefronts
+//    per SIMD so that one wavefront's LDS reads, waits and barriers hide behind the other's MFMAs.
+//  * K is consumed in slabs of 64 (32 when K is not a multiple of 64, or when a second A operand
+//    is staged).  Slabs travel global memory -> LDS directly (global_load_lds_dwordx4: no VGPR
+//    staging, no ds_write instructions) into a ring of 2 LDS stages of 64 KB (4 stages of 32 KB for
+//    slabs of 32, 3 with a second A operand): the loads of the next slab(s) are in flight while the
+//    current one is multiplied.  The wavefront counts its own outstanding slab loads with
+//    s_waitcnt vmcnt(n) and one workgroup barrier per slab publishes a landed slab and frees the
+//    stage consumed before it.
 //  * A direct-to-LDS load puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that makes the
 //    16-lane b128 fragment reads bank-conflict free is applied on the global side: lane i fetches
 //    the chunk that belongs at position i.
@@ -25,6 +27,12 @@
 //    of one row: 8-byte packed stores, lane-local rotary / SiLU-mul pairing, in-lane row sums.
 //  * Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous range
 //    of tiles in groups of 4 row panels: concurrently running tiles share A and B panels in L2.
+//  * One workgroup fits a CU, so tiles run in rounds of 256.  When the last round is partly filled
+//    its tiles are split over K (tail split-K): several workgroups each take a share of K, write
+//    fp32 partial tiles, and a small second kernel sums them and applies the epilogue.  A GEMM with
+//    fewer than 256 tiles is the special case without whole rounds.
+//  * The plain-store epilogue can take its B rows from two matrices (columns [0, N/2) from B0,
+//    [N/2, N) from B1): the two down-projections of the proxy run as one launch.
 //
 // Epilogues: plain store (+ optional transposed copy for V), rotary embedding (pairs (j, j+d/2) sit
 // in the same lane because an N block pair is d/2 apart), SiLU(gate)*up with gate and up columns
