@@ -4,7 +4,7 @@
 //
 // A softmax needs the full-row denominator before any probability can be averaged over rows, so
 // K is streamed twice:
-//   pass 1  per (kv head g, chunk of 512 keys): running (max, sum-exp) of every probe row of that
+//   pass 1  per (kv head g, chunk of 256 keys): running (max, sum-exp) of every probe row of that
 //           head group over the chunk  ->  stats_part[chunk][g][row]
 //   combine per (g, row): global max M and 1/sum over the chunks
 //   pass 2  per (g, chunk): logits again, p = exp2(s - M) / L summed over the rows of the group
@@ -21,7 +21,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int PKV = 64;          // keys per tile
-constexpr int CHUNK_TILES = 8;   // tiles per workgroup
+constexpr int CHUNK_TILES = 4;   // tiles per workgroup
 constexpr int CHUNK = PKV * CHUNK_TILES;
 
 template <int D> struct ProbeLds {
@@ -200,22 +200,31 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
     }
 }
 
-// stats[g][rr] = (M, 1/L) over the chunks; padded rows rr >= R get (huge, 0)
-__global__ void probe_combine_kernel(const float* __restrict__ stats_part, float* __restrict__ stats, int nchunks, int Hkv,
-                                     int Rp, int R) {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
+// stats[g][rr] = (M, 1/L) over the chunks; padded rows rr >= R get (huge, 0).  One wavefront per (g, rr):
+// lane c takes chunks c, c + 64, ...; maximum and sum are reduced over a fixed shuffle tree (deterministic).
+__global__ void __launch_bounds__(256) probe_combine_kernel(const float* __restrict__ stats_part, float* __restrict__ stats,
+                                                            int nchunks, int Hkv, int Rp, int R) {
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (i >= Hkv * Rp) return;
-    int g = i / Rp, rr = i % Rp;
-    if (rr >= R) { stats[2 * i] = 1e30f; stats[2 * i + 1] = 0.f; return; }   // padded rows weigh nothing
+    const int g = i / Rp, rr = i % Rp;
+    if (rr >= R) {   // padded rows weigh nothing
+        if (lane == 0) { stats[2 * i] = 1e30f; stats[2 * i + 1] = 0.f; }
+        return;
+    }
     float M = -INFINITY;
-    for (int c = 0; c < nchunks; ++c) M = fmaxf(M, stats_part[(((int64_t)c * Hkv + g) * Rp + rr) * 2]);
+    for (int c = lane; c < nchunks; c += 64) M = fmaxf(M, stats_part[(((int64_t)c * Hkv + g) * Rp + rr) * 2]);
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
     float Lsum = 0.f;
-    for (int c = 0; c < nchunks; ++c) {
+    for (int c = lane; c < nchunks; c += 64) {
         const float* s = stats_part + (((int64_t)c * Hkv + g) * Rp + rr) * 2;
         if (s[0] != -INFINITY) Lsum += s[1] * __builtin_amdgcn_exp2f(s[0] - M);
     }
-    stats[2 * i] = M;
-    stats[2 * i + 1] = Lsum > 0.f ? 1.0f / Lsum : 0.f;
+    for (int off = 32; off > 0; off >>= 1) Lsum += __shfl_xor(Lsum, off);
+    if (lane == 0) {
+        stats[2 * i] = M;
+        stats[2 * i + 1] = Lsum > 0.f ? 1.0f / Lsum : 0.f;
+    }
 }
 
 __global__ void probe_final_kernel(const float* __restrict__ part, float* __restrict__ S, int64_t N, int64_t Np, int Hkv,
@@ -259,7 +268,7 @@ static hipError_t launch_probe_t(const ProbeArgs& a, int Rp, hipStream_t s) {
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
     dim3 grid(nchunks, a.Hkv), block(256);
     probe_mfma_kernel<D, RB, 1><<<grid, block, 0, s>>>(b, Rp, Np, scale_log2e, stats_part, nullptr);
-    probe_combine_kernel<<<dim3((a.Hkv * Rp + 255) / 256), block, 0, s>>>(stats_part, stats, nchunks, a.Hkv, Rp, R);
+    probe_combine_kernel<<<dim3((a.Hkv * Rp + 3) / 4), block, 0, s>>>(stats_part, stats, nchunks, a.Hkv, Rp, R);
     probe_mfma_kernel<D, RB, 2><<<grid, block, 0, s>>>(b, Rp, Np, scale_log2e, nullptr, stats);
     probe_final_kernel<<<dim3((unsigned)((a.N + 255) / 256)), block, 0, s>>>(part, a.S, a.N, Np, a.Hkv, 1.0f / (float)(a.P * a.H));
     return hipGetLastError();

@@ -7,11 +7,16 @@
 //      LDS histogram per pass (integer LDS atomics: order-independent, hence deterministic) -> the
 //      exact key T of the k-th largest element, the number of keys above it, and how many keys equal
 //      to T are still needed (those are taken lowest index first: the tie rule).
+//      Scores of one layer are probabilities of similar magnitude, so almost all keys share their
+//      top bits and fall into one or two bins: lanes whose bin equals that of the wavefront's first
+//      active lane are counted with one ballot and a single atomic instead of 64 serialised ones.
 //   2. Ordered stream compaction without a per-chunk workgroup barrier: every wavefront owns one
 //      contiguous slice; a first sweep counts its (greater, equal) elements with ballots, a 16-entry
 //      LDS prefix gives each wavefront its output offsets, a second sweep ranks every element inside
 //      the wavefront with ballot + mbcnt (lane prefix popcount) and writes
 //      out[gt_before + min(eq_before, need_eq)].
+// Up to 32768 scores the keys are read once and stay in registers (KPT per lane, wavefront w holding
+// the contiguous slice [64*KPT*w, 64*KPT*(w+1))); longer inputs re-read the scores in every sweep.
 #include "spts_internal.h"
 
 namespace spts {
@@ -36,6 +41,113 @@ __device__ inline int lane_prefix_popc(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
+// hist[bin] += 1 for every active lane.  Lanes that share the bin of the first active lane are
+// counted by that lane alone (one atomic for the whole group); the others add for themselves.
+__device__ inline void hist_add(int* hist, bool active, int bin) {
+    const uint64_t act = __ballot(active);
+    if (act == 0) return;
+    const int first = __builtin_ctzll(act);
+    const int lead = __builtin_amdgcn_readlane(bin, first);
+    const bool same = active && bin == lead;
+    const uint64_t m = __ballot(same);
+    const int lane = threadIdx.x & 63;
+    if (lane == first) atomicAdd(&hist[lead], (int)__popcll(m));
+    else if (active && !same) atomicAdd(&hist[bin], 1);
+}
+
+// wavefront 0: from the 256-bin histogram and the rank `need` still wanted, the bin that holds the
+// need-th largest element of the current bucket; updates (prefix, need) in LDS
+__device__ inline void pick_bin(const int* hist, int lane, int shift, uint32_t prefix, int64_t need, uint32_t* sh_prefix,
+                                int64_t* sh_need) {
+    // bins in descending order: lane l owns bins 255-4l .. 252-4l
+    int c0 = hist[255 - 4 * lane], c1 = hist[254 - 4 * lane], c2 = hist[253 - 4 * lane], c3 = hist[252 - 4 * lane];
+    int64_t tot = (int64_t)c0 + c1 + c2 + c3;
+    int64_t incl = tot;
+    for (int off = 1; off < 64; off <<= 1) {
+        int64_t o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    int64_t excl = incl - tot;  // elements in bins above this lane's bins
+    if (excl < need && need <= incl) {
+        int64_t rem = need - excl;
+        int bin;
+        if (rem <= c0) { bin = 255 - 4 * lane; }
+        else if (rem <= (int64_t)c0 + c1) { bin = 254 - 4 * lane; rem -= c0; }
+        else if (rem <= (int64_t)c0 + c1 + c2) { bin = 253 - 4 * lane; rem -= (int64_t)c0 + c1; }
+        else { bin = 252 - 4 * lane; rem -= (int64_t)c0 + c1 + c2; }
+        *sh_prefix = prefix | ((uint32_t)bin << shift);
+        *sh_need = rem;
+    }
+}
+
+// Register-resident variant: N <= 1024 * KPT.  Lane keeps keys[j] = key of element lo + 64*j + lane,
+// lo = 64*KPT*wave; slots at or beyond N hold key 0 and are never written out.
+template <int KPT>
+__global__ void __launch_bounds__(TOPK_THREADS) topk_reg_kernel(const float* __restrict__ scores, int64_t N, int64_t k,
+                                                                int protect_last, int32_t* __restrict__ idx_out) {
+    __shared__ int hist[256];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int64_t sh_need;
+    __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int lo = wave * (64 * KPT);
+
+    uint32_t keys[KPT];
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int64_t i = lo + 64 * j + lane;
+        keys[j] = i < N ? load_key(scores, i, N, protect_last) : 0u;
+    }
+
+    if (tid == 0) { sh_prefix = 0; sh_need = k; }
+    uint32_t prefix = 0;
+    int64_t need = k;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const bool valid = lo + 64 * j + lane < N;
+            hist_add(hist, valid && (keys[j] & hi_mask) == prefix, (int)((keys[j] >> shift) & 0xFF));
+        }
+        __syncthreads();
+        if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
+        __syncthreads();
+        prefix = sh_prefix;
+        need = sh_need;
+    }
+    const uint32_t T = prefix;
+    const int need_eq = (int)need;
+
+    int cgt = 0, ceq = 0;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const bool valid = lo + 64 * j + lane < N;
+        cgt += (int)__popcll(__ballot(valid && keys[j] > T));
+        ceq += (int)__popcll(__ballot(valid && keys[j] == T));
+    }
+    if (lane == 0) { wave_gt[wave] = cgt; wave_eq[wave] = ceq; }
+    __syncthreads();
+    int gt_before = 0, eq_before = 0;
+    for (int w = 0; w < wave; ++w) { gt_before += wave_gt[w]; eq_before += wave_eq[w]; }
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int i = lo + 64 * j + lane;
+        const bool valid = i < N;
+        const bool gt = valid && keys[j] > T, eq = valid && keys[j] == T;
+        const uint64_t mgt = __ballot(gt), meq = __ballot(eq);
+        const int my_gt = gt_before + lane_prefix_popc(mgt);
+        const int my_eq = eq_before + lane_prefix_popc(meq);
+        if (gt || (eq && my_eq < need_eq)) idx_out[my_gt + (my_eq < need_eq ? my_eq : need_eq)] = i;
+        gt_before += (int)__popcll(mgt);
+        eq_before += (int)__popcll(meq);
+    }
+}
+
 __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restrict__ scores, int64_t N, int64_t k,
                                                             int protect_last, int32_t* __restrict__ idx_out) {
     __shared__ int hist[256];
@@ -56,32 +168,14 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restr
         const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
-        for (int64_t i = tid; i < N; i += TOPK_THREADS) {
-            uint32_t key = load_key(scores, i, N, protect_last);
-            if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xFF], 1);
+        // every lane runs the same number of rounds (hist_add uses wavefront-wide ballots)
+        for (int64_t base = 0; base < N; base += TOPK_THREADS) {
+            const int64_t i = base + tid;
+            uint32_t key = i < N ? load_key(scores, i, N, protect_last) : 0u;
+            hist_add(hist, i < N && (key & hi_mask) == prefix, (int)((key >> shift) & 0xFF));
         }
         __syncthreads();
-        if (wave == 0) {
-            // bins in descending order: lane l owns bins 255-4l .. 252-4l
-            int c0 = hist[255 - 4 * lane], c1 = hist[254 - 4 * lane], c2 = hist[253 - 4 * lane], c3 = hist[252 - 4 * lane];
-            int64_t tot = (int64_t)c0 + c1 + c2 + c3;
-            int64_t incl = tot;
-            for (int off = 1; off < 64; off <<= 1) {
-                int64_t o = __shfl_up(incl, off);
-                if (lane >= off) incl += o;
-            }
-            int64_t excl = incl - tot;  // elements in bins above this lane's bins
-            if (excl < need && need <= incl) {
-                int64_t rem = need - excl;
-                int bin;
-                if (rem <= c0) { bin = 255 - 4 * lane; }
-                else if (rem <= (int64_t)c0 + c1) { bin = 254 - 4 * lane; rem -= c0; }
-                else if (rem <= (int64_t)c0 + c1 + c2) { bin = 253 - 4 * lane; rem -= (int64_t)c0 + c1; }
-                else { bin = 252 - 4 * lane; rem -= (int64_t)c0 + c1 + c2; }
-                sh_prefix = prefix | ((uint32_t)bin << shift);
-                sh_need = rem;
-            }
-        }
+        if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
         __syncthreads();
         prefix = sh_prefix;
         need = sh_need;
@@ -125,7 +219,11 @@ hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_la
                        hipStream_t s) {
     (void)scratch;
     if (k <= 0 || N <= 0) return hipSuccess;
-    topk_kernel<<<dim3(1), dim3(TOPK_THREADS), 0, s>>>(scores, N, k, protect_last, idx_out);
+    const dim3 g(1), b(TOPK_THREADS);
+    if (N <= 1024 * 8) topk_reg_kernel<8><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
+    else if (N <= 1024 * 16) topk_reg_kernel<16><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
+    else if (N <= 1024 * 32) topk_reg_kernel<32><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
+    else topk_kernel<<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
     return hipGetLastError();
 }
 

@@ -32,7 +32,8 @@ def ctx_for(shape, max_tokens, max_probe=128, max_r=256, max_dlow=None):
 
 # ------------------------------------------------------------------------------------------ TopK
 def _topk_cases(rng):
-    for n in (1, 2, 63, 64, 65, 1000, 1024, 1025, 5000, 32768, 40000, 131072):
+    # sizes straddle the register-resident variants of the kernel (8, 16, 32 keys per lane x 1024 lanes)
+    for n in (1, 2, 63, 64, 65, 1000, 1024, 1025, 5000, 8192, 8193, 16384, 16385, 22937, 32768, 32769, 40000, 131072):
         yield "uniform", rng.random(n).astype(np.float32)
         yield "all_equal", np.full(n, 0.5, dtype=np.float32)
         z = rng.random(n).astype(np.float32); z[rng.random(n) < 0.7] = 0.0
@@ -41,6 +42,8 @@ def _topk_cases(rng):
         e = np.exp(-rng.random(n) * 100).astype(np.float32); e[::7] = -0.0
         yield "softmax_like_signed_zero", e
         yield "tiny_denormal", (rng.random(n) * 1e-44).astype(np.float32)
+        # probabilities of similar magnitude (what a probe produces): nearly all keys share their top bits
+        yield "probability_like", ((1.0 + 0.3 * rng.standard_normal(n)).clip(0.05, None) / n).astype(np.float32)
 
 
 def test_select_topk_bit_exact(torch):
