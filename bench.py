@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--dense-steps", type=int, default=1, help="timed steps of the dense (skip=0) prefill; 0 = skip it")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096, help="0 = no cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket phases with events in the timed region")
+    ap.add_argument("--topk-batch", type=int, default=2048,
+                    help="rows of the batched TopK micro-benchmark (rows x 131072 fp32 scores; 0 = skip it)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first launch a plain elementwise kernel (dst = src + 1 over 2^28 floats: reads 1 GiB, writes 1 GiB) "
                          "three times; under a counter-collecting profiler its FETCH_SIZE / WRITE_SIZE readings give the "
@@ -194,6 +196,22 @@ def main():
         probe_bytes = sum(item["N"] * shape.Hkv * shape.d * b + 4.0 * item["N"] for item in plan)
         if "probe_attn" in phase_out:
             phase_out["probe_attn"]["gbs"] = probe_bytes / (phase_out["probe_attn"]["ms_per_step"] * 1e-3) / 1e9
+        # TopK (two per layer): scores in, indices out.  K-hat / position gather: rows read and written.
+        topk_bytes = sum(8.0 * item["N"] + 4.0 * (min(item["N"], item["m_attn"]) + min(item["N"], item["m_ffn"]))
+                         for item in plan)
+        if "topk" in phase_out:
+            phase_out["topk"]["gbs"] = topk_bytes / (phase_out["topk"]["ms_per_step"] * 1e-3) / 1e9
+        gather_bytes = sum(min(item["N"], item["m_attn"]) * (2.0 * shape.Hkv * shape.d * b + 12.0) for item in plan)
+        if "gather" in phase_out:
+            phase_out["gather"]["gbs"] = gather_bytes / (phase_out["gather"]["ms_per_step"] * 1e-3) / 1e9
+        comp_bytes = sum(cm.compact_bytes(shape.D, item["N"], item["N_next"], b) for item in plan if item["N_next"] is not None)
+        if "compact" in phase_out and phase_out["compact"]["ms_per_step"] > 0:
+            phase_out["compact"]["gbs"] = comp_bytes / (phase_out["compact"]["ms_per_step"] * 1e-3) / 1e9
+        for v in phase_out.values():
+            if "gbs" in v:
+                v["hbm_frac"] = v["gbs"] / PEAK_HBM_GBS
+            if "tflops" in v:
+                v["mfma_frac"] = v["tflops"] / PEAK_BF16_TFLOPS
 
     # ---- dense prefill of the same stack through the same library (skip = 0 on every layer)
     dense = None
@@ -205,6 +223,29 @@ def main():
         dense = {"ms_per_step": dms, "tokens_per_s": wl.N / (dms * 1e-3), "speedup_spts_over_dense": dms / ms,
                  "tflops": dflops / (dms * 1e-3) / 1e12, "steps": args.dense_steps}
         log(f"[dense] {dms:.2f} ms/step -> SPTS speedup {dms / ms:.2f}x")
+
+    # ---- batched TopK: one workgroup per row, so the whole chip streams scores (a single row is latency-bound)
+    topk_batched = None
+    if args.topk_batch > 0:
+        tn, tb = 131072, args.topk_batch
+        tk = int(0.4 * tn)
+        tctx = runtime.make_context(synth.TINY, tn, 1, 1, synth.TINY.Dff)
+        sc = torch.rand((tb, tn), dtype=torch.float32, device="cuda")
+        ti = torch.empty((tb, tk), dtype=torch.int32, device="cuda")
+        tctx.spts_select_topk_batched(sc, tn, tk, 1, tb, ti)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            tctx.spts_select_topk_batched(sc, tn, tk, 1, tb, ti)
+        e1.record()
+        torch.cuda.synchronize()
+        tms = e0.elapsed_time(e1) / 3
+        tbytes = tb * (4.0 * tn + 4.0 * tk)
+        topk_batched = {"rows": tb, "N": tn, "k": tk, "ms": tms, "gbs": tbytes / (tms * 1e-3) / 1e9,
+                        "hbm_frac": tbytes / (tms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                        "note": "algorithmic bytes (scores once + indices) / time; the kernel reads the scores six times"}
+        del sc, ti, tctx
 
     cpu = None
     if args.cpu_sample_tokens > 0:
@@ -223,7 +264,7 @@ def main():
                    "weight_pool": pool, "batch": 1},
         "algorithmic_tflop_per_step": total_flops / 1e12,
         "achieved_tflops_whole_step": total_flops / (ms * 1e-3) / 1e12,
-        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out,
+        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched,
     }
     print(json.dumps(out), flush=True)
 

@@ -136,6 +136,13 @@ int spts_probe_ffn(spts_ctx *ctx, const void *x, int64_t N, const spts_layer_wei
 int spts_select_topk(spts_ctx *ctx, const float *scores, int64_t N, int64_t k, int32_t protect_last,
                      int32_t *idx_out);
 
+/* TopK over `batch` independent score rows (Sec. 3.2 TopK applied per sequence of a batch):
+ * scores [batch, N] row-major, idx_out [batch, k], every row selected and ordered as by
+ * spts_select_topk.  0 <= batch <= 65535, N <= the context's max_tokens (as for the single-row
+ * call), 0 <= k <= N.  Device pointers, 16-byte aligned; the call uses no workspace. */
+int spts_select_topk_batched(spts_ctx *ctx, const float *scores, int64_t N, int64_t k,
+                             int32_t protect_last, int32_t batch, int32_t *idx_out);
+
 /* One decoder layer of Alg. 1 in place on x [N, D] (PAP block then LTP block, or the dense
  * branches when cfg->skip == 0).  Optional outputs (NULL = not wanted): kv, s_mha [N],
  * idx_attn [min(N, m_attn)], idx_ffn [min(N, m_ffn)].  With skip == 0 the optional score/index

@@ -61,7 +61,12 @@ template <int BK> struct Slab {
 };
 
 __device__ inline uint32_t pack_bf16x2(float a, float b) { return cvt_pk_bf16(a, b); }
-__device__ inline float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+// SiLU with the hardware exponential and reciprocal (about 1 ulp each in fp32; the result is rounded to
+// bf16): an IEEE division would cost ten more instructions per element, which shows in the short-K
+// proxy GEMM whose epilogue is a quarter of the tile time
+__device__ inline float silu_f(float g) {
+    return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+}
 
 // tile number -> (row tile, column tile): grouped raster, GM row tiles per group, rows fastest inside
 // a group, so that workgroups running together share A and B tiles in L2

@@ -90,6 +90,8 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_reg_kernel(const float* __r
     __shared__ int64_t sh_need;
     __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
 
+    scores += (int64_t)blockIdx.x * N;   // one independent problem per workgroup
+    idx_out += (int64_t)blockIdx.x * k;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int lo = wave * (64 * KPT);
@@ -155,6 +157,8 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restr
     __shared__ int64_t sh_need;        // how many elements are still to be taken inside the current bucket
     __shared__ int64_t wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
 
+    scores += (int64_t)blockIdx.x * N;   // one independent problem per workgroup
+    idx_out += (int64_t)blockIdx.x * k;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
 
@@ -215,11 +219,10 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restr
     }
 }
 
-hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out, int32_t* scratch,
+hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out, int batch,
                        hipStream_t s) {
-    (void)scratch;
-    if (k <= 0 || N <= 0) return hipSuccess;
-    const dim3 g(1), b(TOPK_THREADS);
+    if (k <= 0 || N <= 0 || batch <= 0) return hipSuccess;
+    const dim3 g((unsigned)batch), b(TOPK_THREADS);
     if (N <= 1024 * 8) topk_reg_kernel<8><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
     else if (N <= 1024 * 16) topk_reg_kernel<16><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
     else if (N <= 1024 * 32) topk_reg_kernel<32><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);

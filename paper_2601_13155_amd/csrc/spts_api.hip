@@ -390,7 +390,19 @@ int spts_select_topk(spts_ctx* c, const float* scores, int64_t N, int64_t k, int
     if (!scores || !idx_out) return SPTS_EINVAL;
     if (!aligned16(scores) || !aligned16(idx_out)) return SPTS_EALIGN;
     PHASE(c, PH_TOPK);
-    SPTS_HIP(c, launch_topk(scores, N, k, protect_last, idx_out, c->p<int32_t>(c->off.misc), c->stream));
+    SPTS_HIP(c, launch_topk(scores, N, k, protect_last, idx_out, 1, c->stream));
+    return SPTS_OK;
+}
+
+int spts_select_topk_batched(spts_ctx* c, const float* scores, int64_t N, int64_t k, int32_t protect_last, int32_t batch,
+                             int32_t* idx_out) {
+    SPTS_TRY(common_call_checks(c, N));
+    if (k < 0 || k > N || batch < 0 || batch > 65535) return SPTS_EINVAL;
+    if (k == 0 || batch == 0) return SPTS_OK;
+    if (!scores || !idx_out) return SPTS_EINVAL;
+    if (!aligned16(scores) || !aligned16(idx_out)) return SPTS_EALIGN;
+    PHASE(c, PH_TOPK);
+    SPTS_HIP(c, launch_topk(scores, N, k, protect_last, idx_out, batch, c->stream));
     return SPTS_OK;
 }
 
@@ -415,7 +427,7 @@ int spts_msdp_compact(spts_ctx* c, const void* x_in, const int32_t* pos_in, cons
     PHASE(c, PH_COMPACT);
     if (map_old2new) SPTS_HIP(c, launch_fill_i32(map_old2new, -1, N, c->stream));
     if (keep == 0) return SPTS_OK;
-    SPTS_HIP(c, launch_topk(s_mha, N, keep, protect_last, map_new2old, c->p<int32_t>(c->off.misc), c->stream));
+    SPTS_HIP(c, launch_topk(s_mha, N, keep, protect_last, map_new2old, 1, c->stream));
     const int64_t row_bytes = (int64_t)c->m.D * (c->bf16 ? 2 : 4);
     SPTS_HIP(c, launch_gather_rows(x_in, map_new2old, x_out, keep, row_bytes, c->stream));
     SPTS_HIP(c, launch_gather_i32(pos_in, map_new2old, pos_out, keep, c->stream));
@@ -465,7 +477,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
     if (skip) {
         idxA = idx_attn ? idx_attn : c->p<int32_t>(c->off.idxA);
         PHASE(c, PH_TOPK);
-        SPTS_HIP(c, launch_topk(S, N, Ma, cfg->protect_last, idxA, c->p<int32_t>(c->off.misc), st));
+        SPTS_HIP(c, launch_topk(S, N, Ma, cfg->protect_last, idxA, 1, st));
     }
     if (Ma > 0) {
         // queries of the active rows (rows gathered through idxA inside the GEMM's A loads)
@@ -528,7 +540,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         SPTS_TRY(proxy_scores_impl(c, xn, N, w, S, nullptr, SF));
         idxF = idx_ffn ? idx_ffn : c->p<int32_t>(c->off.idxF);
         PHASE(c, PH_TOPK);
-        SPTS_HIP(c, launch_topk(SF, N, Mf, cfg->protect_last, idxF, c->p<int32_t>(c->off.misc), st));
+        SPTS_HIP(c, launch_topk(SF, N, Mf, cfg->protect_last, idxF, 1, st));
     }
     GemmArgs gh = gemm_args(xn, m.D, idxF, w->Wgate, m.D, c->p<void>(c->off.big), m.Dff, Mf, m.Dff, m.D, EPI_SILU_MUL);
     gh.B1 = w->Wup;

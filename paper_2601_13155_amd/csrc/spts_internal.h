@@ -115,9 +115,9 @@ hipError_t launch_finish_ffn_scores(const float* part, int nparts, const float* 
 hipError_t launch_transpose_pad(const void* v, void* vt, int64_t M, int C, int64_t ldvt, bool bf16, hipStream_t s);
 
 // ------------------------------------------------------------------ TopK
-// idx_out[0..k) ascending.  scratch: >= 64 int32.
+// `batch` independent problems: scores [batch, N] -> idx_out [batch, k], every row ascending.
 hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out,
-                       int32_t* scratch, hipStream_t s);
+                       int batch, hipStream_t s);
 
 // ------------------------------------------------------------------ attention
 struct AttnArgs {

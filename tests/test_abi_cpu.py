@@ -63,6 +63,9 @@ def test_workspace_and_create_validation(lib):
         assert lib.spts_select_topk(h, A + 4, 100, 10, 0, A) == binding.SPTS_EALIGN
         assert lib.spts_select_topk(h, None, 100, 10, 0, A) == binding.SPTS_EINVAL
         assert lib.spts_select_topk(h, A, 513, 10, 0, A) == binding.SPTS_EWORKSPACE       # N > max_tokens
+        assert lib.spts_select_topk_batched(h, A, 100, 10, 0, -1, A) == binding.SPTS_EINVAL
+        assert lib.spts_select_topk_batched(h, A, 100, 101, 0, 2, A) == binding.SPTS_EINVAL
+        assert lib.spts_select_topk_batched(h, A, 100, 10, 0, 0, None) == binding.SPTS_OK  # empty batch
         w = binding.spts_layer_weights()
         assert lib.spts_probe_attn(h, A, A, 100, C.byref(w), 8, A, A) == binding.SPTS_EINVAL      # null weights
         w.Wq = w.Wk = w.gamma1 = A

@@ -84,6 +84,21 @@ def test_select_topk_deterministic_and_nested(torch):
         prev = cur
 
 
+def test_select_topk_batched_rows_match_oracle(torch):
+    rng = np.random.default_rng(2)
+    ctx = ctx_for(synth.TINY, 131072)
+    for n, batch in ((1000, 7), (8193, 5), (40000, 3)):
+        s = ((1.0 + 0.3 * rng.standard_normal((batch, n))).clip(0.05, None) / n).astype(np.float32)
+        s[1, ::3] = s[1, 0]   # a row with many ties
+        sd = torch.from_numpy(s).cuda()
+        for k in (1, int(0.4 * n), n):
+            out = torch.full((batch, k), -7, dtype=torch.int32, device="cuda")
+            ctx.spts_select_topk_batched(sd, n, k, 1, batch, out)
+            got = out.cpu().numpy()
+            for b in range(batch):
+                assert np.array_equal(got[b], orc.topk_select(s[b], k, 1)), (n, k, b)
+
+
 # ------------------------------------------------------------------------------------------ MSDP
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_msdp_compact_bit_exact(torch, dtype):
