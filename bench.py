@@ -47,7 +47,9 @@ def cpu_baseline(wl, w_host, sample_tokens, layers_equiv):
     x = synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype)[:n]
     pos = synth.positions(n)
     mdl = orc.Model(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, shape.rms_eps, shape.rope_base)
-    cfg = orc.LayerCfg(1, min(wl.probe_len, n), int(wl.attn_keep * n), int(wl.ffn_keep * n), wl.protect_last, 0)
+    first_skip = next(it for it in wl.layer_plan() if it.get("skip", 1))   # budgets of the first skip layer, scaled to n
+    ka, kf = first_skip["m_attn"] / first_skip["N"], first_skip["m_ffn"] / first_skip["N"]
+    cfg = orc.LayerCfg(1, min(wl.probe_len, n), int(ka * n), int(kf * n), wl.protect_last, 0)
     t0 = time.perf_counter()
     orc.layer_prefill(x, pos, w_host, mdl, cfg, rnd=orc.bf16_round if shape.dtype == "bf16" else orc.identity,
                       score_cast=orc.f32_round)
@@ -61,7 +63,7 @@ def cpu_baseline(wl, w_host, sample_tokens, layers_equiv):
     return {
         "value": n / (dt * layers_equiv), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
         "sample": (f"oracle.layer_prefill (numpy fp64, bf16-faithful rounding) on ONE skip layer over the first {n} "
-                   f"tokens of the workload input (keep {wl.attn_keep}/{wl.ffn_keep}, P={min(wl.probe_len, n)}, r={wl.r}): "
+                   f"tokens of the workload input (keep {ka:.3f}/{kf:.3f}, P={min(wl.probe_len, n)}, r={wl.r}): "
                    f"{dt:.2f} s; tokens/s extrapolated as {n} / ({dt:.2f} s x {layers_equiv} layers), i.e. ignoring "
                    f"both the MSDP shrink and the growth of attention cost with length"),
         "seconds_one_layer": dt,
@@ -73,7 +75,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "p32"],
+                    help="c2 = the configuration the metric is quoted on; p32 = the paper's own LLaMA schedule at 32K")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's)")
     ap.add_argument("--weight-pool", type=int, default=2,
                     help="distinct synthetic weight sets; layers cycle through them (bounds set-up time)")
@@ -111,20 +114,20 @@ def main():
         wl = synth.scaled(wl, layers=args.layers, stage_end_layers=ends, stage_cum_keep=wl.stage_cum_keep[:len(ends) + 1])
     shape = wl.shape
     plan = wl.layer_plan()
-    Dlow = shape.Dff
+    Dlow = wl.proxy_dlow
 
     t_setup = time.perf_counter()
     pool = max(1, min(args.weight_pool, wl.layers))
     host_sets, dev_sets = [], []
     for i in range(pool):
-        w = synth.make_layer(wl.seed, i, shape, wl.r)
-        dev_sets.append(runtime.upload_layer(w, shape, wl.r))
+        w = synth.make_layer(wl.seed, i, shape, wl.r, wl.dlow, wl.r_pad)
+        dev_sets.append(runtime.upload_layer(w, shape, wl.proxy_r))
         host_sets.append(w if i == 0 else None)
         log(f"[setup] weight set {i + 1}/{pool} ready ({time.perf_counter() - t_setup:.1f} s)")
     layers = [dev_sets[l % pool] for l in range(wl.layers)]
     x0 = runtime.to_device(synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype), shape.dtype)
     pos0 = torch.from_numpy(synth.positions(wl.N)).cuda()
-    ctx = runtime.make_context(shape, wl.N, wl.probe_len, wl.r, Dlow)
+    ctx = runtime.make_context(shape, wl.N, wl.probe_len, wl.proxy_r, Dlow)
     assert ctx.uses_mfma(), "matrix-core kernels are not serving this workload"
     runner = runtime.StackRunner(ctx, shape, layers, plan, wl.probe_len, wl.protect_last, skip=1)
     log(f"[setup] done in {time.perf_counter() - t_setup:.1f} s; workload {wl.name}: N={wl.N}, layers={wl.layers}")
@@ -158,10 +161,19 @@ def main():
     # ---- algorithmic work of the timed region
     flops_by = {}
     for item in plan:
-        f = cm.layer_flops(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, item["N"], wl.probe_len,
-                           min(item["N"], item["m_attn"]), min(item["N"], item["m_ffn"]), wl.r, Dlow, True)
+        if item.get("skip", 1):
+            f = cm.layer_flops(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, item["N"], wl.probe_len,
+                               min(item["N"], item["m_attn"]), min(item["N"], item["m_ffn"]), wl.r, Dlow, True)
+        else:   # dense layer of the schedule: same phases, all tokens, no probe / proxy
+            f = cm.layer_flops(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, item["N"], wl.probe_len,
+                               item["N"], item["N"], wl.r, Dlow, False)
+            qkv = f.pop("qkv_proj")
+            f["k_proj"] = qkv * shape.Hkv / (shape.H + 2 * shape.Hkv)
+            f["qv_proj"] = qkv - f["k_proj"]
         for k, v in f.items():
             flops_by[k] = flops_by.get(k, 0.0) + v
+    for k in ("probe_q", "probe_attn", "proxy"):
+        flops_by.setdefault(k, 0.0)
     total_flops = sum(flops_by.values())
     gate_up_flops = flops_by["ffn"] * 2.0 / 3.0   # gate + up projections of the gathered rows
     roofline = None
@@ -193,15 +205,16 @@ def main():
         norm_bytes = sum(2 * 2.0 * item["N"] * shape.D * b for item in plan)
         if "rmsnorm" in phase_out:
             phase_out["rmsnorm"]["gbs"] = norm_bytes / (phase_out["rmsnorm"]["ms_per_step"] * 1e-3) / 1e9
-        probe_bytes = sum(item["N"] * shape.Hkv * shape.d * b + 4.0 * item["N"] for item in plan)
+        probe_bytes = sum(item["N"] * shape.Hkv * shape.d * b + 4.0 * item["N"] for item in plan if item.get("skip", 1))
         if "probe_attn" in phase_out:
             phase_out["probe_attn"]["gbs"] = probe_bytes / (phase_out["probe_attn"]["ms_per_step"] * 1e-3) / 1e9
         # TopK (two per layer): scores in, indices out.  K-hat / position gather: rows read and written.
         topk_bytes = sum(8.0 * item["N"] + 4.0 * (min(item["N"], item["m_attn"]) + min(item["N"], item["m_ffn"]))
-                         for item in plan)
+                         for item in plan if item.get("skip", 1))
         if "topk" in phase_out:
             phase_out["topk"]["gbs"] = topk_bytes / (phase_out["topk"]["ms_per_step"] * 1e-3) / 1e9
-        gather_bytes = sum(min(item["N"], item["m_attn"]) * (2.0 * shape.Hkv * shape.d * b + 12.0) for item in plan)
+        gather_bytes = sum(min(item["N"], item["m_attn"]) * (2.0 * shape.Hkv * shape.d * b + 12.0) for item in plan
+                           if item.get("skip", 1))
         if "gather" in phase_out:
             phase_out["gather"]["gbs"] = gather_bytes / (phase_out["gather"]["ms_per_step"] * 1e-3) / 1e9
         comp_bytes = sum(cm.compact_bytes(shape.D, item["N"], item["N_next"], b) for item in plan if item["N_next"] is not None)
@@ -253,13 +266,15 @@ def main():
         log(f"[cpu] oracle layer on {min(args.cpu_sample_tokens, wl.N)} tokens: {cpu['seconds_one_layer']:.2f} s")
 
     out = {
-        "metric": "SPTS prefill tokens/s (TTFT = ms_per_step) at %dK, %s-shaped, 1 GPU" % (wl.N // 1024,
-                  "LLaMA-3.1-8B" if shape.D == 4096 else "Qwen2.5-7B"),
+        "metric": "SPTS prefill tokens/s (TTFT = ms_per_step) at %dK, %s-shaped, 1 GPU%s" % (
+            wl.N // 1024, "LLaMA-3.1-8B" if shape.D == 4096 else "Qwen2.5-7B",
+            " (the paper's own schedule)" if wl.stage_budgets else ""),
         "value": wl.N / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "ttft_ms": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "seq_len": wl.N, "layers": wl.layers, "probe_len": wl.probe_len,
                    "attn_keep": wl.attn_keep, "ffn_keep": wl.ffn_keep, "proxy_rank": wl.r, "proxy_dlow": Dlow,
+                   "dense_layers": wl.dense_layers, "stage_budgets": list(wl.stage_budgets), "stage_prune": wl.stage_prune,
                    "stage_end_layers": list(wl.stage_end_layers), "stage_cum_keep": list(wl.stage_cum_keep),
                    "weight_pool": pool, "batch": 1},
         "algorithmic_tflop_per_step": total_flops / 1e12,

@@ -362,16 +362,18 @@ def msdp_compact(x: Array, pos: Array, s_mha: Array, N_next: int, protect_last: 
 
 def stack_prefill(x: Array, pos: Array, layers, mdl: Model, plan, probe_len: int,
                   protect_last: int = 1, skip: int = 1, rnd=identity, score_cast=identity):
-    """Alg. 1 outer loop: ``layers[l]`` weights, ``plan[l]`` = dict(m_attn, m_ffn, N_next|None)."""
+    """Alg. 1 outer loop: ``layers[l]`` weights, ``plan[l]`` = dict(m_attn, m_ffn, N_next|None[, skip])."""
     x = np.array(x, dtype=np.float64, copy=True)
     pos = np.array(pos, copy=True)
     trace = []
     for w, item in zip(layers, plan):
-        cfg = LayerCfg(skip=skip, probe_len=probe_len, m_attn=item["m_attn"], m_ffn=item["m_ffn"],
+        # a plan item may mark its layer dense (the paper's schedule keeps the first layers dense)
+        skip_l = 1 if (skip and item.get("skip", 1)) else 0
+        cfg = LayerCfg(skip=skip_l, probe_len=probe_len, m_attn=item["m_attn"], m_ffn=item["m_ffn"],
                        protect_last=protect_last)
         lo = layer_prefill(x, pos, w, mdl, cfg, rnd, score_cast)
         x = lo.x
-        if skip and item.get("N_next") is not None:
+        if skip_l and item.get("N_next") is not None:
             x, pos, new2old, _ = msdp_compact(x, pos, lo.s_mha, item["N_next"], protect_last)
             lo.map_new2old = new2old
         trace.append(lo)

@@ -95,7 +95,8 @@ class StackRunner:
         self.trace = []
         self.cfgs = []
         for item in plan:
-            self.cfgs.append(binding.spts_layer_cfg(skip, probe_len, item["m_attn"], item["m_ffn"], protect_last, 0))
+            skip_l = 1 if (skip and item.get("skip", 1)) else 0   # a plan item may mark its layer dense
+            self.cfgs.append(binding.spts_layer_cfg(skip_l, probe_len, item["m_attn"], item["m_ffn"], protect_last, 0))
 
     def run(self, x0, pos0):
         """x0 [N0, D] device tensor (copied, not modified), pos0 [N0] int32 device tensor.
@@ -117,7 +118,7 @@ class StackRunner:
             if tr is not None:
                 tr["x_out"] = xa[:N].clone()
                 tr["s_mha"] = self.s[:N].clone()
-            if self.skip and item.get("N_next") is not None:
+            if cfg.skip and item.get("N_next") is not None:
                 n_next = min(N, item["N_next"])
                 self.ctx.spts_msdp_compact(xa, pa, self.s, N, n_next, self.protect_last, xb, pb, self.new2old, None)
                 if tr is not None:

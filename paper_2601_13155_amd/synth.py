@@ -68,27 +68,53 @@ class Workload:
     stage_end_layers: Tuple[int, ...] = ()
     stage_cum_keep: Tuple[float, ...] = (1.0,)
     protect_last: int = 1
+    # The paper's own schedule (Sec. 4.1, implementation details) instead of ratios: the first
+    # `dense_layers` layers run dense; stage s then uses the absolute budget stage_budgets[s] for both
+    # branches, and every stage end removes `stage_prune` candidates.  Empty stage_budgets = ratios.
+    dense_layers: int = 0
+    stage_budgets: Tuple[int, ...] = ()
+    stage_prune: int = 0
+    # proxy: Dlow channels of the FFN (0 = all Dff), rank r zero-padded to r_pad columns (0 = no padding)
+    dlow: int = 0
+    r_pad: int = 0
 
     def stage_sizes(self) -> List[int]:
-        """Candidate counts N_s = floor(cum_keep_s * N_0)."""
+        """Candidate counts per stage: floor(cum_keep_s * N_0), or N_0 - s * stage_prune."""
+        if self.stage_budgets:
+            return [max(0, self.N - s * self.stage_prune) for s in range(len(self.stage_end_layers) + 1)]
         return [int(math.floor(c * self.N + 1e-9)) for c in self.stage_cum_keep]
 
     def layer_plan(self) -> List[dict]:
-        """Per layer: candidate count, budgets and the compaction target (or None)."""
+        """Per layer: skip flag, candidate count, budgets and the compaction target (or None)."""
         sizes = self.stage_sizes()
         plan = []
         s = 0
         for l in range(1, self.layers + 1):
             n = sizes[s]
-            item = dict(layer=l, N=n,
-                        m_attn=int(math.floor(self.attn_keep * n + 1e-9)),
-                        m_ffn=int(math.floor(self.ffn_keep * n + 1e-9)),
-                        N_next=None)
+            if l <= self.dense_layers:
+                item = dict(layer=l, N=n, m_attn=n, m_ffn=n, N_next=None, skip=0)
+            elif self.stage_budgets:
+                b = min(n, self.stage_budgets[s])
+                item = dict(layer=l, N=n, m_attn=b, m_ffn=b, N_next=None, skip=1)
+            else:
+                item = dict(layer=l, N=n,
+                            m_attn=int(math.floor(self.attn_keep * n + 1e-9)),
+                            m_ffn=int(math.floor(self.ffn_keep * n + 1e-9)),
+                            N_next=None, skip=1)
             if s < len(self.stage_end_layers) and l == self.stage_end_layers[s]:
                 item["N_next"] = sizes[s + 1]
                 s += 1
             plan.append(item)
         return plan
+
+    @property
+    def proxy_r(self) -> int:
+        """Rank of the stored proxy factors (the true rank r, or its zero-padded size)."""
+        return self.r_pad if self.r_pad else self.r
+
+    @property
+    def proxy_dlow(self) -> int:
+        return self.dlow if self.dlow else self.shape.Dff
 
 
 LLAMA8B = ModelShape(D=4096, H=32, Hkv=8, d=128, Dff=14336, rms_eps=1e-5, rope_base=500000.0, dtype="bf16")
@@ -103,6 +129,13 @@ WORKLOADS: Dict[str, Workload] = {
     "c3": Workload("c3", LLAMA8B, N=131072, layers=4, probe_len=128, attn_keep=0.25, ffn_keep=0.3, r=256, seed=3),
     "c4": Workload("c4", QWEN7B, N=32768, layers=28, probe_len=64, attn_keep=0.4, ffn_keep=0.4, r=256, seed=4,
                    stage_end_layers=(7, 14, 21), stage_cum_keep=(1.0, 0.7, 0.5, 0.35)),
+    # The paper's LLaMA schedule at 32K (Sec. 4.1): layers 1-10 dense, then (4, 5, 5, 5, 3) layers with active
+    # budgets (9, 7, 4, 2, 1)K, 1K candidates pruned at each of the four stage ends, single-row probe,
+    # (Dlow, r) = (512, 192).  The fifth budget is the one the KV-cache table of Sec. 4.3 implies.  The rank-192
+    # factors are stored zero-padded to 256 columns (identical result; 256 is what the matrix-core tiles divide).
+    "p32": Workload("p32", LLAMA8B, N=32768, layers=32, probe_len=1, attn_keep=0.0, ffn_keep=0.0, r=192, seed=5,
+                    stage_end_layers=(14, 19, 24, 29), dense_layers=10,
+                    stage_budgets=(9216, 7168, 4096, 2048, 1024), stage_prune=1024, dlow=512, r_pad=256),
 }
 
 
@@ -207,19 +240,34 @@ def truncated_svd(W: np.ndarray, r: int) -> Tuple[np.ndarray, np.ndarray]:
     return U, U.T @ W64
 
 
-def proxy_factors(weights: Dict[str, np.ndarray], r: int, dtype: str) -> Dict[str, np.ndarray]:
-    """Ug,Vg,Uu,Vu,Ud,Vd with W_gate ~= Ug Vg, W_up ~= Uu Vu, W_down ~= Ud Vd (Dlow = Dff)."""
+def proxy_channels(seed: int, layer: int, Dff: int, dlow: int) -> np.ndarray:
+    """The Dlow FFN channels the proxy keeps, ascending.  A seeded random subset: it stands in for the
+    calibration-based channel selection of Eq. (channel_importance), which needs text activations."""
+    if not dlow or dlow >= Dff:
+        return np.arange(Dff)
+    return np.sort(_gen(seed, 7000 + layer).choice(Dff, size=dlow, replace=False))
+
+
+def proxy_factors(weights: Dict[str, np.ndarray], r: int, dtype: str, channels: Optional[np.ndarray] = None,
+                  r_pad: int = 0) -> Dict[str, np.ndarray]:
+    """Ug,Vg,Uu,Vu,Ud,Vd with W_gate[:, ch] ~= Ug Vg, W_up[:, ch] ~= Uu Vu, W_down[:, ch] ~= Ud Vd
+    (ch = all channels unless given).  r_pad > r appends zero columns / rows (same products)."""
     out: Dict[str, np.ndarray] = {}
     for tag, name in (("g", "Wgate"), ("u", "Wup"), ("d", "Wdown")):
-        U, V = truncated_svd(weights[name], r)
+        W = weights[name] if channels is None else np.ascontiguousarray(weights[name][:, channels])
+        U, V = truncated_svd(W, r)
+        if r_pad and r_pad > r:
+            U = np.concatenate([U, np.zeros((U.shape[0], r_pad - r), U.dtype)], axis=1)
+            V = np.concatenate([V, np.zeros((r_pad - r, V.shape[1]), V.dtype)], axis=0)
         out["U" + tag] = storage_round(U.astype(np.float32), dtype)
         out["V" + tag] = storage_round(V.astype(np.float32), dtype)
     return out
 
 
-def make_layer(seed: int, layer: int, shape: ModelShape, r: int) -> Dict[str, np.ndarray]:
+def make_layer(seed: int, layer: int, shape: ModelShape, r: int, dlow: int = 0, r_pad: int = 0) -> Dict[str, np.ndarray]:
     w = layer_weights(seed, layer, shape)
-    w.update(proxy_factors(w, r, shape.dtype))
+    ch = proxy_channels(seed, layer, shape.Dff, dlow) if dlow else None
+    w.update(proxy_factors(w, r, shape.dtype, ch, r_pad))
     return w
 
 

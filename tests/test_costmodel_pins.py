@@ -45,6 +45,23 @@ def test_kv_cache_memory_table():
         assert abs((1.0 - ratio) * 100.0 - float(saving)) < 0.06
 
 
+def test_paper_schedule_plan_reproduces_the_cache_table():
+    """The layer plan of the paper-schedule workload (the object the stack driver executes) caches the
+    same number of tokens as the closed form behind the KV-cache table, at every length of the table."""
+    from paper_2601_13155_amd import synth
+    K = 1024
+    for ctx in (4, 8, 12, 16):
+        wl = synth.scaled(synth.WORKLOADS["p32"], N=ctx * K)
+        plan = wl.layer_plan()
+        assert len(plan) == 32 and sum(1 - it["skip"] for it in plan) == 10
+        cached = sum(min(it["N"], it["m_attn"]) for it in plan)
+        assert cached == cm.kv_cached_tokens(ctx * K, dense_layers=10, stage_layers=(4, 5, 5, 5, 3),
+                                             budgets=(9 * K, 7 * K, 4 * K, 2 * K, 1 * K), prune_per_stage=K)
+    # 32K (beyond the table): 6.625 of 16 parts cached
+    plan = synth.WORKLOADS["p32"].layer_plan()
+    assert sum(min(it["N"], it["m_attn"]) for it in plan) / (32.0 * 32768) == 6.625 / 16
+
+
 def test_layer_flops_matches_hand_count():
     # 8B-shaped layer at N = 8192, keep 0.4, P = 64, r = 256, Dlow = Dff
     f = cm.layer_flops(4096, 32, 8, 128, 14336, 8192, 64, 3276, 3276, 256, 14336)

@@ -222,3 +222,26 @@ def test_c3_long_sequence_properties():
     assert H.row_rel_err(gpu["k_cache"][sel].reshape(len(sel), -1), k_ref.reshape(len(sel), -1)) <= H.TOL["bf16"]["hidden"]
     assert np.array_equal(gpu["pos_cache"], pos[gpu["idx_attn"]]) and gpu["kv_count"] == item["m_attn"]
     torch.cuda.empty_cache()
+
+
+def test_paper_schedule_layer_lockstep():
+    """An 8B-shaped skip layer with the paper's own settings (Sec. 4.1): single-row probe, absolute budget,
+    proxy on Dlow = 512 channels with rank 192 stored zero-padded to 256; N = 8192, matrix-core kernels."""
+    import torch
+    wl = synth.WORKLOADS["p32"]
+    shape = wl.shape
+    w = synth.make_layer(wl.seed, 11, shape, wl.r, wl.dlow, wl.r_pad)
+    assert w["Vg"].shape == (256, 512) and w["Vd"].shape == (256, 512)
+    dw = runtime.upload_layer(w, shape, wl.proxy_r)
+    ctx = ctx_for(32768)
+    N, budget = 8192, 2304
+    x = synth.hidden_states(wl.seed, N, shape.D, shape.dtype)
+    pos = synth.positions(N)
+    gpu = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=1, m_attn=budget, m_ffn=budget, protect_last=1)
+    cfg = orc.LayerCfg(1, 1, budget, budget, 1, 0)
+    res = H.lockstep_layer(gpu, x, pos, w, H.oracle_model(shape), cfg, shape.dtype)
+    print(f"p32 layer: swaps attn={res['swaps_attn']} ffn={res['swaps_ffn']} hidden err={res['err']:.3e}")
+    assert res["swaps_attn"] <= budget // 50 and res["swaps_ffn"] <= budget // 50
+    assert np.array_equal(gpu["idx_attn"], orc.topk_select(gpu["s_mha"], budget, 1))
+    del dw
+    torch.cuda.empty_cache()

@@ -292,3 +292,38 @@ def test_stack_with_msdp_lockstep(torch, dtype):
             _, rp, rn2o, _ = orc.msdp_compact(gpu["x"], pos_in, gpu["s_mha"], item["N_next"], 1)
             assert np.array_equal(tr["map_new2old"].cpu().numpy(), rn2o)
     assert po[-1].item() == wl.N - 1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stack_paper_schedule_lockstep(torch, dtype):
+    """The paper's own schedule in miniature (Sec. 4.1): dense first layers, absolute budgets per stage,
+    a fixed number of candidates pruned at every stage end, single-row probe, proxy on a channel subset
+    (Dlow < Dff) with a zero-padded rank."""
+    shape = synth.TINY if dtype == "f32" else synth.ModelShape(D=256, H=4, Hkv=2, d=64, Dff=688, dtype="bf16")
+    wl = synth.scaled(synth.WORKLOADS["p32"], shape=shape, N=500, layers=6, dense_layers=2, stage_end_layers=(3, 4, 5),
+                      stage_budgets=(200, 150, 100, 50), stage_prune=30, r=12, r_pad=16, dlow=256)
+    plan = wl.layer_plan()
+    assert [it["skip"] for it in plan] == [0, 0, 1, 1, 1, 1] and [it["N"] for it in plan] == [500, 500, 500, 470, 440, 410]
+    ws = [synth.make_layer(wl.seed, l, shape, wl.r, wl.dlow, wl.r_pad) for l in range(wl.layers)]
+    assert ws[0]["Vg"].shape == (16, 256) and not ws[0]["Ug"][:, 12:].any()
+    dws = [runtime.upload_layer(w, shape, wl.proxy_r) for w in ws]
+    ctx = ctx_for(shape, 2048)
+    runner = runtime.StackRunner(ctx, shape, dws, plan, wl.probe_len, keep_trace=True)
+    x0 = synth.hidden_states(wl.seed, wl.N, shape.D, dtype)
+    pos0 = synth.positions(wl.N)
+    xo, po, n_final = runner.run(runtime.to_device(x0, dtype), torch.from_numpy(pos0).cuda())
+    torch.cuda.synchronize()
+    assert n_final == 410
+    mdl = H.oracle_model(shape)
+    for tr, item, w in zip(runner.trace, plan, ws):
+        N = tr["N"]
+        x_in = runtime.to_host(tr["x_in"]); pos_in = tr["pos_in"].cpu().numpy()
+        gpu = dict(x=runtime.to_host(tr["x_out"]).astype(np.float64), s_mha=tr["s_mha"].cpu().numpy(),
+                   idx_attn=tr["idx_attn"][:min(N, item["m_attn"])].cpu().numpy(),
+                   idx_ffn=tr["idx_ffn"][:min(N, item["m_ffn"])].cpu().numpy())
+        cfg = orc.LayerCfg(item["skip"], wl.probe_len, item["m_attn"], item["m_ffn"], 1, 0)
+        H.lockstep_layer(gpu, x_in, pos_in, w, mdl, cfg, dtype)
+        if item["N_next"] is not None:
+            _, rp, rn2o, _ = orc.msdp_compact(gpu["x"], pos_in, gpu["s_mha"], item["N_next"], 1)
+            assert np.array_equal(tr["map_new2old"].cpu().numpy(), rn2o)
+    assert po[-1].item() == wl.N - 1
