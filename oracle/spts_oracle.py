@@ -50,6 +50,17 @@ matrix; full-rank proxy == exact FFN norm; TopK against a stable sort;
 permutation invariance with positions attached; FFN token independence.
 Numerical values of scores/selected sets on real text are not printed anywhere
 in the paper: parity unpinned for those (only the properties above pin them).
+
+Decode phase (Alg. 1 with ``skip`` false because ``Is_prefill_phase`` is false;
+Sec. 3.2 last paragraph and Appendix "KV Cache flexibility" for what the cache
+holds): ``decode_layer`` / ``decode_step`` run one new token through the dense
+branches over each layer's cache of active key/value pairs and append the
+token's own pair; ``greedy_token`` is a final norm, a vocabulary projection and
+an argmax (a synthetic head: the vocabulary table is not part of the method).
+Pins (tests/test_oracle_decode_pins.py): dense prefill of N+1 tokens == dense
+prefill of N tokens + one decode step (last row and caches); attention over the
+cache against a loop-by-loop softmax; invariance under a permutation of the
+cache rows; argmax tie rule.
 """
 from __future__ import annotations
 
@@ -378,3 +389,57 @@ def stack_prefill(x: Array, pos: Array, layers, mdl: Model, plan, probe_len: int
             lo.map_new2old = new2old
         trace.append(lo)
     return x, pos, trace
+
+
+# ------------------------------------------------------------------------------------------------
+# Decode phase over the per-layer caches left by the prefill
+# ------------------------------------------------------------------------------------------------
+@dataclass
+class LayerCache:
+    """Key/value pairs one layer holds: k, v [M, Hkv, d] (keys post-rotary), pos [M] absolute."""
+    k: Array
+    v: Array
+    pos: Array
+
+
+def decode_layer(x_t: Array, pos_t: int, w: Dict[str, Array], mdl: Model, cache: LayerCache, rnd=identity):
+    """One decoder layer for one new token in the decode phase (Alg. 1 else-branches: standard MHA
+    with residual, the cache is updated; standard FFN).  x_t [D]; returns (x_out [D], new cache).
+
+    The token's rotary key and its value join the cache first; its query then attends to every
+    cached pair (all cached positions are <= pos_t, so the causal mask hides nothing).
+    """
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    x = rnd(np.array(x_t, dtype=np.float64, copy=True)).reshape(1, -1)
+    p = np.array([pos_t])
+    xn = rnd(rmsnorm(x, w["gamma1"], mdl.rms_eps))
+    k_new = project_keys(xn, p, w["Wk"], mdl, rnd)
+    v_new = rnd((xn @ f64(w["Wv"])).reshape(1, mdl.Hkv, mdl.d))
+    q = project_queries(xn, p, w["Wq"], mdl, rnd)
+    kk = np.concatenate([f64(cache.k), k_new], axis=0)
+    vv = np.concatenate([f64(cache.v), v_new], axis=0)
+    kpos = np.concatenate([np.asarray(cache.pos), p])
+    att = rnd(causal_attention(q, kk, vv, p, kpos, mdl)).reshape(1, mdl.H * mdl.d)
+    x = rnd(x + att @ f64(w["Wo"]))
+    xn2 = rnd(rmsnorm(x, w["gamma2"], mdl.rms_eps))
+    x = rnd(x + ffn(xn2, w["Wgate"], w["Wup"], w["Wdown"], rnd))
+    return x[0], LayerCache(kk, vv, kpos)
+
+
+def decode_step(x_t: Array, pos_t: int, layers, mdl: Model, caches, rnd=identity):
+    """All layers for one new token: returns (final hidden state [D], list of updated caches)."""
+    x = np.asarray(x_t, dtype=np.float64)
+    out = []
+    for w, c in zip(layers, caches):
+        x, c2 = decode_layer(x, pos_t, w, mdl, c, rnd)
+        out.append(c2)
+    return x, out
+
+
+def greedy_token(h: Array, gamma_f: Array, table: Array, mdl: Model, rnd=identity, logit_cast=identity):
+    """Final RMSNorm, logits against the vocabulary table [V, D], argmax with ties to the lowest
+    token id.  Returns (token, logits [V]); ``logit_cast`` is applied before the decision."""
+    hn = rnd(rmsnorm(np.asarray(h, dtype=np.float64).reshape(1, -1), gamma_f, mdl.rms_eps))
+    logits = logit_cast((hn @ np.asarray(table, dtype=np.float64).T)[0])
+    best = np.flatnonzero(logits == np.max(logits))
+    return int(best[0]), logits
