@@ -151,6 +151,25 @@ int spts_layer_prefill(spts_ctx *ctx, void *x, const int32_t *pos, int64_t N,
                        const spts_layer_weights *w, const spts_layer_cfg *cfg, spts_kv_out *kv,
                        float *s_mha, int32_t *idx_attn, int32_t *idx_ffn);
 
+/* Decode phase of Alg. 1 for one new token (Is_prefill_phase() is false, so skip is false: standard
+ * MHA with residual and cache update, standard FFN).  x [D] in/out: the token's hidden state.
+ * The token's rotary key and its value are written to row cache->count of the cache (Sec. 3.2 last
+ * paragraph and the appendix on KV-cache flexibility: the cache holds the prefill's active pairs plus
+ * the decoded tokens), attention runs over rows [0, count], then cache->count is incremented on the
+ * host.  `pos` is the token's absolute position (prefill length + decode step).  Needs
+ * count < capacity, H / Hkv <= 8, d in {16, 32, 64, 128}, D, H*d, Hkv*d and Dff multiples of 4
+ * (SPTS_ESHAPE otherwise).  Uses the context's workspace; device pointers, 16-byte aligned. */
+int spts_decode_layer(spts_ctx *ctx, void *x, int32_t pos, const spts_layer_weights *w,
+                      spts_kv_out *cache);
+
+/* Greedy next token after the last layer: RMSNorm with gamma_f [D], logits = table [V, D] applied
+ * to the normed state (fp32), token = argmax with ties to the lowest id.  The vocabulary table is a
+ * harness input (the method does not define one); it also serves as the embedding: x_next [D]
+ * receives table[token, :] when not NULL.  token_out: device int32.  logits_out [V] fp32 may be
+ * NULL (then the workspace must hold V floats: SPTS_EWORKSPACE otherwise).  V % 4 == 0. */
+int spts_greedy_token(spts_ctx *ctx, const void *x, const void *gamma_f, const void *table,
+                      int32_t V, int32_t *token_out, float *logits_out, void *x_next);
+
 /* Stage-end pruning (Sec. 3.4, Eq. (stage_prune); Alg. 1 last block): keeps the
  * N' = min(N, N_next) candidates with the largest s_mha.  Out of place: x_out [N', D],
  * pos_out [N'], map_new2old [N'] (ascending), map_old2new [N] (-1 for dropped rows; may be NULL).

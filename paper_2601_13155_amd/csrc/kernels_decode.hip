@@ -1,0 +1,412 @@
+// Decode phase over the per-layer KV caches left by the token-skipped prefill (Alg. 1 with
+// Is_prefill_phase() false: both branches dense for the one new token; Sec. 3.2 last paragraph and
+// the appendix on KV-cache flexibility say what a cache holds: the active pairs of the prefill plus
+// every decoded token's pair).
+//
+// One token means every contraction is a matrix-vector product whose cost is reading the weights
+// once, so the whole step is HBM-bound (8B-shaped model: 13.9 GB of bf16 weights per token):
+//   * gemv_kernel: y = W x with W [R, K] row-major.  A workgroup of 4 wavefronts owns 4 rows (2 gate
+//     + 2 up rows for the SwiGLU variant) and splits K across its 256 lanes in 16-byte chunks, so
+//     8 (16) independent 16-byte weight loads per lane are in flight before the first use; bf16
+//     pairs are multiplied with v_dot2c_f32_bf16 (fp32 accumulate, no conversion instructions).
+//     Lanes reduce by shuffles, wavefronts through LDS.  Up to three matrices that share x run as
+//     one launch (Q, K, V).  Epilogues: store, SiLU(gate)*up, residual add, fp32 store (logits).
+//   * decode_attn_kernel: flash-decoding.  Grid = (key splits, KV heads); 64/LPK keys per wavefront
+//     step (LPK lanes hold one key row as 16-byte pieces), every lane group keeps its own running
+//     (max, sum, weighted values) for all query heads of the KV head; groups, wavefronts and splits
+//     are merged with the usual (max, sum) algebra in a fixed order (deterministic).
+//   * small kernels: rotary embedding of q / k for the new position + cache append, merge of the
+//     splits, argmax with ties to the lowest token id, table row gather.
+#include "spts_internal.h"
+
+namespace spts {
+
+typedef __bf16 hbf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes of T against 16 bytes of T, accumulated in fp32.  The bf16 pairs are taken out of the
+// 8-element vector with constant shuffles (written out: indexing the dwords in a loop and
+// bit-casting each made the compiler read element 0 four times).
+typedef __bf16 hbf16x8 __attribute__((ext_vector_type(8)));
+__device__ inline float dot16(u32x4 w, u32x4 x, float acc, bf16_t) {
+    const hbf16x8 a = __builtin_bit_cast(hbf16x8, w), b = __builtin_bit_cast(hbf16x8, x);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(b, b, 0, 1), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(b, b, 2, 3), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(b, b, 4, 5), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(b, b, 6, 7), acc, false);
+    return acc;
+}
+__device__ inline float dot16(u32x4 w, u32x4 x, float acc, float) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc = fmaf(__uint_as_float(w[i]), __uint_as_float(x[i]), acc);
+    return acc;
+}
+// element e of a 16-byte chunk as fp32
+__device__ inline float chunk_elem(u32x4 v, int e, bf16_t) {
+    const uint32_t w = v[e >> 1];
+    return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+}
+__device__ inline float chunk_elem(u32x4 v, int e, float) { return __uint_as_float(v[e]); }
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------- GEMV
+template <typename T, int MODE>
+__global__ void __launch_bounds__(256) gemv_kernel(GemvArgs a) {
+    constexpr int EPC = 16 / (int)sizeof(T);          // elements per 16-byte chunk
+    constexpr int ROWS = 4;                           // dot products per workgroup
+    __shared__ float sred[4][ROWS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // rows of this workgroup: ROWS consecutive rows of one matrix, or (SiLU) 2 gate rows + the same 2 up rows
+    const T* wrow[ROWS];
+    int64_t out_row;      // first output element of this workgroup
+    int which = 0;        // matrix the rows belong to
+    if (MODE == GEMV_SILU) {
+        out_row = (int64_t)blockIdx.x * 2;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r)
+            wrow[r] = (const T*)(r < 2 ? a.W[0] : a.W[1]) + (out_row + (r & 1)) * a.K;
+    } else {
+        int64_t row = (int64_t)blockIdx.x * ROWS;
+        if (row >= a.R[0]) { row -= a.R[0]; which = 1; if (row >= a.R[1]) { row -= a.R[1]; which = 2; } }
+        out_row = row;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) wrow[r] = (const T*)a.W[which] + (row + r) * a.K;
+    }
+
+    const int nchunks = a.K / EPC;
+    const T* x = (const T*)a.x;
+    float acc[ROWS] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int c = tid; c < nchunks; c += 256) {
+        const u32x4 xv = *reinterpret_cast<const u32x4*>(x + (int64_t)c * EPC);
+        u32x4 wv[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) wv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow[r] + (int64_t)c * EPC));
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) acc[r] = dot16(wv[r], xv, acc[r], T{});
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        acc[r] = wave_sum(acc[r]);
+        if (lane == 0) sred[wave][r] = acc[r];
+    }
+    __syncthreads();
+    if (tid >= ROWS) return;
+    const float v = sred[0][tid] + sred[1][tid] + sred[2][tid] + sred[3][tid];
+    if (MODE == GEMV_SILU) {
+        if (tid < 2) {
+            const float g = v;
+            const float u = sred[0][tid + 2] + sred[1][tid + 2] + sred[2][tid + 2] + sred[3][tid + 2];
+            const float h = g / (1.0f + __expf(-g)) * u;
+            ((T*)a.y[0])[out_row + tid] = from_f32<T>(h);
+        }
+    } else if (MODE == GEMV_RESID) {
+        T* y = (T*)a.y[which] + out_row + tid;
+        *y = from_f32<T>(to_f32(*y) + v);
+    } else if (MODE == GEMV_F32) {
+        ((float*)a.y[which])[out_row + tid] = v;
+    } else {
+        ((T*)a.y[which])[out_row + tid] = from_f32<T>(v);
+    }
+}
+
+bool gemv_supported(const GemvArgs& a, bool bf16) {
+    const int epc = bf16 ? 8 : 4;
+    if (a.K <= 0 || a.K % epc != 0) return false;
+    for (int i = 0; i < 3; ++i) {
+        if (a.R[i] < 0 || a.R[i] % 4 != 0) return false;
+        if (a.R[i] > 0 && (!a.W[i] || (reinterpret_cast<uintptr_t>(a.W[i]) & 15u))) return false;
+    }
+    if (!a.x || (reinterpret_cast<uintptr_t>(a.x) & 15u)) return false;
+    return true;
+}
+
+template <typename T>
+static hipError_t launch_gemv_t(const GemvArgs& a, hipStream_t s) {
+    const int64_t rows = (int64_t)a.R[0] + a.R[1] + a.R[2];
+    if (rows == 0) return hipSuccess;
+    const dim3 b(256);
+    switch (a.mode) {
+        case GEMV_STORE: gemv_kernel<T, GEMV_STORE><<<dim3((unsigned)(rows / 4)), b, 0, s>>>(a); break;
+        case GEMV_SILU: gemv_kernel<T, GEMV_SILU><<<dim3((unsigned)(a.R[0] / 2)), b, 0, s>>>(a); break;
+        case GEMV_RESID: gemv_kernel<T, GEMV_RESID><<<dim3((unsigned)(rows / 4)), b, 0, s>>>(a); break;
+        case GEMV_F32: gemv_kernel<T, GEMV_F32><<<dim3((unsigned)(rows / 4)), b, 0, s>>>(a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s) {
+    return bf16 ? launch_gemv_t<bf16_t>(a, s) : launch_gemv_t<float>(a, s);
+}
+
+// ------------------------------------------------------------------- rotary + cache append
+// q [H, d] is rotated in place for position pos; k [Hkv, d] is rotated and written, with v, to row
+// `row` of the cache; cache_pos[row] = pos.  Angles in fp64 like the prefill's rotary table.
+template <typename T>
+__global__ void decode_rope_append_kernel(T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, int pos,
+                                          int H, int Hkv, int d, double neg2_over_d_log2base, T* __restrict__ cache_k,
+                                          T* __restrict__ cache_v, int32_t* __restrict__ cache_pos, int64_t row) {
+    const int half = d / 2;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) cache_pos[row] = pos;
+    if (i >= (H + Hkv) * half) return;
+    const int head = i / half, j = i % half;
+    double sn, cs;
+    sincos((double)pos * exp2((double)j * neg2_over_d_log2base), &sn, &cs);
+    const float c = (float)cs, s = (float)sn;
+    if (head < H) {
+        T* p = q + (int64_t)head * d + j;
+        const float a = to_f32(p[0]), b = to_f32(p[half]);
+        p[0] = from_f32<T>(a * c - b * s);
+        p[half] = from_f32<T>(b * c + a * s);
+    } else {
+        const int g = head - H;
+        const T* p = k + (int64_t)g * d + j;
+        const float a = to_f32(p[0]), b = to_f32(p[half]);
+        T* o = cache_k + (row * Hkv + g) * (int64_t)d + j;
+        o[0] = from_f32<T>(a * c - b * s);
+        o[half] = from_f32<T>(b * c + a * s);
+        T* ov = cache_v + (row * Hkv + g) * (int64_t)d + j;
+        const T* pv = v + (int64_t)g * d + j;
+        ov[0] = pv[0];
+        ov[half] = pv[half];
+    }
+}
+
+hipError_t launch_decode_rope_append(void* q, const void* k, const void* v, int pos, int H, int Hkv, int d, float base,
+                                     void* cache_k, void* cache_v, int32_t* cache_pos, int64_t row, bool bf16, hipStream_t s) {
+    const int n = (H + Hkv) * (d / 2);
+    const double kk = -2.0 / (double)d * log2((double)base);
+    const dim3 g((unsigned)((n + 255) / 256)), b(256);
+    if (bf16)
+        decode_rope_append_kernel<bf16_t><<<g, b, 0, s>>>((bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, pos, H, Hkv, d, kk,
+                                                          (bf16_t*)cache_k, (bf16_t*)cache_v, cache_pos, row);
+    else
+        decode_rope_append_kernel<float><<<g, b, 0, s>>>((float*)q, (const float*)k, (const float*)v, pos, H, Hkv, d, kk,
+                                                        (float*)cache_k, (float*)cache_v, cache_pos, row);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------- decode attention
+// partial layout: part[((g * nsplit + split) * GRP_MAX + hg) * (d + 2)] = (max, sum, weighted values[d])
+constexpr int GRP_MAX = 8;
+
+template <typename T, int D>
+__global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ q, const T* __restrict__ K,
+                                                          const T* __restrict__ V, int64_t M, int H, int Hkv, float scale_log2e,
+                                                          float* __restrict__ part) {
+    constexpr int EPC = 16 / (int)sizeof(T);
+    constexpr int LPK = D / EPC;          // lanes that hold one key row
+    constexpr int KPW = 64 / LPK;         // keys per wavefront step
+    __shared__ float sm[4][GRP_MAX][2];
+    __shared__ float sacc[4][GRP_MAX][D];
+
+    const int split = blockIdx.x, nsplit = gridDim.x, g = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane % LPK, kslot = lane / LPK;
+    const int grp = H / Hkv;
+    const int64_t per = (M + nsplit - 1) / nsplit;
+    const int64_t m_begin = (int64_t)split * per;
+    const int64_t m_end = m_begin + per < M ? m_begin + per : M;
+
+    // this lane's piece of every query head of the group
+    u32x4 qv[GRP_MAX];
+#pragma unroll
+    for (int hg = 0; hg < GRP_MAX; ++hg) {
+        const int h = g * grp + (hg < grp ? hg : 0);
+        qv[hg] = *reinterpret_cast<const u32x4*>(q + (int64_t)h * D + sub * EPC);
+    }
+    float mrun[GRP_MAX], lrun[GRP_MAX], acc[GRP_MAX][EPC];
+#pragma unroll
+    for (int hg = 0; hg < GRP_MAX; ++hg) {
+        mrun[hg] = -INFINITY; lrun[hg] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[hg][e] = 0.f;
+    }
+
+    for (int64_t m0 = m_begin + wave * KPW; m0 < m_end; m0 += 4 * KPW) {
+        const int64_t m = m0 + kslot;
+        const bool valid = m < m_end;
+        const int64_t mc = valid ? m : m_end - 1;
+        const u32x4 kv = *reinterpret_cast<const u32x4*>(K + (mc * Hkv + g) * (int64_t)D + sub * EPC);
+        const u32x4 vv = *reinterpret_cast<const u32x4*>(V + (mc * Hkv + g) * (int64_t)D + sub * EPC);
+#pragma unroll
+        for (int hg = 0; hg < GRP_MAX; ++hg) {
+            if (hg < grp) {
+                float s = dot16(kv, qv[hg], 0.f, T{});
+#pragma unroll
+                for (int off = 1; off < LPK; off <<= 1) s += __shfl_xor(s, off);
+                s = valid ? s * scale_log2e : -INFINITY;
+                const float mn = fmaxf(mrun[hg], s);
+                const float mu = mn == -INFINITY ? 0.f : mn;
+                const float alpha = __builtin_amdgcn_exp2f(mrun[hg] - mu);
+                const float p = __builtin_amdgcn_exp2f(s - mu);
+                lrun[hg] = lrun[hg] * alpha + p;
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) acc[hg][e] = acc[hg][e] * alpha + p * chunk_elem(vv, e, T{});
+                mrun[hg] = mn;
+            }
+        }
+    }
+    // merge the KPW lane groups of the wavefront (lanes with equal `sub`)
+#pragma unroll
+    for (int hg = 0; hg < GRP_MAX; ++hg) {
+        if (hg < grp) {
+#pragma unroll
+            for (int off = LPK; off < 64; off <<= 1) {
+                const float mo = __shfl_xor(mrun[hg], off), lo = __shfl_xor(lrun[hg], off);
+                const float mn = fmaxf(mrun[hg], mo);
+                const float mu = mn == -INFINITY ? 0.f : mn;
+                const float a0 = __builtin_amdgcn_exp2f(mrun[hg] - mu), a1 = __builtin_amdgcn_exp2f(mo - mu);
+                lrun[hg] = lrun[hg] * a0 + lo * a1;
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) acc[hg][e] = acc[hg][e] * a0 + __shfl_xor(acc[hg][e], off) * a1;
+                mrun[hg] = mn;
+            }
+            if (kslot == 0) {
+                if (sub == 0) { sm[wave][hg][0] = mrun[hg]; sm[wave][hg][1] = lrun[hg]; }
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) sacc[wave][hg][sub * EPC + e] = acc[hg][e];
+            }
+        }
+    }
+    __syncthreads();
+    // merge the 4 wavefronts: thread t < grp * D handles (hg, element)
+    for (int t = tid; t < grp * D; t += 256) {
+        const int hg = t / D, e = t % D;
+        float mn = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mn = fmaxf(mn, sm[w][hg][0]);
+        const float mu = mn == -INFINITY ? 0.f : mn;
+        float l = 0.f, o = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float aw = __builtin_amdgcn_exp2f(sm[w][hg][0] - mu);
+            l += sm[w][hg][1] * aw;
+            o += sacc[w][hg][e] * aw;
+        }
+        float* dst = part + (((int64_t)g * nsplit + split) * GRP_MAX + hg) * (D + 2);
+        if (e == 0) { dst[0] = mn; dst[1] = l; }
+        dst[2 + e] = o;
+    }
+}
+
+// out[h, e] = sum over splits of the weighted values / sum of sums
+template <typename T>
+__global__ void decode_attn_merge_kernel(const float* __restrict__ part, int nsplit, int H, int Hkv, int D, T* __restrict__ out) {
+    const int h = blockIdx.x, e = threadIdx.x;
+    if (e >= D) return;
+    const int grp = H / Hkv, g = h / grp, hg = h % grp;
+    const float* base = part + ((int64_t)g * nsplit * GRP_MAX + hg) * (D + 2);
+    const int64_t stride = (int64_t)GRP_MAX * (D + 2);
+    float mn = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) mn = fmaxf(mn, base[s * stride]);
+    const float mu = mn == -INFINITY ? 0.f : mn;
+    float l = 0.f, o = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        const float a = __builtin_amdgcn_exp2f(base[s * stride] - mu);
+        l += base[s * stride + 1] * a;
+        o += base[s * stride + 2 + e] * a;
+    }
+    out[(int64_t)h * D + e] = from_f32<T>(l > 0.f ? o / l : 0.f);
+}
+
+// number of key splits: enough workgroups to fill 256 CUs a few times over, at least 64 keys each,
+// and no more than the scratch buffer (scratch_floats) holds
+int decode_attn_splits(int64_t M, int Hkv, int d, size_t scratch_floats) {
+    int64_t s = 1024 / (Hkv > 0 ? Hkv : 1);
+    if (s > (M + 63) / 64) s = (M + 63) / 64;
+    const int64_t cap = (int64_t)(scratch_floats / ((size_t)Hkv * GRP_MAX * (d + 2)));
+    if (s > cap) s = cap;
+    if (s > 256) s = 256;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+size_t decode_attn_min_scratch_floats(int Hkv, int d) { return (size_t)Hkv * GRP_MAX * (d + 2); }
+
+bool decode_attn_supported(int H, int Hkv, int d, bool bf16) {
+    (void)bf16;
+    if (Hkv <= 0 || H % Hkv != 0 || H / Hkv > GRP_MAX) return false;
+    return d == 16 || d == 32 || d == 64 || d == 128;
+}
+
+template <typename T>
+static hipError_t launch_decode_attn_t(const T* q, const T* K, const T* V, int64_t M, int H, int Hkv, int d, float* part,
+                                       size_t part_floats, T* out, hipStream_t s) {
+    const int nsplit = decode_attn_splits(M, Hkv, d, part_floats);
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
+    const dim3 g((unsigned)nsplit, (unsigned)Hkv), b(256);
+    switch (d) {
+        case 128: decode_attn_kernel<T, 128><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part); break;
+        case 64: decode_attn_kernel<T, 64><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part); break;
+        case 32: decode_attn_kernel<T, 32><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part); break;
+        case 16: decode_attn_kernel<T, 16><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part); break;
+        default: return hipErrorInvalidValue;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    decode_attn_merge_kernel<T><<<dim3((unsigned)H), dim3((unsigned)((d + 63) / 64 * 64)), 0, s>>>(part, nsplit, H, Hkv, d, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_attn(const void* q, const void* K, const void* V, int64_t M, int H, int Hkv, int d, float* part,
+                              size_t part_floats, void* out, bool bf16, hipStream_t s) {
+    if (M <= 0 || part_floats < decode_attn_min_scratch_floats(Hkv, d)) return hipErrorInvalidValue;
+    if (bf16)
+        return launch_decode_attn_t<bf16_t>((const bf16_t*)q, (const bf16_t*)K, (const bf16_t*)V, M, H, Hkv, d, part, part_floats,
+                                            (bf16_t*)out, s);
+    return launch_decode_attn_t<float>((const float*)q, (const float*)K, (const float*)V, M, H, Hkv, d, part, part_floats, (float*)out, s);
+}
+
+// ------------------------------------------------------------------------------ greedy head
+// token = argmax of logits [V], ties to the lowest id; one workgroup
+__global__ void __launch_bounds__(1024) argmax_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ token) {
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < V; i += 1024) {
+        const float v = logits[i];
+        if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(best, off);
+        const int oi = __shfl_xor(bi, off);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sv[wave] = best; si[wave] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w)
+            if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+        *token = bi == 0x7fffffff ? 0 : bi;
+    }
+}
+
+template <typename T>
+__global__ void table_row_kernel(const T* __restrict__ table, const int32_t* __restrict__ token, int D, T* __restrict__ out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < D) out[i] = table[(int64_t)(*token) * D + i];
+}
+
+hipError_t launch_argmax_row(const float* logits, int V, int32_t* token, const void* table, int D, void* x_next, bool bf16,
+                             hipStream_t s) {
+    argmax_kernel<<<dim3(1), dim3(1024), 0, s>>>(logits, V, token);
+    if (x_next) {
+        const dim3 g((unsigned)((D + 255) / 256)), b(256);
+        if (bf16) table_row_kernel<bf16_t><<<g, b, 0, s>>>((const bf16_t*)table, token, D, (bf16_t*)x_next);
+        else table_row_kernel<float><<<g, b, 0, s>>>((const float*)table, token, D, (float*)x_next);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace spts

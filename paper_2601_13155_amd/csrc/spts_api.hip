@@ -89,11 +89,13 @@ struct spts_ctx {
 enum PhaseId {
     PH_ROPE_TABLE = 0, PH_RMSNORM, PH_K_PROJ, PH_PROBE_Q, PH_PROBE_ATTN, PH_TOPK, PH_GATHER, PH_Q_PROJ, PH_V_PROJ,
     PH_ATTENTION, PH_O_PROJ, PH_PROXY_IN, PH_PROXY_MID, PH_PROXY_Z, PH_PROXY_OUT, PH_FFN_GATE_UP, PH_FFN_DOWN,
-    PH_COMPACT, PH_COUNT
+    PH_COMPACT, PH_DEC_NORM, PH_DEC_QKV, PH_DEC_ROPE_APPEND, PH_DEC_ATTN, PH_DEC_O, PH_DEC_GATE_UP, PH_DEC_DOWN, PH_DEC_HEAD,
+    PH_COUNT
 };
 static const char* const kPhaseNames[PH_COUNT] = {
     "rope_table", "rmsnorm", "k_proj", "probe_q", "probe_attn", "topk", "gather", "q_proj", "v_proj",
-    "attention", "o_proj", "proxy_in", "proxy_mid", "proxy_z", "proxy_out", "ffn_gate_up", "ffn_down", "compact"};
+    "attention", "o_proj", "proxy_in", "proxy_mid", "proxy_z", "proxy_out", "ffn_gate_up", "ffn_down", "compact",
+    "dec_rmsnorm", "dec_qkv", "dec_rope_append", "dec_attention", "dec_o_proj", "dec_gate_up", "dec_down", "dec_head"};
 
 // Brackets the launches issued during its lifetime with two events when profiling is on.
 struct PhaseScope {
@@ -403,6 +405,78 @@ int spts_select_topk_batched(spts_ctx* c, const float* scores, int64_t N, int64_
     if (!aligned16(scores) || !aligned16(idx_out)) return SPTS_EALIGN;
     PHASE(c, PH_TOPK);
     SPTS_HIP(c, launch_topk(scores, N, k, protect_last, idx_out, batch, c->stream));
+    return SPTS_OK;
+}
+
+int spts_decode_layer(spts_ctx* c, void* x, int32_t pos, const spts_layer_weights* w, spts_kv_out* cache) {
+    if (!c || !x || !w || !cache) return SPTS_EINVAL;
+    if (pos < 0 || cache->count < 0 || cache->count >= cache->capacity) return SPTS_EINVAL;
+    if (!cache->k || !cache->v || !cache->pos) return SPTS_EINVAL;
+    if (!w->Wq || !w->Wk || !w->Wv || !w->Wo || !w->gamma1 || !w->Wgate || !w->Wup || !w->Wdown || !w->gamma2) return SPTS_EINVAL;
+    if (!aligned16(x) || !aligned16(cache->k) || !aligned16(cache->v) || !aligned16(cache->pos) || !aligned16(w->gamma1) ||
+        !aligned16(w->gamma2))
+        return SPTS_EALIGN;
+    const auto& m = c->m;
+    const int QD = m.H * m.d, KV = m.Hkv * m.d;
+    void* xn = c->p<void>(c->off.xn);
+    void* q = c->p<void>(c->off.q);
+    void* kx = c->p<void>(c->off.khat);
+    void* vx = c->p<void>(c->off.vhat);
+    void* att = c->p<void>(c->off.att);
+    void* hbuf = c->p<void>(c->off.big);
+    float* part = c->p<float>(c->off.tmp32);
+    const size_t part_floats = (c->off.qp - c->off.tmp32) / sizeof(float);
+
+    GemvArgs qkv{}; qkv.mode = GEMV_STORE; qkv.x = xn; qkv.K = m.D;
+    qkv.W[0] = w->Wq; qkv.W[1] = w->Wk; qkv.W[2] = w->Wv; qkv.R[0] = QD; qkv.R[1] = KV; qkv.R[2] = KV;
+    qkv.y[0] = q; qkv.y[1] = kx; qkv.y[2] = vx;
+    GemvArgs o{}; o.mode = GEMV_RESID; o.x = att; o.K = QD; o.W[0] = w->Wo; o.R[0] = m.D; o.y[0] = x;
+    GemvArgs gu{}; gu.mode = GEMV_SILU; gu.x = xn; gu.K = m.D; gu.W[0] = w->Wgate; gu.W[1] = w->Wup; gu.R[0] = m.Dff; gu.y[0] = hbuf;
+    GemvArgs dn{}; dn.mode = GEMV_RESID; dn.x = hbuf; dn.K = m.Dff; dn.W[0] = w->Wdown; dn.R[0] = m.D; dn.y[0] = x;
+    if (!gemv_supported(qkv, c->bf16) || !gemv_supported(o, c->bf16) || !gemv_supported(dn, c->bf16)) return SPTS_ESHAPE;
+    {   // the SiLU variant addresses two matrices through W[0], W[1] with R[0] rows each
+        GemvArgs chk = gu; chk.R[1] = m.Dff;
+        if (!gemv_supported(chk, c->bf16)) return SPTS_ESHAPE;
+    }
+    if (!decode_attn_supported(m.H, m.Hkv, m.d, c->bf16)) return SPTS_ESHAPE;
+    if (part_floats < decode_attn_min_scratch_floats(m.Hkv, m.d)) return SPTS_EWORKSPACE;
+
+    hipStream_t st = c->stream;
+    const int64_t row = cache->count;
+    { PHASE(c, PH_DEC_NORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, xn, 1, m.D, c->bf16, st)); }
+    { PHASE(c, PH_DEC_QKV); SPTS_HIP(c, launch_gemv(qkv, c->bf16, st)); }
+    { PHASE(c, PH_DEC_ROPE_APPEND);
+      SPTS_HIP(c, launch_decode_rope_append(q, kx, vx, pos, m.H, m.Hkv, m.d, m.rope_base, cache->k, cache->v, cache->pos, row,
+                                            c->bf16, st)); }
+    { PHASE(c, PH_DEC_ATTN);
+      SPTS_HIP(c, launch_decode_attn(q, cache->k, cache->v, row + 1, m.H, m.Hkv, m.d, part, part_floats, att, c->bf16, st)); }
+    { PHASE(c, PH_DEC_O); SPTS_HIP(c, launch_gemv(o, c->bf16, st)); }
+    { PHASE(c, PH_DEC_NORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, m.rms_eps, xn, 1, m.D, c->bf16, st)); }
+    { PHASE(c, PH_DEC_GATE_UP); SPTS_HIP(c, launch_gemv(gu, c->bf16, st)); }
+    { PHASE(c, PH_DEC_DOWN); SPTS_HIP(c, launch_gemv(dn, c->bf16, st)); }
+    cache->count = row + 1;
+    return SPTS_OK;
+}
+
+int spts_greedy_token(spts_ctx* c, const void* x, const void* gamma_f, const void* table, int32_t V, int32_t* token_out,
+                      float* logits_out, void* x_next) {
+    if (!c || !x || !gamma_f || !table || !token_out || V <= 0) return SPTS_EINVAL;
+    if (!aligned16(x) || !aligned16(gamma_f) || !aligned16(table) || (logits_out && !aligned16(logits_out)) ||
+        (x_next && !aligned16(x_next)))
+        return SPTS_EALIGN;
+    const auto& m = c->m;
+    float* logits = logits_out;
+    if (!logits) {
+        if ((size_t)V * sizeof(float) > c->off.misc - c->off.big) return SPTS_EWORKSPACE;
+        logits = c->p<float>(c->off.big);
+    }
+    void* xn = c->p<void>(c->off.xn);
+    GemvArgs g{}; g.mode = GEMV_F32; g.x = xn; g.K = m.D; g.W[0] = table; g.R[0] = V; g.y[0] = logits;
+    if (!gemv_supported(g, c->bf16)) return SPTS_ESHAPE;
+    PHASE(c, PH_DEC_HEAD);
+    SPTS_HIP(c, launch_rmsnorm(x, gamma_f, m.rms_eps, xn, 1, m.D, c->bf16, c->stream));
+    SPTS_HIP(c, launch_gemv(g, c->bf16, c->stream));
+    SPTS_HIP(c, launch_argmax_row(logits, V, token_out, table, m.D, x_next, c->bf16, c->stream));
     return SPTS_OK;
 }
 

@@ -144,4 +144,31 @@ bool probe_mfma_supported(const ProbeArgs& a);
 hipError_t launch_probe_mfma(const ProbeArgs& a, hipStream_t s);
 size_t probe_scratch_floats(int64_t N, int P, int H, int Hkv);
 
+// ------------------------------------------------------------------ decode phase (one new token)
+enum GemvMode : int {
+    GEMV_STORE = 0,   // y[r] = W[r,:].x                     (T)
+    GEMV_SILU = 1,    // y[r] = silu(W0[r,:].x) * W1[r,:].x  (T; R[0] rows each)
+    GEMV_RESID = 2,   // y[r] += W[r,:].x                    (T, read-modify-write)
+    GEMV_F32 = 3,     // y[r] = W[r,:].x                     (fp32)
+};
+// Up to three row-major matrices W[i] [R[i], K] that share the input vector x [K]; y[i] [R[i]].
+// R[i] % 4 == 0, K a multiple of the 16-byte chunk; GEMV_SILU uses W[0] (gate), W[1] (up), y[0].
+struct GemvArgs {
+    const void* W[3]; void* y[3]; int32_t R[3];
+    const void* x; int32_t K; int mode;
+};
+bool gemv_supported(const GemvArgs& a, bool bf16);
+hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s);
+// rotary embedding of q [H, d] in place and of k [Hkv, d] into cache row `row`, v copied to that row
+hipError_t launch_decode_rope_append(void* q, const void* k, const void* v, int pos, int H, int Hkv, int d, float base,
+                                     void* cache_k, void* cache_v, int32_t* cache_pos, int64_t row, bool bf16, hipStream_t s);
+// out [H, d] = softmax(q K^T / sqrt(d)) V over the M cached pairs K, V [M, Hkv, d]; part: fp32 scratch
+bool decode_attn_supported(int H, int Hkv, int d, bool bf16);
+size_t decode_attn_min_scratch_floats(int Hkv, int d);
+hipError_t launch_decode_attn(const void* q, const void* K, const void* V, int64_t M, int H, int Hkv, int d, float* part,
+                              size_t part_floats, void* out, bool bf16, hipStream_t s);
+// token = argmax(logits [V]) with ties to the lowest id; x_next [D] = table[token, :] (skipped when NULL)
+hipError_t launch_argmax_row(const float* logits, int V, int32_t* token, const void* table, int D, void* x_next, bool bf16,
+                             hipStream_t s);
+
 }  // namespace spts

@@ -74,14 +74,72 @@ def run_layer(ctx: binding.Context, x: np.ndarray, pos: np.ndarray, dw: binding.
     return out
 
 
+class KVCache:
+    """Device buffers of one layer's cache: k, v [capacity, Hkv, d], pos [capacity]; count lives on the host."""
+
+    def __init__(self, shape, capacity: int):
+        torch = _torch()
+        tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        self.k = torch.zeros((max(capacity, 1), shape.Hkv, shape.d), dtype=tdt, device="cuda")
+        self.v = torch.zeros_like(self.k)
+        self.pos = torch.zeros(max(capacity, 1), dtype=torch.int32, device="cuda")
+        self.struct = binding.spts_kv_out(self.k.data_ptr(), self.v.data_ptr(), self.pos.data_ptr(), capacity, 0)
+
+    @property
+    def count(self) -> int:
+        return int(self.struct.count)
+
+    def host(self):
+        """(k, v, pos) of the filled rows as host arrays (fp64 / int32)."""
+        n = self.count
+        return to_host(self.k[:n]).astype(np.float64), to_host(self.v[:n]).astype(np.float64), self.pos[:n].cpu().numpy()
+
+
+class DecodeRunner:
+    """Decode phase on the GPU: per token one spts_decode_layer per layer over that layer's cache, then
+    (optionally) spts_greedy_token.  Only enqueues work; token ids stay on the device."""
+
+    def __init__(self, ctx: binding.Context, shape, layers: List[binding.spts_layer_weights], caches: List[KVCache],
+                 gamma_f=None, table=None):
+        torch = _torch()
+        self.ctx, self.shape, self.layers, self.caches = ctx, shape, layers, caches
+        self.gamma_f, self.table = gamma_f, table
+        tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        self.x = torch.zeros(shape.D, dtype=tdt, device="cuda")
+        self.x_next = torch.zeros(shape.D, dtype=tdt, device="cuda")
+        self.token = torch.zeros(4, dtype=torch.int32, device="cuda")
+        self.logits = torch.zeros(table.shape[0], dtype=torch.float32, device="cuda") if table is not None else None
+
+    def step(self, pos: int):
+        """Runs self.x (in place) through every layer as the token at absolute position pos."""
+        for w, c in zip(self.layers, self.caches):
+            self.ctx.spts_decode_layer(self.x, pos, w, c.struct)
+
+    def greedy(self):
+        """token = argmax over the table of the final-normed self.x; self.x_next = table[token]."""
+        self.ctx.spts_greedy_token(self.x, self.gamma_f, self.table, int(self.table.shape[0]), self.token, self.logits,
+                                   self.x_next)
+
+    def generate(self, pos0: int, steps: int, tokens_out=None):
+        """steps greedy decode steps starting from self.x at position pos0; tokens_out [steps] int32 device."""
+        for t in range(steps):
+            self.step(pos0 + t)
+            self.greedy()
+            if tokens_out is not None:
+                tokens_out[t:t + 1].copy_(self.token[:1])
+            self.x.copy_(self.x_next)
+
+
 class StackRunner:
     """Runs Alg. 1's outer loop on the GPU: per layer one spts_layer_prefill, at stage ends one
     spts_msdp_compact.  Buffers are allocated once; run() only enqueues work (no host sync)."""
 
     def __init__(self, ctx: binding.Context, shape, layers: List[binding.spts_layer_weights], plan: List[dict],
-                 probe_len: int, protect_last: int = 1, skip: int = 1, keep_trace: bool = False):
+                 probe_len: int, protect_last: int = 1, skip: int = 1, keep_trace: bool = False,
+                 caches: Optional[List["KVCache"]] = None):
         torch = _torch()
         self.ctx, self.shape, self.layers, self.plan = ctx, shape, layers, plan
+        self.caches = caches   # per-layer KV caches filled by the prefill (None = not kept)
         self.probe_len, self.protect_last, self.skip = probe_len, protect_last, skip
         N0 = plan[0]["N"]
         tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
@@ -113,7 +171,7 @@ class StackRunner:
                 tr = dict(N=N, x_in=xa[:N].clone(), pos_in=pa[:N].clone(),
                           idx_attn=torch.empty(max(min(N, item["m_attn"]), 1), dtype=torch.int32, device="cuda"),
                           idx_ffn=torch.empty(max(min(N, item["m_ffn"]), 1), dtype=torch.int32, device="cuda"))
-            self.ctx.spts_layer_prefill(xa, pa, N, w, cfg, None, self.s,
+            self.ctx.spts_layer_prefill(xa, pa, N, w, cfg, self.caches[li].struct if self.caches else None, self.s,
                                         tr["idx_attn"] if tr else None, tr["idx_ffn"] if tr else None)
             if tr is not None:
                 tr["x_out"] = xa[:N].clone()

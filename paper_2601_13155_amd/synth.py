@@ -271,6 +271,13 @@ def make_layer(seed: int, layer: int, shape: ModelShape, r: int, dlow: int = 0, 
     return w
 
 
+def vocab_table(seed: int, V: int, D: int, dtype: str) -> np.ndarray:
+    """Synthetic vocabulary table [V, D], i.i.d. N(0, 1): serves as LM head and as embedding in the
+    decode harness (the method defines neither)."""
+    t = _gen(seed, 9001).standard_normal((V, D), dtype=np.float32)
+    return storage_round(t, dtype)
+
+
 def to_abi_layout(w: Dict[str, np.ndarray]) -> Dict[str, np.ndarray]:
     """Paper orientation -> the C-ABI's ``[d_out, d_in]`` row-major matrices."""
     out = {}

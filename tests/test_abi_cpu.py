@@ -23,7 +23,8 @@ def test_exports_every_declared_symbol(lib):
     text = open(os.path.join(ROOT, "include", "spts.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(spts_[a-z_0-9]+)\s*\(", text))
-    assert {"spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_layer_prefill", "spts_msdp_compact"} <= declared
+    assert {"spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_layer_prefill", "spts_msdp_compact",
+            "spts_decode_layer", "spts_greedy_token"} <= declared
     for name in declared:
         assert hasattr(lib, name), name
     assert declared == set(binding.EXPORTS)

@@ -1,0 +1,141 @@
+"""GPU parity of the decode phase (one new token over the per-layer caches left by the prefill)
+against the oracle, lock-step: at every step the oracle starts from the GPU's own input state and
+the GPU's own cache contents, so differences do not accumulate across steps or layers."""
+import numpy as np
+import pytest
+
+from oracle import spts_oracle as orc
+from paper_2601_13155_amd import binding, runtime, synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+_CTX = {}
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def ctx_for(shape, max_tokens):
+    key = (shape, max_tokens)
+    if key not in _CTX:
+        _CTX[key] = runtime.make_context(shape, max_tokens, 128, 256, shape.Dff)
+    return _CTX[key]
+
+
+def _shape(dtype):
+    return synth.TINY if dtype == "f32" else synth.ModelShape(D=256, H=4, Hkv=2, d=64, Dff=688, dtype="bf16")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("skip", [1, 0])
+def test_decode_layer_lockstep(torch, dtype, skip):
+    """Prefill one layer on the GPU (token-skipped: the cache holds the active pairs only; or dense),
+    then push three new tokens through spts_decode_layer."""
+    shape = _shape(dtype)
+    mdl = H.oracle_model(shape)
+    rnd = H.rnd_for(dtype)
+    tol = H.TOL[dtype]["hidden"]
+    N, P, r = 300, 8, 16
+    w = synth.make_layer(21, 0, shape, r)
+    dw = runtime.upload_layer(w, shape, r)
+    ctx = ctx_for(shape, 2048)
+    x = synth.hidden_states(21, N, shape.D, dtype)
+    pos = synth.positions(N)
+    m = int(0.4 * N)
+    cache = runtime.KVCache(shape, (m if skip else N) + 3)
+    cfg = binding.spts_layer_cfg(skip, P, m, m, 1, 0)
+    xd = runtime.to_device(x, dtype)
+    ctx.spts_layer_prefill(xd, torch.from_numpy(pos).cuda(), N, dw, cfg, cache.struct, None, None, None)
+    torch.cuda.synchronize()
+    assert cache.count == (m if skip else N)
+    new = synth.hidden_states(22, 3, shape.D, dtype)
+    for t in range(3):
+        kh, vh, ph = cache.host()
+        xt = runtime.to_device(new[t:t + 1].copy(), dtype).reshape(-1)
+        x_in = runtime.to_host(xt).astype(np.float64)
+        ctx.spts_decode_layer(xt, N + t, dw, cache.struct)
+        torch.cuda.synchronize()
+        ref_x, ref_c = orc.decode_layer(x_in, N + t, w, mdl, orc.LayerCache(kh, vh, ph), rnd)
+        got = runtime.to_host(xt).astype(np.float64)
+        assert H.row_rel_err(got[None, :], ref_x[None, :]) <= tol, (t, H.row_rel_err(got[None, :], ref_x[None, :]))
+        k2, v2, p2 = cache.host()
+        assert k2.shape[0] == kh.shape[0] + 1 and p2[-1] == N + t
+        assert np.array_equal(k2[:-1], kh) and np.array_equal(v2[:-1], vh) and np.array_equal(p2[:-1], ph)
+        assert H.row_rel_err(k2[-1].reshape(1, -1), ref_c.k[-1].reshape(1, -1)) <= tol
+        assert H.row_rel_err(v2[-1].reshape(1, -1), ref_c.v[-1].reshape(1, -1)) <= tol
+
+
+def test_decode_rejects_a_full_cache(torch):
+    shape = _shape("f32")
+    w = synth.make_layer(21, 0, shape, 16)
+    dw = runtime.upload_layer(w, shape, 16)
+    ctx = ctx_for(shape, 2048)
+    cache = runtime.KVCache(shape, 4)
+    cache.struct.count = 4
+    xt = torch.zeros(shape.D, dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.SptsError):
+        ctx.spts_decode_layer(xt, 4, dw, cache.struct)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stack_prefill_then_greedy_decode_lockstep(torch, dtype):
+    """Token-skipped prefill of a 3-layer stack with stage-end pruning fills the per-layer caches (ragged:
+    different lengths per layer); then 4 greedy decode steps.  Per step: every layer against the oracle
+    from the GPU's own state, logits against the oracle, and the token is the oracle's argmax of the
+    GPU's own logits (ties to the lowest id)."""
+    shape = _shape(dtype)
+    mdl = H.oracle_model(shape)
+    rnd = H.rnd_for(dtype)
+    tol = H.TOL[dtype]["hidden"]
+    wl = synth.scaled(synth.WORKLOADS["c2"], shape=shape, N=400, layers=3, stage_end_layers=(1, 2), probe_len=16, r=16,
+                      stage_cum_keep=(1.0, 0.7, 0.5))
+    plan = wl.layer_plan()
+    ws = [synth.make_layer(wl.seed, l, shape, wl.r) for l in range(wl.layers)]
+    dws = [runtime.upload_layer(w, shape, wl.r) for w in ws]
+    ctx = ctx_for(shape, 2048)
+    steps = 4
+    caches = [runtime.KVCache(shape, min(it["N"], it["m_attn"]) + steps) for it in plan]
+    runner = runtime.StackRunner(ctx, shape, dws, plan, wl.probe_len, caches=caches)
+    x0 = synth.hidden_states(wl.seed, wl.N, shape.D, dtype)
+    runner.run(runtime.to_device(x0, dtype), torch.from_numpy(synth.positions(wl.N)).cuda())
+    torch.cuda.synchronize()
+    assert [c.count for c in caches] == [min(it["N"], it["m_attn"]) for it in plan] == [160, 112, 80]
+
+    V = 1000
+    table = synth.vocab_table(wl.seed, V, shape.D, dtype)
+    gamma_f = np.ones(shape.D, dtype=np.float32)
+    td, gd = runtime.to_device(table, dtype), runtime.to_device(gamma_f, dtype)
+    dec = runtime.DecodeRunner(ctx, shape, dws, caches, gd, td)
+    dec.x.copy_(td[17])          # first decode input: the table row of an arbitrary prompt-final token
+    tokens = []
+    for t in range(steps):
+        # lock-step per layer
+        for li, (w, dw, c) in enumerate(zip(ws, dws, caches)):
+            kh, vh, ph = c.host()
+            x_in = runtime.to_host(dec.x).astype(np.float64)
+            ctx.spts_decode_layer(dec.x, wl.N + t, dw, c.struct)
+            torch.cuda.synchronize()
+            ref_x, _ = orc.decode_layer(x_in, wl.N + t, w, mdl, orc.LayerCache(kh, vh, ph), rnd)
+            got = runtime.to_host(dec.x).astype(np.float64)
+            assert H.row_rel_err(got[None, :], ref_x[None, :]) <= tol, (t, li)
+        h = runtime.to_host(dec.x).astype(np.float64)
+        dec.greedy()
+        torch.cuda.synchronize()
+        tok = int(dec.token[0])
+        lg = dec.logits.cpu().numpy()
+        ref_tok, ref_lg = orc.greedy_token(h, gamma_f, table, mdl, rnd, orc.f32_round)
+        assert np.max(np.abs(lg - ref_lg)) <= tol * np.max(np.abs(ref_lg))
+        assert tok == int(np.flatnonzero(lg == lg.max())[0])          # the decision, on the GPU's own logits
+        if tok != ref_tok:                                             # only a near-tie may differ
+            assert abs(ref_lg[tok] - ref_lg[ref_tok]) <= 2 * tol * np.max(np.abs(ref_lg))
+        assert np.array_equal(runtime.to_host(dec.x_next), table[tok].astype(runtime.to_host(dec.x_next).dtype))
+        tokens.append(tok)
+        dec.x.copy_(dec.x_next)
+    assert [c.count for c in caches] == [160 + steps, 112 + steps, 80 + steps]
+    assert all(int(c.pos[c.count - 1]) == wl.N + steps - 1 for c in caches)
+    assert len(set(tokens)) >= 1
