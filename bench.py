@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="do not bracket phases with events in the timed region")
     ap.add_argument("--topk-batch", type=int, default=2048,
                     help="rows of the batched TopK micro-benchmark (rows x 131072 fp32 scores; 0 = skip it)")
+    ap.add_argument("--decode-steps", type=int, default=32,
+                    help="greedy decode steps over the caches the prefill leaves (0 = skip the decode leg)")
+    ap.add_argument("--vocab", type=int, default=128256, help="rows of the synthetic vocabulary table of the decode leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first launch a plain elementwise kernel (dst = src + 1 over 2^28 floats: reads 1 GiB, writes 1 GiB) "
                          "three times; under a counter-collecting profiler its FETCH_SIZE / WRITE_SIZE readings give the "
@@ -237,6 +240,56 @@ def main():
                  "tflops": dflops / (dms * 1e-3) / 1e12, "steps": args.dense_steps}
         log(f"[dense] {dms:.2f} ms/step -> SPTS speedup {dms / ms:.2f}x")
 
+    # ---- decode leg: the prefill runs once more with per-layer caches attached, then greedy decode steps
+    decode = None
+    if args.decode_steps > 0:
+        steps_d = args.decode_steps
+        prof_steps = min(steps_d, 8)
+        caches = [runtime.KVCache(shape, (min(it["N"], it["m_attn"]) if it.get("skip", 1) else it["N"]) + steps_d + prof_steps + 1)
+                  for it in plan]
+        crunner = runtime.StackRunner(ctx, shape, layers, plan, wl.probe_len, wl.protect_last, skip=1, caches=caches)
+        crunner.run(x0, pos0)
+        torch.cuda.synchronize()
+        cached = [c.count for c in caches]
+        table = runtime.to_device(synth.vocab_table(wl.seed, args.vocab, shape.D, shape.dtype), shape.dtype)
+        gamma_f = runtime.to_device(np.ones(shape.D, dtype=np.float32), shape.dtype)
+        dec = runtime.DecodeRunner(ctx, shape, layers, caches, gamma_f, table)
+        dec.x.copy_(table[1])
+        dec.generate(wl.N, 1)                       # warm-up step (also the first appended pair)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        toks = torch.zeros(steps_d, dtype=torch.int32, device="cuda")
+        e0.record()
+        dec.generate(wl.N + 1, steps_d, toks)
+        e1.record()
+        torch.cuda.synchronize()
+        dms = e0.elapsed_time(e1) / steps_d
+        # phase split from a few more steps with the library's events on (they cost time: not part of dms)
+        ctx.spts_profile_begin()
+        dec.generate(wl.N + 1 + steps_d, prof_steps)
+        torch.cuda.synchronize()
+        dphases = ctx.spts_profile_end()
+        b = 2 if shape.dtype == "bf16" else 4
+        wbytes = wl.layers * b * (shape.D * (shape.H + 2 * shape.Hkv) * shape.d + shape.H * shape.d * shape.D
+                                  + 3 * shape.D * shape.Dff)
+        kvbytes = sum(2.0 * (cn + 1 + steps_d / 2.0) * shape.Hkv * shape.d * b for cn in cached)
+        head_bytes = float(args.vocab) * shape.D * b
+        tot = wbytes + kvbytes + head_bytes
+        decode = {"steps": steps_d, "ms_per_token": dms, "tokens_per_s": 1e3 / dms,
+                  "bytes_per_token": {"layer_weights": wbytes, "kv_cache": kvbytes, "vocab_table": head_bytes},
+                  "gbs": tot / (dms * 1e-3) / 1e9, "hbm_frac": tot / (dms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                  "cached_pairs_per_layer": cached, "cached_fraction": sum(cached) / float(wl.layers * wl.N),
+                  "distinct_tokens": int(torch.unique(toks).numel()),
+                  "phases": {k: {"ms_per_token": v[0] / prof_steps, "launches_per_token": v[1] / prof_steps}
+                             for k, v in dphases.items() if k.startswith("dec_")}}
+        gemv_ms = sum(decode["phases"][k]["ms_per_token"] for k in ("dec_qkv", "dec_o_proj", "dec_gate_up", "dec_down")
+                      if k in decode["phases"])
+        if gemv_ms > 0:
+            decode["gemv_gbs"] = wbytes / (gemv_ms * 1e-3) / 1e9
+            decode["gemv_hbm_frac"] = decode["gemv_gbs"] / PEAK_HBM_GBS
+        log(f"[decode] {dms:.3f} ms/token ({1e3 / dms:.1f} tokens/s), {decode['gbs']:.0f} GB/s of weights + cache + table")
+        del caches, crunner, dec, table
+
     # ---- batched TopK: one workgroup per row, so the whole chip streams scores (a single row is latency-bound)
     topk_batched = None
     if args.topk_batch > 0:
@@ -279,7 +332,7 @@ def main():
                    "weight_pool": pool, "batch": 1},
         "algorithmic_tflop_per_step": total_flops / 1e12,
         "achieved_tflops_whole_step": total_flops / (ms * 1e-3) / 1e12,
-        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched,
+        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched, "decode": decode,
     }
     print(json.dumps(out), flush=True)
 

@@ -55,11 +55,46 @@ __device__ inline float wave_sum(float v) {
 }
 
 // ------------------------------------------------------------------------------------------- GEMV
-template <typename T, int MODE>
+// 16-byte chunk of T -> chunk of T holding from_f32(x[e] * inv * gamma[e]) (RMSNorm's last step)
+__device__ inline u32x4 norm_chunk(u32x4 xv, u32x4 gv, float inv, bf16_t) {
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float x0 = __uint_as_float(xv[i] << 16), x1 = __uint_as_float(xv[i] & 0xffff0000u);
+        const float g0 = __uint_as_float(gv[i] << 16), g1 = __uint_as_float(gv[i] & 0xffff0000u);
+        o[i] = (uint32_t)f32_to_bf16(x0 * inv * g0).v | ((uint32_t)f32_to_bf16(x1 * inv * g1).v << 16);
+    }
+    return o;
+}
+__device__ inline u32x4 norm_chunk(u32x4 xv, u32x4 gv, float inv, float) {
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = __float_as_uint(__uint_as_float(xv[i]) * inv * __uint_as_float(gv[i]));
+    return o;
+}
+__device__ inline float chunk_sumsq(u32x4 v, bf16_t) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float a = __uint_as_float(v[i] << 16), b = __uint_as_float(v[i] & 0xffff0000u);
+        s += a * a; s += b * b;
+    }
+    return s;
+}
+__device__ inline float chunk_sumsq(u32x4 v, float) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { const float a = __uint_as_float(v[i]); s += a * a; }
+    return s;
+}
+
+template <typename T, int MODE, bool NORM>
 __global__ void __launch_bounds__(256) gemv_kernel(GemvArgs a) {
     constexpr int EPC = 16 / (int)sizeof(T);          // elements per 16-byte chunk
     constexpr int ROWS = 4;                           // dot products per workgroup
+    constexpr int NCH = 4;                            // chunks of x a lane may hold (fused norm)
     __shared__ float sred[4][ROWS];
+    __shared__ float snorm[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     // rows of this workgroup: ROWS consecutive rows of one matrix, or (SiLU) 2 gate rows + the same 2 up rows
@@ -82,14 +117,46 @@ __global__ void __launch_bounds__(256) gemv_kernel(GemvArgs a) {
     const int nchunks = a.K / EPC;
     const T* x = (const T*)a.x;
     float acc[ROWS] = {0.f, 0.f, 0.f, 0.f};
+    if (NORM) {
+        // the weight loads do not depend on the norm: issue them first, then normalise x while they fly
+        u32x4 wv[NCH][ROWS], xc[NCH], gc[NCH];
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int c = tid + 256 * i;
+            if (c < nchunks) {
+                xc[i] = *reinterpret_cast<const u32x4*>(x + (int64_t)c * EPC);
+                gc[i] = *reinterpret_cast<const u32x4*>((const T*)a.gamma + (int64_t)c * EPC);
+#pragma unroll
+                for (int r = 0; r < ROWS; ++r) wv[i][r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow[r] + (int64_t)c * EPC));
+            }
+        }
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i)
+            if (tid + 256 * i < nchunks) ss += chunk_sumsq(xc[i], T{});
+        ss = wave_sum(ss);
+        if (lane == 0) snorm[wave] = ss;
+        __syncthreads();
+        const float inv = 1.0f / sqrtf((snorm[0] + snorm[1] + snorm[2] + snorm[3]) / (float)a.K + a.eps);
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int c = tid + 256 * i;
+            if (c < nchunks) {
+                const u32x4 xn = norm_chunk(xc[i], gc[i], inv, T{});
+#pragma unroll
+                for (int r = 0; r < ROWS; ++r) acc[r] = dot16(wv[i][r], xn, acc[r], T{});
+            }
+        }
+    } else {
 #pragma unroll 4
-    for (int c = tid; c < nchunks; c += 256) {
-        const u32x4 xv = *reinterpret_cast<const u32x4*>(x + (int64_t)c * EPC);
-        u32x4 wv[ROWS];
+        for (int c = tid; c < nchunks; c += 256) {
+            const u32x4 xv = *reinterpret_cast<const u32x4*>(x + (int64_t)c * EPC);
+            u32x4 wv[ROWS];
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) wv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow[r] + (int64_t)c * EPC));
+            for (int r = 0; r < ROWS; ++r) wv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow[r] + (int64_t)c * EPC));
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) acc[r] = dot16(wv[r], xv, acc[r], T{});
+            for (int r = 0; r < ROWS; ++r) acc[r] = dot16(wv[r], xv, acc[r], T{});
+        }
     }
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
@@ -124,6 +191,7 @@ bool gemv_supported(const GemvArgs& a, bool bf16) {
         if (a.R[i] > 0 && (!a.W[i] || (reinterpret_cast<uintptr_t>(a.W[i]) & 15u))) return false;
     }
     if (!a.x || (reinterpret_cast<uintptr_t>(a.x) & 15u)) return false;
+    if (a.gamma && ((reinterpret_cast<uintptr_t>(a.gamma) & 15u) || a.K / epc > 1024)) return false;
     return true;
 }
 
@@ -132,11 +200,13 @@ static hipError_t launch_gemv_t(const GemvArgs& a, hipStream_t s) {
     const int64_t rows = (int64_t)a.R[0] + a.R[1] + a.R[2];
     if (rows == 0) return hipSuccess;
     const dim3 b(256);
+    const dim3 g((unsigned)(a.mode == GEMV_SILU ? a.R[0] / 2 : rows / 4));
+    const bool n = a.gamma != nullptr;
     switch (a.mode) {
-        case GEMV_STORE: gemv_kernel<T, GEMV_STORE><<<dim3((unsigned)(rows / 4)), b, 0, s>>>(a); break;
-        case GEMV_SILU: gemv_kernel<T, GEMV_SILU><<<dim3((unsigned)(a.R[0] / 2)), b, 0, s>>>(a); break;
-        case GEMV_RESID: gemv_kernel<T, GEMV_RESID><<<dim3((unsigned)(rows / 4)), b, 0, s>>>(a); break;
-        case GEMV_F32: gemv_kernel<T, GEMV_F32><<<dim3((unsigned)(rows / 4)), b, 0, s>>>(a); break;
+        case GEMV_STORE: if (n) gemv_kernel<T, GEMV_STORE, true><<<g, b, 0, s>>>(a); else gemv_kernel<T, GEMV_STORE, false><<<g, b, 0, s>>>(a); break;
+        case GEMV_SILU: if (n) gemv_kernel<T, GEMV_SILU, true><<<g, b, 0, s>>>(a); else gemv_kernel<T, GEMV_SILU, false><<<g, b, 0, s>>>(a); break;
+        case GEMV_RESID: if (n) return hipErrorInvalidValue; gemv_kernel<T, GEMV_RESID, false><<<g, b, 0, s>>>(a); break;
+        case GEMV_F32: if (n) gemv_kernel<T, GEMV_F32, true><<<g, b, 0, s>>>(a); else gemv_kernel<T, GEMV_F32, false><<<g, b, 0, s>>>(a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -194,6 +264,20 @@ hipError_t launch_decode_rope_append(void* q, const void* k, const void* v, int 
     return hipGetLastError();
 }
 
+// Sum over aligned groups of LPK lanes (LPK = 2 .. 32), every lane of a group receiving the total.
+// Steps 1, 2, 4, 8 stay inside a row of 16 lanes and use DPP operands (quad permutes, then mirror of
+// 8 / 16 lanes: after the earlier steps both halves are uniform, so a mirror exchanges them); only a
+// step of 16 crosses rows and goes through the LDS crossbar.
+template <int LPK>
+__device__ inline float group_sum(float v) {
+    if (LPK >= 2) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+    if (LPK >= 4) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+    if (LPK >= 8) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));  // row_half_mirror
+    if (LPK >= 16) v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false)); // row_mirror
+    if (LPK >= 32) v += __shfl_xor(v, 16);
+    return v;
+}
+
 // ------------------------------------------------------------------------- decode attention
 // partial layout: part[((g * nsplit + split) * GRP_MAX + hg) * (d + 2)] = (max, sum, weighted values[d])
 constexpr int GRP_MAX = 8;
@@ -231,18 +315,28 @@ __global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ 
         for (int e = 0; e < EPC; ++e) acc[hg][e] = 0.f;
     }
 
-    for (int64_t m0 = m_begin + wave * KPW; m0 < m_end; m0 += 4 * KPW) {
-        const int64_t m = m0 + kslot;
+    // keys of this lane: m_begin + wave*KPW + kslot + it * 4*KPW; the next pair is loaded before the
+    // current one is used
+    const T* Kg = K + (int64_t)g * D + sub * EPC;
+    const T* Vg = V + (int64_t)g * D + sub * EPC;
+    const int64_t rstride = (int64_t)Hkv * D;
+    int64_t m = m_begin + wave * KPW + kslot;
+    u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+    if (m_begin < m_end) {
+        const int64_t mc = m < m_end ? m : m_end - 1;
+        kv = *reinterpret_cast<const u32x4*>(Kg + mc * rstride);
+        vv = *reinterpret_cast<const u32x4*>(Vg + mc * rstride);
+    }
+    for (int64_t m0 = m_begin + wave * KPW; m0 < m_end; m0 += 4 * KPW, m += 4 * KPW) {
         const bool valid = m < m_end;
-        const int64_t mc = valid ? m : m_end - 1;
-        const u32x4 kv = *reinterpret_cast<const u32x4*>(K + (mc * Hkv + g) * (int64_t)D + sub * EPC);
-        const u32x4 vv = *reinterpret_cast<const u32x4*>(V + (mc * Hkv + g) * (int64_t)D + sub * EPC);
+        const int64_t mn_ = m + 4 * KPW;
+        const int64_t mnc = mn_ < m_end ? mn_ : m_end - 1;
+        const u32x4 kvn = *reinterpret_cast<const u32x4*>(Kg + mnc * rstride);
+        const u32x4 vvn = *reinterpret_cast<const u32x4*>(Vg + mnc * rstride);
 #pragma unroll
         for (int hg = 0; hg < GRP_MAX; ++hg) {
             if (hg < grp) {
-                float s = dot16(kv, qv[hg], 0.f, T{});
-#pragma unroll
-                for (int off = 1; off < LPK; off <<= 1) s += __shfl_xor(s, off);
+                float s = group_sum<LPK>(dot16(kv, qv[hg], 0.f, T{}));
                 s = valid ? s * scale_log2e : -INFINITY;
                 const float mn = fmaxf(mrun[hg], s);
                 const float mu = mn == -INFINITY ? 0.f : mn;
@@ -254,6 +348,8 @@ __global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ 
                 mrun[hg] = mn;
             }
         }
+        kv = kvn;
+        vv = vvn;
     }
     // merge the KPW lane groups of the wavefront (lanes with equal `sub`)
 #pragma unroll
@@ -298,24 +394,47 @@ __global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ 
     }
 }
 
-// out[h, e] = sum over splits of the weighted values / sum of sums
+// out[h, e] = sum over splits of the weighted values / sum of sums.  One workgroup per query head:
+// thread s takes split s for the (max, sum) part; the weighted values are summed by 256 / D thread
+// groups that each walk a strided subset of the splits with independent loads.
 template <typename T>
-__global__ void decode_attn_merge_kernel(const float* __restrict__ part, int nsplit, int H, int Hkv, int D, T* __restrict__ out) {
-    const int h = blockIdx.x, e = threadIdx.x;
-    if (e >= D) return;
+__global__ void __launch_bounds__(256) decode_attn_merge_kernel(const float* __restrict__ part, int nsplit, int H, int Hkv, int D,
+                                                                T* __restrict__ out) {
+    __shared__ float sa[256];
+    __shared__ float sw[4], sl[4];
+    __shared__ float so[256];
+    const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = H / Hkv, g = h / grp, hg = h % grp;
     const float* base = part + ((int64_t)g * nsplit * GRP_MAX + hg) * (D + 2);
     const int64_t stride = (int64_t)GRP_MAX * (D + 2);
-    float mn = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) mn = fmaxf(mn, base[s * stride]);
-    const float mu = mn == -INFINITY ? 0.f : mn;
-    float l = 0.f, o = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-        const float a = __builtin_amdgcn_exp2f(base[s * stride] - mu);
-        l += base[s * stride + 1] * a;
-        o += base[s * stride + 2 + e] * a;
+    const float m = tid < nsplit ? base[tid * stride] : -INFINITY;
+    const float l = tid < nsplit ? base[tid * stride + 1] : 0.f;
+    float mx = m;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if (lane == 0) sw[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(sw[0], sw[1]), fmaxf(sw[2], sw[3]));
+    const float mu = mx == -INFINITY ? 0.f : mx;
+    const float a = __builtin_amdgcn_exp2f(m - mu);     // 0 for absent or empty splits
+    sa[tid] = a;
+    float ls = wave_sum(l * a);
+    if (lane == 0) sl[wave] = ls;
+    __syncthreads();
+    const float L = sl[0] + sl[1] + sl[2] + sl[3];
+    const int ngroups = 256 / D, grp_id = tid / D, e = tid % D;
+    float o = 0.f;
+    if (grp_id < ngroups) {
+#pragma unroll 8
+        for (int s = grp_id; s < nsplit; s += ngroups) o += base[s * stride + 2 + e] * sa[s];
     }
-    out[(int64_t)h * D + e] = from_f32<T>(l > 0.f ? o / l : 0.f);
+    so[tid] = o;
+    __syncthreads();
+    if (tid < D) {
+        float t = 0.f;
+        for (int k = 0; k < ngroups; ++k) t += so[k * D + tid];
+        out[(int64_t)h * D + tid] = from_f32<T>(L > 0.f ? t / L : 0.f);
+    }
 }
 
 // number of key splits: enough workgroups to fill 256 CUs a few times over, at least 64 keys each,
@@ -352,7 +471,7 @@ static hipError_t launch_decode_attn_t(const T* q, const T* K, const T* V, int64
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_attn_merge_kernel<T><<<dim3((unsigned)H), dim3((unsigned)((d + 63) / 64 * 64)), 0, s>>>(part, nsplit, H, Hkv, d, out);
+    decode_attn_merge_kernel<T><<<dim3((unsigned)H), dim3(256), 0, s>>>(part, nsplit, H, Hkv, d, out);
     return hipGetLastError();
 }
 

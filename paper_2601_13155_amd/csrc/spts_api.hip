@@ -427,6 +427,7 @@ int spts_decode_layer(spts_ctx* c, void* x, int32_t pos, const spts_layer_weight
     float* part = c->p<float>(c->off.tmp32);
     const size_t part_floats = (c->off.qp - c->off.tmp32) / sizeof(float);
 
+    // the two RMSNorms run inside the GEMVs that consume them when the row fits the kernel's registers
     GemvArgs qkv{}; qkv.mode = GEMV_STORE; qkv.x = xn; qkv.K = m.D;
     qkv.W[0] = w->Wq; qkv.W[1] = w->Wk; qkv.W[2] = w->Wv; qkv.R[0] = QD; qkv.R[1] = KV; qkv.R[2] = KV;
     qkv.y[0] = q; qkv.y[1] = kx; qkv.y[2] = vx;
@@ -443,7 +444,16 @@ int spts_decode_layer(spts_ctx* c, void* x, int32_t pos, const spts_layer_weight
 
     hipStream_t st = c->stream;
     const int64_t row = cache->count;
-    { PHASE(c, PH_DEC_NORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, xn, 1, m.D, c->bf16, st)); }
+    bool fuse_norm;
+    {
+        GemvArgs t = qkv; t.x = x; t.gamma = w->gamma1; t.eps = m.rms_eps;
+        fuse_norm = gemv_supported(t, c->bf16);
+    }
+    if (fuse_norm) {   // pays for Q/K/V (one launch less); the gate/up product is faster with the leaner plain kernel
+        qkv.x = x; qkv.gamma = w->gamma1; qkv.eps = m.rms_eps;
+    } else {
+        PHASE(c, PH_DEC_NORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, xn, 1, m.D, c->bf16, st));
+    }
     { PHASE(c, PH_DEC_QKV); SPTS_HIP(c, launch_gemv(qkv, c->bf16, st)); }
     { PHASE(c, PH_DEC_ROPE_APPEND);
       SPTS_HIP(c, launch_decode_rope_append(q, kx, vx, pos, m.H, m.Hkv, m.d, m.rope_base, cache->k, cache->v, cache->pos, row,
@@ -474,7 +484,11 @@ int spts_greedy_token(spts_ctx* c, const void* x, const void* gamma_f, const voi
     GemvArgs g{}; g.mode = GEMV_F32; g.x = xn; g.K = m.D; g.W[0] = table; g.R[0] = V; g.y[0] = logits;
     if (!gemv_supported(g, c->bf16)) return SPTS_ESHAPE;
     PHASE(c, PH_DEC_HEAD);
-    SPTS_HIP(c, launch_rmsnorm(x, gamma_f, m.rms_eps, xn, 1, m.D, c->bf16, c->stream));
+    {
+        GemvArgs t = g; t.x = x; t.gamma = gamma_f; t.eps = m.rms_eps;
+        if (gemv_supported(t, c->bf16)) g = t;
+        else SPTS_HIP(c, launch_rmsnorm(x, gamma_f, m.rms_eps, xn, 1, m.D, c->bf16, c->stream));
+    }
     SPTS_HIP(c, launch_gemv(g, c->bf16, c->stream));
     SPTS_HIP(c, launch_argmax_row(logits, V, token_out, table, m.D, x_next, c->bf16, c->stream));
     return SPTS_OK;

@@ -153,9 +153,12 @@ enum GemvMode : int {
 };
 // Up to three row-major matrices W[i] [R[i], K] that share the input vector x [K]; y[i] [R[i]].
 // R[i] % 4 == 0, K a multiple of the 16-byte chunk; GEMV_SILU uses W[0] (gate), W[1] (up), y[0].
+// gamma != NULL: x is the raw hidden state and every workgroup applies RMSNorm(x; gamma, eps) to it
+// first (same arithmetic as the RMSNorm kernel); needs K <= 1024 chunks of 16 bytes.
 struct GemvArgs {
     const void* W[3]; void* y[3]; int32_t R[3];
     const void* x; int32_t K; int mode;
+    const void* gamma; float eps;
 };
 bool gemv_supported(const GemvArgs& a, bool bf16);
 hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s);

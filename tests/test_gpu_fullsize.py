@@ -245,3 +245,41 @@ def test_paper_schedule_layer_lockstep():
     assert np.array_equal(gpu["idx_attn"], orc.topk_select(gpu["s_mha"], budget, 1))
     del dw
     torch.cuda.empty_cache()
+
+
+def test_decode_8b_shaped_layer_after_skipped_prefill():
+    """8B-shaped bf16 layer: token-skipped prefill of 8192 tokens fills the cache with the 3276 active pairs;
+    two new tokens then go through spts_decode_layer, each checked against the oracle from the GPU's own
+    input state and cache contents."""
+    import torch
+    from paper_2601_13155_amd import binding
+    wl = synth.WORKLOADS["c1"]
+    shape = wl.shape
+    w, dw = llama_layer()
+    ctx = ctx_for(32768)
+    item = wl.layer_plan()[0]
+    N = wl.N
+    cache = runtime.KVCache(shape, item["m_attn"] + 2)
+    cfg = binding.spts_layer_cfg(1, wl.probe_len, item["m_attn"], item["m_ffn"], 1, 0)
+    xd = runtime.to_device(synth.hidden_states(wl.seed, N, shape.D, shape.dtype), shape.dtype)
+    ctx.spts_layer_prefill(xd, torch.from_numpy(synth.positions(N)).cuda(), N, dw, cfg, cache.struct, None, None, None)
+    torch.cuda.synchronize()
+    assert cache.count == item["m_attn"] == 3276
+    mdl = H.oracle_model(shape)
+    new = synth.hidden_states(77, 3, shape.D, shape.dtype)[1:]
+    for t in range(2):
+        kh, vh, ph = cache.host()
+        xt = runtime.to_device(new[t:t + 1].copy(), shape.dtype).reshape(-1)
+        x_in = runtime.to_host(xt).astype(np.float64)
+        ctx.spts_decode_layer(xt, N + t, dw, cache.struct)
+        torch.cuda.synchronize()
+        ref_x, ref_c = orc.decode_layer(x_in, N + t, w, mdl, orc.LayerCache(kh, vh, ph), orc.bf16_round)
+        got = runtime.to_host(xt).astype(np.float64)
+        err = H.row_rel_err(got[None, :], ref_x[None, :])
+        print(f"decode step {t}: hidden err {err:.3e}")
+        assert err <= H.TOL["bf16"]["hidden"]
+        k2, v2, p2 = cache.host()
+        assert p2[-1] == N + t and k2.shape[0] == kh.shape[0] + 1
+        assert H.row_rel_err(k2[-1].reshape(1, -1), ref_c.k[-1].reshape(1, -1)) <= H.TOL["bf16"]["hidden"]
+        assert H.row_rel_err(v2[-1].reshape(1, -1), ref_c.v[-1].reshape(1, -1)) <= H.TOL["bf16"]["hidden"]
+    torch.cuda.empty_cache()
