@@ -2,9 +2,10 @@
 bench.py times (matrix-core kernels, 8B-shaped bf16 layer).
 
 * c1 (N = 8192): the whole layer against the oracle, lock-step.
-* c2 (N = 32768): the first layer of the stack on sampled rows the oracle computes one by one from the
-  GPU's own layer input, plus properties that hold at any size (selection = oracle TopK of the
-  GPU's scores, untouched rows, compaction maps, score sum).
+* c2 (N = 32768): the whole 32-layer stack; the first layer of every stage and the last layer on sampled
+  rows the oracle computes one by one from the GPU's own layer input, plus, on every layer, properties
+  that hold at any size (selection = oracle TopK of the GPU's scores, untouched rows, all three
+  compaction maps, score sum).
 * c3 (N = 131072): properties of the probe / TopK / skip rule at long length.
 """
 import math
@@ -104,7 +105,7 @@ def _sampled_layer_check(x_in, pos, w, shape, cfg, gpu, n_samples, seed):
     return swaps_a, err, len(rows)
 
 
-def test_c2_first_layer_sampled_and_stack_properties():
+def test_c2_whole_stack_properties_and_sampled_layers():
     import torch
     wl = synth.WORKLOADS["c2"]
     shape = wl.shape
@@ -113,12 +114,12 @@ def test_c2_first_layer_sampled_and_stack_properties():
     plan = wl.layer_plan()
     x0 = synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype)
     pos0 = synth.positions(wl.N)
-    # stack of 10 layers (crosses the first stage end after layer 8) with the bench's runner
-    n_layers = 10
+    # the whole 32-layer stack (three stage ends) with the bench's runner
+    n_layers = wl.layers
     runner = runtime.StackRunner(ctx, shape, [dw] * n_layers, plan[:n_layers], wl.probe_len, keep_trace=True)
     xo, po, n_final = runner.run(runtime.to_device(x0, shape.dtype), torch.from_numpy(pos0).cuda())
     torch.cuda.synchronize()
-    assert n_final == 22937
+    assert n_final == 11468
     for li, (tr, item) in enumerate(zip(runner.trace, plan[:n_layers])):
         N = tr["N"]
         s = tr["s_mha"].cpu().numpy()
@@ -142,15 +143,18 @@ def test_c2_first_layer_sampled_and_stack_properties():
             assert torch.equal(nxt["x_in"], tr["x_out"][tr["map_new2old"].long()])          # bitwise row copies
             assert torch.equal(nxt["pos_in"], tr["pos_in"][tr["map_new2old"].long()])
     assert bool(torch.isfinite(xo.float()).all())
-    # first layer: sampled rows against the oracle
-    tr = runner.trace[0]
-    item = plan[0]
-    gpu = dict(x=runtime.to_host(tr["x_out"]).astype(np.float64), s_mha=tr["s_mha"].cpu().numpy(),
-               idx_attn=tr["idx_attn"][: item["m_attn"]].cpu().numpy(), idx_ffn=tr["idx_ffn"][: item["m_ffn"]].cpu().numpy())
-    cfg = orc.LayerCfg(1, wl.probe_len, item["m_attn"], item["m_ffn"], 1, 0)
-    swaps, err, n_rows = _sampled_layer_check(x0, pos0, w, shape, cfg, gpu, n_samples=24, seed=7)
-    print(f"c2 layer 1: attention-set swaps={swaps} sampled rows={n_rows} err={err:.3e}")
-    assert swaps <= item["m_attn"] // 50
+    # first layer of every stage and the last layer: sampled rows against the oracle, from the GPU's own layer input
+    for li in (0, 8, 16, 24, n_layers - 1):
+        tr = runner.trace[li]
+        item = plan[li]
+        gpu = dict(x=runtime.to_host(tr["x_out"]).astype(np.float64), s_mha=tr["s_mha"].cpu().numpy(),
+                   idx_attn=tr["idx_attn"][: item["m_attn"]].cpu().numpy(), idx_ffn=tr["idx_ffn"][: item["m_ffn"]].cpu().numpy())
+        cfg = orc.LayerCfg(1, wl.probe_len, item["m_attn"], item["m_ffn"], 1, 0)
+        x_in = runtime.to_host(tr["x_in"]).astype(np.float64)
+        swaps, err, n_rows = _sampled_layer_check(x_in, tr["pos_in"].cpu().numpy(), w, shape, cfg, gpu,
+                                                  n_samples=24 if li == 0 else 10, seed=7 + li)
+        print(f"c2 layer {li + 1} (N={tr['N']}): attention-set swaps={swaps} sampled rows={n_rows} err={err:.3e}", flush=True)
+        assert swaps <= item["m_attn"] // 50
     del runner
     torch.cuda.empty_cache()
 
