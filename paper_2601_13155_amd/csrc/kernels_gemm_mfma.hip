@@ -585,7 +585,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
         case EPI_ROPE: e = (a.K % 64 == 0 ? launch_t<EPI_ROPE, 64, false, NW>(a, s) : launch_t<EPI_ROPE, 32, false, NW>(a, s)); break;
         case EPI_SILU_MUL:
             if (a.A1) e = launch_t<EPI_SILU_MUL, 32, true, NW>(a, s);
-            else e = a.K % 64 == 0 ? launch_t<EPI_SILU_MUL, 64, false, NW>(a, s) : launch_t<EPI_SILU_MUL, 32, false, NW>(a, s);
+            else e = launch_t<EPI_SILU_MUL, 32, false, NW>(a, s);   // 4 stages of 32 measured 2 % faster here than 2 of 64
             break;
         default: return hipErrorInvalidValue;
     }
