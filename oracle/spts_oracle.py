@@ -57,6 +57,14 @@ holds): ``decode_layer`` / ``decode_step`` run one new token through the dense
 branches over each layer's cache of active key/value pairs and append the
 token's own pair; ``greedy_token`` is a final norm, a vocabulary projection and
 an argmax (a synthetic head: the vocabulary table is not part of the method).
+Offline proxy construction (Sec. 3.3, activation saliency and Eq. (channel_importance)):
+``channel_saliency`` / ``channel_importance`` / ``select_channels`` give the per-channel score
+(mean of the top-rho fraction of saliencies over a calibration token set) and the Dlow channels
+the proxy keeps.  Reading R20: the calibration set holds the FFN's inputs, i.e. the states after
+the pre-FFN RMSNorm.  Pins (tests/test_oracle_builder_pins.py): loops on tiny inputs, rho = 1
+(plain column mean), k = 1 (column maximum), invariance under a permutation of the tokens,
+a planted dominant channel.
+
 Pins (tests/test_oracle_decode_pins.py): dense prefill of N+1 tokens == dense
 prefill of N tokens + one decode step (last row and caches); attention over the
 cache against a loop-by-loop softmax; invariance under a permutation of the
@@ -443,3 +451,28 @@ def greedy_token(h: Array, gamma_f: Array, table: Array, mdl: Model, rnd=identit
     logits = logit_cast((hn @ np.asarray(table, dtype=np.float64).T)[0])
     best = np.flatnonzero(logits == np.max(logits))
     return int(best[0]), logits
+
+
+# ------------------------------------------------------------------------------------------------
+# Offline proxy construction: data-driven choice of the Dlow channels (Sec. 3.3)
+# ------------------------------------------------------------------------------------------------
+def channel_saliency(x_cal: Array, Wgate: Array, Wup: Array, rnd=identity) -> Array:
+    """z(x) = |silu(x W_gate) * (x W_up)| for every calibration token: [T, Dff] (Sec. 3.3)."""
+    x = np.asarray(x_cal, dtype=np.float64)
+    g = x @ np.asarray(Wgate, dtype=np.float64)
+    u = x @ np.asarray(Wup, dtype=np.float64)
+    return np.abs(rnd(silu(g) * u))
+
+
+def channel_importance(x_cal: Array, Wgate: Array, Wup: Array, k: int, rnd=identity) -> Array:
+    """Eq. (channel_importance): I_j = mean of the k = rho*|G| largest saliencies of channel j."""
+    z = channel_saliency(x_cal, Wgate, Wup, rnd)
+    T = z.shape[0]
+    k = int(min(max(k, 1), T))
+    top = -np.sort(-z, axis=0)[:k]          # k largest per column
+    return top.sum(axis=0) / float(k)
+
+
+def select_channels(importance: Array, dlow: int) -> Array:
+    """C = TopK(I, Dlow), ascending channel ids; ties to the lower id (the TopK rule of R6)."""
+    return topk_select(importance, dlow, 0)
