@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=32,
                     help="greedy decode steps over the caches the prefill leaves (0 = skip the decode leg)")
     ap.add_argument("--vocab", type=int, default=128256, help="rows of the synthetic vocabulary table of the decode leg")
+    ap.add_argument("--builder-tokens", type=int, default=8192,
+                    help="calibration tokens of the offline channel-importance leg (0 = skip it)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first launch a plain elementwise kernel (dst = src + 1 over 2^28 floats: reads 1 GiB, writes 1 GiB) "
                          "three times; under a counter-collecting profiler its FETCH_SIZE / WRITE_SIZE readings give the "
@@ -313,6 +315,27 @@ def main():
                         "note": "algorithmic bytes (scores once + indices) / time; the kernel reads the scores six times"}
         del sc, ti, tctx
 
+    # ---- offline proxy construction: channel scores on a synthetic calibration set (rho = 0.2)
+    builder = None
+    if args.builder_tokens > 0:
+        Tc = min(args.builder_tokens, wl.N)
+        kc = max(1, int(0.2 * Tc))
+        xc = runtime.to_device(synth.calibration_states(wl.seed, Tc, shape.D, shape.dtype), shape.dtype)
+        imp = torch.zeros(shape.Dff, dtype=torch.float32, device="cuda")
+        ctx.spts_channel_importance(xc, Tc, layers[0], kc, imp)
+        torch.cuda.synchronize()
+        ctx.spts_profile_begin()
+        for _ in range(3):
+            ctx.spts_channel_importance(xc, Tc, layers[0], kc, imp)
+        torch.cuda.synchronize()
+        bph = ctx.spts_profile_end()
+        b = 2 if shape.dtype == "bf16" else 4
+        sal_ms, top_ms = bph["build_saliency"][0] / 3, bph["build_topmean"][0] / 3
+        builder = {"tokens": Tc, "k": kc, "saliency_ms": sal_ms, "saliency_tflops": 4.0 * Tc * shape.D * shape.Dff / (sal_ms * 1e-3) / 1e12,
+                   "topmean_ms": top_ms, "topmean_gbs": (float(shape.Dff) * Tc * b + 4.0 * shape.Dff) / (top_ms * 1e-3) / 1e9}
+        builder["topmean_hbm_frac"] = builder["topmean_gbs"] / PEAK_HBM_GBS
+        del xc, imp
+
     cpu = None
     if args.cpu_sample_tokens > 0:
         cpu = cpu_baseline(wl, host_sets[0], args.cpu_sample_tokens, wl.layers)
@@ -332,7 +355,7 @@ def main():
                    "weight_pool": pool, "batch": 1},
         "algorithmic_tflop_per_step": total_flops / 1e12,
         "achieved_tflops_whole_step": total_flops / (ms * 1e-3) / 1e12,
-        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched, "decode": decode,
+        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched, "decode": decode, "proxy_builder": builder,
     }
     print(json.dumps(out), flush=True)
 

@@ -170,6 +170,15 @@ int spts_decode_layer(spts_ctx *ctx, void *x, int32_t pos, const spts_layer_weig
 int spts_greedy_token(spts_ctx *ctx, const void *x, const void *gamma_f, const void *table,
                       int32_t V, int32_t *token_out, float *logits_out, void *x_next);
 
+/* Offline proxy construction, channel scores (Sec. 3.3: activation saliency and
+ * Eq. (channel_importance)).  x_cal [T, D]: calibration tokens as the FFN sees them (states after
+ * the pre-FFN RMSNorm).  importance_out [Dff] fp32: for every FFN channel the mean of the k
+ * largest |silu(x Wgate) * (x Wup)| over the T tokens (k = rho * T in the paper).  The Dlow
+ * channels to keep are spts_select_topk(importance_out, Dff, Dlow, 0).  1 <= k <= T <= max_tokens;
+ * uses w->Wgate, w->Wup only; device pointers, 16-byte aligned. */
+int spts_channel_importance(spts_ctx *ctx, const void *x_cal, int64_t T, const spts_layer_weights *w,
+                            int64_t k, float *importance_out);
+
 /* Stage-end pruning (Sec. 3.4, Eq. (stage_prune); Alg. 1 last block): keeps the
  * N' = min(N, N_next) candidates with the largest s_mha.  Out of place: x_out [N', D],
  * pos_out [N'], map_new2old [N'] (ascending), map_old2new [N] (-1 for dropped rows; may be NULL).

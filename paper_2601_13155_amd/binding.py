@@ -21,7 +21,7 @@ SPTS_F32, SPTS_BF16 = 0, 1
 EXPORTS = (
     "spts_workspace_bytes", "spts_create", "spts_destroy", "spts_strerror", "spts_last_hip_error", "spts_uses_mfma",
     "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_layer_prefill", "spts_msdp_compact",
-    "spts_decode_layer", "spts_greedy_token",
+    "spts_decode_layer", "spts_greedy_token", "spts_channel_importance",
     "spts_profile_begin", "spts_profile_end", "spts_profile_count", "spts_profile_get",
 )
 
@@ -86,6 +86,8 @@ def load() -> C.CDLL:
     lib.spts_decode_layer.argtypes = [vp, vp, i32, C.POINTER(spts_layer_weights), C.POINTER(spts_kv_out)]
     lib.spts_greedy_token.restype = C.c_int
     lib.spts_greedy_token.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.spts_channel_importance.restype = C.c_int
+    lib.spts_channel_importance.argtypes = [vp, vp, i64, C.POINTER(spts_layer_weights), i64, vp]
     lib.spts_profile_begin.restype = C.c_int
     lib.spts_profile_begin.argtypes = [vp]
     lib.spts_profile_end.restype = C.c_int
@@ -200,6 +202,10 @@ class Context:
     def spts_greedy_token(self, x, gamma_f, table, V: int, token_out, logits_out=None, x_next=None):
         _check(load().spts_greedy_token(self.handle, _ptr(x), _ptr(gamma_f), _ptr(table), V, _ptr(token_out),
                                         _ptr(logits_out), _ptr(x_next)), "spts_greedy_token")
+
+    def spts_channel_importance(self, x_cal, T: int, w: spts_layer_weights, k: int, importance_out):
+        _check(load().spts_channel_importance(self.handle, _ptr(x_cal), T, C.byref(w), k, _ptr(importance_out)),
+               "spts_channel_importance")
 
     def spts_msdp_compact(self, x_in, pos_in, s_mha, N, N_next, protect_last, x_out, pos_out, map_new2old,
                           map_old2new=None):

@@ -219,6 +219,75 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restr
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Mean of the k largest |values| of every row of a [rows, T] matrix (Eq. (channel_importance): the
+// importance of an FFN channel is the mean of the top-rho fraction of its saliencies over the
+// calibration tokens; rows = channels).  Same radix select as above on the keys of |v| (exact
+// k-th value and how many copies of it count), then a sum of everything above it in a fixed order
+// (per lane, shuffle tree, wavefronts in order): deterministic.  One workgroup per row; the row is
+// re-read in every sweep and stays in L2 meanwhile.
+template <typename T>
+__global__ void __launch_bounds__(TOPK_THREADS) topk_mean_kernel(const T* __restrict__ vals, int64_t ld, int64_t n, int64_t k,
+                                                                 float* __restrict__ out) {
+    __shared__ int hist[256];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int64_t sh_need;
+    __shared__ float wsum[TOPK_WAVES];
+    const T* row = vals + (int64_t)blockIdx.x * ld;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) { sh_prefix = 0; sh_need = k; }
+    uint32_t prefix = 0;
+    int64_t need = k;
+    // bf16 values widen to keys whose low 16 bits are zero: two 8-bit passes decide the whole key
+    constexpr int NPASS = sizeof(T) == 2 ? 2 : 4;
+    for (int pass = 0; pass < NPASS; ++pass) {
+        const int shift = 24 - 8 * pass;
+        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int64_t base = 0; base < n; base += TOPK_THREADS) {
+            const int64_t i = base + tid;
+            const uint32_t key = i < n ? order_key(fabsf(to_f32(row[i]))) : 0u;
+            hist_add(hist, i < n && (key & hi_mask) == prefix, (int)((key >> shift) & 0xFF));
+        }
+        __syncthreads();
+        if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
+        __syncthreads();
+        prefix = sh_prefix;
+        need = sh_need;
+    }
+    const uint32_t Tk = prefix;       // key of the k-th largest |value|
+    float s = 0.f, tval = 0.f;
+    for (int64_t base = 0; base < n; base += TOPK_THREADS) {
+        const int64_t i = base + tid;
+        if (i < n) {
+            const float v = fabsf(to_f32(row[i]));
+            const uint32_t key = order_key(v);
+            if (key > Tk) s += v;
+            if (key == Tk) tval = v;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { s += __shfl_xor(s, off); tval = fmaxf(tval, __shfl_xor(tval, off)); }
+    __shared__ float wt[TOPK_WAVES];
+    if (lane == 0) { wsum[wave] = s; wt[wave] = tval; }
+    __syncthreads();
+    if (tid == 0) {
+        float tot = 0.f, tv = 0.f;
+        for (int w = 0; w < TOPK_WAVES; ++w) { tot += wsum[w]; tv = fmaxf(tv, wt[w]); }
+        out[blockIdx.x] = (tot + (float)need * tv) / (float)k;
+    }
+}
+
+hipError_t launch_topk_mean(const void* vals, int64_t ld, int64_t rows, int64_t n, int64_t k, float* out, bool bf16,
+                            hipStream_t s) {
+    if (rows <= 0 || n <= 0 || k <= 0) return hipSuccess;
+    const dim3 g((unsigned)rows), b(TOPK_THREADS);
+    if (bf16) topk_mean_kernel<bf16_t><<<g, b, 0, s>>>((const bf16_t*)vals, ld, n, k, out);
+    else topk_mean_kernel<float><<<g, b, 0, s>>>((const float*)vals, ld, n, k, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out, int batch,
                        hipStream_t s) {
     if (k <= 0 || N <= 0 || batch <= 0) return hipSuccess;

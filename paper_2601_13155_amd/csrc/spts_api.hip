@@ -90,12 +90,14 @@ enum PhaseId {
     PH_ROPE_TABLE = 0, PH_RMSNORM, PH_K_PROJ, PH_PROBE_Q, PH_PROBE_ATTN, PH_TOPK, PH_GATHER, PH_Q_PROJ, PH_V_PROJ,
     PH_ATTENTION, PH_O_PROJ, PH_PROXY_IN, PH_PROXY_MID, PH_PROXY_Z, PH_PROXY_OUT, PH_FFN_GATE_UP, PH_FFN_DOWN,
     PH_COMPACT, PH_DEC_NORM, PH_DEC_QKV, PH_DEC_ROPE_APPEND, PH_DEC_ATTN, PH_DEC_O, PH_DEC_GATE_UP, PH_DEC_DOWN, PH_DEC_HEAD,
+    PH_BUILD_SALIENCY, PH_BUILD_TOPMEAN,
     PH_COUNT
 };
 static const char* const kPhaseNames[PH_COUNT] = {
     "rope_table", "rmsnorm", "k_proj", "probe_q", "probe_attn", "topk", "gather", "q_proj", "v_proj",
     "attention", "o_proj", "proxy_in", "proxy_mid", "proxy_z", "proxy_out", "ffn_gate_up", "ffn_down", "compact",
-    "dec_rmsnorm", "dec_qkv", "dec_rope_append", "dec_attention", "dec_o_proj", "dec_gate_up", "dec_down", "dec_head"};
+    "dec_rmsnorm", "dec_qkv", "dec_rope_append", "dec_attention", "dec_o_proj", "dec_gate_up", "dec_down", "dec_head",
+    "build_saliency", "build_topmean"};
 
 // Brackets the launches issued during its lifetime with two events when profiling is on.
 struct PhaseScope {
@@ -488,6 +490,22 @@ int spts_greedy_token(spts_ctx* c, const void* x, const void* gamma_f, const voi
     SPTS_HIP(c, launch_rmsnorm(x, gamma_f, m.rms_eps, xn, 1, m.D, c->bf16, c->stream));
     SPTS_HIP(c, launch_gemv(g, c->bf16, c->stream));
     SPTS_HIP(c, launch_argmax_row(logits, V, token_out, table, m.D, x_next, c->bf16, c->stream));
+    return SPTS_OK;
+}
+
+int spts_channel_importance(spts_ctx* c, const void* x_cal, int64_t T, const spts_layer_weights* w, int64_t k,
+                            float* importance_out) {
+    SPTS_TRY(common_call_checks(c, T));
+    if (!x_cal || !w || !w->Wgate || !w->Wup || !importance_out) return SPTS_EINVAL;
+    if (T < 1 || k < 1 || k > T) return SPTS_EINVAL;
+    if (!aligned16(x_cal) || !aligned16(w->Wgate) || !aligned16(w->Wup) || !aligned16(importance_out)) return SPTS_EALIGN;
+    const auto& m = c->m;
+    void* zt = c->p<void>(c->off.big);   // Z^T [Dff, T]: channel-major, so that a channel's saliencies are one row
+    GemmArgs g = gemm_args(w->Wgate, m.D, nullptr, x_cal, m.D, zt, T, m.Dff, (int32_t)T, m.D, EPI_SILU_MUL);
+    g.A1 = w->Wup; g.B1 = x_cal;
+    { PHASE(c, PH_BUILD_SALIENCY); SPTS_TRY(run_gemm(c, g)); }
+    PHASE(c, PH_BUILD_TOPMEAN);
+    SPTS_HIP(c, launch_topk_mean(zt, T, m.Dff, T, k, importance_out, c->bf16, c->stream));
     return SPTS_OK;
 }
 

@@ -144,6 +144,10 @@ bool probe_mfma_supported(const ProbeArgs& a);
 hipError_t launch_probe_mfma(const ProbeArgs& a, hipStream_t s);
 size_t probe_scratch_floats(int64_t N, int P, int H, int Hkv);
 
+// out[r] = mean of the k largest |vals[r, 0..n)|, rows of T with leading dimension ld (elements)
+hipError_t launch_topk_mean(const void* vals, int64_t ld, int64_t rows, int64_t n, int64_t k, float* out, bool bf16,
+                            hipStream_t s);
+
 // ------------------------------------------------------------------ decode phase (one new token)
 enum GemvMode : int {
     GEMV_STORE = 0,   // y[r] = W[r,:].x                     (T)

@@ -271,6 +271,13 @@ def make_layer(seed: int, layer: int, shape: ModelShape, r: int, dlow: int = 0, 
     return w
 
 
+def calibration_states(seed: int, T: int, D: int, dtype: str) -> np.ndarray:
+    """Synthetic calibration token set for the offline proxy construction: [T, D] i.i.d. N(0, 1) rows
+    (unit RMS in expectation, like states after an RMSNorm with gamma = 1).  Stands in for the FFN
+    inputs collected on calibration text, which this build does not have."""
+    return storage_round(_gen(seed, 9002).standard_normal((T, D), dtype=np.float32), dtype)
+
+
 def vocab_table(seed: int, V: int, D: int, dtype: str) -> np.ndarray:
     """Synthetic vocabulary table [V, D], i.i.d. N(0, 1): serves as LM head and as embedding in the
     decode harness (the method defines neither)."""

@@ -287,3 +287,27 @@ def test_decode_8b_shaped_layer_after_skipped_prefill():
         assert H.row_rel_err(k2[-1].reshape(1, -1), ref_c.k[-1].reshape(1, -1)) <= H.TOL["bf16"]["hidden"]
         assert H.row_rel_err(v2[-1].reshape(1, -1), ref_c.v[-1].reshape(1, -1)) <= H.TOL["bf16"]["hidden"]
     torch.cuda.empty_cache()
+
+
+def test_channel_importance_8b_shaped():
+    """Offline channel scores (Eq. (channel_importance)) for an 8B-shaped FFN on 1024 synthetic calibration
+    tokens with rho = 0.2 (matrix-core saliency GEMM, channel-major), then the paper's Dlow = 512 selection."""
+    import torch
+    shape = synth.LLAMA8B
+    w, dw = llama_layer()
+    ctx = ctx_for(32768)
+    T, k, dlow = 1024, 204, 512
+    xc = synth.calibration_states(3, T, shape.D, shape.dtype)
+    imp = torch.zeros(shape.Dff, dtype=torch.float32, device="cuda")
+    ctx.spts_channel_importance(runtime.to_device(xc, shape.dtype), T, dw, k, imp)
+    got = imp.cpu().numpy()
+    ref = orc.channel_importance(xc, w["Wgate"], w["Wup"], k, orc.bf16_round)
+    tol = H.TOL["bf16"]["score"]
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    sel = torch.empty(dlow, dtype=torch.int32, device="cuda")
+    ctx.spts_select_topk(imp, shape.Dff, dlow, 0, sel)
+    sel = sel.cpu().numpy()
+    assert np.array_equal(sel, orc.select_channels(got, dlow))
+    swaps = H.count_swaps(sel, orc.select_channels(ref, dlow), ref, tol, 0)
+    print(f"channel importance: max rel err {err:.3e}, selection swaps {swaps} of {dlow}")
+    assert err <= tol

@@ -327,3 +327,29 @@ def test_stack_paper_schedule_lockstep(torch, dtype):
             _, rp, rn2o, _ = orc.msdp_compact(gpu["x"], pos_in, gpu["s_mha"], item["N_next"], 1)
             assert np.array_equal(tr["map_new2old"].cpu().numpy(), rn2o)
     assert po[-1].item() == wl.N - 1
+
+
+# ------------------------------------------------------------------------------------------ proxy builder
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_channel_importance_and_selection(torch, dtype):
+    """Eq. (channel_importance) on a synthetic calibration set; the channel choice is the library's TopK
+    of the scores (bit-exact against the oracle's TopK of the same scores, swap-counted against the
+    oracle's own scores)."""
+    shape = synth.TINY if dtype == "f32" else synth.ModelShape(D=256, H=4, Hkv=2, d=64, Dff=688, dtype="bf16")
+    w = synth.make_layer(31, 0, shape, 16)
+    dw = runtime.upload_layer(w, shape, 16)
+    ctx = ctx_for(shape, 2048)
+    tol = H.TOL[dtype]["score"]
+    for T, k in ((300, 60), (1, 1), (257, 257), (1024, 5)):
+        xc = synth.calibration_states(31, T, shape.D, dtype)
+        imp = torch.full((shape.Dff,), -1.0, dtype=torch.float32, device="cuda")
+        ctx.spts_channel_importance(runtime.to_device(xc, dtype), T, dw, k, imp)
+        got = imp.cpu().numpy()
+        ref = orc.channel_importance(xc, w["Wgate"], w["Wup"], k, H.rnd_for(dtype))
+        assert np.max(np.abs(got - ref)) <= tol * np.max(np.abs(ref)), (T, k, np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+        dlow = 256
+        sel = torch.empty(dlow, dtype=torch.int32, device="cuda")
+        ctx.spts_select_topk(imp, shape.Dff, dlow, 0, sel)
+        sel = sel.cpu().numpy()
+        assert np.array_equal(sel, orc.select_channels(got, dlow))
+        H.count_swaps(sel, orc.select_channels(ref, dlow), ref, tol, 0)
