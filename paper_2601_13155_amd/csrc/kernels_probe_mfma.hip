@@ -244,7 +244,9 @@ size_t probe_scratch_floats(int64_t N, int P, int H, int Hkv) {
     int64_t Np = (N + 255) / 256 * 256;
     int64_t nchunks = (N + CHUNK - 1) / CHUNK;
     int64_t Rp = probe_rp(P, H, Hkv);
-    return (size_t)(2 * (int64_t)P * H + 64) + (size_t)(nchunks * Hkv * Rp * 2 + Hkv * Rp * 2 + Hkv * Np + 256);
+    const size_t windowed = (size_t)(2 * (int64_t)P * H + 64) + (size_t)(nchunks * Hkv * Rp * 2 + Hkv * Rp * 2 + Hkv * Np + 256);
+    const size_t single = probe_p1_scratch_floats(N, H);   // the single-row probe uses the same region from its start
+    return windowed > single ? windowed : single;
 }
 
 bool probe_mfma_supported(const ProbeArgs& a) {

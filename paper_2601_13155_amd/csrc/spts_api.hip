@@ -218,7 +218,8 @@ int probe_attn_impl(spts_ctx* c, const void* x, const int32_t* pos, int64_t N, c
     pa.partial = c->p<float>(c->off.probe) + (2 * (size_t)P * m.H + 64);
     pa.N = N; pa.P = P; pa.H = m.H; pa.Hkv = m.Hkv; pa.d = m.d;
     PHASE(c, PH_PROBE_ATTN);
-    if (c->bf16 && probe_mfma_supported(pa)) SPTS_HIP(c, launch_probe_mfma(pa, c->stream));
+    if (probe_p1_supported(pa)) SPTS_HIP(c, launch_probe_p1(pa, c->p<float>(c->off.probe), c->bf16, c->stream));
+    else if (c->bf16 && probe_mfma_supported(pa)) SPTS_HIP(c, launch_probe_mfma(pa, c->stream));
     else SPTS_HIP(c, launch_probe_generic(pa, c->bf16, c->stream));
     return SPTS_OK;
 }

@@ -143,6 +143,10 @@ hipError_t launch_probe_generic(const ProbeArgs& a, bool bf16, hipStream_t s);
 bool probe_mfma_supported(const ProbeArgs& a);
 hipError_t launch_probe_mfma(const ProbeArgs& a, hipStream_t s);
 size_t probe_scratch_floats(int64_t N, int P, int H, int Hkv);
+// single probe row (P = 1): a scan of K with one query per head; scratch: probe_p1_scratch_floats(N, H) floats
+bool probe_p1_supported(const ProbeArgs& a);
+size_t probe_p1_scratch_floats(int64_t N, int H);
+hipError_t launch_probe_p1(const ProbeArgs& a, float* scratch, bool bf16, hipStream_t s);
 
 // out[r] = mean of the k largest |vals[r, 0..n)|, rows of T with leading dimension ld (elements)
 hipError_t launch_topk_mean(const void* vals, int64_t ld, int64_t rows, int64_t n, int64_t k, float* out, bool bf16,

@@ -138,6 +138,12 @@ PROBE_CASES = [
     ("c0", synth.TINY, 512, 32, 16),
     ("c0_ragged", synth.TINY, 333, 7, 16),
     ("c0_p1", synth.TINY, 200, 1, 16),
+    # single probe row (the paper's default): the scan kernel, several 1024-key chunks, ragged tails
+    ("c0_p1_chunks", synth.TINY, 2500, 1, 16),
+    ("p1_n1", synth.TINY, 1, 1, 16),
+    ("p1_small_bf16_d16", H.small_shape(dtype="bf16"), 1300, 1, 8),
+    ("p1_bf16_d128", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 3001, 1, 64),
+    ("p1_bf16_d64_grp7", synth.ModelShape(D=448, H=7, Hkv=1, d=64, Dff=1024, dtype="bf16"), 1025, 1, 64),
     ("small_bf16", H.small_shape(dtype="bf16"), 150, 5, 8),
     ("bf16_d128", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 700, 64, 64),
     ("bf16_d128_ragged", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 1111, 33, 64),
@@ -148,7 +154,7 @@ PROBE_CASES = [
 
 @pytest.mark.parametrize("name,shape,N,P,r", PROBE_CASES, ids=[c[0] for c in PROBE_CASES])
 def test_probe_attn_and_ffn(torch, name, shape, N, P, r):
-    ctx = ctx_for(shape, 2048)
+    ctx = ctx_for(shape, 4096)
     w, x, pos = _mk(shape, N, r, seed=5)
     dw = runtime.upload_layer(w, shape, r)
     mdl = H.oracle_model(shape)
