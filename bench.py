@@ -280,6 +280,7 @@ def main():
         decode = {"steps": steps_d, "ms_per_token": dms, "tokens_per_s": 1e3 / dms,
                   "bytes_per_token": {"layer_weights": wbytes, "kv_cache": kvbytes, "vocab_table": head_bytes},
                   "gbs": tot / (dms * 1e-3) / 1e9, "hbm_frac": tot / (dms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                  "e2e_ms": ms + steps_d * dms,   # prefill (TTFT) + the decode steps: end-to-end latency of the request
                   "cached_pairs_per_layer": cached, "cached_fraction": sum(cached) / float(wl.layers * wl.N),
                   "distinct_tokens": int(torch.unique(toks).numel()),
                   "phases": {k: {"ms_per_token": v[0] / prof_steps, "launches_per_token": v[1] / prof_steps}
@@ -290,7 +291,30 @@ def main():
             decode["gemv_gbs"] = wbytes / (gemv_ms * 1e-3) / 1e9
             decode["gemv_hbm_frac"] = decode["gemv_gbs"] / PEAK_HBM_GBS
         log(f"[decode] {dms:.3f} ms/token ({1e3 / dms:.1f} tokens/s), {decode['gbs']:.0f} GB/s of weights + cache + table")
-        del caches, crunner, dec, table
+        del caches, crunner, dec
+        # the same decode over the full caches of a dense prefill (every layer keeps all N pairs): the library's own
+        # baseline for the end-to-end figure
+        if dense is not None:
+            dsteps = min(steps_d, 16)
+            dcaches = [runtime.KVCache(shape, wl.N + dsteps + 2) for _ in plan]
+            dr = runtime.StackRunner(ctx, shape, layers, plan, wl.probe_len, wl.protect_last, skip=0, caches=dcaches)
+            dr.run(x0, pos0)
+            ddec = runtime.DecodeRunner(ctx, shape, layers, dcaches, gamma_f, table)
+            ddec.x.copy_(table[1])
+            ddec.generate(wl.N, 1)
+            torch.cuda.synchronize()
+            e0.record()
+            ddec.generate(wl.N + 1, dsteps)
+            e1.record()
+            torch.cuda.synchronize()
+            ddms = e0.elapsed_time(e1) / dsteps
+            decode["dense_cache"] = {"steps": dsteps, "ms_per_token": ddms,
+                                     "e2e_ms": dense["ms_per_step"] + steps_d * ddms,
+                                     "e2e_speedup_spts_over_dense": (dense["ms_per_step"] + steps_d * ddms) / decode["e2e_ms"]}
+            log(f"[decode, dense caches] {ddms:.3f} ms/token -> end-to-end speedup {decode['dense_cache']['e2e_speedup_spts_over_dense']:.2f}x "
+                f"for {steps_d} tokens")
+            del dcaches, dr, ddec
+        del table
 
     # ---- batched TopK: one workgroup per row, so the whole chip streams scores (a single row is latency-bound)
     topk_batched = None
