@@ -143,6 +143,16 @@ int spts_select_topk(spts_ctx *ctx, const float *scores, int64_t N, int64_t k, i
 int spts_select_topk_batched(spts_ctx *ctx, const float *scores, int64_t N, int64_t k,
                              int32_t protect_last, int32_t batch, int32_t *idx_out);
 
+/* TopK per sequence of a variable-length batch (Sec. 3.2 TopK on each sequence's scores): sequence b
+ * owns scores[seg_offsets[b] .. seg_offsets[b+1]), keeps min(seg_k[b], its length) candidates and
+ * writes their indices (local to the sequence, ascending) at idx_out + out_offsets[b].  The three
+ * descriptor arrays are device int64 arrays ([batch+1], [batch], [batch]); max_len >= the longest
+ * sequence (it selects the kernel variant; longer sequences than max_len are a caller error) and
+ * max_len <= the context's max_tokens.  A sequence with budget <= 0 writes nothing. */
+int spts_select_topk_segmented(spts_ctx *ctx, const float *scores, const int64_t *seg_offsets,
+                               const int64_t *seg_k, const int64_t *out_offsets, int32_t batch,
+                               int64_t max_len, int32_t protect_last, int32_t *idx_out);
+
 /* One decoder layer of Alg. 1 in place on x [N, D] (PAP block then LTP block, or the dense
  * branches when cfg->skip == 0).  Optional outputs (NULL = not wanted): kv, s_mha [N],
  * idx_attn [min(N, m_attn)], idx_ffn [min(N, m_ffn)].  With skip == 0 the optional score/index

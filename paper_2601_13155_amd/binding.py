@@ -20,7 +20,7 @@ SPTS_F32, SPTS_BF16 = 0, 1
 
 EXPORTS = (
     "spts_workspace_bytes", "spts_create", "spts_destroy", "spts_strerror", "spts_last_hip_error", "spts_uses_mfma",
-    "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_layer_prefill", "spts_msdp_compact",
+    "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_select_topk_segmented", "spts_layer_prefill", "spts_msdp_compact",
     "spts_decode_layer", "spts_greedy_token", "spts_channel_importance",
     "spts_profile_begin", "spts_profile_end", "spts_profile_count", "spts_profile_get",
 )
@@ -77,6 +77,8 @@ def load() -> C.CDLL:
     lib.spts_select_topk.argtypes = [vp, vp, i64, i64, i32, vp]
     lib.spts_select_topk_batched.restype = C.c_int
     lib.spts_select_topk_batched.argtypes = [vp, vp, i64, i64, i32, i32, vp]
+    lib.spts_select_topk_segmented.restype = C.c_int
+    lib.spts_select_topk_segmented.argtypes = [vp, vp, vp, vp, vp, i32, i64, i32, vp]
     lib.spts_layer_prefill.restype = C.c_int
     lib.spts_layer_prefill.argtypes = [vp, vp, vp, i64, C.POINTER(spts_layer_weights), C.POINTER(spts_layer_cfg),
                                        C.POINTER(spts_kv_out), vp, vp, vp]
@@ -189,6 +191,10 @@ class Context:
     def spts_select_topk_batched(self, scores, N, k, protect_last, batch, idx_out):
         _check(load().spts_select_topk_batched(self.handle, _ptr(scores), N, k, protect_last, batch, _ptr(idx_out)),
                "spts_select_topk_batched")
+
+    def spts_select_topk_segmented(self, scores, seg_offsets, seg_k, out_offsets, batch, max_len, protect_last, idx_out):
+        _check(load().spts_select_topk_segmented(self.handle, _ptr(scores), _ptr(seg_offsets), _ptr(seg_k), _ptr(out_offsets),
+                                                 batch, max_len, protect_last, _ptr(idx_out)), "spts_select_topk_segmented")
 
     def spts_layer_prefill(self, x, pos, N, w: spts_layer_weights, cfg: spts_layer_cfg, kv: Optional[spts_kv_out] = None,
                            s_mha=None, idx_attn=None, idx_ffn=None):

@@ -84,14 +84,25 @@ __device__ inline void pick_bin(const int* hist, int lane, int shift, uint32_t p
 // lo = 64*KPT*wave; slots at or beyond N hold key 0 and are never written out.
 template <int KPT>
 __global__ void __launch_bounds__(TOPK_THREADS) topk_reg_kernel(const float* __restrict__ scores, int64_t N, int64_t k,
-                                                                int protect_last, int32_t* __restrict__ idx_out) {
+                                                                int protect_last, int32_t* __restrict__ idx_out, TopkSegments seg) {
     __shared__ int hist[256];
     __shared__ uint32_t sh_prefix;
     __shared__ int64_t sh_need;
     __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
 
-    scores += (int64_t)blockIdx.x * N;   // one independent problem per workgroup
-    idx_out += (int64_t)blockIdx.x * k;
+    // one independent problem per workgroup: equal rows, or the segment the descriptors give it
+    if (seg.offsets) {
+        const int64_t b0 = seg.offsets[blockIdx.x];
+        N = seg.offsets[blockIdx.x + 1] - b0;
+        k = seg.k[blockIdx.x];
+        scores += b0;
+        idx_out += seg.out_offsets[blockIdx.x];
+        if (k > N) k = N;
+        if (k <= 0 || N <= 0) return;
+    } else {
+        scores += (int64_t)blockIdx.x * N;
+        idx_out += (int64_t)blockIdx.x * k;
+    }
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int lo = wave * (64 * KPT);
@@ -151,14 +162,25 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_reg_kernel(const float* __r
 }
 
 __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restrict__ scores, int64_t N, int64_t k,
-                                                            int protect_last, int32_t* __restrict__ idx_out) {
+                                                            int protect_last, int32_t* __restrict__ idx_out, TopkSegments seg) {
     __shared__ int hist[256];
     __shared__ uint32_t sh_prefix;     // key bits decided so far
     __shared__ int64_t sh_need;        // how many elements are still to be taken inside the current bucket
     __shared__ int64_t wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
 
-    scores += (int64_t)blockIdx.x * N;   // one independent problem per workgroup
-    idx_out += (int64_t)blockIdx.x * k;
+    // one independent problem per workgroup: equal rows, or the segment the descriptors give it
+    if (seg.offsets) {
+        const int64_t b0 = seg.offsets[blockIdx.x];
+        N = seg.offsets[blockIdx.x + 1] - b0;
+        k = seg.k[blockIdx.x];
+        scores += b0;
+        idx_out += seg.out_offsets[blockIdx.x];
+        if (k > N) k = N;
+        if (k <= 0 || N <= 0) return;
+    } else {
+        scores += (int64_t)blockIdx.x * N;
+        idx_out += (int64_t)blockIdx.x * k;
+    }
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
 
@@ -289,13 +311,14 @@ hipError_t launch_topk_mean(const void* vals, int64_t ld, int64_t rows, int64_t 
 }
 
 hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out, int batch,
-                       hipStream_t s) {
-    if (k <= 0 || N <= 0 || batch <= 0) return hipSuccess;
+                       hipStream_t s, TopkSegments seg) {
+    // with segments N is the longest segment (it picks the kernel variant) and k is ignored
+    if ((k <= 0 && !seg.offsets) || N <= 0 || batch <= 0) return hipSuccess;
     const dim3 g((unsigned)batch), b(TOPK_THREADS);
-    if (N <= 1024 * 8) topk_reg_kernel<8><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
-    else if (N <= 1024 * 16) topk_reg_kernel<16><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
-    else if (N <= 1024 * 32) topk_reg_kernel<32><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
-    else topk_kernel<<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
+    if (N <= 1024 * 8) topk_reg_kernel<8><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
+    else if (N <= 1024 * 16) topk_reg_kernel<16><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
+    else if (N <= 1024 * 32) topk_reg_kernel<32><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
+    else topk_kernel<<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
     return hipGetLastError();
 }
 

@@ -494,6 +494,22 @@ int spts_greedy_token(spts_ctx* c, const void* x, const void* gamma_f, const voi
     return SPTS_OK;
 }
 
+int spts_select_topk_segmented(spts_ctx* c, const float* scores, const int64_t* seg_offsets, const int64_t* seg_k,
+                               const int64_t* out_offsets, int32_t batch, int64_t max_len, int32_t protect_last,
+                               int32_t* idx_out) {
+    SPTS_TRY(common_call_checks(c, max_len));
+    if (batch < 0 || batch > 65535) return SPTS_EINVAL;
+    if (batch == 0 || max_len == 0) return SPTS_OK;
+    if (!scores || !seg_offsets || !seg_k || !out_offsets || !idx_out) return SPTS_EINVAL;
+    if (!aligned16(scores) || !aligned16(idx_out) || (reinterpret_cast<uintptr_t>(seg_offsets) & 7u) ||
+        (reinterpret_cast<uintptr_t>(seg_k) & 7u) || (reinterpret_cast<uintptr_t>(out_offsets) & 7u))
+        return SPTS_EALIGN;
+    PHASE(c, PH_TOPK);
+    SPTS_HIP(c, launch_topk(scores, max_len, 0, protect_last, idx_out, batch, c->stream,
+                            TopkSegments{seg_offsets, seg_k, out_offsets}));
+    return SPTS_OK;
+}
+
 int spts_channel_importance(spts_ctx* c, const void* x_cal, int64_t T, const spts_layer_weights* w, int64_t k,
                             float* importance_out) {
     SPTS_TRY(common_call_checks(c, T));

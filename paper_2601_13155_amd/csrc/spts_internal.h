@@ -116,8 +116,12 @@ hipError_t launch_transpose_pad(const void* v, void* vt, int64_t M, int C, int64
 
 // ------------------------------------------------------------------ TopK
 // `batch` independent problems: scores [batch, N] -> idx_out [batch, k], every row ascending.
+// With segment descriptors (device arrays) problem b is scores[offsets[b] .. offsets[b+1]) with budget
+// min(k[b], length), written to idx_out + out_offsets[b] as indices local to the segment; N is then the
+// longest segment.
+struct TopkSegments { const int64_t* offsets; const int64_t* k; const int64_t* out_offsets; };
 hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out,
-                       int batch, hipStream_t s);
+                       int batch, hipStream_t s, TopkSegments seg = TopkSegments{nullptr, nullptr, nullptr});
 
 // ------------------------------------------------------------------ attention
 struct AttnArgs {

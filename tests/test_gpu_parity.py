@@ -99,6 +99,29 @@ def test_select_topk_batched_rows_match_oracle(torch):
                 assert np.array_equal(got[b], orc.topk_select(s[b], k, 1)), (n, k, b)
 
 
+def test_select_topk_segmented_matches_oracle_per_sequence(torch):
+    rng = np.random.default_rng(4)
+    ctx = ctx_for(synth.TINY, 131072)
+    for lens in ((5, 1, 900, 64, 1025), (9000, 100, 8192), (20000, 3)):
+        lens = np.array(lens, dtype=np.int64)
+        offs = np.concatenate([[0], np.cumsum(lens)])
+        ks = np.array([max(0, int(0.4 * n)) if i % 2 == 0 else n + 3 for i, n in enumerate(lens)], dtype=np.int64)  # some budgets exceed the length
+        kept = np.minimum(ks, lens)
+        ooffs = np.concatenate([[0], np.cumsum(kept)])[:-1]
+        s = ((1.0 + 0.3 * rng.standard_normal(int(offs[-1]))).clip(0.05, None) / 1000.0).astype(np.float32)
+        s[int(offs[1]):int(offs[1]) + 3] = s[int(offs[1])]      # ties at the start of the second sequence
+        sd = torch.from_numpy(s).cuda()
+        out = torch.full((int(kept.sum()) + 1,), -7, dtype=torch.int32, device="cuda")
+        ctx.spts_select_topk_segmented(sd, torch.from_numpy(offs).cuda(), torch.from_numpy(ks).cuda(),
+                                       torch.from_numpy(ooffs).cuda(), len(lens), int(lens.max()), 1, out)
+        got = out.cpu().numpy()
+        for b in range(len(lens)):
+            seg = s[offs[b]:offs[b + 1]]
+            ref = orc.topk_select(seg, int(kept[b]), 1)
+            assert np.array_equal(got[ooffs[b]:ooffs[b] + kept[b]], ref), (lens, b)
+        assert got[-1] == -7
+
+
 # ------------------------------------------------------------------------------------------ MSDP
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_msdp_compact_bit_exact(torch, dtype):
