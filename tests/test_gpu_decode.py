@@ -139,3 +139,34 @@ def test_stack_prefill_then_greedy_decode_lockstep(torch, dtype):
     assert [c.count for c in caches] == [160 + steps, 112 + steps, 80 + steps]
     assert all(int(c.pos[c.count - 1]) == wl.N + steps - 1 for c in caches)
     assert len(set(tokens)) >= 1
+
+
+def test_decode_is_deterministic_and_consistent_with_dense_prefill(torch):
+    """Two identical decode calls give bitwise identical states (all merges run in a fixed order), and a dense
+    GPU prefill of N tokens + one decode step lands within tolerance of the last row of a dense GPU prefill of
+    N+1 tokens (the oracle pins the same identity for itself)."""
+    dtype = "bf16"
+    shape = _shape(dtype)
+    N, r = 257, 16
+    w = synth.make_layer(23, 0, shape, r)
+    dw = runtime.upload_layer(w, shape, r)
+    ctx = ctx_for(shape, 2048)
+    x = synth.hidden_states(23, N + 1, shape.D, dtype)
+    pos = torch.from_numpy(synth.positions(N + 1)).cuda()
+    cfg = binding.spts_layer_cfg(0, 1, N + 1, N + 1, 1, 0)
+    outs = []
+    for rep in range(2):
+        cache = runtime.KVCache(shape, N + 1)
+        xd = runtime.to_device(x[:N].copy(), dtype)
+        ctx.spts_layer_prefill(xd, pos[:N].contiguous(), N, dw, cfg, cache.struct, None, None, None)
+        xt = runtime.to_device(x[N:N + 1].copy(), dtype).reshape(-1)
+        ctx.spts_decode_layer(xt, N, dw, cache.struct)
+        torch.cuda.synchronize()
+        outs.append((xt.clone(), cache.k.clone(), cache.v.clone()))
+    assert all(torch.equal(a, b) for a, b in zip(outs[0], outs[1]))
+    full = runtime.to_device(x.copy(), dtype)
+    ctx.spts_layer_prefill(full, pos, N + 1, dw, cfg, None, None, None, None)
+    torch.cuda.synchronize()
+    a = runtime.to_host(outs[0][0]).astype(np.float64)[None, :]
+    b = runtime.to_host(full[N]).astype(np.float64)[None, :]
+    assert H.row_rel_err(a, b) <= H.TOL[dtype]["hidden"]
