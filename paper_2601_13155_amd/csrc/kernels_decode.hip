@@ -74,6 +74,22 @@ __global__ void __launch_bounds__(256) gemv_kernel(GemvArgs a) {
 #pragma unroll
         for (int r = 0; r < ROWS; ++r)
             wrow[r] = (const T*)(r < 2 ? a.W[0] : a.W[1]) + (out_row + (r & 1)) * a.K;
+    } else if (MODE == GEMV_QKV_ROPE) {
+        // Q and K blocks own the rows (j, j+1, j+d/2, j+d/2+1) of one head, so that both members of the
+        // two rotary pairs are reduced by the same workgroup; V blocks own 4 consecutive rows
+        int64_t blk = blockIdx.x;
+        if (blk >= a.R[0] / 4) { blk -= a.R[0] / 4; which = 1; if (blk >= a.R[1] / 4) { blk -= a.R[1] / 4; which = 2; } }
+        if (which < 2) {
+            const int qd = a.head_dim / 4;                       // blocks per head
+            out_row = (blk / qd) * a.head_dim + 2 * (blk % qd);  // j of the first pair
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r)
+                wrow[r] = (const T*)a.W[which] + (out_row + (r & 1) + (r >> 1) * (a.head_dim / 2)) * a.K;
+        } else {
+            out_row = blk * ROWS;
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) wrow[r] = (const T*)a.W[2] + (out_row + r) * a.K;
+        }
     } else {
         int64_t row = (int64_t)blockIdx.x * ROWS;
         if (row >= a.R[0]) { row -= a.R[0]; which = 1; if (row >= a.R[1]) { row -= a.R[1]; which = 2; } }
@@ -141,6 +157,19 @@ __global__ void __launch_bounds__(256) gemv_kernel(GemvArgs a) {
             const float h = g / (1.0f + __expf(-g)) * u;
             ((T*)a.y[0])[out_row + tid] = from_f32<T>(h);
         }
+    } else if (MODE == GEMV_QKV_ROPE) {
+        if (blockIdx.x == 0 && tid == 0 && a.pos_out) *a.pos_out = a.pos_val;
+        if (which == 2) {
+            ((T*)a.y[2])[out_row + tid] = from_f32<T>(v);
+        } else {
+            // tid: 0, 1 = first members (j, j+1), 2, 3 = their partners at +d/2
+            const int half = a.head_dim / 2;
+            const int j = (int)(out_row % a.head_dim) + (tid & 1);
+            const float2 cs = a.rope[j];
+            const float other = sred[0][tid ^ 2] + sred[1][tid ^ 2] + sred[2][tid ^ 2] + sred[3][tid ^ 2];
+            const float res = tid < 2 ? v * cs.x - other * cs.y : v * cs.x + other * cs.y;
+            ((T*)a.y[which])[out_row + (tid & 1) + (tid >> 1) * half] = from_f32<T>(res);
+        }
     } else if (MODE == GEMV_RESID) {
         T* y = (T*)a.y[which] + out_row + tid;
         *y = from_f32<T>(to_f32(*y) + v);
@@ -175,6 +204,10 @@ static hipError_t launch_gemv_t(const GemvArgs& a, hipStream_t s) {
         case GEMV_SILU: if (n) gemv_kernel<T, GEMV_SILU, true><<<g, b, 0, s>>>(a); else gemv_kernel<T, GEMV_SILU, false><<<g, b, 0, s>>>(a); break;
         case GEMV_RESID: if (n) return hipErrorInvalidValue; gemv_kernel<T, GEMV_RESID, false><<<g, b, 0, s>>>(a); break;
         case GEMV_F32: if (n) gemv_kernel<T, GEMV_F32, true><<<g, b, 0, s>>>(a); else gemv_kernel<T, GEMV_F32, false><<<g, b, 0, s>>>(a); break;
+        case GEMV_QKV_ROPE:
+            if (!a.rope || a.head_dim % 4 != 0 || a.R[0] % a.head_dim != 0 || a.R[1] % a.head_dim != 0) return hipErrorInvalidValue;
+            if (n) gemv_kernel<T, GEMV_QKV_ROPE, true><<<g, b, 0, s>>>(a); else gemv_kernel<T, GEMV_QKV_ROPE, false><<<g, b, 0, s>>>(a);
+            break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -182,6 +215,22 @@ static hipError_t launch_gemv_t(const GemvArgs& a, hipStream_t s) {
 
 hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s) {
     return bf16 ? launch_gemv_t<bf16_t>(a, s) : launch_gemv_t<float>(a, s);
+}
+
+// ------------------------------------------------------------------- rotary table of one position
+__global__ void decode_rope_row_kernel(int pos, int half, double neg2_over_d_log2base, float2* __restrict__ table) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= half) return;
+    double sn, cs;
+    sincos((double)pos * exp2((double)j * neg2_over_d_log2base), &sn, &cs);
+    table[j] = make_float2((float)cs, (float)sn);
+}
+
+hipError_t launch_decode_rope_row(int pos, int d, float base, float2* table, hipStream_t s) {
+    const int half = d / 2;
+    decode_rope_row_kernel<<<dim3((unsigned)((half + 63) / 64)), dim3(64), 0, s>>>(pos, half, -2.0 / (double)d * log2((double)base),
+                                                                                 table);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------- rotary + cache append

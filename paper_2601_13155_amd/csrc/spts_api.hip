@@ -75,6 +75,7 @@ struct spts_ctx {
     Workspace off;
     bool bf16;
     int last_hip;
+    int64_t dec_rope_pos = -1;   // position whose (cos, sin) row sits at the start of the rotary table (decode), -1 = none
     // per-phase timing (spts_profile_*): events recorded around the launches of each phase
     bool prof_on = false;
     std::vector<hipEvent_t> ev_pool;
@@ -202,6 +203,7 @@ int check_weights_full(const spts_ctx* c, const spts_layer_weights* w, bool need
 int probe_attn_impl(spts_ctx* c, const void* x, const int32_t* pos, int64_t N, const spts_layer_weights* w, int P,
                     bool want_scores, void* k_out, float* s_out) {
     const auto& m = c->m;
+    c->dec_rope_pos = -1;   // the prefill's table overwrites the decode row
     { PHASE(c, PH_ROPE_TABLE); SPTS_HIP(c, launch_rope_table(pos, N, m.d, m.rope_base, c->p<float2>(c->off.rope), c->stream)); }
     { PHASE(c, PH_RMSNORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, c->p<void>(c->off.xn), N, m.D, c->bf16, c->stream)); }
     const int KV = m.Hkv * m.d, QD = m.H * m.d;
@@ -457,10 +459,26 @@ int spts_decode_layer(spts_ctx* c, void* x, int32_t pos, const spts_layer_weight
     } else {
         PHASE(c, PH_DEC_NORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, xn, 1, m.D, c->bf16, st));
     }
-    { PHASE(c, PH_DEC_QKV); SPTS_HIP(c, launch_gemv(qkv, c->bf16, st)); }
-    { PHASE(c, PH_DEC_ROPE_APPEND);
-      SPTS_HIP(c, launch_decode_rope_append(q, kx, vx, pos, m.H, m.Hkv, m.d, m.rope_base, cache->k, cache->v, cache->pos, row,
-                                            c->bf16, st)); }
+    const size_t eb = c->bf16 ? 2 : 4;
+    if (m.d % 4 == 0) {
+        // rotary embedding in the GEMV's epilogue: q goes to the workspace, the rotated key and the value straight into
+        // row `row` of the cache.  The (cos, sin) row of this position is shared by all layers of the token.
+        if (c->dec_rope_pos != pos) {
+            PHASE(c, PH_DEC_ROPE_APPEND);
+            SPTS_HIP(c, launch_decode_rope_row(pos, m.d, m.rope_base, c->p<float2>(c->off.rope), st));
+            c->dec_rope_pos = pos;
+        }
+        qkv.mode = GEMV_QKV_ROPE; qkv.rope = c->p<float2>(c->off.rope); qkv.head_dim = m.d;
+        qkv.y[1] = (char*)cache->k + (size_t)row * KV * eb;
+        qkv.y[2] = (char*)cache->v + (size_t)row * KV * eb;
+        qkv.pos_out = cache->pos + row; qkv.pos_val = pos;
+        PHASE(c, PH_DEC_QKV); SPTS_HIP(c, launch_gemv(qkv, c->bf16, st));
+    } else {
+        { PHASE(c, PH_DEC_QKV); SPTS_HIP(c, launch_gemv(qkv, c->bf16, st)); }
+        PHASE(c, PH_DEC_ROPE_APPEND);
+        SPTS_HIP(c, launch_decode_rope_append(q, kx, vx, pos, m.H, m.Hkv, m.d, m.rope_base, cache->k, cache->v, cache->pos, row,
+                                              c->bf16, st));
+    }
     { PHASE(c, PH_DEC_ATTN);
       SPTS_HIP(c, launch_decode_attn(q, cache->k, cache->v, row + 1, m.H, m.Hkv, m.d, part, part_floats, att, c->bf16, st)); }
     { PHASE(c, PH_DEC_O); SPTS_HIP(c, launch_gemv(o, c->bf16, st)); }

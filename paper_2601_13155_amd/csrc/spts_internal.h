@@ -162,6 +162,7 @@ enum GemvMode : int {
     GEMV_SILU = 1,    // y[r] = silu(W0[r,:].x) * W1[r,:].x  (T; R[0] rows each)
     GEMV_RESID = 2,   // y[r] += W[r,:].x                    (T, read-modify-write)
     GEMV_F32 = 3,     // y[r] = W[r,:].x                     (fp32)
+    GEMV_QKV_ROPE = 4, // W[0], W[1]: rotary embedding of the products for one position (table `rope`), W[2]: plain store
 };
 // Up to three row-major matrices W[i] [R[i], K] that share the input vector x [K]; y[i] [R[i]].
 // R[i] % 4 == 0, K a multiple of the 16-byte chunk; GEMV_SILU uses W[0] (gate), W[1] (up), y[0].
@@ -171,9 +172,13 @@ struct GemvArgs {
     const void* W[3]; void* y[3]; int32_t R[3];
     const void* x; int32_t K; int mode;
     const void* gamma; float eps;
+    const float2* rope; int32_t head_dim;   // GEMV_QKV_ROPE: (cos, sin)[head_dim / 2] of the token's position
+    int32_t* pos_out; int32_t pos_val;      // GEMV_QKV_ROPE: *pos_out = pos_val (the cache row's position), when not NULL
 };
 bool gemv_supported(const GemvArgs& a, bool bf16);
 hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s);
+// (cos, sin) of one position for the decode GEMV's rotary epilogue: table[j] = (cos, sin)(pos * base^(-2j/d))
+hipError_t launch_decode_rope_row(int pos, int d, float base, float2* table, hipStream_t s);
 // rotary embedding of q [H, d] in place and of k [Hkv, d] into cache row `row`, v copied to that row
 hipError_t launch_decode_rope_append(void* q, const void* k, const void* v, int pos, int H, int Hkv, int d, float base,
                                      void* cache_k, void* cache_v, int32_t* cache_pos, int64_t row, bool bf16, hipStream_t s);
