@@ -248,6 +248,30 @@ def test_layer_prefill_lockstep(torch, name, shape, N, P, r, ka, kf):
     assert H.row_rel_err(gpu["v_cache"].reshape(m_attn, -1), ref.v_cache.reshape(m_attn, -1)) <= tol
 
 
+@pytest.mark.parametrize("name,shape,N,P,r", [
+    ("d128", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 64, 256),
+    ("d64", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16"), 1100, 16, 256),
+], ids=["d128", "d64"])
+def test_layer_modes_on_matrix_core_kernels(torch, name, shape, N, P, r):
+    """The matrix-core attention with separate query / key sets (kv_mode = 1: active queries against the keys
+    and values of all candidates, visible prefix found by search), the dense branch and the literal TopK
+    (protect_last = 0) at tile-sized shapes."""
+    ctx = ctx_for(shape, 2048)
+    assert ctx.uses_mfma()
+    w, x, pos = _mk(shape, N, r, seed=8)
+    dw = runtime.upload_layer(w, shape, r)
+    mdl = H.oracle_model(shape)
+    ma, mf = int(0.3 * N), int(0.45 * N)
+    kv1 = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=ma, m_ffn=mf, kv_mode=1, want_kv=True)
+    H.lockstep_layer(kv1, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 1), shape.dtype)
+    assert kv1["kv_count"] == N and np.array_equal(kv1["pos_cache"], pos)
+    lit = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=ma, m_ffn=mf, protect_last=0)
+    H.lockstep_layer(lit, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 0, 0), shape.dtype)
+    dense = runtime.run_layer(ctx, x, pos, dw, shape, skip=0, probe_len=P, m_attn=0, m_ffn=0, want_kv=True)
+    H.lockstep_layer(dense, x, pos, w, mdl, orc.LayerCfg(0, P, N, N, 1, 0), shape.dtype)
+    assert dense["kv_count"] == N
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_layer_dense_keepall_keepzero_and_modes(torch, dtype):
     shape = synth.TINY if dtype == "f32" else synth.ModelShape(D=256, H=4, Hkv=2, d=64, Dff=688, dtype="bf16")
