@@ -73,8 +73,8 @@ def cpu_baseline(wl, w_host, sample_tokens, layers_equiv):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "p32"],
                     help="c2 = the configuration the metric is quoted on; p32 = the paper's own LLaMA schedule at 32K")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's)")
