@@ -161,7 +161,8 @@ def test_c2_whole_stack_properties_and_sampled_layers():
 
 def test_c4_qwen_shaped_layer_lockstep():
     """Config c4's layer shape (D = 3584, 28 query / 4 KV heads: 7 query heads per KV head, Dff = 18944) at
-    N = 4096: the whole layer against the oracle, lock-step, plus a stage-end compaction."""
+    N = 4096: the whole layer against the oracle, lock-step, plus a stage-end compaction and two decode steps
+    over the layer's compressed cache."""
     import torch
     wl = synth.WORKLOADS["c4"]
     shape = wl.shape
@@ -193,6 +194,30 @@ def test_c4_qwen_shaped_layer_lockstep():
     assert np.array_equal(n2o.cpu().numpy(), rn2o) and np.array_equal(o2n.cpu().numpy(), ro2n)
     assert np.array_equal(po.cpu().numpy(), rp)
     assert torch.equal(xo, xd[n2o.long()])
+    # decode over this layer's compressed cache (7 query heads per KV head; D and Dff of the Qwen shape)
+    from paper_2601_13155_amd import binding
+    cache = runtime.KVCache(shape, m_attn + 2)
+    xd2 = runtime.to_device(x, shape.dtype)
+    ctx.spts_layer_prefill(xd2, pd, N, dw, binding.spts_layer_cfg(1, wl.probe_len, m_attn, m_ffn, 1, 0), cache.struct,
+                           None, None, None)
+    torch.cuda.synchronize()
+    assert cache.count == m_attn
+    mdl = H.oracle_model(shape)
+    new = synth.hidden_states(91, 3, shape.D, shape.dtype)[1:]
+    for t in range(2):
+        kh, vh, ph = cache.host()
+        xt = runtime.to_device(new[t:t + 1].copy(), shape.dtype).reshape(-1)
+        x_in = runtime.to_host(xt).astype(np.float64)
+        ctx.spts_decode_layer(xt, N + t, dw, cache.struct)
+        torch.cuda.synchronize()
+        ref_x, ref_c = orc.decode_layer(x_in, N + t, w, mdl, orc.LayerCache(kh, vh, ph), orc.bf16_round)
+        got = runtime.to_host(xt).astype(np.float64)
+        err = H.row_rel_err(got[None, :], ref_x[None, :])
+        print(f"c4 decode step {t}: hidden err {err:.3e}")
+        assert err <= H.TOL["bf16"]["hidden"]
+        k2, v2, p2 = cache.host()
+        assert H.row_rel_err(k2[-1].reshape(1, -1), ref_c.k[-1].reshape(1, -1)) <= H.TOL["bf16"]["hidden"]
+        assert H.row_rel_err(v2[-1].reshape(1, -1), ref_c.v[-1].reshape(1, -1)) <= H.TOL["bf16"]["hidden"]
     del ctx, dw
     torch.cuda.empty_cache()
 
