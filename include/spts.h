@@ -88,9 +88,10 @@ typedef struct {
     int32_t kv_mode;      /* 0: keys/values of the active set only (Alg. 1); 1: of all candidates  */
 } spts_layer_cfg;
 
-/* Optional KV-cache output of a layer (Sec. 3.2 last paragraph: only active pairs are cached).
- * k, v: [capacity, Hkv, d] model dtype, post-rotary keys; pos: [capacity] int32.
- * count is written by the library on the host: number of rows filled. */
+/* KV cache of one layer (Sec. 3.2 last paragraph: only active pairs are cached).
+ * k, v: [capacity, Hkv, d] model dtype, post-rotary keys; pos: [capacity] int32; caller-owned
+ * device memory.  count lives on the host: spts_layer_prefill sets it to the number of rows it
+ * filled, spts_decode_layer appends one row at index count and increments it. */
 typedef struct {
     void *k, *v;
     int32_t *pos;
