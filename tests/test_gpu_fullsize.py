@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of the benchmark's configurations, in the launch configuration that
+"""GPU parity at the full sizes of the benchmark configurations (synth.WORKLOADS), in the launch configuration that
 bench.py times (matrix-core kernels, 8B-shaped bf16 layer).
 
 * c1 (N = 8192): the whole layer against the oracle, lock-step.
