@@ -24,7 +24,10 @@
 //    folded into the A loads: a row is 2*K contiguous bytes, so nothing is lost in coalescing),
 //    rows of C may be scattered through one (the residual update X[T] += ...).
 //  * The MFMA is issued as D^T = B * A^T so that a lane ends up with 4 consecutive output columns
-//    of one row: 8-byte packed stores, lane-local rotary / SiLU-mul pairing, in-lane row sums.
+//    of one row: lane-local rotary / SiLU-mul pairing, in-lane row sums, 8-byte packed pieces.
+//  * The finished bf16 tile is staged through LDS (the operand ring is free by then) and leaves in
+//    whole rows, 16 bytes per lane: stores straight from the fragment layout reach memory as 16-byte
+//    pieces of 32 different rows per instruction, which cost a short-K GEMM a quarter of its time.
 //  * Workgroup ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous range
 //    of tiles in groups of 4 row panels: concurrently running tiles share A and B panels in L2.
 //  * One workgroup fits a CU, so tiles run in rounds of 256.  When the last round is partly filled
@@ -312,9 +315,20 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
         }
         return;
     }
+    // The finished values are packed to bf16 and staged through LDS (the operand ring is free now) so that
+    // the tile leaves in whole rows: a lane owns 4 consecutive columns of 16 different rows per N block,
+    // and stores straight from the fragment layout would reach memory as 16-byte pieces of 32 rows per
+    // instruction.  Staged row tr keeps 16-byte chunk c at chunk position c ^ (tr % NCH): the 32 lanes of a
+    // fragment write (32 rows, same chunk) and the row-wise reads are both spread over all banks.
+    constexpr int NCH = OUT_COLS / 8;            // 16-byte chunks per staged row
+    constexpr int ROWB = OUT_COLS * 2;           // bytes per staged row
+    auto stage = [&](int tr, int tc, uint2 o) {
+        *reinterpret_cast<uint2*>(smem + tr * ROWB + ((((tc >> 3) ^ tr) & (NCH - 1)) << 4) + ((tc & 4) << 1)) = o;
+    };
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
-        const int64_t grow = row0 + wm * WROWS + i * 32 + l32;
+        const int tr = wm * WROWS + i * 32 + l32;
+        const int64_t grow = row0 + tr;
         const bool rok = grow < a.M;
         const int64_t growc = rok ? grow : a.M - 1;
         const int64_t crow = a.c_idx ? (int64_t)a.c_idx[growc] : growc;
@@ -327,7 +341,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
                     uint2 o;
                     o.x = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
                     o.y = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                    if (rok) *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q) = o;
+                    stage(tr, cb - col0 + 8 * q, o);
                     if (a.Ct && grow < a.ldct) {
                         bf16_t* ct = (bf16_t*)a.Ct;
                         const uint16_t e[4] = {(uint16_t)(o.x & 0xffff), (uint16_t)(o.x >> 16), (uint16_t)(o.y & 0xffff), (uint16_t)(o.y >> 16)};
@@ -337,25 +351,24 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
                 }
             }
         } else if (EPI == EPI_RESIDUAL) {
-            if (rok) {
+            // the old values are read in the fragment layout (rows past M read the last row; they are not
+            // stored): one rounding of old + acc, as without the staging
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int cb = col0 + wn * 128 + j * 32 + 4 * lh;
+            for (int j = 0; j < 4; ++j) {
+                const int cb = col0 + wn * 128 + j * 32 + 4 * lh;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        uint2* p = reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q);
-                        uint2 old = *p;
-                        float x0 = __uint_as_float(old.x << 16), x1 = __uint_as_float(old.x & 0xffff0000u);
-                        float x2 = __uint_as_float(old.y << 16), x3 = __uint_as_float(old.y & 0xffff0000u);
-                        uint2 o;
-                        o.x = pack_bf16x2(x0 + acc[i][j][4 * q], x1 + acc[i][j][4 * q + 1]);
-                        o.y = pack_bf16x2(x2 + acc[i][j][4 * q + 2], x3 + acc[i][j][4 * q + 3]);
-                        *p = o;
-                    }
+                for (int q = 0; q < 4; ++q) {
+                    const uint2 old = *reinterpret_cast<const uint2*>(Cb + crow * a.ldc + cb + 8 * q);
+                    float x0 = __uint_as_float(old.x << 16), x1 = __uint_as_float(old.x & 0xffff0000u);
+                    float x2 = __uint_as_float(old.y << 16), x3 = __uint_as_float(old.y & 0xffff0000u);
+                    uint2 o;
+                    o.x = pack_bf16x2(x0 + acc[i][j][4 * q], x1 + acc[i][j][4 * q + 1]);
+                    o.y = pack_bf16x2(x2 + acc[i][j][4 * q + 2], x3 + acc[i][j][4 * q + 3]);
+                    stage(tr, cb - col0 + 8 * q, o);
                 }
             }
         } else if (EPI == EPI_SILU_MUL) {
-            if (rok) {
+            {
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int cb = col0 + wn * 64 + j * 32 + 4 * lh;
@@ -366,13 +379,13 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
                         float h2 = silu_f(acc[i][j][4 * q + 2]) * acc[i][j + 2][4 * q + 2];
                         float h3 = silu_f(acc[i][j][4 * q + 3]) * acc[i][j + 2][4 * q + 3];
                         uint2 o; o.x = pack_bf16x2(h0, h1); o.y = pack_bf16x2(h2, h3);
-                        *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q) = o;
+                        stage(tr, cb - col0 + 8 * q, o);
                     }
                 }
             }
         } else if (EPI == EPI_ROPE) {
-            if (rok) {
-                const int64_t trow = a.rope_idx ? (int64_t)a.rope_idx[grow] : grow;
+            {
+                const int64_t trow = a.rope_idx ? (int64_t)a.rope_idx[growc] : growc;
                 const int half = a.head_dim >> 1;
                 const float2* tab = a.rope + trow * half;
                 if (half == 64) {
@@ -394,8 +407,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
                             uint2 o1, o2;
                             o1.x = pack_bf16x2(lo[0], lo[1]); o1.y = pack_bf16x2(lo[2], lo[3]);
                             o2.x = pack_bf16x2(hi[0], hi[1]); o2.y = pack_bf16x2(hi[2], hi[3]);
-                            *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q) = o1;
-                            *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 64 + 8 * q) = o2;
+                            stage(tr, cb - col0 + 8 * q, o1);
+                            stage(tr, cb - col0 + 64 + 8 * q, o2);
                         }
                     }
                 } else {
@@ -417,12 +430,27 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
                             uint2 o1, o2;
                             o1.x = pack_bf16x2(lo[0], lo[1]); o1.y = pack_bf16x2(lo[2], lo[3]);
                             o2.x = pack_bf16x2(hi[0], hi[1]); o2.y = pack_bf16x2(hi[2], hi[3]);
-                            *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 8 * q) = o1;
-                            *reinterpret_cast<uint2*>(Cb + crow * a.ldc + cb + 32 + 8 * q) = o2;
+                            stage(tr, cb - col0 + 8 * q, o1);
+                            stage(tr, cb - col0 + 32 + 8 * q, o2);
                         }
                     }
                 }
             }
+        }
+    }
+    // ---- the staged tile leaves row by row: NCH consecutive lanes write one row's OUT_COLS columns as
+    //      16-byte pieces (whole 128-byte lines), rows through the scatter list when there is one
+    __syncthreads();
+    constexpr int RPP = NW * 64 / NCH;           // rows per pass of the workgroup
+    const int oc = tid % NCH, orow = tid / NCH;
+#pragma unroll 4
+    for (int p = 0; p < 256 / RPP; ++p) {
+        const int tr = p * RPP + orow;
+        const int64_t grow = row0 + tr;
+        if (grow < a.M) {
+            const int64_t crow = a.c_idx ? (int64_t)a.c_idx[grow] : grow;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(smem + tr * ROWB + (((oc ^ tr) & (NCH - 1)) << 4));
+            *reinterpret_cast<u32x4*>(Cb + crow * a.ldc + col0 + oc * 8) = v;
         }
     }
 }
@@ -440,7 +468,7 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     if (a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
     if (!al16(a.A) || !al16(a.B0) || (a.A1 && !al16(a.A1)) || (dual && !al16(a.B1))) return false;
     if (a.epi != EPI_SUMSQ) {
-        if (a.ldc % 4 != 0 || (reinterpret_cast<uintptr_t>(a.C) & 7u)) return false;
+        if (a.ldc % 8 != 0 || !al16(a.C)) return false;
     }
     if (a.epi == EPI_ROPE && a.head_dim != 128 && a.head_dim != 64) return false;
     if (a.Ct && a.epi != EPI_STORE) return false;
