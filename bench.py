@@ -75,8 +75,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "p32"],
-                    help="c2 = the configuration the metric is quoted on; p32 = the paper's own LLaMA schedule at 32K")
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "p32", "q32"],
+                    help="c2 = the configuration the metric is quoted on; p32 / q32 = the paper's own LLaMA / Qwen schedule at 32K")
+    ap.add_argument("--length", type=int, default=0, help="override the context length N (0 = the workload's)")
+    ap.add_argument("--components", default="full", choices=["full", "pap+ltp", "pap"],
+                    help="modules switched on: all three, no stage pruning, or attention skipping only")
+    ap.add_argument("--ablation", action="store_true",
+                    help="p32 / q32: also time dense, PAP, PAP+LTP and PAP+LTP+MSDP prefills at 8K, 16K, 24K and 32K tokens, "
+                         "and the end-to-end latency with 16 decoded tokens (the measurements of Sec. 4.2 / Table "
+                         "ablation_main_speed, on synthetic data)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's)")
     ap.add_argument("--weight-pool", type=int, default=2,
                     help="distinct synthetic weight sets; layers cycle through them (bounds set-up time)")
@@ -114,6 +121,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     wl = synth.WORKLOADS[args.workload]
+    if args.length or args.components != "full":
+        wl = synth.scaled(wl, N=args.length or wl.N, components=args.components)
     if args.layers:
         ends = tuple(e for e in wl.stage_end_layers if e < args.layers)
         wl = synth.scaled(wl, layers=args.layers, stage_end_layers=ends, stage_cum_keep=wl.stage_cum_keep[:len(ends) + 1])
@@ -169,6 +178,8 @@ def main():
         if item.get("skip", 1):
             f = cm.layer_flops(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, item["N"], wl.probe_len,
                                min(item["N"], item["m_attn"]), min(item["N"], item["m_ffn"]), wl.r, Dlow, True)
+            if item["m_ffn"] >= item["N"]:
+                f["proxy"] = 0.0   # every candidate takes the FFN: the library does not run the proxy
         else:   # dense layer of the schedule: same phases, all tokens, no probe / proxy
             f = cm.layer_flops(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, item["N"], wl.probe_len,
                                item["N"], item["N"], wl.r, Dlow, False)
@@ -316,6 +327,55 @@ def main():
             del dcaches, dr, ddec
         del table
 
+    # ---- component ablation over context lengths (paper schedules only)
+    ablation = None
+    if args.ablation and wl.stage_budgets:
+        lengths = [n for n in (8192, 16384, 24576, 32768) if n <= wl.N]
+        variants = ("dense", "pap", "pap+ltp", "full")
+        ttft = {v: [] for v in variants}
+        e2e = {"dense": [], "full": []}
+        nsteps = max(2, min(args.steps, 5))
+        table = runtime.to_device(synth.vocab_table(wl.seed, args.vocab, shape.D, shape.dtype), shape.dtype)
+        gamma_f = runtime.to_device(np.ones(shape.D, dtype=np.float32), shape.dtype)
+
+        def decode16(pl, skip_flag, n_tok, xs, ps):
+            caches_ = [runtime.KVCache(shape, ((min(it["N"], it["m_attn"]) if it.get("skip", 1) else it["N"]) if skip_flag
+                                               else n_tok) + 20) for it in pl]
+            runtime.StackRunner(ctx, shape, layers, pl, wl.probe_len, wl.protect_last, skip=skip_flag, caches=caches_).run(xs, ps)
+            d_ = runtime.DecodeRunner(ctx, shape, layers, caches_, gamma_f, table)
+            d_.x.copy_(table[1])
+            d_.generate(n_tok, 1)
+            torch.cuda.synchronize()
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            d_.generate(n_tok + 1, 16)
+            a1.record()
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1)
+
+        for n_tok in lengths:
+            xs, ps = x0[:n_tok].contiguous(), pos0[:n_tok].contiguous()
+            for v in variants:
+                pl = synth.scaled(wl, N=n_tok, components="full" if v == "dense" else v).layer_plan()
+                rn = runtime.StackRunner(ctx, shape, layers, pl, wl.probe_len, wl.protect_last, skip=0 if v == "dense" else 1)
+                rn.run(xs, ps)
+                torch.cuda.synchronize()
+                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a0.record()
+                for _ in range(nsteps):
+                    rn.run(xs, ps)
+                a1.record()
+                torch.cuda.synchronize()
+                ttft[v].append(a0.elapsed_time(a1) / nsteps)
+                if v in e2e:
+                    e2e[v].append(ttft[v][-1] + decode16(pl, 0 if v == "dense" else 1, n_tok, xs, ps))
+            log(f"[ablation] N={n_tok}: " + ", ".join(f"{v} {ttft[v][-1]:.1f} ms" for v in variants)
+                + f"; e2e(16) dense {e2e['dense'][-1]:.1f} / full {e2e['full'][-1]:.1f} ms")
+        ablation = {"lengths": lengths, "steps": nsteps, "ttft_ms": ttft,
+                    "ttft_speedup_over_dense": {v: [d / t for d, t in zip(ttft["dense"], ttft[v])] for v in variants[1:]},
+                    "e2e16_ms": e2e, "e2e16_speedup_over_dense": [d / t for d, t in zip(e2e["dense"], e2e["full"])]}
+        del table
+
     # ---- batched TopK: one workgroup per row, so the whole chip streams scores (a single row is latency-bound)
     topk_batched = None
     if args.topk_batch > 0:
@@ -376,10 +436,10 @@ def main():
                    "attn_keep": wl.attn_keep, "ffn_keep": wl.ffn_keep, "proxy_rank": wl.r, "proxy_dlow": Dlow,
                    "dense_layers": wl.dense_layers, "stage_budgets": list(wl.stage_budgets), "stage_prune": wl.stage_prune,
                    "stage_end_layers": list(wl.stage_end_layers), "stage_cum_keep": list(wl.stage_cum_keep),
-                   "weight_pool": pool, "batch": 1},
+                   "components": wl.components, "weight_pool": pool, "batch": 1},
         "algorithmic_tflop_per_step": total_flops / 1e12,
         "achieved_tflops_whole_step": total_flops / (ms * 1e-3) / 1e12,
-        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched, "decode": decode, "proxy_builder": builder,
+        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched, "decode": decode, "proxy_builder": builder, "ablation": ablation,
     }
     print(json.dumps(out), flush=True)
 

@@ -83,7 +83,8 @@ typedef struct {
     int32_t skip;         /* 0: dense layer (the else-branches of Alg. 1); 1: PAP + LTP          */
     int32_t probe_len;    /* P >= 1 trailing candidates used as probe queries (P = 1 in Sec. 3.2)  */
     int64_t m_attn;       /* M_fixed for attention; the library applies min(N, m)                  */
-    int64_t m_ffn;        /* M_fixed for the FFN                                                   */
+    int64_t m_ffn;        /* M_fixed for the FFN; >= N: every candidate is active, the proxy is
+                           * not evaluated (TopK of all N is the whole set)                      */
     int32_t protect_last; /* != 0: the last candidate is always active                             */
     int32_t kv_mode;      /* 0: keys/values of the active set only (Alg. 1); 1: of all candidates  */
 } spts_layer_cfg;

@@ -673,7 +673,11 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
     if (Mf == 0) return SPTS_OK;
     { PHASE(c, PH_RMSNORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, m.rms_eps, xn, N, m.D, c->bf16, st)); }
     int32_t* idxF = nullptr;
-    if (skip) {
+    if (skip && Mf >= N) {
+        // the budget covers every candidate: TopK of all N is the whole set whatever the scores are, so the
+        // proxy is not run and the FFN takes the rows in place
+        if (idx_ffn) SPTS_HIP(c, launch_iota_i32(idx_ffn, N, st));
+    } else if (skip) {
         float* SF = c->p<float>(c->off.SF);
         SPTS_TRY(proxy_scores_impl(c, xn, N, w, S, nullptr, SF));
         idxF = idx_ffn ? idx_ffn : c->p<int32_t>(c->off.idxF);

@@ -77,9 +77,15 @@ class Workload:
     # proxy: Dlow channels of the FFN (0 = all Dff), rank r zero-padded to r_pad columns (0 = no padding)
     dlow: int = 0
     r_pad: int = 0
+    # Which modules are switched on (the rows of Table ablation_main_speed): "full" = PAP + LTP + MSDP;
+    # "pap+ltp" = the same budgets but the candidate set is never pruned; "pap" = additionally every
+    # candidate takes the FFN (no proxy, no FFN selection).
+    components: str = "full"
 
     def stage_sizes(self) -> List[int]:
         """Candidate counts per stage: floor(cum_keep_s * N_0), or N_0 - s * stage_prune."""
+        if self.components != "full":
+            return [self.N] * (len(self.stage_end_layers) + 1)
         if self.stage_budgets:
             return [max(0, self.N - s * self.stage_prune) for s in range(len(self.stage_end_layers) + 1)]
         return [int(math.floor(c * self.N + 1e-9)) for c in self.stage_cum_keep]
@@ -101,8 +107,11 @@ class Workload:
                             m_attn=int(math.floor(self.attn_keep * n + 1e-9)),
                             m_ffn=int(math.floor(self.ffn_keep * n + 1e-9)),
                             N_next=None, skip=1)
+            if self.components == "pap" and item["skip"]:
+                item["m_ffn"] = n
             if s < len(self.stage_end_layers) and l == self.stage_end_layers[s]:
-                item["N_next"] = sizes[s + 1]
+                if self.components == "full":
+                    item["N_next"] = sizes[s + 1]
                 s += 1
             plan.append(item)
         return plan
@@ -136,6 +145,12 @@ WORKLOADS: Dict[str, Workload] = {
     "p32": Workload("p32", LLAMA8B, N=32768, layers=32, probe_len=1, attn_keep=0.0, ffn_keep=0.0, r=192, seed=5,
                     stage_end_layers=(14, 19, 24, 29), dense_layers=10,
                     stage_budgets=(9216, 7168, 4096, 2048, 1024), stage_prune=1024, dlow=512, r_pad=256),
+    # The paper's Qwen schedule at 32K (Sec. 4.1): 28 layers, layers 1-9 dense, then (4, 4, 4, 4, 3) layers with
+    # budgets (13, 10, 7, 4, 1)K, 2K candidates pruned at each stage end, (Dlow, r) = (1024, 256).  The paper
+    # prints four budgets; the fifth continues their step of 3K, as the LLaMA schedule's fifth continues its own.
+    "q32": Workload("q32", QWEN7B, N=32768, layers=28, probe_len=1, attn_keep=0.0, ffn_keep=0.0, r=256, seed=6,
+                    stage_end_layers=(13, 17, 21, 25), dense_layers=9,
+                    stage_budgets=(13312, 10240, 7168, 4096, 1024), stage_prune=2048, dlow=1024),
 }
 
 

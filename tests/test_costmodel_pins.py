@@ -70,3 +70,30 @@ def test_layer_flops_matches_hand_count():
     assert abs(sum(f.values()) / 1e12 - 1.80) < 0.02
     dense = cm.layer_flops(4096, 32, 8, 128, 14336, 8192, 64, 8192, 8192, 256, 14336, skip=False)
     assert abs(sum(dense.values()) / 1e12 - 4.12) < 0.02
+
+
+def test_component_toggles_and_qwen_schedule_plans():
+    """Plans behind the component ablation (Table ablation_main_speed: PAP, +LTP, +MSDP) and the Qwen
+    schedule of Sec. 4.1, checked against numbers written out by hand from the text."""
+    from paper_2601_13155_amd import synth
+    K = 1024
+    q = synth.WORKLOADS["q32"].layer_plan()
+    assert len(q) == 28 and [it["skip"] for it in q] == [0] * 9 + [1] * 19
+    # stage ends after the 13th, 17th, 21st and 25th layer; 2K candidates go at each
+    assert [it["layer"] for it in q if it["N_next"] is not None] == [13, 17, 21, 25]
+    assert [it["N"] for it in q][9:] == [32 * K] * 4 + [30 * K] * 4 + [28 * K] * 4 + [26 * K] * 4 + [24 * K] * 3
+    assert [it["m_attn"] for it in q][9:] == [13 * K] * 4 + [10 * K] * 4 + [7 * K] * 4 + [4 * K] * 4 + [1 * K] * 3
+    assert all(it["m_attn"] == it["m_ffn"] for it in q)
+    # at 8K the first LLaMA budget (9K) exceeds the sequence: min(N, M_fixed) keeps every token
+    p8 = synth.scaled(synth.WORKLOADS["p32"], N=8 * K).layer_plan()
+    assert [min(it["N"], it["m_attn"]) for it in p8][10:14] == [8 * K] * 4 and p8[14]["N"] == 7 * K
+    for name in ("p32", "q32"):
+        full = synth.WORKLOADS[name].layer_plan()
+        nl = synth.scaled(synth.WORKLOADS[name], components="pap+ltp").layer_plan()
+        pap = synth.scaled(synth.WORKLOADS[name], components="pap").layer_plan()
+        for f, a, b in zip(full, nl, pap):
+            assert a["N"] == b["N"] == 32 * K and a["N_next"] is None and b["N_next"] is None
+            assert a["skip"] == b["skip"] == f["skip"]
+            assert a["m_attn"] == b["m_attn"] == (f["m_attn"] if f["skip"] else 32 * K)   # same budgets, set never pruned
+            assert a["m_ffn"] == a["m_attn"] and b["m_ffn"] == 32 * K                      # PAP alone: FFN for every token
+

@@ -276,6 +276,30 @@ def test_paper_schedule_layer_lockstep():
     torch.cuda.empty_cache()
 
 
+def test_qwen_paper_schedule_layer_lockstep():
+    """A Qwen-shaped skip layer with the paper's settings for that model (Sec. 4.1): single-row probe,
+    (Dlow, r) = (1024, 256), first-stage budget 13K of 32K scaled to N = 4096 (1664 active tokens)."""
+    import torch
+    wl = synth.WORKLOADS["q32"]
+    shape = wl.shape
+    N, budget = 4096, 1664
+    w = synth.make_layer(wl.seed, 10, shape, wl.r, wl.dlow, wl.r_pad)
+    assert w["Vg"].shape == (256, 1024) and w["Ug"].shape == (shape.D, 256)
+    dw = runtime.upload_layer(w, shape, wl.proxy_r)
+    ctx = runtime.make_context(shape, N, 1, wl.proxy_r, wl.proxy_dlow)
+    assert ctx.uses_mfma()
+    x = synth.hidden_states(wl.seed, N, shape.D, shape.dtype)
+    pos = synth.positions(N)
+    gpu = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=1, m_attn=budget, m_ffn=budget, protect_last=1)
+    cfg = orc.LayerCfg(1, 1, budget, budget, 1, 0)
+    res = H.lockstep_layer(gpu, x, pos, w, H.oracle_model(shape), cfg, shape.dtype)
+    print(f"q32 layer: swaps attn={res['swaps_attn']} ffn={res['swaps_ffn']} hidden err={res['err']:.3e}")
+    assert res["swaps_attn"] <= budget // 50 and res["swaps_ffn"] <= budget // 50
+    assert np.array_equal(gpu["idx_attn"], orc.topk_select(gpu["s_mha"], budget, 1))
+    del dw, ctx
+    torch.cuda.empty_cache()
+
+
 def test_decode_8b_shaped_layer_after_skipped_prefill():
     """8B-shaped bf16 layer: token-skipped prefill of 8192 tokens fills the cache with the 3276 active pairs;
     two new tokens then go through spts_decode_layer, each checked against the oracle from the GPU's own

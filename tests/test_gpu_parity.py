@@ -347,16 +347,20 @@ def test_stack_with_msdp_lockstep(torch, dtype):
     assert po[-1].item() == wl.N - 1
 
 
+@pytest.mark.parametrize("components", ["full", "pap+ltp", "pap"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_stack_paper_schedule_lockstep(torch, dtype):
+def test_stack_paper_schedule_lockstep(torch, dtype, components):
     """The paper's own schedule in miniature (Sec. 4.1): dense first layers, absolute budgets per stage,
     a fixed number of candidates pruned at every stage end, single-row probe, proxy on a channel subset
-    (Dlow < Dff) with a zero-padded rank."""
+    (Dlow < Dff) with a zero-padded rank; and the two reduced variants of Table ablation_main_speed (no
+    stage pruning; attention skipping only, where the FFN budget covers every candidate)."""
     shape = synth.TINY if dtype == "f32" else synth.ModelShape(D=256, H=4, Hkv=2, d=64, Dff=688, dtype="bf16")
     wl = synth.scaled(synth.WORKLOADS["p32"], shape=shape, N=500, layers=6, dense_layers=2, stage_end_layers=(3, 4, 5),
-                      stage_budgets=(200, 150, 100, 50), stage_prune=30, r=12, r_pad=16, dlow=256)
+                      stage_budgets=(200, 150, 100, 50), stage_prune=30, r=12, r_pad=16, dlow=256, components=components)
     plan = wl.layer_plan()
-    assert [it["skip"] for it in plan] == [0, 0, 1, 1, 1, 1] and [it["N"] for it in plan] == [500, 500, 500, 470, 440, 410]
+    n_expect = [500, 500, 500, 470, 440, 410] if components == "full" else [500] * 6
+    assert [it["skip"] for it in plan] == [0, 0, 1, 1, 1, 1] and [it["N"] for it in plan] == n_expect
+    assert [it["m_ffn"] for it in plan][2:] == ([500] * 4 if components == "pap" else [200, 150, 100, 50])
     ws = [synth.make_layer(wl.seed, l, shape, wl.r, wl.dlow, wl.r_pad) for l in range(wl.layers)]
     assert ws[0]["Vg"].shape == (16, 256) and not ws[0]["Ug"][:, 12:].any()
     dws = [runtime.upload_layer(w, shape, wl.proxy_r) for w in ws]
@@ -366,7 +370,7 @@ def test_stack_paper_schedule_lockstep(torch, dtype):
     pos0 = synth.positions(wl.N)
     xo, po, n_final = runner.run(runtime.to_device(x0, dtype), torch.from_numpy(pos0).cuda())
     torch.cuda.synchronize()
-    assert n_final == 410
+    assert n_final == n_expect[-1]
     mdl = H.oracle_model(shape)
     for tr, item, w in zip(runner.trace, plan, ws):
         N = tr["N"]
