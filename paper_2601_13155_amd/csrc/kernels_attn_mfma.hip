@@ -35,7 +35,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BKV = 64;
-constexpr int ATT_NST = 4;
+constexpr int ATT_NST = 5;
 
 template <int D> struct AttnLds {
     static constexpr int K_BYTES = BKV * D * 2;
@@ -65,6 +65,13 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
     constexpr int K_LOADS = L::template k_loads<NW>();
     constexpr int V_LOADS = L::template v_loads<NW>();
     constexpr int PER = K_LOADS + V_LOADS;
+    constexpr int NSTEP = KS + 2 * DB;   // MFMAs per pipeline slot: QK^T of one block + PV of another
+    constexpr int NA = NSTEP / 8;
+#ifndef SPTS_ATT_FD
+#define SPTS_ATT_FD 3
+#endif
+    constexpr int FD = SPTS_ATT_FD;      // fragment reads run FD steps ahead of the MFMA that consumes them
+    static_assert(QB == 1 && (NSTEP == 16 || NSTEP == 8), "the pipeline slot is written for one 32-query block per wavefront");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int per = (total + 7) / 8;
@@ -160,7 +167,15 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
     f32x16 sa[QB], sb[QB];   // S^T of two consecutive 32-key blocks (one being produced, one in the softmax)
-    bf16x8 pf[QB][2];
+    bf16x8 pfa[QB][2], pfb[QB][2];   // probabilities of two consecutive blocks (one being produced, one multiplied)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {   // slot 0 multiplies an all-zero "block -1"
+            const u32x4 z_ = {0u, 0u, 0u, 0u};
+            pfa[qb][hf] = __builtin_bit_cast(bf16x8, z_);
+            pfb[qb][hf] = __builtin_bit_cast(bf16x8, z_);
+        }
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // S^T block: 32 keys (block kb_ of the tile in `stage_`) x QB*32 queries
@@ -185,84 +200,105 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
                 SSRC[qb][r] = kp_ > qpos_l[qb] ? -INFINITY : SSRC[qb][r];                                  \
         }                                                                                                  \
     }
-    // online softmax of one S^T block: probabilities -> pf (bf16 fragments), new running maximum
-#define SPTS_ATT_SOFTMAX(SSRC)                                                                             \
-    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                                    \
-        float mx_ = -INFINITY;                                                                             \
-        _Pragma("unroll") for (int r = 0; r < 16; ++r) mx_ = fmaxf(mx_, SSRC[qb][r]);                      \
-        mx_ = fmaxf(mx_, __shfl_xor(mx_, 32));                                                             \
-        m_old[qb] = m_run[qb];                                                                             \
-        const float m_new_ = fmaxf(m_old[qb], mx_);                                                        \
-        m_use[qb] = (m_new_ == -INFINITY) ? 0.f : m_new_;                                                  \
-        const float msc_ = m_use[qb] * scale_log2e;                                                        \
-        m_run[qb] = m_new_;                                                                                \
-        float sum_ = 0.f;                                                                                  \
-        _Pragma("unroll") for (int hf = 0; hf < 2; ++hf) {                                                 \
-            float p_[8];                                                                                   \
-            _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                                \
-                p_[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(SSRC[qb][8 * hf + e], scale_log2e, -msc_));  \
-                sum_ += p_[e];                                                                             \
+    // Slot b_ of the wavefront's pipeline (block = 2*tile + kb).  Three independent instruction streams
+    // share it: the QK^T MFMAs of block b_+1, the PV MFMAs of block b_-1 and the softmax arithmetic of
+    // block b_.  The matrix pipe and the vector ALU work side by side only when a wavefront offers both
+    // kinds of work at once (it issues in order: behind a run of MFMAs it can only wait for the pipe), so
+    // the slot is written as NSTEP steps of one MFMA + one fragment read (FD steps ahead) + a share of
+    // the softmax, fenced off from each other for the scheduler:
+    //   steps [0, NA)   running maximum over the lane's 16 logits       (NA = NSTEP/8)
+    //   step  NA        exchange with lane^32, new maximum, exponent offset
+    //   next NSTEP/2    the 16 exponentials and their sum
+    //   next NSTEP/4    packing to bf16 operand fragments
+    // The accumulator is rescaled after the PV product of block b_-1 (it then holds the blocks <= b_-1
+    // relative to the old maximum).  Slot 0 multiplies an all-zero block -1; the slot after a wavefront's
+    // last block (live_ false) only multiplies that block's probabilities: its QK^T product and softmax
+    // run on stale data and leave the running maximum and sum untouched.
+#define SPTS_ATT_FRAG(s_)                                                                                  \
+    ((s_) < KS ? *reinterpret_cast<const bf16x8*>(sQ_ + L::koff(kbq_ * 32 + l32, 2 * ((s_) % KS) + lh))    \
+               : *reinterpret_cast<const bf16x8*>(sP_ + L::voff((((s_) - KS) % DB) * 32 + l32,             \
+                                                              2 * (2 * kbp_ + ((s_) - KS) / DB) + lh)))
+#define SPTS_ATT_BLOCK(b_, SC, SN, PC, PP)                                                                 \
+    if ((b_) <= nbw) {                                                                                     \
+        const bool live_ = (b_) < nbw;                                                                     \
+        if (live_ && (b_) >= nbfull) SPTS_ATT_MASK(SC, b_)                                                 \
+        const int bn_ = (b_) + 1, bp_ = (b_) >= 1 ? (b_) - 1 : 0;                                          \
+        const char* sQ_ = smem + ((bn_ >> 1) % ATT_NST) * L::STAGE;                                        \
+        const char* sP_ = smem + ((bp_ >> 1) % ATT_NST) * L::STAGE + L::K_BYTES;                           \
+        const int kbq_ = bn_ & 1, kbp_ = bp_ & 1;                                                          \
+        bf16x8 fr_[FD + 1];                                                                                \
+        _Pragma("unroll") for (int i_ = 0; i_ < FD; ++i_) fr_[i_] = SPTS_ATT_FRAG(i_);                     \
+        float mx_ = -INFINITY, p_[16], sum_ = 0.f, msc_ = 0.f, m_new_ = 0.f, m_use_ = 0.f;                 \
+        const float m_old_ = m_run[0];                                                                     \
+        u32x4 pk_[2];                                                                                      \
+        _Pragma("unroll") for (int i_ = 0; i_ < NSTEP; ++i_) {                                             \
+            if (i_ + FD < NSTEP) fr_[(i_ + FD) % (FD + 1)] = SPTS_ATT_FRAG(i_ + FD);                       \
+            if (i_ < KS)                                                                                   \
+                SN[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr_[i_ % (FD + 1)], qf[0][i_ % KS], i_ == 0 ? zero16 : SN[0], 0, 0, 0); \
+            else                                                                                           \
+                o[(i_ - KS) % DB][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr_[i_ % (FD + 1)], PP[0][(i_ - KS) / DB], \
+                                                                               o[(i_ - KS) % DB][0], 0, 0, 0); \
+            if (i_ < NA) {                                                                                 \
+                _Pragma("unroll") for (int r = i_ * (16 / NA); r < (i_ + 1) * (16 / NA); ++r) mx_ = fmaxf(mx_, SC[0][r]); \
+            } else if (i_ == NA) {                                                                         \
+                const auto sw_ = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx_), __float_as_uint(mx_), false, false); \
+                mx_ = fmaxf(__uint_as_float(sw_[0]), __uint_as_float(sw_[1]));                             \
+                m_new_ = live_ ? fmaxf(m_old_, mx_) : m_old_;                                              \
+                m_use_ = (m_new_ == -INFINITY) ? 0.f : m_new_;                                             \
+                msc_ = m_use_ * scale_log2e;                                                               \
+            } else if (i_ < NA + 1 + NSTEP / 2) {                                                          \
+                constexpr int EPS_ = 32 / NSTEP;   /* exponentials per step */                             \
+                _Pragma("unroll") for (int e = (i_ - NA - 1) * EPS_; e < (i_ - NA) * EPS_; ++e) {          \
+                    p_[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(SC[0][e], scale_log2e, -msc_));          \
+                    sum_ += p_[e];                                                                         \
+                }                                                                                          \
+            } else if (i_ < NA + 1 + NSTEP / 2 + NSTEP / 4) {                                              \
+                constexpr int CPS_ = 32 / NSTEP;   /* packed pairs per step */                             \
+                _Pragma("unroll") for (int c = (i_ - NA - 1 - NSTEP / 2) * CPS_; c < (i_ - NA - NSTEP / 2) * CPS_; ++c) \
+                    pk_[c >> 2][c & 3] = pk2(p_[2 * c], p_[2 * c + 1]);                                    \
             }                                                                                              \
-            const u32x4 pk_ = {pk2(p_[0], p_[1]), pk2(p_[2], p_[3]), pk2(p_[4], p_[5]), pk2(p_[6], p_[7])}; \
-            pf[qb][hf] = __builtin_bit_cast(bf16x8, pk_);                                                  \
+            __builtin_amdgcn_sched_barrier(0);                                                             \
         }                                                                                                  \
-        psum[qb] = sum_;                                                                                   \
-    }
-    // rescale (only when some lane's maximum moved) and accumulate the row sums
-#define SPTS_ATT_RESCALE                                                                                   \
-    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                                    \
-        if (__ballot(m_run[qb] != m_old[qb]) != 0) {                                                       \
-            const float alpha_ = __builtin_amdgcn_exp2f((m_old[qb] - m_use[qb]) * scale_log2e);            \
-            l_run[qb] *= alpha_;                                                                           \
+        PC[0][0] = __builtin_bit_cast(bf16x8, pk_[0]);                                                     \
+        PC[0][1] = __builtin_bit_cast(bf16x8, pk_[1]);                                                     \
+        /* a use of the probabilities in this basic block: without it the exponentials are sunk past */   \
+        /* the rescale branch below, out of reach of the MFMAs they are meant to overlap             */   \
+        asm volatile("" ::"v"(PC[0][0]), "v"(PC[0][1]), "v"(sum_));                                        \
+        m_run[0] = m_new_;                                                                                 \
+        /* rescale (only when some lane's maximum moved) and accumulate the row sums */                    \
+        if (__ballot(m_new_ != m_old_) != 0) {                                                             \
+            const float alpha_ = __builtin_amdgcn_exp2f((m_old_ - m_use_) * scale_log2e);                  \
+            l_run[0] *= alpha_;                                                                            \
             _Pragma("unroll") for (int db = 0; db < DB; ++db)                                              \
-                _Pragma("unroll") for (int r = 0; r < 16; ++r) o[db][qb][r] *= alpha_;                     \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) o[db][0][r] *= alpha_;                      \
         }                                                                                                  \
-        l_run[qb] += psum[qb];                                                                             \
-    }
-    // O^T += V^T P^T for the 32 keys of block kb_ of the V^T tile in `stage_`
-#define SPTS_ATT_PV(stage_, kb_)                                                                           \
-    {                                                                                                      \
-        const char* sV_ = smem + (stage_) * L::STAGE + L::K_BYTES;                                         \
-        _Pragma("unroll") for (int hf = 0; hf < 2; ++hf)                                                   \
-            _Pragma("unroll") for (int db = 0; db < DB; ++db) {                                            \
-                const bf16x8 vf_ = *reinterpret_cast<const bf16x8*>(sV_ + L::voff(db * 32 + l32, 2 * (2 * (kb_) + hf) + lh)); \
-                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)                                          \
-                    o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf_, pf[qb][hf], o[db][qb], 0, 0, 0); \
-            }                                                                                              \
-    }
-    // One 32-key block b_ = 2*tile + kb: (QK of block b_+1 || softmax of block b_), then PV of block b_.
-#define SPTS_ATT_BLOCK(b_, SC, SN)                                                                         \
-    if ((b_) < nbw) {                                                                                      \
-        float m_old[QB], m_use[QB], psum[QB];                                                              \
-        if ((b_) >= nbfull) SPTS_ATT_MASK(SC, b_)                                                          \
-        if ((b_) + 1 < nbw) {                                                                              \
-            SPTS_ATT_QK(SN, (((b_) + 1) >> 1) % ATT_NST, ((b_) + 1) & 1)                                   \
-            SPTS_ATT_SOFTMAX(SC)                                                                           \
-        } else {                                                                                           \
-            SPTS_ATT_SOFTMAX(SC)                                                                           \
-        }                                                                                                  \
-        SPTS_ATT_RESCALE                                                                                   \
-        SPTS_ATT_PV(((b_) >> 1) % ATT_NST, (b_) & 1)                                                       \
+        l_run[0] += live_ ? sum_ : 0.f;                                                                    \
     }
 
     // ---- prologue: tiles 0..2 in flight, tile 0 landed, S^T of block 0
     if (n_tiles > 0) SPTS_ATT_DMA(0)
     if (n_tiles > 1) SPTS_ATT_DMA(1)
     if (n_tiles > 2) SPTS_ATT_DMA(2)
-    if (n_tiles > 2) { SPTS_WAIT_VMCNT(2 * PER); } else if (n_tiles > 1) { SPTS_WAIT_VMCNT(PER); } else { SPTS_WAIT_VMCNT(0); }
+    // Everything in flight must land here, the query fragments included: the compiler does not see the
+    // direct-to-LDS loads, so a wait it places inside the loop for one of its own earlier loads (vmcnt
+    // counts both kinds) would drain the ring on every block.  After an explicit vmcnt(0) it has none left.
+    SPTS_WAIT_VMCNT(0);
     __syncthreads();
     if (nbw > 0) SPTS_ATT_QK(sa, 0, 0)
     for (int t = 0; t < n_tiles; ++t) {
-        // publish tile t+1 (its blocks are fetched / multiplied during this step), then refill the ring:
-        // stage (t+3)%4 held tile t-1, which nobody reads any more after this barrier
+        // publish tile t+1 (its keys are multiplied during this step), then refill the ring: stage
+        // (t+3)%5 held tile t-2, which nobody reads any more after this barrier (the values of tile t-1
+        // are still multiplied in this step)
         if (t + 1 < n_tiles) {
             if (t + 2 < n_tiles) { SPTS_WAIT_VMCNT(PER); } else { SPTS_WAIT_VMCNT(0); }
         }
         __syncthreads();
         if (t + 3 < n_tiles) SPTS_ATT_DMA(t + 3)
-        SPTS_ATT_BLOCK(2 * t, sa, sb)
-        SPTS_ATT_BLOCK(2 * t + 1, sb, sa)
+        SPTS_ATT_BLOCK(2 * t, sa, sb, pfa, pfb)
+        SPTS_ATT_BLOCK(2 * t + 1, sb, sa, pfb, pfa)
     }
+    // the slot after the last block of a wavefront that worked through the last tile
+    if (n_tiles > 0) SPTS_ATT_BLOCK(2 * n_tiles, sa, sb, pfa, pfb)
 
     // ---- normalise and store: lane holds 4 consecutive value columns of its query per r/4
     bf16_t* O = (bf16_t*)a.out;
