@@ -16,13 +16,17 @@
 //    one wavefront's softmax arithmetic and LDS latencies hide behind the other's MFMAs (4 wavefronts
 //    x 64 queries halve the LDS traffic but leave every LDS round trip exposed: 540 vs 820 TFLOP/s).
 //    K / V^T tiles of 64 keys travel global memory -> LDS directly (global_load_lds_dwordx4, swizzle
-//    applied on the global side) into a ring of 4 stages: tile t+3 is in flight while tile t is
-//    consumed; one barrier per tile.
-//  * Software pipeline inside the wavefront at 32-key block granularity: the QK^T MFMAs of block
-//    b+1 are issued in the same region as the softmax arithmetic of block b (independent
-//    registers), then the PV MFMAs of block b.
+//    applied on the global side) into a ring of 5 stages (all 160 KB): tile t+3 is in flight while the
+//    keys of tiles t and t+1 and the values of tiles t-1 and t are multiplied; one barrier per tile.
+//  * Software pipeline inside the wavefront at 32-key block granularity: a slot holds the QK^T MFMAs of
+//    block b+1, the PV MFMAs of block b-1 and the softmax arithmetic of block b (three independent
+//    register sets), written as 16 steps of one MFMA + one fragment read (a few steps ahead) + a share
+//    of the softmax.  A wavefront issues in order, so vector instructions only run in the shadow of an
+//    MFMA when they sit right behind it in the instruction stream (measured on this chip: a 1:1 mix of
+//    MFMA time and vector time takes 0.75 of their sum when interleaved, their sum when not).
 //    The softmax scale is folded into the exponent's FMA, probabilities are packed with the hardware
-//    bf16 converter, the accumulator is rescaled only when some lane's running maximum moved.
+//    bf16 converter, the row maximum crosses the two lane halves with v_permlane32_swap, the accumulator
+//    is rescaled only when some lane's running maximum moved.
 //  * Key tiles beyond the last visible position are never visited; tiles that are entirely visible
 //    to a wavefront skip the mask; a wavefront whose queries see nothing of a tile skips its work.
 //  * Work ids are laid out (kv head, query tile descending, head in group) and split contiguously
