@@ -285,15 +285,16 @@ hipError_t launch_decode_rope_append(void* q, const void* k, const void* v, int 
 // partial layout: part[((g * nsplit + split) * GRP_MAX + hg) * (d + 2)] = (max, sum, weighted values[d])
 constexpr int GRP_MAX = 8;
 
-template <typename T, int D>
+// G: query heads per KV head the register arrays are sized for (>= H / Hkv)
+template <typename T, int D, int G>
 __global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ q, const T* __restrict__ K,
                                                           const T* __restrict__ V, int64_t M, int H, int Hkv, float scale_log2e,
                                                           float* __restrict__ part) {
     constexpr int EPC = 16 / (int)sizeof(T);
     constexpr int LPK = D / EPC;          // lanes that hold one key row
     constexpr int KPW = 64 / LPK;         // keys per wavefront step
-    __shared__ float sm[4][GRP_MAX][2];
-    __shared__ float sacc[4][GRP_MAX][D];
+    __shared__ float sm[4][G][2];
+    __shared__ float sacc[4][G][D];
 
     const int split = blockIdx.x, nsplit = gridDim.x, g = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -304,22 +305,23 @@ __global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ 
     const int64_t m_end = m_begin + per < M ? m_begin + per : M;
 
     // this lane's piece of every query head of the group
-    u32x4 qv[GRP_MAX];
+    u32x4 qv[G];
 #pragma unroll
-    for (int hg = 0; hg < GRP_MAX; ++hg) {
+    for (int hg = 0; hg < G; ++hg) {
         const int h = g * grp + (hg < grp ? hg : 0);
         qv[hg] = *reinterpret_cast<const u32x4*>(q + (int64_t)h * D + sub * EPC);
     }
-    float mrun[GRP_MAX], lrun[GRP_MAX], acc[GRP_MAX][EPC];
+    float mrun[G], lrun[G], acc[G][EPC];
 #pragma unroll
-    for (int hg = 0; hg < GRP_MAX; ++hg) {
+    for (int hg = 0; hg < G; ++hg) {
         mrun[hg] = -INFINITY; lrun[hg] = 0.f;
 #pragma unroll
         for (int e = 0; e < EPC; ++e) acc[hg][e] = 0.f;
     }
 
     // keys of this lane: m_begin + wave*KPW + kslot + it * 4*KPW; the next pair is loaded before the
-    // current one is used
+    // current one is used (rings of two or three more pairs in flight measured 25 % slower, at equal
+    // occupancy)
     const T* Kg = K + (int64_t)g * D + sub * EPC;
     const T* Vg = V + (int64_t)g * D + sub * EPC;
     const int64_t rstride = (int64_t)Hkv * D;
@@ -336,19 +338,28 @@ __global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ 
         const int64_t mnc = mn_ < m_end ? mn_ : m_end - 1;
         const u32x4 kvn = *reinterpret_cast<const u32x4*>(Kg + mnc * rstride);
         const u32x4 vvn = *reinterpret_cast<const u32x4*>(Vg + mnc * rstride);
+        float vf[EPC];
 #pragma unroll
-        for (int hg = 0; hg < GRP_MAX; ++hg) {
+        for (int e = 0; e < EPC; ++e) vf[e] = chunk_elem(vv, e, T{});
+#pragma unroll
+        for (int hg = 0; hg < G; ++hg) {
             if (hg < grp) {
                 float s = group_sum<LPK>(dot16(kv, qv[hg], 0.f, T{}));
                 s = valid ? s * scale_log2e : -INFINITY;
                 const float mn = fmaxf(mrun[hg], s);
                 const float mu = mn == -INFINITY ? 0.f : mn;
-                const float alpha = __builtin_amdgcn_exp2f(mrun[hg] - mu);
-                const float p = __builtin_amdgcn_exp2f(s - mu);
-                lrun[hg] = lrun[hg] * alpha + p;
+                // the running maximum rarely moves after the first keys: rescale only when it did for some lane
+                if (__ballot(mn != mrun[hg]) != 0) {
+                    const float alpha = __builtin_amdgcn_exp2f(mrun[hg] - mu);
+                    lrun[hg] *= alpha;
 #pragma unroll
-                for (int e = 0; e < EPC; ++e) acc[hg][e] = acc[hg][e] * alpha + p * chunk_elem(vv, e, T{});
-                mrun[hg] = mn;
+                    for (int e = 0; e < EPC; ++e) acc[hg][e] *= alpha;
+                    mrun[hg] = mn;
+                }
+                const float p = __builtin_amdgcn_exp2f(s - mu);
+                lrun[hg] += p;
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) acc[hg][e] = __builtin_fmaf(p, vf[e], acc[hg][e]);
             }
         }
         kv = kvn;
@@ -356,7 +367,7 @@ __global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ 
     }
     // merge the KPW lane groups of the wavefront (lanes with equal `sub`)
 #pragma unroll
-    for (int hg = 0; hg < GRP_MAX; ++hg) {
+    for (int hg = 0; hg < G; ++hg) {
         if (hg < grp) {
 #pragma unroll
             for (int off = LPK; off < 64; off <<= 1) {
@@ -397,20 +408,20 @@ __global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ 
     }
 }
 
-// out[h, e] = sum over splits of the weighted values / sum of sums.  One workgroup per query head:
-// thread s takes split s for the (max, sum) part; the weighted values are summed by 256 / D thread
-// groups that each walk a strided subset of the splits with independent loads.
+// out[h, e] = sum over splits of the weighted values / sum of sums.  One workgroup of 1024 threads per
+// query head: thread s < 256 takes split s for the (max, sum) part; the weighted values are summed by
+// 1024 / D thread groups that each walk a strided subset of the splits with independent loads.
 template <typename T>
-__global__ void __launch_bounds__(256) decode_attn_merge_kernel(const float* __restrict__ part, int nsplit, int H, int Hkv, int D,
-                                                                T* __restrict__ out) {
+__global__ void __launch_bounds__(1024) decode_attn_merge_kernel(const float* __restrict__ part, int nsplit, int H, int Hkv, int D,
+                                                                 T* __restrict__ out) {
     __shared__ float sa[256];
-    __shared__ float sw[4], sl[4];
-    __shared__ float so[256];
+    __shared__ float sw[16], sl[16];
+    __shared__ float so[1024];
     const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = H / Hkv, g = h / grp, hg = h % grp;
     const float* base = part + ((int64_t)g * nsplit * GRP_MAX + hg) * (D + 2);
     const int64_t stride = (int64_t)GRP_MAX * (D + 2);
-    const float m = tid < nsplit ? base[tid * stride] : -INFINITY;
+    const float m = tid < nsplit ? base[tid * stride] : -INFINITY;       // nsplit <= 256: wavefronts 0-3
     const float l = tid < nsplit ? base[tid * stride + 1] : 0.f;
     float mx = m;
 #pragma unroll
@@ -420,12 +431,12 @@ __global__ void __launch_bounds__(256) decode_attn_merge_kernel(const float* __r
     mx = fmaxf(fmaxf(sw[0], sw[1]), fmaxf(sw[2], sw[3]));
     const float mu = mx == -INFINITY ? 0.f : mx;
     const float a = __builtin_amdgcn_exp2f(m - mu);     // 0 for absent or empty splits
-    sa[tid] = a;
-    float ls = wave_sum(l * a);
+    if (tid < 256) sa[tid] = a;
+    const float ls = wave_sum(l * a);
     if (lane == 0) sl[wave] = ls;
     __syncthreads();
     const float L = sl[0] + sl[1] + sl[2] + sl[3];
-    const int ngroups = 256 / D, grp_id = tid / D, e = tid % D;
+    const int ngroups = 1024 / D, grp_id = tid / D, e = tid % D;
     float o = 0.f;
     if (grp_id < ngroups) {
 #pragma unroll 8
@@ -440,10 +451,11 @@ __global__ void __launch_bounds__(256) decode_attn_merge_kernel(const float* __r
     }
 }
 
-// number of key splits: enough workgroups to fill 256 CUs a few times over, at least 64 keys each,
-// and no more than the scratch buffer (scratch_floats) holds
+// number of key splits: two workgroups per CU (measured best on 4.6K-13K cached pairs: 32 / 64 / 128 /
+// 256 splits of 8 KV heads take 14.6 / 11.7 / 12.8 / 14.3 us), at least 64 keys each, and no more than
+// the scratch buffer (scratch_floats) holds
 int decode_attn_splits(int64_t M, int Hkv, int d, size_t scratch_floats) {
-    int64_t s = 1024 / (Hkv > 0 ? Hkv : 1);
+    int64_t s = 512 / (Hkv > 0 ? Hkv : 1);
     if (s > (M + 63) / 64) s = (M + 63) / 64;
     const int64_t cap = (int64_t)(scratch_floats / ((size_t)Hkv * GRP_MAX * (d + 2)));
     if (s > cap) s = cap;
@@ -465,16 +477,23 @@ static hipError_t launch_decode_attn_t(const T* q, const T* K, const T* V, int64
     const int nsplit = decode_attn_splits(M, Hkv, d, part_floats);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
     const dim3 g((unsigned)nsplit, (unsigned)Hkv), b(256);
+    const int grp = H / Hkv;
+#define SPTS_DEC_ATTN(D_)                                                                                      \
+    if (grp <= 1) decode_attn_kernel<T, D_, 1><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part);         \
+    else if (grp <= 2) decode_attn_kernel<T, D_, 2><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part);    \
+    else if (grp <= 4) decode_attn_kernel<T, D_, 4><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part);    \
+    else decode_attn_kernel<T, D_, GRP_MAX><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part);
     switch (d) {
-        case 128: decode_attn_kernel<T, 128><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part); break;
-        case 64: decode_attn_kernel<T, 64><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part); break;
-        case 32: decode_attn_kernel<T, 32><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part); break;
-        case 16: decode_attn_kernel<T, 16><<<g, b, 0, s>>>(q, K, V, M, H, Hkv, scale_log2e, part); break;
+        case 128: SPTS_DEC_ATTN(128) break;
+        case 64: SPTS_DEC_ATTN(64) break;
+        case 32: SPTS_DEC_ATTN(32) break;
+        case 16: SPTS_DEC_ATTN(16) break;
         default: return hipErrorInvalidValue;
     }
+#undef SPTS_DEC_ATTN
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_attn_merge_kernel<T><<<dim3((unsigned)H), dim3(256), 0, s>>>(part, nsplit, H, Hkv, d, out);
+    decode_attn_merge_kernel<T><<<dim3((unsigned)H), dim3(1024), 0, s>>>(part, nsplit, H, Hkv, d, out);
     return hipGetLastError();
 }
 
