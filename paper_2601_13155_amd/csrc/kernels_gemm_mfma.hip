@@ -14,6 +14,10 @@
 //    current one is multiplied.  The wavefront counts its own outstanding slab loads with
 //    s_waitcnt vmcnt(n) and one workgroup barrier per slab publishes a landed slab and frees the
 //    stage consumed before it.
+//  * The address of a load is a wavefront-uniform base in SGPRs, advanced along K by scalar adds, plus
+//    a 32-bit per-lane offset fixed for the whole tile, and the steady state is unrolled over the ring
+//    so that LDS stage offsets are immediates: the loop holds no vector address arithmetic (vector
+//    instructions barely overlap with MFMAs on this chip: interleaved 1:1 they take 0.75 of the sum).
 //  * A direct-to-LDS load puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that makes the
 //    16-lane b128 fragment reads bank-conflict free is applied on the global side: lane i fetches
 //    the chunk that belongs at position i.
@@ -49,6 +53,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256;
+#ifndef SPTS_GEMM_UNROLL_RING
+#define SPTS_GEMM_UNROLL_RING 1
+#endif
 
 // K slab geometry.  A tile row holds BK bf16 = CPR 16-byte chunks; chunk c of row `row` is stored at
 // chunk position c ^ ((row / RP) % CPR) (RP = rows per 256 bytes), so the 16 lanes of a b128
@@ -136,24 +143,31 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     // ---- direct-to-LDS assignment: wavefront w moves tile rows [64w, 64w+64) of every operand, 16
     //      (BK=32) or 8 (BK=64) rows = 1 KB per load; lane -> (row, LDS chunk position), and fetches
     //      the global chunk that the swizzle maps to that LDS position.
-    const bf16_t* ga[LPO];
-    const bf16_t* ga1[DUAL_A ? LPO : 1];
-    const bf16_t* gb[LPO];
+    // A load's address is a wavefront-uniform base (SGPR pair, advanced along K with scalar adds) plus a
+    // 32-bit per-lane byte offset that never changes: no vector instructions for addresses in the loop.
+    // Bases: A rows from row0 on (or the whole gather source when rows come through an index list, whose
+    // byte size must then fit 32 bits); the B rows this wavefront moves.
+    uint32_t oa[LPO], ob[LPO];
+    const char* abase = (const char*)a.A + (a.a_idx ? (int64_t)0 : row0 * a.lda * 2);
+    const char* a1base = DUAL_A ? (const char*)a.A1 + (a.a_idx ? (int64_t)0 : row0 * a.lda * 2) : abase;
+    const char* bbase;
+    {
+        const int rw = wave * LROWS;   // first B tile row of this wavefront
+        if (DUAL) bbase = rw < 128 ? (const char*)a.B0 + (int64_t)(col0 + rw) * a.ldb * 2
+                                   : (const char*)a.B1 + (int64_t)(col0 + rw - 128) * a.ldb * 2;
+        else if (a.B1 && col0 >= a.N / 2) bbase = (const char*)a.B1 + (int64_t)(col0 - a.N / 2 + rw) * a.ldb * 2;
+        else bbase = (const char*)a.B0 + (int64_t)(col0 + rw) * a.ldb * 2;
+    }
 #pragma unroll
     for (int q = 0; q < LPO; ++q) {
-        const int r = wave * LROWS + q * S::ROWS_PER_LOAD + lane / S::CPR;
+        const int rl = q * S::ROWS_PER_LOAD + lane / S::CPR;   // row inside the wavefront's share
+        const int r = wave * LROWS + rl;
         const int c = (lane % S::CPR) ^ S::swz(r);
         int64_t grow = row0 + r;
         if (grow >= a.M) grow = a.M - 1;  // clamp: duplicates of the last row are never stored
-        const int64_t srow = a.a_idx ? (int64_t)a.a_idx[grow] : grow;
-        ga[q] = (const bf16_t*)a.A + srow * a.lda + c * 8;
-        if (DUAL_A) ga1[q] = (const bf16_t*)a.A1 + srow * a.lda + c * 8;
-        const bf16_t* bsrc;
-        if (DUAL) bsrc = (r < 128) ? (const bf16_t*)a.B0 + (int64_t)(col0 + r) * a.ldb
-                                   : (const bf16_t*)a.B1 + (int64_t)(col0 + r - 128) * a.ldb;
-        else if (a.B1 && col0 >= a.N / 2) bsrc = (const bf16_t*)a.B1 + (int64_t)(col0 - a.N / 2 + r) * a.ldb;
-        else bsrc = (const bf16_t*)a.B0 + (int64_t)(col0 + r) * a.ldb;
-        gb[q] = bsrc + c * 8;
+        const int64_t srow = a.a_idx ? (int64_t)a.a_idx[grow] : grow - row0;
+        oa[q] = (uint32_t)((srow * a.lda + c * 8) * 2);
+        ob[q] = (uint32_t)(((int64_t)rl * a.ldb + c * 8) * 2);
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t lds_w = lds0 + wave * (LROWS * S::ROW_BYTES);   // this wavefront's rows inside an operand tile
@@ -162,9 +176,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     {                                                                                          \
         const uint32_t sb_ = lds_w + ((kt_) % NST) * STAGE + ((u) / NOPS) * 1024;              \
         const int ko_ = (kbeg + (kt_)) * BK;                                                   \
-        if ((u) % NOPS == 0) dma16(ga[(u) / NOPS] + ko_, sb_);                                 \
-        else if ((u) % NOPS == 1) dma16(gb[(u) / NOPS] + ko_, sb_ + TILE_BYTES);               \
-        else dma16(ga1[DUAL_A ? (u) / NOPS : 0] + ko_, sb_ + 2 * TILE_BYTES);                  \
+        if ((u) % NOPS == 0) dma16s(oa[(u) / NOPS], abase + ko_ * 2, sb_);                     \
+        else if ((u) % NOPS == 1) dma16s(ob[(u) / NOPS], bbase + ko_ * 2, sb_ + TILE_BYTES);   \
+        else dma16s(oa[(u) / NOPS], a1base + ko_ * 2, sb_ + 2 * TILE_BYTES);                   \
     }
 #define SPTS_DMA_SLAB(kt_)                                                                     \
     { _Pragma("unroll") for (int u_ = 0; u_ < PER; ++u_) SPTS_DMA_ONE(kt_, u_) }
@@ -278,7 +292,15 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
 
     int kt = 0;
     // steady state: slab kt+NST-1 exists; after its loads are issued the slabs behind kt+1 in flight
-    // are kt+2 .. kt+NST-1
+    // are kt+2 .. kt+NST-1.  First in groups of NST slabs, where the ring stage of every slab is a
+    // compile-time constant and the LDS addresses of the fragment reads need no arithmetic in the loop.
+    if (SPTS_GEMM_UNROLL_RING && (NST & (NST - 1)) == 0) {
+        int kb = 0;
+        for (; kb * NST + 2 * NST - 2 < nk; ++kb) {
+            _Pragma("unroll") for (int u = 0; u < NST; ++u) SPTS_SLAB(kb * NST + u, true, true, (NST - 2) * PER)
+        }
+        kt = kb * NST;
+    }
     for (; kt + NST - 1 < nk; ++kt) SPTS_SLAB(kt, true, true, (NST - 2) * PER)
     // drain: nothing left to issue; wait for everything that is still in flight
     for (; kt + 1 < nk; ++kt) SPTS_SLAB(kt, false, true, 0)
@@ -478,6 +500,9 @@ bool gemm_mfma_supported(const GemmArgs& a) {
         if (a.K / 64 < a.ksplit || a.nfull < 0 || a.nfull > (a.M + BM - 1) / BM * (a.N / 256)) return false;
     }
     if (a.M > (int64_t)1 << 30) return false;
+    // 32-bit byte offsets from the load bases: the gather source as a whole, 256 rows of A or B otherwise
+    if (a.a_idx && (a.a_rows <= 0 || a.a_rows * a.lda * 2 >= ((int64_t)1 << 32))) return false;
+    if (256 * a.lda * 2 >= ((int64_t)1 << 32) || 256 * a.ldb * 2 >= ((int64_t)1 << 32)) return false;
     return true;
 }
 

@@ -620,6 +620,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
     if (Ma > 0) {
         // queries of the active rows (rows gathered through idxA inside the GEMM's A loads)
         GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, Ma, QD, m.D);
+        gq.a_rows = N;
         { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q))); }
         const int32_t* qpos = pos;
         const int32_t* kpos = pos;
@@ -646,6 +647,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         aa.ldvt = (Mk + 255) / 256 * 256; aa.vt = c->p<void>(c->off.vt);
         const bool amf = c->bf16 && attention_mfma_supported(aa);
         GemmArgs gv = gemm_args(xn, m.D, full_kv ? nullptr : idxA, w->Wv, m.D, vv, KV, Mk, KV, m.D);
+        gv.a_rows = N;
         bool vt_done = false;
         if (amf) {
             // the matrix-core projection writes the transposed copy (keys contiguous) in its epilogue
@@ -685,6 +687,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         SPTS_HIP(c, launch_topk(SF, N, Mf, cfg->protect_last, idxF, 1, st));
     }
     GemmArgs gh = gemm_args(xn, m.D, idxF, w->Wgate, m.D, c->p<void>(c->off.big), m.Dff, Mf, m.Dff, m.D, EPI_SILU_MUL);
+    gh.a_rows = N;
     gh.B1 = w->Wup;
     { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
     GemmArgs gd = gemm_args(c->p<void>(c->off.big), m.Dff, nullptr, w->Wdown, m.Dff, x, m.D, Mf, m.D, m.Dff, EPI_RESIDUAL);

@@ -46,6 +46,11 @@ template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return f32_to_b
 __device__ inline void dma16(const void* gptr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n\t" ::"v"(gptr), "s"(lds_base) : "memory");
 }
+// The same load with the address split into a wavefront-uniform 64-bit base (SGPR pair) and a 32-bit
+// unsigned per-lane byte offset.
+__device__ inline void dma16s(uint32_t voff, const void* sbase, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\t" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory");
+}
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt fields left at "no wait")
 #define SPTS_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 0xF) | (((n) >> 4) << 14))
 
@@ -65,6 +70,7 @@ enum GemmEpilogue : int {
 
 struct GemmArgs {
     const void* A; int64_t lda; const int32_t* a_idx;   // A [*, K] rows optionally gathered
+    int64_t a_rows;                                     // with a_idx: rows of the gather source (every index is below it)
     const void* A1;                                     // EPI_SILU_MUL: A operand of the second product (null = A)
     const void* B0; const void* B1; int64_t ldb;        // B [N, K]; EPI_STORE with B1: columns [N/2, N) come from B1
     void* C; int64_t ldc; const int32_t* c_idx;         // output rows optionally scattered
