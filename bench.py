@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--vocab", type=int, default=128256, help="rows of the synthetic vocabulary table of the decode leg")
     ap.add_argument("--builder-tokens", type=int, default=8192,
                     help="calibration tokens of the offline channel-importance leg (0 = skip it)")
+    ap.add_argument("--batch-seqs", type=int, default=4,
+                    help="sequences of the batched-layer leg (one skip layer over that many sequences of 8192 tokens, "
+                         "as one spts_layer_prefill_batched call and as single calls; 0 = skip it)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first launch a plain elementwise kernel (dst = src + 1 over 2^28 floats: reads 1 GiB, writes 1 GiB) "
                          "three times; under a counter-collecting profiler its FETCH_SIZE / WRITE_SIZE readings give the "
@@ -399,6 +402,39 @@ def main():
                         "note": "algorithmic bytes (scores once + indices) / time; the kernel reads the scores six times"}
         del sc, ti, tctx
 
+    # ---- one skip layer over a batch of sequences: one batched call against one call per sequence
+    batched = None
+    if args.batch_seqs > 0 and wl.N >= 8192 * args.batch_seqs:
+        from paper_2601_13155_amd import binding
+        nb, ln = args.batch_seqs, 8192
+        offs = [i * ln for i in range(nb + 1)]
+        keep_a = wl.attn_keep if wl.attn_keep > 0 else 0.4
+        keep_f = wl.ffn_keep if wl.ffn_keep > 0 else 0.4
+        ma, mf = [int(keep_a * ln)] * nb, [int(keep_f * ln)] * nb
+        xb = x0[:nb * ln].clone()
+        pb = torch.cat([pos0[:ln]] * nb).contiguous()
+        cfg1 = binding.spts_layer_cfg(1, wl.probe_len, ma[0], mf[0], wl.protect_last, 0)
+
+        def run_batched():
+            ctx.spts_layer_prefill_batched(xb, pb, offs, layers[0], wl.probe_len, ma, mf, wl.protect_last)
+
+        def run_single():
+            for i in range(nb):
+                ctx.spts_layer_prefill(xb[i * ln:(i + 1) * ln], pb[i * ln:(i + 1) * ln], ln, layers[0], cfg1, None, None, None, None)
+
+        res = {}
+        for nm, fn in (("batched", run_batched), ("single_calls", run_single)):
+            xb.copy_(x0[:nb * ln]); fn(); torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            res[nm] = e0.elapsed_time(e1) / 3
+        batched = {"sequences": nb, "tokens_per_sequence": ln, "ms_batched": res["batched"], "ms_single_calls": res["single_calls"],
+                   "tokens_per_s_batched": nb * ln / (res["batched"] * 1e-3)}
+        del xb, pb
+
     # ---- offline proxy construction: channel scores on a synthetic calibration set (rho = 0.2)
     builder = None
     if args.builder_tokens > 0:
@@ -439,7 +475,7 @@ def main():
                    "components": wl.components, "weight_pool": pool, "batch": 1},
         "algorithmic_tflop_per_step": total_flops / 1e12,
         "achieved_tflops_whole_step": total_flops / (ms * 1e-3) / 1e12,
-        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched, "decode": decode, "proxy_builder": builder, "ablation": ablation,
+        "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched, "decode": decode, "proxy_builder": builder, "ablation": ablation, "batched_layer": batched,
     }
     print(json.dumps(out), flush=True)
 

@@ -20,7 +20,7 @@ SPTS_F32, SPTS_BF16 = 0, 1
 
 EXPORTS = (
     "spts_workspace_bytes", "spts_create", "spts_destroy", "spts_strerror", "spts_last_hip_error", "spts_uses_mfma",
-    "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_select_topk_segmented", "spts_layer_prefill", "spts_msdp_compact",
+    "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_select_topk_segmented", "spts_layer_prefill", "spts_layer_prefill_batched", "spts_msdp_compact",
     "spts_decode_layer", "spts_greedy_token", "spts_channel_importance",
     "spts_profile_begin", "spts_profile_end", "spts_profile_count", "spts_profile_get",
 )
@@ -82,6 +82,10 @@ def load() -> C.CDLL:
     lib.spts_layer_prefill.restype = C.c_int
     lib.spts_layer_prefill.argtypes = [vp, vp, vp, i64, C.POINTER(spts_layer_weights), C.POINTER(spts_layer_cfg),
                                        C.POINTER(spts_kv_out), vp, vp, vp]
+    lib.spts_layer_prefill_batched.restype = C.c_int
+    lib.spts_layer_prefill_batched.argtypes = [vp, vp, vp, C.POINTER(C.c_int64), i32, C.POINTER(spts_layer_weights), i32,
+                                               C.POINTER(C.c_int64), C.POINTER(C.c_int64), i32, C.POINTER(spts_kv_out),
+                                               vp, vp, vp]
     lib.spts_msdp_compact.restype = C.c_int
     lib.spts_msdp_compact.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     lib.spts_decode_layer.restype = C.c_int
@@ -201,6 +205,24 @@ class Context:
         _check(load().spts_layer_prefill(self.handle, _ptr(x), _ptr(pos), N, C.byref(w), C.byref(cfg),
                                          C.byref(kv) if kv is not None else None, _ptr(s_mha), _ptr(idx_attn),
                                          _ptr(idx_ffn)), "spts_layer_prefill")
+
+    def spts_layer_prefill_batched(self, x, pos, seq_offsets, w: spts_layer_weights, probe_len: int, m_attn, m_ffn,
+                                   protect_last: int = 1, kv=None, s_mha=None, idx_attn=None, idx_ffn=None):
+        """seq_offsets [batch+1], m_attn / m_ffn [batch]: host integer sequences; kv: list of spts_kv_out or None
+        (their count fields are updated in place)."""
+        batch = len(seq_offsets) - 1
+        so = (C.c_int64 * (batch + 1))(*[int(v) for v in seq_offsets])
+        ma = (C.c_int64 * max(batch, 1))(*[int(v) for v in m_attn])
+        mf = (C.c_int64 * max(batch, 1))(*[int(v) for v in m_ffn])
+        kva = None
+        if kv is not None:
+            kva = (spts_kv_out * batch)(*kv)
+        _check(load().spts_layer_prefill_batched(self.handle, _ptr(x), _ptr(pos), so, batch, C.byref(w), probe_len, ma, mf,
+                                                 protect_last, kva, _ptr(s_mha), _ptr(idx_attn), _ptr(idx_ffn)),
+               "spts_layer_prefill_batched")
+        if kv is not None:
+            for dst, src in zip(kv, kva):
+                dst.count = src.count
 
     def spts_decode_layer(self, x, pos: int, w: spts_layer_weights, cache: spts_kv_out):
         _check(load().spts_decode_layer(self.handle, _ptr(x), pos, C.byref(w), C.byref(cache)), "spts_decode_layer")

@@ -223,6 +223,26 @@ hipError_t launch_iota_i32(int32_t* p, int64_t n, hipStream_t s) {
     iota_i32_kernel<<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s>>>(p, n);
     return hipGetLastError();
 }
+// idx[i] += seg_offsets[b] for the segment b whose output range [out_offsets[b], out_offsets[b+1]) holds i
+// (per-sequence TopK writes indices relative to its sequence; the batched layer wants rows of the batch)
+__global__ void add_segment_base_kernel(int32_t* __restrict__ idx, const int64_t* __restrict__ out_offsets,
+                                        const int64_t* __restrict__ seg_offsets, int nseg, int64_t total) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int lo = 0, hi = nseg;   // last b with out_offsets[b] <= i
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (out_offsets[mid] <= i) lo = mid; else hi = mid;
+    }
+    idx[i] += (int32_t)seg_offsets[lo];
+}
+hipError_t launch_add_segment_base(int32_t* idx, const int64_t* out_offsets, const int64_t* seg_offsets, int nseg, int64_t total,
+                                   hipStream_t s) {
+    if (total <= 0 || nseg <= 0) return hipSuccess;
+    add_segment_base_kernel<<<dim3((unsigned)cdiv(total, 256)), dim3(256), 0, s>>>(idx, out_offsets, seg_offsets, nseg, total);
+    return hipGetLastError();
+}
+
 __global__ void scatter_iota_kernel(const int32_t* __restrict__ idx, int32_t* __restrict__ old2new, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) old2new[idx[i]] = (int32_t)i;

@@ -3,6 +3,7 @@
 #include "../../include/spts.h"
 #include "spts_internal.h"
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -13,7 +14,7 @@ namespace {
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Workspace {
-    size_t rope, xn, kall, tmp32, qp, probe, S, C, SF, part, idxA, idxF, posA, q, khat, vhat, vt, att, t, z, big, misc;
+    size_t rope, xn, kall, tmp32, qp, probe, S, C, SF, part, idxA, idxF, posA, q, khat, vhat, vt, att, t, z, big, misc, seg;
     size_t total;
 };
 
@@ -49,6 +50,7 @@ Workspace carve(const spts_model_desc& m, const Limits& L) {
     size_t inner = (size_t)(m.Dff > L.max_dlow ? m.Dff : L.max_dlow);
     w.big = take(Np * inner * b);
     w.misc = take(4096);
+    w.seg = take(3 * (size_t)(SPTS_MAX_BATCH + 1) * sizeof(int64_t));   // segment descriptors of a batched call
     w.total = off;
     return w;
 }
@@ -199,6 +201,27 @@ int check_weights_full(const spts_ctx* c, const spts_layer_weights* w, bool need
 }
 
 // ---- PAP probe: norm, keys, probe queries, scores ----------------------------------------------
+// scores of the candidates [row0, row0 + n) of the rows that norm_keys_impl prepared: the last P of them
+// are the probe queries, k_rows points at the keys of row row0
+int probe_scores_rows(spts_ctx* c, int64_t row0, int64_t n, const spts_layer_weights* w, int P, const void* k_rows, float* s_out) {
+    const auto& m = c->m;
+    const int QD = m.H * m.d;
+    const size_t eb = c->bf16 ? 2 : 4;
+    const char* xn_probe = c->p<char>(c->off.xn) + (size_t)(row0 + n - P) * m.D * eb;
+    GemmArgs gq = gemm_args(xn_probe, m.D, nullptr, w->Wq, m.D, nullptr, QD, P, QD, m.D);
+    { PHASE(c, PH_PROBE_Q); SPTS_TRY(run_gemm_rope(c, gq, m.H, nullptr, row0 + n - P, c->p<void>(c->off.qp))); }
+    ProbeArgs pa{};
+    pa.qp = c->p<void>(c->off.qp); pa.k = k_rows; pa.S = s_out;
+    pa.stats = c->p<float>(c->off.probe);
+    pa.partial = c->p<float>(c->off.probe) + (2 * (size_t)P * m.H + 64);
+    pa.N = n; pa.P = P; pa.H = m.H; pa.Hkv = m.Hkv; pa.d = m.d;
+    PHASE(c, PH_PROBE_ATTN);
+    if (probe_p1_supported(pa)) SPTS_HIP(c, launch_probe_p1(pa, c->p<float>(c->off.probe), c->bf16, c->stream));
+    else if (c->bf16 && probe_mfma_supported(pa)) SPTS_HIP(c, launch_probe_mfma(pa, c->stream));
+    else SPTS_HIP(c, launch_probe_generic(pa, c->bf16, c->stream));
+    return SPTS_OK;
+}
+
 // leaves xn (normalised x) and the rotary table in the workspace for the caller
 int probe_attn_impl(spts_ctx* c, const void* x, const int32_t* pos, int64_t N, const spts_layer_weights* w, int P,
                     bool want_scores, void* k_out, float* s_out) {
@@ -206,24 +229,11 @@ int probe_attn_impl(spts_ctx* c, const void* x, const int32_t* pos, int64_t N, c
     c->dec_rope_pos = -1;   // the prefill's table overwrites the decode row
     { PHASE(c, PH_ROPE_TABLE); SPTS_HIP(c, launch_rope_table(pos, N, m.d, m.rope_base, c->p<float2>(c->off.rope), c->stream)); }
     { PHASE(c, PH_RMSNORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, c->p<void>(c->off.xn), N, m.D, c->bf16, c->stream)); }
-    const int KV = m.Hkv * m.d, QD = m.H * m.d;
+    const int KV = m.Hkv * m.d;
     GemmArgs gk = gemm_args(c->p<void>(c->off.xn), m.D, nullptr, w->Wk, m.D, nullptr, KV, N, KV, m.D);
     { PHASE(c, PH_K_PROJ); SPTS_TRY(run_gemm_rope(c, gk, m.Hkv, nullptr, 0, k_out)); }
     if (!want_scores) return SPTS_OK;
-    const size_t eb = c->bf16 ? 2 : 4;
-    const char* xn_probe = c->p<char>(c->off.xn) + (size_t)(N - P) * m.D * eb;
-    GemmArgs gq = gemm_args(xn_probe, m.D, nullptr, w->Wq, m.D, nullptr, QD, P, QD, m.D);
-    { PHASE(c, PH_PROBE_Q); SPTS_TRY(run_gemm_rope(c, gq, m.H, nullptr, N - P, c->p<void>(c->off.qp))); }
-    ProbeArgs pa{};
-    pa.qp = c->p<void>(c->off.qp); pa.k = k_out; pa.S = s_out;
-    pa.stats = c->p<float>(c->off.probe);
-    pa.partial = c->p<float>(c->off.probe) + (2 * (size_t)P * m.H + 64);
-    pa.N = N; pa.P = P; pa.H = m.H; pa.Hkv = m.Hkv; pa.d = m.d;
-    PHASE(c, PH_PROBE_ATTN);
-    if (probe_p1_supported(pa)) SPTS_HIP(c, launch_probe_p1(pa, c->p<float>(c->off.probe), c->bf16, c->stream));
-    else if (c->bf16 && probe_mfma_supported(pa)) SPTS_HIP(c, launch_probe_mfma(pa, c->stream));
-    else SPTS_HIP(c, launch_probe_generic(pa, c->bf16, c->stream));
-    return SPTS_OK;
+    return probe_scores_rows(c, 0, N, w, P, k_out, s_out);
 }
 
 // ---- LTP probe on an already normalised xn2 [N, D] ---------------------------------------------
@@ -691,6 +701,141 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
     gh.B1 = w->Wup;
     { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
     GemmArgs gd = gemm_args(c->p<void>(c->off.big), m.Dff, nullptr, w->Wdown, m.Dff, x, m.D, Mf, m.D, m.Dff, EPI_RESIDUAL);
+    gd.c_idx = idxF;
+    { PHASE(c, PH_FFN_DOWN); SPTS_TRY(run_gemm(c, gd)); }
+    return SPTS_OK;
+}
+
+int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const int64_t* seq_offsets, int32_t batch,
+                               const spts_layer_weights* w, int32_t probe_len, const int64_t* m_attn, const int64_t* m_ffn,
+                               int32_t protect_last, spts_kv_out* kv, float* s_mha, int32_t* idx_attn, int32_t* idx_ffn) {
+    if (!c || batch < 0 || batch > SPTS_MAX_BATCH) return SPTS_EINVAL;
+    if (batch == 0) return SPTS_OK;
+    if (!seq_offsets || !m_attn || !m_ffn || seq_offsets[0] != 0) return SPTS_EINVAL;
+    const int64_t N = seq_offsets[batch];
+    SPTS_TRY(common_call_checks(c, N));
+    if (!x || !pos) return SPTS_EINVAL;
+    if (!aligned16(x) || !aligned16(pos)) return SPTS_EALIGN;
+    if ((s_mha && !aligned16(s_mha)) || (idx_attn && !aligned16(idx_attn)) || (idx_ffn && !aligned16(idx_ffn))) return SPTS_EALIGN;
+    SPTS_TRY(check_weights_full(c, w, true));
+    if (probe_len < 1) return SPTS_EINVAL;
+    if (probe_len > c->lim.max_probe) return SPTS_EWORKSPACE;
+    const auto& m = c->m;
+    const int KV = m.Hkv * m.d, QD = m.H * m.d;
+    const size_t eb = c->bf16 ? 2 : 4;
+    // host-side plan: per sequence its length, budgets and the start of its slice in the index lists
+    std::vector<int64_t> desc(3 * (size_t)(batch + 1));
+    int64_t* dOff = desc.data();                 // [batch+1] first row of each sequence
+    int64_t* dKa = dOff + (batch + 1);            // [batch]   attention budgets (then reused for the FFN)
+    int64_t* dOut = dKa + (batch + 1);            // [batch+1] first entry of each sequence in the index list
+    std::vector<int64_t> ma(batch), mf(batch), oa(batch + 1), of(batch + 1);
+    oa[0] = of[0] = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int64_t nb = seq_offsets[b + 1] - seq_offsets[b];
+        if (nb < probe_len || m_attn[b] < 0 || m_ffn[b] < 0) return SPTS_EINVAL;   // every sequence holds its probe rows
+        ma[b] = m_attn[b] < nb ? m_attn[b] : nb;
+        mf[b] = m_ffn[b] < nb ? m_ffn[b] : nb;
+        oa[b + 1] = oa[b] + ma[b];
+        of[b + 1] = of[b] + mf[b];
+        if (kv) {
+            kv[b].count = 0;
+            if (ma[b] > 0) {
+                if (!kv[b].k || !kv[b].v || !kv[b].pos) return SPTS_EINVAL;
+                if (!aligned16(kv[b].k) || !aligned16(kv[b].v) || !aligned16(kv[b].pos)) return SPTS_EALIGN;
+                if (kv[b].capacity < ma[b]) return SPTS_EINVAL;
+            }
+        }
+    }
+    const int64_t MaT = oa[batch], MfT = of[batch];
+    hipStream_t st = c->stream;
+    void* xn = c->p<void>(c->off.xn);
+    int64_t* seg = c->p<int64_t>(c->off.seg);
+    auto upload = [&](const std::vector<int64_t>& k, const std::vector<int64_t>& out) -> hipError_t {
+        for (int b = 0; b <= batch; ++b) { dOff[b] = seq_offsets[b]; dOut[b] = out[b]; if (b < batch) dKa[b] = k[b]; }
+        dKa[batch] = 0;
+        // the descriptors of the previous selection may still be read by work in flight: the copy is stream-ordered
+        return hipMemcpyAsync(seg, desc.data(), desc.size() * sizeof(int64_t), hipMemcpyHostToDevice, st);
+    };
+    const TopkSegments segs{seg, seg + (batch + 1), seg + 2 * (batch + 1)};
+    int64_t max_len = 0;
+    for (int b = 0; b < batch; ++b) max_len = std::max<int64_t>(max_len, seq_offsets[b + 1] - seq_offsets[b]);
+
+    // ------------------------------------------------ attention block: PAP per sequence, projections over the batch
+    float* S = s_mha ? s_mha : c->p<float>(c->off.S);
+    void* kall = c->p<void>(c->off.kall);
+    SPTS_TRY(probe_attn_impl(c, x, pos, N, w, 0, false, kall, nullptr));
+    for (int b = 0; b < batch; ++b) {
+        const int64_t r0 = seq_offsets[b], nb = seq_offsets[b + 1] - r0;
+        SPTS_TRY(probe_scores_rows(c, r0, nb, w, probe_len, (const char*)kall + (size_t)r0 * KV * eb, S + r0));
+    }
+    int32_t* idxA = idx_attn ? idx_attn : c->p<int32_t>(c->off.idxA);
+    {
+        PHASE(c, PH_TOPK);
+        SPTS_HIP(c, upload(ma, oa));
+        SPTS_HIP(c, launch_topk(S, max_len, 0, protect_last, idxA, batch, st, segs));
+        SPTS_HIP(c, launch_add_segment_base(idxA, segs.out_offsets, segs.offsets, batch, MaT, st));
+    }
+    if (MaT > 0) {
+        GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, MaT, QD, m.D);
+        gq.a_rows = N;
+        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q))); }
+        int32_t* posA = c->p<int32_t>(c->off.posA);
+        char* khat = c->p<char>(c->off.khat);
+        char* vhat = c->p<char>(c->off.vhat);
+        {
+            PHASE(c, PH_GATHER);
+            SPTS_HIP(c, launch_gather_i32(pos, idxA, posA, MaT, st));
+            SPTS_HIP(c, launch_gather_rows(kall, idxA, khat, MaT, (int64_t)KV * eb, st));
+        }
+        GemmArgs gv = gemm_args(xn, m.D, idxA, w->Wv, m.D, vhat, KV, MaT, KV, m.D);
+        gv.a_rows = N;
+        { PHASE(c, PH_V_PROJ); SPTS_TRY(run_gemm(c, gv)); }
+        for (int b = 0; b < batch; ++b) {
+            if (ma[b] == 0) continue;
+            AttnArgs aa{};
+            aa.q = c->p<char>(c->off.q) + (size_t)oa[b] * QD * eb;
+            aa.k = khat + (size_t)oa[b] * KV * eb; aa.v = vhat + (size_t)oa[b] * KV * eb;
+            aa.qpos = posA + oa[b]; aa.kpos = posA + oa[b];
+            aa.out = c->p<char>(c->off.att) + (size_t)oa[b] * QD * eb;
+            aa.Mq = ma[b]; aa.Mk = ma[b]; aa.H = m.H; aa.Hkv = m.Hkv; aa.d = m.d;
+            aa.ldvt = (ma[b] + 255) / 256 * 256; aa.vt = c->p<void>(c->off.vt);
+            const bool amf = c->bf16 && attention_mfma_supported(aa);
+            PHASE(c, PH_ATTENTION);
+            if (amf) {
+                SPTS_HIP(c, launch_transpose_pad(aa.v, c->p<void>(c->off.vt), ma[b], KV, aa.ldvt, c->bf16, st));
+                SPTS_HIP(c, launch_attention_mfma(aa, st));
+            } else {
+                SPTS_HIP(c, launch_attention_generic(aa, c->bf16, st));
+            }
+            if (kv) {
+                SPTS_HIP(c, launch_copy_bytes(aa.k, kv[b].k, ma[b] * (int64_t)KV * eb, st));
+                SPTS_HIP(c, launch_copy_bytes(aa.v, kv[b].v, ma[b] * (int64_t)KV * eb, st));
+                SPTS_HIP(c, launch_copy_bytes(posA + oa[b], kv[b].pos, ma[b] * 4, st));
+                kv[b].count = ma[b];
+            }
+        }
+        GemmArgs go = gemm_args(c->p<void>(c->off.att), QD, nullptr, w->Wo, QD, x, m.D, MaT, m.D, QD, EPI_RESIDUAL);
+        go.c_idx = idxA;
+        { PHASE(c, PH_O_PROJ); SPTS_TRY(run_gemm(c, go)); }
+    }
+
+    // ------------------------------------------------ FFN block: proxy over the batch, TopK per sequence
+    if (MfT == 0) return SPTS_OK;
+    { PHASE(c, PH_RMSNORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, m.rms_eps, xn, N, m.D, c->bf16, st)); }
+    float* SF = c->p<float>(c->off.SF);
+    SPTS_TRY(proxy_scores_impl(c, xn, N, w, S, nullptr, SF));
+    int32_t* idxF = idx_ffn ? idx_ffn : c->p<int32_t>(c->off.idxF);
+    {
+        PHASE(c, PH_TOPK);
+        SPTS_HIP(c, upload(mf, of));
+        SPTS_HIP(c, launch_topk(SF, max_len, 0, protect_last, idxF, batch, st, segs));
+        SPTS_HIP(c, launch_add_segment_base(idxF, segs.out_offsets, segs.offsets, batch, MfT, st));
+    }
+    GemmArgs gh = gemm_args(xn, m.D, idxF, w->Wgate, m.D, c->p<void>(c->off.big), m.Dff, MfT, m.Dff, m.D, EPI_SILU_MUL);
+    gh.a_rows = N;
+    gh.B1 = w->Wup;
+    { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
+    GemmArgs gd = gemm_args(c->p<void>(c->off.big), m.Dff, nullptr, w->Wdown, m.Dff, x, m.D, MfT, m.D, m.Dff, EPI_RESIDUAL);
     gd.c_idx = idxF;
     { PHASE(c, PH_FFN_DOWN); SPTS_TRY(run_gemm(c, gd)); }
     return SPTS_OK;

@@ -112,6 +112,9 @@ hipError_t launch_gather_i32(const int32_t* in, const int32_t* idx, int32_t* out
 hipError_t launch_copy_bytes(const void* in, void* out, int64_t bytes, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 hipError_t launch_iota_i32(int32_t* p, int64_t n, hipStream_t s);
+// idx[i] += seg_offsets[b] for i in [out_offsets[b], out_offsets[b+1]); device descriptor arrays
+hipError_t launch_add_segment_base(int32_t* idx, const int64_t* out_offsets, const int64_t* seg_offsets, int nseg, int64_t total,
+                                   hipStream_t s);
 // old2new[idx[i]] = i
 hipError_t launch_scatter_iota(const int32_t* idx, int32_t* old2new, int64_t n, hipStream_t s);
 // c = sqrt(sum_j part[n, j]); s_ffn = c * (s_mha ? s_mha[n] : 1)

@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(lib):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(spts_[a-z_0-9]+)\s*\(", text))
     assert {"spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_layer_prefill", "spts_msdp_compact",
-            "spts_decode_layer", "spts_greedy_token", "spts_channel_importance", "spts_select_topk_segmented", "spts_select_topk_batched"} <= declared
+            "spts_decode_layer", "spts_greedy_token", "spts_channel_importance", "spts_select_topk_segmented", "spts_select_topk_batched", "spts_layer_prefill_batched"} <= declared
     for name in declared:
         assert hasattr(lib, name), name
     assert declared == set(binding.EXPORTS)
@@ -76,6 +76,14 @@ def test_workspace_and_create_validation(lib):
         assert lib.spts_probe_attn(h, A, A, 0, C.byref(w), 8, A, A) == binding.SPTS_OK            # N == 0
         cfg = binding.spts_layer_cfg(1, 8, -1, 10, 1, 0)
         assert lib.spts_layer_prefill(h, A, A, 100, C.byref(w), C.byref(cfg), None, None, None, None) == binding.SPTS_EINVAL
+        so = (C.c_int64 * 3)(0, 60, 100); bud = (C.c_int64 * 2)(10, 10)
+        bat = lambda offs, b, P, m1=bud: lib.spts_layer_prefill_batched(h, A, A, offs, b, C.byref(w), P, m1, bud, 1, None, None, None, None)
+        assert bat(so, -1, 8) == binding.SPTS_EINVAL
+        assert bat(so, 0, 8) == binding.SPTS_OK                                            # empty batch
+        assert bat(None, 2, 8) == binding.SPTS_EINVAL
+        assert bat((C.c_int64 * 3)(4, 60, 100), 2, 8) == binding.SPTS_EINVAL               # offsets must start at 0
+        assert bat((C.c_int64 * 3)(0, 60, 600), 2, 8) == binding.SPTS_EWORKSPACE           # more rows than max_tokens
+        assert bat(so, 2, 8) == binding.SPTS_EINVAL                                        # incomplete weights
         assert lib.spts_msdp_compact(h, A, A, A, 100, -5, 1, A, A, A, None) == binding.SPTS_EINVAL
         assert lib.spts_msdp_compact(h, A, A, A, 100, 50, 1, A, A, A, None) == binding.SPTS_EINVAL  # x_out overlaps x_in
         assert lib.spts_last_hip_error(h) == 0

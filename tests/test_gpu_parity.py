@@ -386,6 +386,59 @@ def test_stack_paper_schedule_lockstep(torch, dtype, components):
     assert po[-1].item() == wl.N - 1
 
 
+# ------------------------------------------------------------------------------------------ batch of sequences
+@pytest.mark.parametrize("name,shape,lens,P,r", [
+    ("f32", synth.TINY, (301, 37, 512), 4, 16),
+    ("bf16_mfma", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), (700, 260, 1333), 64, 256),
+    ("bf16_p1", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16"), (64, 1, 900, 129), 1, 64),
+], ids=lambda v: v if isinstance(v, str) else None)
+def test_layer_prefill_batched_lockstep_per_sequence(torch, name, shape, lens, P, r):
+    """spts_layer_prefill_batched on sequences of different lengths laid back to back: every sequence must come
+    out as the oracle's single-sequence layer gives it (probe, selections and attention stay inside the sequence),
+    lock-step as for the single-sequence call; the per-sequence caches hold each sequence's active pairs."""
+    dtype = shape.dtype
+    w = synth.make_layer(41, 0, shape, r)
+    dw = runtime.upload_layer(w, shape, r)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    Ntot = int(offs[-1])
+    ctx = ctx_for(shape, 4096)
+    xs = [synth.hidden_states(100 + b, n, shape.D, dtype) for b, n in enumerate(lens)]
+    # positions with gaps, restarting in every sequence
+    rng = np.random.default_rng(7)
+    ps = [np.sort(rng.choice(3 * n + 5, size=n, replace=False)).astype(np.int32) for n in lens]
+    ma = [int(0.4 * n) for n in lens]
+    mf = [max(1, int(0.55 * n)) for n in lens]
+    ma[1] = lens[1] + 10                      # budget above the length: the whole sequence is active
+    xd = runtime.to_device(np.concatenate(xs), dtype)
+    posd = torch.from_numpy(np.concatenate(ps)).cuda()
+    MaT = sum(min(n, m) for n, m in zip(lens, ma)); MfT = sum(min(n, m) for n, m in zip(lens, mf))
+    s = torch.zeros(Ntot, dtype=torch.float32, device="cuda")
+    ia = torch.full((max(MaT, 1),), -1, dtype=torch.int32, device="cuda")
+    iff = torch.full((max(MfT, 1),), -1, dtype=torch.int32, device="cuda")
+    caches = [runtime.KVCache(shape, min(n, m)) for n, m in zip(lens, ma)]
+    kvs = [c.struct for c in caches]
+    ctx.spts_layer_prefill_batched(xd, posd, offs, dw, P, ma, mf, 1, kvs, s, ia, iff)
+    torch.cuda.synchronize()
+    x_out = runtime.to_host(xd).astype(np.float64)
+    s_out, ia, iff = s.cpu().numpy(), ia.cpu().numpy(), iff.cpu().numpy()
+    mdl = H.oracle_model(shape)
+    oa = of = 0
+    for b, n in enumerate(lens):
+        r0 = int(offs[b]); a_b, f_b = min(n, ma[b]), min(n, mf[b])
+        gpu = dict(x=x_out[r0:r0 + n], s_mha=s_out[r0:r0 + n], idx_attn=ia[oa:oa + a_b] - r0, idx_ffn=iff[of:of + f_b] - r0)
+        assert gpu["idx_attn"].min(initial=0) >= 0 and gpu["idx_attn"].max(initial=0) < n
+        res = H.lockstep_layer(gpu, xs[b], ps[b], w, mdl, orc.LayerCfg(1, P, ma[b], mf[b], 1, 0), dtype)
+        assert res["swaps_attn"] <= max(1, a_b // 50) and res["swaps_ffn"] <= max(1, f_b // 50), (b, res["swaps_attn"], res["swaps_ffn"])
+        assert kvs[b].count == a_b
+        kh, vh, ph = caches[b].k[:a_b], caches[b].v[:a_b], caches[b].pos[:a_b].cpu().numpy()
+        assert np.array_equal(ph, ps[b][gpu["idx_attn"]])
+        ref = res["ref"]
+        tol = H.TOL[dtype]["hidden"]
+        assert H.row_rel_err(runtime.to_host(kh).reshape(a_b, -1).astype(np.float64), ref.k_cache.reshape(a_b, -1)) <= tol
+        assert H.row_rel_err(runtime.to_host(vh).reshape(a_b, -1).astype(np.float64), ref.v_cache.reshape(a_b, -1)) <= tol
+        oa += a_b; of += f_b
+
+
 # ------------------------------------------------------------------------------------------ proxy builder
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_channel_importance_and_selection(torch, dtype):
