@@ -216,6 +216,17 @@ int spts_msdp_compact(spts_ctx *ctx, const void *x_in, const int32_t *pos_in, co
                       int64_t N, int64_t N_next, int32_t protect_last, void *x_out, int32_t *pos_out,
                       int32_t *map_new2old, int32_t *map_old2new);
 
+/* Stage-end pruning of a batch of sequences laid back to back (layout as in
+ * spts_layer_prefill_batched; seq_offsets [batch+1] and n_next [batch] are HOST arrays): every sequence
+ * keeps its own min(length, n_next[b]) candidates with the largest s_mha.  The kept rows of the
+ * sequences follow each other in x_out / pos_out; the new offsets are the prefix sums of the kept
+ * counts (the caller computes them on the host).  map_new2old [sum kept] and map_old2new [Ntot]
+ * (-1 for dropped rows; may be NULL) are rows of the batch.  x_out must not overlap x_in. */
+int spts_msdp_compact_batched(spts_ctx *ctx, const void *x_in, const int32_t *pos_in, const float *s_mha,
+                              const int64_t *seq_offsets, int32_t batch, const int64_t *n_next,
+                              int32_t protect_last, void *x_out, int32_t *pos_out,
+                              int32_t *map_new2old, int32_t *map_old2new);
+
 /* Per-phase timing for benchmarks.  Between spts_profile_begin and spts_profile_end every phase of
  * every call on this context (k_proj, probe_attn, topk, attention, ffn_gate_up, ...) is bracketed
  * by two HIP events on the context's stream.  spts_profile_end synchronises the stream (the only

@@ -20,7 +20,7 @@ SPTS_F32, SPTS_BF16 = 0, 1
 
 EXPORTS = (
     "spts_workspace_bytes", "spts_create", "spts_destroy", "spts_strerror", "spts_last_hip_error", "spts_uses_mfma",
-    "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_select_topk_segmented", "spts_layer_prefill", "spts_layer_prefill_batched", "spts_msdp_compact",
+    "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_select_topk_segmented", "spts_layer_prefill", "spts_layer_prefill_batched", "spts_msdp_compact", "spts_msdp_compact_batched",
     "spts_decode_layer", "spts_greedy_token", "spts_channel_importance",
     "spts_profile_begin", "spts_profile_end", "spts_profile_count", "spts_profile_get",
 )
@@ -88,6 +88,8 @@ def load() -> C.CDLL:
                                                vp, vp, vp]
     lib.spts_msdp_compact.restype = C.c_int
     lib.spts_msdp_compact.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    lib.spts_msdp_compact_batched.restype = C.c_int
+    lib.spts_msdp_compact_batched.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int64), i32, C.POINTER(C.c_int64), i32, vp, vp, vp, vp]
     lib.spts_decode_layer.restype = C.c_int
     lib.spts_decode_layer.argtypes = [vp, vp, i32, C.POINTER(spts_layer_weights), C.POINTER(spts_kv_out)]
     lib.spts_greedy_token.restype = C.c_int
@@ -223,6 +225,20 @@ class Context:
         if kv is not None:
             for dst, src in zip(kv, kva):
                 dst.count = src.count
+
+    def spts_msdp_compact_batched(self, x_in, pos_in, s_mha, seq_offsets, n_next, protect_last, x_out, pos_out, map_new2old,
+                                  map_old2new=None):
+        """seq_offsets [batch+1], n_next [batch]: host integer sequences.  Returns the new offsets (host list)."""
+        batch = len(seq_offsets) - 1
+        so = (C.c_int64 * (batch + 1))(*[int(v) for v in seq_offsets])
+        nn = (C.c_int64 * max(batch, 1))(*[int(v) for v in n_next])
+        _check(load().spts_msdp_compact_batched(self.handle, _ptr(x_in), _ptr(pos_in), _ptr(s_mha), so, batch, nn, protect_last,
+                                                _ptr(x_out), _ptr(pos_out), _ptr(map_new2old), _ptr(map_old2new)),
+               "spts_msdp_compact_batched")
+        new = [0]
+        for b in range(batch):
+            new.append(new[-1] + min(int(seq_offsets[b + 1]) - int(seq_offsets[b]), int(n_next[b])))
+        return new
 
     def spts_decode_layer(self, x, pos: int, w: spts_layer_weights, cache: spts_kv_out):
         _check(load().spts_decode_layer(self.handle, _ptr(x), pos, C.byref(w), C.byref(cache)), "spts_decode_layer")

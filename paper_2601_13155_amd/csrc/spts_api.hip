@@ -583,6 +583,54 @@ int spts_msdp_compact(spts_ctx* c, const void* x_in, const int32_t* pos_in, cons
     return SPTS_OK;
 }
 
+int spts_msdp_compact_batched(spts_ctx* c, const void* x_in, const int32_t* pos_in, const float* s_mha,
+                              const int64_t* seq_offsets, int32_t batch, const int64_t* n_next, int32_t protect_last,
+                              void* x_out, int32_t* pos_out, int32_t* map_new2old, int32_t* map_old2new) {
+    if (!c || batch < 0 || batch > SPTS_MAX_BATCH) return SPTS_EINVAL;
+    if (batch == 0) return SPTS_OK;
+    if (!seq_offsets || !n_next || seq_offsets[0] != 0) return SPTS_EINVAL;
+    const int64_t N = seq_offsets[batch];
+    SPTS_TRY(common_call_checks(c, N));
+    std::vector<int64_t> desc(3 * (size_t)(batch + 1));
+    int64_t* dOff = desc.data(); int64_t* dK = dOff + (batch + 1); int64_t* dOut = dK + (batch + 1);
+    int64_t max_len = 0;
+    dOut[0] = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int64_t nb = seq_offsets[b + 1] - seq_offsets[b];
+        if (nb < 0 || n_next[b] < 0) return SPTS_EINVAL;
+        dOff[b] = seq_offsets[b];
+        dK[b] = n_next[b] < nb ? n_next[b] : nb;
+        dOut[b + 1] = dOut[b] + dK[b];
+        max_len = std::max(max_len, nb);
+    }
+    dOff[batch] = N; dK[batch] = 0;
+    const int64_t keep = dOut[batch];
+    if (N == 0) return SPTS_OK;
+    if (map_old2new && !aligned16(map_old2new)) return SPTS_EALIGN;
+    if (keep > 0) {
+        if (!x_in || !pos_in || !s_mha || !x_out || !pos_out || !map_new2old) return SPTS_EINVAL;
+        if (!aligned16(x_in) || !aligned16(pos_in) || !aligned16(s_mha) || !aligned16(x_out) || !aligned16(pos_out) ||
+            !aligned16(map_new2old))
+            return SPTS_EALIGN;
+        const size_t row_bytes = (size_t)c->m.D * (c->bf16 ? 2 : 4);
+        const char* a = (const char*)x_in; const char* b = (const char*)x_out;
+        if (a < b + (size_t)keep * row_bytes && b < a + (size_t)N * row_bytes) return SPTS_EINVAL;  // overlap
+    }
+    PHASE(c, PH_COMPACT);
+    if (map_old2new) SPTS_HIP(c, launch_fill_i32(map_old2new, -1, N, c->stream));
+    if (keep == 0) return SPTS_OK;
+    int64_t* seg = c->p<int64_t>(c->off.seg);
+    SPTS_HIP(c, hipMemcpyAsync(seg, desc.data(), desc.size() * sizeof(int64_t), hipMemcpyHostToDevice, c->stream));
+    const TopkSegments segs{seg, seg + (batch + 1), seg + 2 * (batch + 1)};
+    SPTS_HIP(c, launch_topk(s_mha, max_len, 0, protect_last, map_new2old, batch, c->stream, segs));
+    SPTS_HIP(c, launch_add_segment_base(map_new2old, segs.out_offsets, segs.offsets, batch, keep, c->stream));
+    const int64_t row_bytes = (int64_t)c->m.D * (c->bf16 ? 2 : 4);
+    SPTS_HIP(c, launch_gather_rows(x_in, map_new2old, x_out, keep, row_bytes, c->stream));
+    SPTS_HIP(c, launch_gather_i32(pos_in, map_new2old, pos_out, keep, c->stream));
+    if (map_old2new) SPTS_HIP(c, launch_scatter_iota(map_new2old, map_old2new, keep, c->stream));
+    return SPTS_OK;
+}
+
 int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, const spts_layer_weights* w,
                        const spts_layer_cfg* cfg, spts_kv_out* kv, float* s_mha, int32_t* idx_attn, int32_t* idx_ffn) {
     SPTS_TRY(common_call_checks(c, N));

@@ -187,3 +187,44 @@ class StackRunner:
             if tr is not None:
                 self.trace.append(tr)
         return xa[:N], pa[:N], N
+
+
+class BatchedStackRunner:
+    """Alg. 1's outer loop over a batch of sequences laid back to back: per layer one spts_layer_prefill_batched,
+    at stage ends one spts_msdp_compact_batched.  `plans` holds one layer plan (Workload.layer_plan()) per sequence;
+    all plans have the same layers, stage ends and skip flags (only skip layers are supported by the batched call)."""
+
+    def __init__(self, ctx: binding.Context, shape, layers: List[binding.spts_layer_weights], plans: List[List[dict]],
+                 probe_len: int, protect_last: int = 1):
+        torch = _torch()
+        self.ctx, self.shape, self.layers, self.plans = ctx, shape, layers, plans
+        self.probe_len, self.protect_last = probe_len, protect_last
+        n0 = sum(p[0]["N"] for p in plans)
+        tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        self.xa = torch.empty((n0, shape.D), dtype=tdt, device="cuda")
+        self.xb = torch.empty((n0, shape.D), dtype=tdt, device="cuda")
+        self.posa = torch.empty(n0, dtype=torch.int32, device="cuda")
+        self.posb = torch.empty(n0, dtype=torch.int32, device="cuda")
+        self.s = torch.empty(n0, dtype=torch.float32, device="cuda")
+        self.new2old = torch.empty(n0, dtype=torch.int32, device="cuda")
+
+    def run(self, x0, pos0):
+        """x0 [sum N0_b, D], pos0 [sum N0_b]: the sequences back to back.  Returns (x, pos, offsets)."""
+        xa, xb, pa, pb = self.xa, self.xb, self.posa, self.posb
+        offs = [0]
+        for p in self.plans:
+            offs.append(offs[-1] + p[0]["N"])
+        xa[:offs[-1]].copy_(x0)
+        pa[:offs[-1]].copy_(pos0)
+        for li, w in enumerate(self.layers):
+            items = [p[li] for p in self.plans]
+            assert all(it.get("skip", 1) for it in items), "the batched call runs skip layers only"
+            self.ctx.spts_layer_prefill_batched(xa, pa, offs, w, self.probe_len, [it["m_attn"] for it in items],
+                                                [it["m_ffn"] for it in items], self.protect_last, None, self.s)
+            if items[0].get("N_next") is not None:
+                offs = self.ctx.spts_msdp_compact_batched(xa, pa, self.s, offs, [it["N_next"] for it in items],
+                                                          self.protect_last, xb, pb, self.new2old)
+                xa, xb = xb, xa
+                pa, pb = pb, pa
+        return xa[:offs[-1]], pa[:offs[-1]], offs
+

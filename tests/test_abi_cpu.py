@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(lib):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(spts_[a-z_0-9]+)\s*\(", text))
     assert {"spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_layer_prefill", "spts_msdp_compact",
-            "spts_decode_layer", "spts_greedy_token", "spts_channel_importance", "spts_select_topk_segmented", "spts_select_topk_batched", "spts_layer_prefill_batched"} <= declared
+            "spts_decode_layer", "spts_greedy_token", "spts_channel_importance", "spts_select_topk_segmented", "spts_select_topk_batched", "spts_layer_prefill_batched", "spts_msdp_compact_batched"} <= declared
     for name in declared:
         assert hasattr(lib, name), name
     assert declared == set(binding.EXPORTS)
@@ -84,6 +84,9 @@ def test_workspace_and_create_validation(lib):
         assert bat((C.c_int64 * 3)(4, 60, 100), 2, 8) == binding.SPTS_EINVAL               # offsets must start at 0
         assert bat((C.c_int64 * 3)(0, 60, 600), 2, 8) == binding.SPTS_EWORKSPACE           # more rows than max_tokens
         assert bat(so, 2, 8) == binding.SPTS_EINVAL                                        # incomplete weights
+        assert lib.spts_msdp_compact_batched(h, A, A, A, so, 2, (C.c_int64 * 2)(10, -1), 1, A, A, A, None) == binding.SPTS_EINVAL
+        assert lib.spts_msdp_compact_batched(h, A, A, A, so, 2, (C.c_int64 * 2)(0, 0), 1, None, None, None, None) == binding.SPTS_OK
+        assert lib.spts_msdp_compact_batched(h, A, A, A, so, 2, bud, 1, A, A, A, None) == binding.SPTS_EINVAL  # x_out overlaps x_in
         assert lib.spts_msdp_compact(h, A, A, A, 100, -5, 1, A, A, A, None) == binding.SPTS_EINVAL
         assert lib.spts_msdp_compact(h, A, A, A, 100, 50, 1, A, A, A, None) == binding.SPTS_EINVAL  # x_out overlaps x_in
         assert lib.spts_last_hip_error(h) == 0
