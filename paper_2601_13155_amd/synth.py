@@ -27,7 +27,7 @@ row-major, i.e. ``y = x @ W_abi^T``).
 from __future__ import annotations
 
 import math
-from dataclasses import dataclass, field, replace
+from dataclasses import dataclass, replace
 from typing import Dict, List, Optional, Tuple
 
 import numpy as np

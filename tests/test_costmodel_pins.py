@@ -1,7 +1,6 @@
 """Pins of the host-side cost model against the two closed-form tables the paper prints."""
 import os
 
-import pytest
 
 from paper_2601_13155_amd import costmodel as cm
 

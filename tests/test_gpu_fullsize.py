@@ -8,7 +8,6 @@ bench.py times (matrix-core kernels, 8B-shaped bf16 layer).
   compaction maps, score sum).
 * c3 (N = 131072): properties of the probe / TopK / skip rule at long length.
 """
-import math
 
 import numpy as np
 import pytest

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from oracle import spts_oracle as orc
-from paper_2601_13155_amd import binding, runtime, synth
+from paper_2601_13155_amd import runtime, synth
 from tests import helpers as H
 
 pytestmark = pytest.mark.gpu
