@@ -163,21 +163,24 @@ int spts_layer_prefill(spts_ctx *ctx, void *x, const int32_t *pos, int64_t N,
                        const spts_layer_weights *w, const spts_layer_cfg *cfg, spts_kv_out *kv,
                        float *s_mha, int32_t *idx_attn, int32_t *idx_ffn);
 
-/* The same layer over a batch of sequences of different lengths (skip = 1, active-pair caches): x
+/* The same layer over a batch of sequences of different lengths (kv_mode 0: active-pair caches): x
  * [Ntot, D] and pos [Ntot] hold the sequences back to back, sequence b in rows
  * [seq_offsets[b], seq_offsets[b+1]).  seq_offsets [batch+1], m_attn [batch] and m_ffn [batch] are HOST
  * arrays (seq_offsets[0] = 0; budgets as in spts_layer_cfg, min(length, m) applies per sequence).  Every
  * sequence is probed with its own last probe_len rows, selects within itself (Eq. (mha_importance),
  * Eq. (ffn_importance) and TopK per sequence) and attends to itself only; the projections and the FFN
  * run over the rows of all sequences at once.  Every sequence needs at least probe_len rows
- * (SPTS_EINVAL otherwise); batch <= SPTS_MAX_BATCH.  Optional outputs: kv [batch] (one cache per
+ * (SPTS_EINVAL otherwise); batch <= SPTS_MAX_BATCH.  skip == 0 runs the dense branches: no probe, no
+ * selection, every row active (probe_len and the budgets are ignored, the score / index outputs are
+ * not written, the caches receive every row).  Optional outputs: kv [batch] (one cache per
  * sequence, filled with its active pairs), s_mha [Ntot], idx_attn / idx_ffn: the active sets of the
  * sequences back to back, as ascending row numbers of the batch (sequence b's share starts at
  * sum over b' < b of min(len_b', m_b')). */
 #define SPTS_MAX_BATCH 1024
 int spts_layer_prefill_batched(spts_ctx *ctx, void *x, const int32_t *pos, const int64_t *seq_offsets,
-                               int32_t batch, const spts_layer_weights *w, int32_t probe_len,
-                               const int64_t *m_attn, const int64_t *m_ffn, int32_t protect_last,
+                               int32_t batch, const spts_layer_weights *w, int32_t skip,
+                               int32_t probe_len, const int64_t *m_attn, const int64_t *m_ffn,
+                               int32_t protect_last,
                                spts_kv_out *kv, float *s_mha, int32_t *idx_attn, int32_t *idx_ffn);
 
 /* Decode phase of Alg. 1 for one new token (Is_prefill_phase() is false, so skip is false: standard

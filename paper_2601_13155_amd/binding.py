@@ -83,7 +83,7 @@ def load() -> C.CDLL:
     lib.spts_layer_prefill.argtypes = [vp, vp, vp, i64, C.POINTER(spts_layer_weights), C.POINTER(spts_layer_cfg),
                                        C.POINTER(spts_kv_out), vp, vp, vp]
     lib.spts_layer_prefill_batched.restype = C.c_int
-    lib.spts_layer_prefill_batched.argtypes = [vp, vp, vp, C.POINTER(C.c_int64), i32, C.POINTER(spts_layer_weights), i32,
+    lib.spts_layer_prefill_batched.argtypes = [vp, vp, vp, C.POINTER(C.c_int64), i32, C.POINTER(spts_layer_weights), i32, i32,
                                                C.POINTER(C.c_int64), C.POINTER(C.c_int64), i32, C.POINTER(spts_kv_out),
                                                vp, vp, vp]
     lib.spts_msdp_compact.restype = C.c_int
@@ -209,7 +209,7 @@ class Context:
                                          _ptr(idx_ffn)), "spts_layer_prefill")
 
     def spts_layer_prefill_batched(self, x, pos, seq_offsets, w: spts_layer_weights, probe_len: int, m_attn, m_ffn,
-                                   protect_last: int = 1, kv=None, s_mha=None, idx_attn=None, idx_ffn=None):
+                                   protect_last: int = 1, kv=None, s_mha=None, idx_attn=None, idx_ffn=None, skip: int = 1):
         """seq_offsets [batch+1], m_attn / m_ffn [batch]: host integer sequences; kv: list of spts_kv_out or None
         (their count fields are updated in place)."""
         batch = len(seq_offsets) - 1
@@ -219,7 +219,7 @@ class Context:
         kva = None
         if kv is not None:
             kva = (spts_kv_out * batch)(*kv)
-        _check(load().spts_layer_prefill_batched(self.handle, _ptr(x), _ptr(pos), so, batch, C.byref(w), probe_len, ma, mf,
+        _check(load().spts_layer_prefill_batched(self.handle, _ptr(x), _ptr(pos), so, batch, C.byref(w), skip, probe_len, ma, mf,
                                                  protect_last, kva, _ptr(s_mha), _ptr(idx_attn), _ptr(idx_ffn)),
                "spts_layer_prefill_batched")
         if kv is not None:

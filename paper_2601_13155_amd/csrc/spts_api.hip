@@ -755,19 +755,22 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
 }
 
 int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const int64_t* seq_offsets, int32_t batch,
-                               const spts_layer_weights* w, int32_t probe_len, const int64_t* m_attn, const int64_t* m_ffn,
+                               const spts_layer_weights* w, int32_t skip, int32_t probe_len, const int64_t* m_attn, const int64_t* m_ffn,
                                int32_t protect_last, spts_kv_out* kv, float* s_mha, int32_t* idx_attn, int32_t* idx_ffn) {
     if (!c || batch < 0 || batch > SPTS_MAX_BATCH) return SPTS_EINVAL;
     if (batch == 0) return SPTS_OK;
-    if (!seq_offsets || !m_attn || !m_ffn || seq_offsets[0] != 0) return SPTS_EINVAL;
+    if (!seq_offsets || seq_offsets[0] != 0) return SPTS_EINVAL;
+    if (skip && (!m_attn || !m_ffn)) return SPTS_EINVAL;
     const int64_t N = seq_offsets[batch];
     SPTS_TRY(common_call_checks(c, N));
     if (!x || !pos) return SPTS_EINVAL;
     if (!aligned16(x) || !aligned16(pos)) return SPTS_EALIGN;
     if ((s_mha && !aligned16(s_mha)) || (idx_attn && !aligned16(idx_attn)) || (idx_ffn && !aligned16(idx_ffn))) return SPTS_EALIGN;
-    SPTS_TRY(check_weights_full(c, w, true));
-    if (probe_len < 1) return SPTS_EINVAL;
-    if (probe_len > c->lim.max_probe) return SPTS_EWORKSPACE;
+    SPTS_TRY(check_weights_full(c, w, skip != 0));
+    if (skip) {
+        if (probe_len < 1) return SPTS_EINVAL;
+        if (probe_len > c->lim.max_probe) return SPTS_EWORKSPACE;
+    }
     const auto& m = c->m;
     const int KV = m.Hkv * m.d, QD = m.H * m.d;
     const size_t eb = c->bf16 ? 2 : 4;
@@ -780,9 +783,10 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
     oa[0] = of[0] = 0;
     for (int b = 0; b < batch; ++b) {
         const int64_t nb = seq_offsets[b + 1] - seq_offsets[b];
-        if (nb < probe_len || m_attn[b] < 0 || m_ffn[b] < 0) return SPTS_EINVAL;   // every sequence holds its probe rows
-        ma[b] = m_attn[b] < nb ? m_attn[b] : nb;
-        mf[b] = m_ffn[b] < nb ? m_ffn[b] : nb;
+        if (nb < 0) return SPTS_EINVAL;
+        if (skip && (nb < probe_len || m_attn[b] < 0 || m_ffn[b] < 0)) return SPTS_EINVAL;   // every sequence holds its probe rows
+        ma[b] = skip && m_attn[b] < nb ? m_attn[b] : nb;   // dense layer: every row is active
+        mf[b] = skip && m_ffn[b] < nb ? m_ffn[b] : nb;
         oa[b + 1] = oa[b] + ma[b];
         of[b + 1] = of[b] + mf[b];
         if (kv) {
@@ -812,12 +816,13 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
     float* S = s_mha ? s_mha : c->p<float>(c->off.S);
     void* kall = c->p<void>(c->off.kall);
     SPTS_TRY(probe_attn_impl(c, x, pos, N, w, 0, false, kall, nullptr));
-    for (int b = 0; b < batch; ++b) {
+    for (int b = 0; skip && b < batch; ++b) {
         const int64_t r0 = seq_offsets[b], nb = seq_offsets[b + 1] - r0;
         SPTS_TRY(probe_scores_rows(c, r0, nb, w, probe_len, (const char*)kall + (size_t)r0 * KV * eb, S + r0));
     }
-    int32_t* idxA = idx_attn ? idx_attn : c->p<int32_t>(c->off.idxA);
-    {
+    // dense layer (the else-branches of Alg. 1): no selection, the "active rows" are the rows themselves
+    int32_t* idxA = !skip ? nullptr : idx_attn ? idx_attn : c->p<int32_t>(c->off.idxA);
+    if (skip) {
         PHASE(c, PH_TOPK);
         SPTS_HIP(c, upload(ma, oa));
         SPTS_HIP(c, launch_topk(S, max_len, 0, protect_last, idxA, batch, st, segs));
@@ -827,13 +832,15 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
         GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, MaT, QD, m.D);
         gq.a_rows = N;
         { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q))); }
-        int32_t* posA = c->p<int32_t>(c->off.posA);
-        char* khat = c->p<char>(c->off.khat);
+        const int32_t* posA = pos;
+        const char* khat = (const char*)kall;
         char* vhat = c->p<char>(c->off.vhat);
-        {
+        if (skip) {
             PHASE(c, PH_GATHER);
-            SPTS_HIP(c, launch_gather_i32(pos, idxA, posA, MaT, st));
-            SPTS_HIP(c, launch_gather_rows(kall, idxA, khat, MaT, (int64_t)KV * eb, st));
+            SPTS_HIP(c, launch_gather_i32(pos, idxA, c->p<int32_t>(c->off.posA), MaT, st));
+            SPTS_HIP(c, launch_gather_rows(kall, idxA, c->p<void>(c->off.khat), MaT, (int64_t)KV * eb, st));
+            posA = c->p<int32_t>(c->off.posA);
+            khat = c->p<char>(c->off.khat);
         }
         GemmArgs gv = gemm_args(xn, m.D, idxA, w->Wv, m.D, vhat, KV, MaT, KV, m.D);
         gv.a_rows = N;
@@ -871,9 +878,9 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
     if (MfT == 0) return SPTS_OK;
     { PHASE(c, PH_RMSNORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, m.rms_eps, xn, N, m.D, c->bf16, st)); }
     float* SF = c->p<float>(c->off.SF);
-    SPTS_TRY(proxy_scores_impl(c, xn, N, w, S, nullptr, SF));
-    int32_t* idxF = idx_ffn ? idx_ffn : c->p<int32_t>(c->off.idxF);
-    {
+    if (skip) SPTS_TRY(proxy_scores_impl(c, xn, N, w, S, nullptr, SF));
+    int32_t* idxF = !skip ? nullptr : idx_ffn ? idx_ffn : c->p<int32_t>(c->off.idxF);
+    if (skip) {
         PHASE(c, PH_TOPK);
         SPTS_HIP(c, upload(mf, of));
         SPTS_HIP(c, launch_topk(SF, max_len, 0, protect_last, idxF, batch, st, segs));

@@ -192,7 +192,7 @@ class StackRunner:
 class BatchedStackRunner:
     """Alg. 1's outer loop over a batch of sequences laid back to back: per layer one spts_layer_prefill_batched,
     at stage ends one spts_msdp_compact_batched.  `plans` holds one layer plan (Workload.layer_plan()) per sequence;
-    all plans have the same layers, stage ends and skip flags (only skip layers are supported by the batched call)."""
+    all plans have the same layers, stage ends and skip flags."""
 
     def __init__(self, ctx: binding.Context, shape, layers: List[binding.spts_layer_weights], plans: List[List[dict]],
                  probe_len: int, protect_last: int = 1):
@@ -218,10 +218,11 @@ class BatchedStackRunner:
         pa[:offs[-1]].copy_(pos0)
         for li, w in enumerate(self.layers):
             items = [p[li] for p in self.plans]
-            assert all(it.get("skip", 1) for it in items), "the batched call runs skip layers only"
+            skip_l = int(items[0].get("skip", 1))
+            assert all(int(it.get("skip", 1)) == skip_l for it in items), "a layer is dense or skipped for the whole batch"
             self.ctx.spts_layer_prefill_batched(xa, pa, offs, w, self.probe_len, [it["m_attn"] for it in items],
-                                                [it["m_ffn"] for it in items], self.protect_last, None, self.s)
-            if items[0].get("N_next") is not None:
+                                                [it["m_ffn"] for it in items], self.protect_last, None, self.s, skip=skip_l)
+            if skip_l and items[0].get("N_next") is not None:
                 offs = self.ctx.spts_msdp_compact_batched(xa, pa, self.s, offs, [it["N_next"] for it in items],
                                                           self.protect_last, xb, pb, self.new2old)
                 xa, xb = xb, xa

@@ -77,7 +77,7 @@ def test_workspace_and_create_validation(lib):
         cfg = binding.spts_layer_cfg(1, 8, -1, 10, 1, 0)
         assert lib.spts_layer_prefill(h, A, A, 100, C.byref(w), C.byref(cfg), None, None, None, None) == binding.SPTS_EINVAL
         so = (C.c_int64 * 3)(0, 60, 100); bud = (C.c_int64 * 2)(10, 10)
-        bat = lambda offs, b, P, m1=bud: lib.spts_layer_prefill_batched(h, A, A, offs, b, C.byref(w), P, m1, bud, 1, None, None, None, None)
+        bat = lambda offs, b, P, m1=bud: lib.spts_layer_prefill_batched(h, A, A, offs, b, C.byref(w), 1, P, m1, bud, 1, None, None, None, None)
         assert bat(so, -1, 8) == binding.SPTS_EINVAL
         assert bat(so, 0, 8) == binding.SPTS_OK                                            # empty batch
         assert bat(None, 2, 8) == binding.SPTS_EINVAL

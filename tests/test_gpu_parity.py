@@ -440,6 +440,37 @@ def test_layer_prefill_batched_lockstep_per_sequence(torch, name, shape, lens, P
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layer_prefill_batched_dense_branch(torch, dtype):
+    """skip = 0 on a batch: every sequence goes through the dense branches of Alg. 1 on its own (attention inside
+    the sequence, all rows in the FFN), and its cache receives all of its pairs."""
+    shape = synth.TINY if dtype == "f32" else synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0)
+    lens = (130, 1, 517)
+    w = synth.make_layer(43, 0, shape, 16)
+    dw = runtime.upload_layer(w, shape, 16)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ctx = ctx_for(shape, 4096)
+    xs = [synth.hidden_states(200 + b, n, shape.D, dtype) for b, n in enumerate(lens)]
+    ps = [synth.positions(n) for n in lens]
+    xd = runtime.to_device(np.concatenate(xs), dtype)
+    posd = torch.from_numpy(np.concatenate(ps)).cuda()
+    caches = [runtime.KVCache(shape, n) for n in lens]
+    kvs = [c.struct for c in caches]
+    ctx.spts_layer_prefill_batched(xd, posd, offs, dw, 0, [0] * 3, [0] * 3, 1, kvs, None, None, None, skip=0)
+    torch.cuda.synchronize()
+    x_out = runtime.to_host(xd).astype(np.float64)
+    mdl = H.oracle_model(shape)
+    tol = H.TOL[dtype]["hidden"]
+    for b, n in enumerate(lens):
+        r0 = int(offs[b])
+        ref = orc.layer_prefill(xs[b], ps[b], w, mdl, orc.LayerCfg(0, 1, n, n, 1, 0), rnd=H.rnd_for(dtype))
+        assert H.row_rel_err(x_out[r0:r0 + n], ref.x) <= tol, b
+        assert kvs[b].count == n
+        assert np.array_equal(caches[b].pos[:n].cpu().numpy(), ps[b])
+        assert H.row_rel_err(runtime.to_host(caches[b].k[:n]).reshape(n, -1).astype(np.float64), ref.k_cache.reshape(n, -1)) <= tol
+        assert H.row_rel_err(runtime.to_host(caches[b].v[:n]).reshape(n, -1).astype(np.float64), ref.v_cache.reshape(n, -1)) <= tol
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_msdp_compact_batched_bit_exact(torch, dtype):
     """Stage-end pruning of a batch: per sequence the maps the oracle's compaction gives on the same fp32 scores
     (as rows of the batch), rows and positions copied bit for bit; ties inside a sequence, an empty target and a
@@ -478,13 +509,13 @@ def test_msdp_compact_batched_bit_exact(torch, dtype):
 
 
 def test_batched_stack_equals_the_sequences_run_alone(torch):
-    """A three-layer stack with two stage ends over a batch of three sequences (bf16, matrix-core shape) gives every
+    """A three-layer stack (one dense layer, two skip layers, a stage end) over a batch of three sequences (bf16, matrix-core shape) gives every
     sequence the candidates, positions and hidden states that the single-sequence stack gives it.  (Each step of the
     single-sequence stack is checked against the oracle elsewhere; this checks the batch plumbing end to end.)"""
     shape = synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0)
     lens = (900, 300, 1500)
     wls = [synth.Workload("b", shape, N=n, layers=3, probe_len=16, attn_keep=0.4, ffn_keep=0.5, r=64, seed=9,
-                          stage_end_layers=(1, 2), stage_cum_keep=(1.0, 0.7, 0.45)) for n in lens]
+                          stage_end_layers=(2,), stage_cum_keep=(1.0, 0.6), dense_layers=1) for n in lens]
     plans = [wl.layer_plan() for wl in wls]
     ws = [synth.make_layer(9, l, shape, 64) for l in range(3)]
     dws = [runtime.upload_layer(w, shape, 64) for w in ws]
