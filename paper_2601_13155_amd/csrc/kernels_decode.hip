@@ -5,9 +5,9 @@
 //
 // One token means every contraction is a matrix-vector product whose cost is reading the weights
 // once, so the whole step is HBM-bound (8B-shaped model: 13.9 GB of bf16 weights per token):
-//   * gemv_kernel: y = W x with W [R, K] row-major.  A workgroup of 4 wavefronts owns 4 rows (2 gate
-//     + 2 up rows for the SwiGLU variant) and splits K across its 256 lanes in 16-byte chunks, so
-//     8 (16) independent 16-byte weight loads per lane are in flight before the first use; bf16
+//   * gemv_kernel: y = W x with W [R, K] row-major.  A workgroup of 4 wavefronts owns 2 rows (a gate
+//     and an up row for the SwiGLU variant; 4 rows for Q/K/V) and splits K across its 256 lanes in
+//     16-byte chunks, with several independent 16-byte weight loads per lane in flight before the first use; bf16
 //     pairs are multiplied with v_dot2c_f32_bf16 (fp32 accumulate, no conversion instructions).
 //     Lanes reduce by shuffles, wavefronts through LDS.  Up to three matrices that share x run as
 //     one launch (Q, K, V).  Epilogues: store, SiLU(gate)*up, residual add, fp32 store (logits).
@@ -59,21 +59,24 @@ __device__ inline float chunk_sumsq(u32x4 v, float) {
 template <typename T, int MODE, bool NORM>
 __global__ void __launch_bounds__(256) gemv_kernel(GemvArgs a) {
     constexpr int EPC = 16 / (int)sizeof(T);          // elements per 16-byte chunk
-    constexpr int ROWS = 4;                           // dot products per workgroup
+    constexpr int ROWS = (MODE == GEMV_RESID) ? 2 : (MODE == GEMV_SILU) ? 2 : 4;   // dot products per workgroup
     constexpr int NCH = 4;                            // chunks of x a lane may hold (fused norm)
     __shared__ float sred[4][ROWS];
     __shared__ float snorm[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    // rows of this workgroup: ROWS consecutive rows of one matrix, or (SiLU) 2 gate rows + the same 2 up rows
+    // rows of this workgroup: ROWS consecutive rows of one matrix, or (SiLU) a gate row and the same up row.
+    // Two rows per workgroup measured best where the epilogue allows it (O-proj 8.0 -> 7.5 us, down 19.7 -> 19.3 us,
+    // gate/up 36.9 -> 35.3 us against four; one row and eight rows are slower); Q/K/V keep the four rows of two
+    // rotary pairs
     const T* wrow[ROWS];
     int64_t out_row;      // first output element of this workgroup
     int which = 0;        // matrix the rows belong to
     if (MODE == GEMV_SILU) {
-        out_row = (int64_t)blockIdx.x * 2;
+        out_row = (int64_t)blockIdx.x * (ROWS / 2);
 #pragma unroll
         for (int r = 0; r < ROWS; ++r)
-            wrow[r] = (const T*)(r < 2 ? a.W[0] : a.W[1]) + (out_row + (r & 1)) * a.K;
+            wrow[r] = (const T*)(r < ROWS / 2 ? a.W[0] : a.W[1]) + (out_row + (r % (ROWS / 2))) * a.K;
     } else if (MODE == GEMV_QKV_ROPE) {
         // Q and K blocks own the rows (j, j+1, j+d/2, j+d/2+1) of one head, so that both members of the
         // two rotary pairs are reduced by the same workgroup; V blocks own 4 consecutive rows
@@ -100,7 +103,8 @@ __global__ void __launch_bounds__(256) gemv_kernel(GemvArgs a) {
 
     const int nchunks = a.K / EPC;
     const T* x = (const T*)a.x;
-    float acc[ROWS] = {0.f, 0.f, 0.f, 0.f};
+    float acc[ROWS];
+    for (int r = 0; r < ROWS; ++r) acc[r] = 0.f;
     if (NORM) {
         // the weight loads do not depend on the norm: issue them first, then normalise x while they fly
         u32x4 wv[NCH][ROWS], xc[NCH], gc[NCH];
@@ -151,9 +155,9 @@ __global__ void __launch_bounds__(256) gemv_kernel(GemvArgs a) {
     if (tid >= ROWS) return;
     const float v = sred[0][tid] + sred[1][tid] + sred[2][tid] + sred[3][tid];
     if (MODE == GEMV_SILU) {
-        if (tid < 2) {
+        if (tid < ROWS / 2) {
             const float g = v;
-            const float u = sred[0][tid + 2] + sred[1][tid + 2] + sred[2][tid + 2] + sred[3][tid + 2];
+            const float u = sred[0][tid + ROWS / 2] + sred[1][tid + ROWS / 2] + sred[2][tid + ROWS / 2] + sred[3][tid + ROWS / 2];
             const float h = g / (1.0f + __expf(-g)) * u;
             ((T*)a.y[0])[out_row + tid] = from_f32<T>(h);
         }
@@ -197,7 +201,7 @@ static hipError_t launch_gemv_t(const GemvArgs& a, hipStream_t s) {
     const int64_t rows = (int64_t)a.R[0] + a.R[1] + a.R[2];
     if (rows == 0) return hipSuccess;
     const dim3 b(256);
-    const dim3 g((unsigned)(a.mode == GEMV_SILU ? a.R[0] / 2 : rows / 4));
+    const dim3 g((unsigned)(a.mode == GEMV_SILU ? a.R[0] : a.mode == GEMV_RESID ? rows / 2 : rows / 4));
     const bool n = a.gamma != nullptr;
     switch (a.mode) {
         case GEMV_STORE: if (n) gemv_kernel<T, GEMV_STORE, true><<<g, b, 0, s>>>(a); else gemv_kernel<T, GEMV_STORE, false><<<g, b, 0, s>>>(a); break;
