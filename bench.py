@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=32,
                     help="greedy decode steps over the caches the prefill leaves (0 = skip the decode leg)")
     ap.add_argument("--vocab", type=int, default=128256, help="rows of the synthetic vocabulary table of the decode leg")
+    ap.add_argument("--decode-batch", type=int, default=8,
+                    help="sequences of the batched decode leg (copies of the prefill caches decoded together, at most 16; 0 or 1 = skip it)")
     ap.add_argument("--builder-tokens", type=int, default=8192,
                     help="calibration tokens of the offline channel-importance leg (0 = skip it)")
     ap.add_argument("--batch-seqs", type=int, default=4,
@@ -305,6 +307,33 @@ def main():
             decode["gemv_gbs"] = wbytes / (gemv_ms * 1e-3) / 1e9
             decode["gemv_hbm_frac"] = decode["gemv_gbs"] / PEAK_HBM_GBS
         log(f"[decode] {dms:.3f} ms/token ({1e3 / dms:.1f} tokens/s), {decode['gbs']:.0f} GB/s of weights + cache + table")
+        # the same step over a batch of sequences (each with its own copy of the caches): the weights are read once per step
+        if 2 <= args.decode_batch <= 16:
+            nb = args.decode_batch
+            bsteps = min(steps_d, 16)
+            bc = []
+            for _ in range(nb):
+                seq = []
+                for c0, cn in zip(caches, cached):
+                    kc = runtime.KVCache(shape, cn + bsteps + 2)
+                    kc.k[:cn].copy_(c0.k[:cn]); kc.v[:cn].copy_(c0.v[:cn]); kc.pos[:cn].copy_(c0.pos[:cn])
+                    kc.struct.count = cn
+                    seq.append(kc)
+                bc.append(seq)
+            bdec = runtime.BatchedDecodeRunner(ctx, shape, layers, bc, gamma_f, table)
+            bdec.x.copy_(table[1:1 + nb])
+            bdec.generate([wl.N] * nb, 1)
+            torch.cuda.synchronize()
+            e0.record()
+            bdec.generate([wl.N + 1] * nb, bsteps)
+            e1.record()
+            torch.cuda.synchronize()
+            bms = e0.elapsed_time(e1) / bsteps
+            btot = wbytes + nb * kvbytes + head_bytes
+            decode["batched"] = {"sequences": nb, "steps": bsteps, "ms_per_step": bms, "tokens_per_s": nb * 1e3 / bms,
+                                 "gbs": btot / (bms * 1e-3) / 1e9, "hbm_frac": btot / (bms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+            log(f"[decode, batch of {nb}] {bms:.3f} ms/step = {nb * 1e3 / bms:.0f} tokens/s")
+            del bc, bdec
         del caches, crunner, dec
         # the same decode over the full caches of a dense prefill (every layer keeps all N pairs): the library's own
         # baseline for the end-to-end figure

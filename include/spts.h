@@ -194,6 +194,14 @@ int spts_layer_prefill_batched(spts_ctx *ctx, void *x, const int32_t *pos, const
 int spts_decode_layer(spts_ctx *ctx, void *x, int32_t pos, const spts_layer_weights *w,
                       spts_kv_out *cache);
 
+/* The decode step for a batch of sequences, one new token each (batch <= SPTS_MAX_DECODE_BATCH): x
+ * [batch, D] in/out, pos [batch] HOST array of the tokens' absolute positions, caches [batch]: one
+ * cache per sequence (distinct buffers), each appended to and attended over as in spts_decode_layer.
+ * The projections and the FFN read the layer's weights once for the whole batch. */
+#define SPTS_MAX_DECODE_BATCH 16
+int spts_decode_layer_batched(spts_ctx *ctx, void *x, const int32_t *pos, int32_t batch,
+                              const spts_layer_weights *w, spts_kv_out *caches);
+
 /* Greedy next token after the last layer: RMSNorm with gamma_f [D], logits = table [V, D] applied
  * to the normed state (fp32), token = argmax with ties to the lowest id.  The vocabulary table is a
  * harness input (the method does not define one); it also serves as the embedding: x_next [D]
@@ -201,6 +209,13 @@ int spts_decode_layer(spts_ctx *ctx, void *x, int32_t pos, const spts_layer_weig
  * NULL (then the workspace must hold V floats: SPTS_EWORKSPACE otherwise).  V % 4 == 0. */
 int spts_greedy_token(spts_ctx *ctx, const void *x, const void *gamma_f, const void *table,
                       int32_t V, int32_t *token_out, float *logits_out, void *x_next);
+
+/* spts_greedy_token for a batch of states x [batch, D] (batch <= SPTS_MAX_DECODE_BATCH): the
+ * vocabulary table is read once.  token_out [batch]; logits_out [batch, V] or NULL (the workspace must
+ * then hold batch * V floats); x_next [batch, D] or NULL. */
+int spts_greedy_token_batched(spts_ctx *ctx, const void *x, const void *gamma_f, const void *table,
+                              int32_t V, int32_t batch, int32_t *token_out, float *logits_out,
+                              void *x_next);
 
 /* Offline proxy construction, channel scores (Sec. 3.3: activation saliency and
  * Eq. (channel_importance)).  x_cal [T, D]: calibration tokens as the FFN sees them (states after

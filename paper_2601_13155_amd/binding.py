@@ -21,7 +21,7 @@ SPTS_F32, SPTS_BF16 = 0, 1
 EXPORTS = (
     "spts_workspace_bytes", "spts_create", "spts_destroy", "spts_strerror", "spts_last_hip_error", "spts_uses_mfma",
     "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_select_topk_segmented", "spts_layer_prefill", "spts_layer_prefill_batched", "spts_msdp_compact", "spts_msdp_compact_batched",
-    "spts_decode_layer", "spts_greedy_token", "spts_channel_importance",
+    "spts_decode_layer", "spts_decode_layer_batched", "spts_greedy_token", "spts_greedy_token_batched", "spts_channel_importance",
     "spts_profile_begin", "spts_profile_end", "spts_profile_count", "spts_profile_get",
 )
 
@@ -92,6 +92,10 @@ def load() -> C.CDLL:
     lib.spts_msdp_compact_batched.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int64), i32, C.POINTER(C.c_int64), i32, vp, vp, vp, vp]
     lib.spts_decode_layer.restype = C.c_int
     lib.spts_decode_layer.argtypes = [vp, vp, i32, C.POINTER(spts_layer_weights), C.POINTER(spts_kv_out)]
+    lib.spts_decode_layer_batched.restype = C.c_int
+    lib.spts_decode_layer_batched.argtypes = [vp, vp, C.POINTER(C.c_int32), i32, C.POINTER(spts_layer_weights), C.POINTER(spts_kv_out)]
+    lib.spts_greedy_token_batched.restype = C.c_int
+    lib.spts_greedy_token_batched.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
     lib.spts_greedy_token.restype = C.c_int
     lib.spts_greedy_token.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
     lib.spts_channel_importance.restype = C.c_int
@@ -242,6 +246,19 @@ class Context:
 
     def spts_decode_layer(self, x, pos: int, w: spts_layer_weights, cache: spts_kv_out):
         _check(load().spts_decode_layer(self.handle, _ptr(x), pos, C.byref(w), C.byref(cache)), "spts_decode_layer")
+
+    def spts_decode_layer_batched(self, x, pos, w: spts_layer_weights, caches):
+        """x [batch, D] device tensor; pos: host integers; caches: list of spts_kv_out (count fields updated in place)."""
+        batch = len(caches)
+        pa = (C.c_int32 * max(batch, 1))(*[int(v) for v in pos])
+        ka = (spts_kv_out * max(batch, 1))(*caches)
+        _check(load().spts_decode_layer_batched(self.handle, _ptr(x), pa, batch, C.byref(w), ka), "spts_decode_layer_batched")
+        for dst, src in zip(caches, ka):
+            dst.count = src.count
+
+    def spts_greedy_token_batched(self, x, gamma_f, table, V: int, batch: int, token_out, logits_out=None, x_next=None):
+        _check(load().spts_greedy_token_batched(self.handle, _ptr(x), _ptr(gamma_f), _ptr(table), V, batch, _ptr(token_out),
+                                                _ptr(logits_out), _ptr(x_next)), "spts_greedy_token_batched")
 
     def spts_greedy_token(self, x, gamma_f, table, V: int, token_out, logits_out=None, x_next=None):
         _check(load().spts_greedy_token(self.handle, _ptr(x), _ptr(gamma_f), _ptr(table), V, _ptr(token_out),

@@ -221,6 +221,255 @@ hipError_t launch_gemv(const GemvArgs& a, bool bf16, hipStream_t s) {
     return bf16 ? launch_gemv_t<bf16_t>(a, s) : launch_gemv_t<float>(a, s);
 }
 
+// ------------------------------------------------------------------- GEMV over a few input vectors
+// Y[b, r] = W[r, :] . X[b, :] for b < NB (a decode step over NB sequences): the weights are still read
+// once, every weight chunk meets the NB input chunks in registers.  X [NB, K] and Y[i] [NB, R[i]] are
+// row-major and contiguous.
+// A wavefront owns RW rows on its own (RW/2 gate rows and the same up rows for the SiLU variant) and
+// splits K over its 64 lanes; a workgroup is four such wavefronts on consecutive rows (they read the
+// same input chunks at about the same time).  The RW*NB accumulators of a lane are reduced over the
+// wavefront with a halving butterfly: at every step a lane hands half of its accumulators to its
+// partner and adds the partner's other half, so 64 sums cost 63 exchanges instead of 64*6; lane
+// (i << (6 - log2(RW*NB))) ends up with the total of accumulator i.
+template <typename T, int MODE, int NB, int RW>
+__global__ void __launch_bounds__(256) gemv_nb_kernel(GemvArgs a) {
+    constexpr int EPC = 16 / (int)sizeof(T);
+    constexpr int HR = RW / 2;
+    constexpr int NA = RW * NB;                     // accumulators per lane (a power of two <= 64)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const T* wrow[RW];
+    int64_t out_row;
+    int which = 0;
+    if (MODE == GEMV_SILU) {
+        out_row = ((int64_t)blockIdx.x * 4 + wave) * HR;
+#pragma unroll
+        for (int r = 0; r < RW; ++r) wrow[r] = (const T*)(r < HR ? a.W[0] : a.W[1]) + (out_row + r % HR) * a.K;
+    } else {
+        int64_t row = ((int64_t)blockIdx.x * 4 + wave) * RW;
+        if (row >= a.R[0]) { row -= a.R[0]; which = 1; if (row >= a.R[1]) { row -= a.R[1]; which = 2; } }
+        out_row = row;
+#pragma unroll
+        for (int r = 0; r < RW; ++r) wrow[r] = (const T*)a.W[which] + (row + r) * a.K;
+    }
+    const int nchunks = a.K / EPC;
+    const T* x = (const T*)a.x;
+    float acc[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) acc[i] = 0.f;
+#pragma unroll 2
+    for (int c = lane; c < nchunks; c += 64) {
+        u32x4 wv[RW], xv[NB];
+#pragma unroll
+        for (int r = 0; r < RW; ++r) wv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow[r] + (int64_t)c * EPC));
+#pragma unroll
+        for (int b = 0; b < NB; ++b) xv[b] = *reinterpret_cast<const u32x4*>(x + ((int64_t)b * a.K + (int64_t)c * EPC));
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc[r * NB + b] = dot16(wv[r], xv[b], acc[r * NB + b], T{});
+    }
+    // halving butterfly over the 64 lanes
+    int n = NA;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        if (n > 1) {
+            const int half = n / 2;
+            const bool up = (lane & off) != 0;
+#pragma unroll
+            for (int i = 0; i < NA / 2; ++i) {
+                if (i < half) {
+                    const float lo = acc[i], hi = acc[i + half];
+                    acc[i] = (up ? hi : lo) + __shfl_xor(up ? lo : hi, off);
+                }
+            }
+            n = half;
+        } else {
+            acc[0] += __shfl_xor(acc[0], off);
+        }
+    }
+    constexpr int SH = NA == 64 ? 0 : NA == 32 ? 1 : NA == 16 ? 2 : NA == 8 ? 3 : NA == 4 ? 4 : NA == 2 ? 5 : 6;
+    const float v = acc[0];
+    const int idx = lane >> SH;                     // accumulator this lane holds the total of
+    const int r = idx / NB, b = idx % NB;
+    float u = 0.f;
+    if (MODE == GEMV_SILU) u = __shfl(v, ((idx + HR * NB) % NA) << SH);   // the up row's total (read by the gate row's lane)
+    if ((lane & ((1 << SH) - 1)) != 0) return;
+    if (MODE == GEMV_SILU) {
+        if (r < HR) ((T*)a.y[0])[(int64_t)b * a.R[0] + out_row + r] = from_f32<T>(v / (1.0f + __expf(-v)) * u);
+    } else if (MODE == GEMV_RESID) {
+        T* y = (T*)a.y[which] + (int64_t)b * a.R[which] + out_row + r;
+        *y = from_f32<T>(to_f32(*y) + v);
+    } else if (MODE == GEMV_F32) {
+        ((float*)a.y[which])[(int64_t)b * a.R[which] + out_row + r] = v;
+    } else {
+        ((T*)a.y[which])[(int64_t)b * a.R[which] + out_row + r] = from_f32<T>(v);
+    }
+}
+
+template <typename T, int NB, int RW>
+static hipError_t launch_gemv_nb_tr(const GemvArgs& a, hipStream_t s) {
+    const int64_t rows = (int64_t)a.R[0] + a.R[1] + a.R[2];
+    const dim3 b(256);
+    const dim3 g((unsigned)(a.mode == GEMV_SILU ? a.R[0] / (4 * (RW / 2)) : rows / (4 * RW)));
+    switch (a.mode) {
+        case GEMV_STORE: gemv_nb_kernel<T, GEMV_STORE, NB, RW><<<g, b, 0, s>>>(a); break;
+        case GEMV_SILU: gemv_nb_kernel<T, GEMV_SILU, NB, RW><<<g, b, 0, s>>>(a); break;
+        case GEMV_RESID: gemv_nb_kernel<T, GEMV_RESID, NB, RW><<<g, b, 0, s>>>(a); break;
+        case GEMV_F32: gemv_nb_kernel<T, GEMV_F32, NB, RW><<<g, b, 0, s>>>(a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// rows per wavefront: 4 when every matrix has a multiple of 16 rows (8 outputs for the SiLU variant), else 2 (multiples
+// of 8 / 4); row counts that divide neither are refused (the callers' shapes are multiples of 16)
+template <typename T, int NB>
+static hipError_t launch_gemv_nb_t(const GemvArgs& a, hipStream_t s) {
+    const int64_t rows = (int64_t)a.R[0] + a.R[1] + a.R[2];
+    if (rows == 0) return hipSuccess;
+    auto divides = [&](int unit) { return a.R[0] % unit == 0 && a.R[1] % unit == 0 && a.R[2] % unit == 0; };
+    const bool silu = a.mode == GEMV_SILU;
+    if (divides(silu ? 8 : 16)) return launch_gemv_nb_tr<T, NB, 4>(a, s);
+    if (divides(silu ? 4 : 8)) return launch_gemv_nb_tr<T, NB, 2>(a, s);
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------- the same on the matrix cores (bf16)
+// Y[b, r] = W[r, :] . X[b, :] for up to 16 input vectors with v_mfma_f32_16x16x32_bf16: a weight row is an MFMA
+// operand row, so a lane's 16-byte weight load IS its fragment (row = lane % 16, 8 consecutive k of group lane / 16)
+// and an input vector is an operand column (lanes >= nb feed zeros).  No dot instructions, no lane reductions: the
+// vector ALU only moves the 4 results per lane.  A workgroup of 8 wavefronts owns a strip of 16 rows (a gate strip
+// and the same up strip for the SiLU variant) and splits K eight ways; the eight partial 16x16 tiles meet in LDS.
+// Needs K % 256 == 0 and row counts that are multiples of 16.
+typedef __bf16 mfma_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float mfma_f32x4 __attribute__((ext_vector_type(4)));
+
+template <int MODE>
+__global__ void __launch_bounds__(512) gemv_mfma_kernel(GemvArgs a, int nb) {
+    constexpr int NS = MODE == GEMV_SILU ? 2 : 1;          // strips per workgroup (gate, up)
+    __shared__ float sred[8][NS][16][17];                  // [wavefront][strip][row][token], padded
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, kg = lane >> 4;
+    int64_t row0 = (int64_t)blockIdx.x * 16;
+    int which = 0;
+    const bf16_t* wbase[NS];
+    if (MODE == GEMV_SILU) {
+        wbase[0] = (const bf16_t*)a.W[0] + (row0 + l16) * a.K;
+        wbase[NS - 1] = (const bf16_t*)a.W[1] + (row0 + l16) * a.K;
+    } else {
+        if (row0 >= a.R[0]) { row0 -= a.R[0]; which = 1; if (row0 >= a.R[1]) { row0 -= a.R[1]; which = 2; } }
+        wbase[0] = (const bf16_t*)a.W[which] + (row0 + l16) * a.K;
+    }
+    // 32-wide k-steps of this wavefront: a contiguous eighth of the row (interleaving the wavefronts' steps so that
+    // they read neighbouring 64-byte pieces at the same time measured 10 % slower)
+    const int ksteps = a.K / 256;
+    const int64_t k0 = (int64_t)wave * ksteps * 32 + kg * 8;
+    const bool tok = l16 < nb;
+    const bf16_t* xrow = (const bf16_t*)a.x + (int64_t)(tok ? l16 : 0) * a.K + k0;
+    mfma_f32x4 acc[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) acc[s] = mfma_f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr int U = 4;                                    // k-steps whose loads are issued together
+    int ks = 0;
+    for (; ks + U <= ksteps; ks += U) {
+        u32x4 wv[U][NS], xv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                wv[u][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wbase[s] + k0 + (int64_t)(ks + u) * 32));
+            xv[u] = *reinterpret_cast<const u32x4*>(xrow + (int64_t)(ks + u) * 32);
+            if (!tok) xv[u] = u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(mfma_bf16x8, wv[u][s]),
+                                                                 __builtin_bit_cast(mfma_bf16x8, xv[u]), acc[s], 0, 0, 0);
+    }
+    for (; ks < ksteps; ++ks) {
+        u32x4 xv = *reinterpret_cast<const u32x4*>(xrow + (int64_t)ks * 32);
+        if (!tok) xv = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const u32x4 wv = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wbase[s] + k0 + (int64_t)ks * 32));
+            acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(mfma_bf16x8, wv), __builtin_bit_cast(mfma_bf16x8, xv),
+                                                             acc[s], 0, 0, 0);
+        }
+    }
+    // lane (token l16, row group kg) holds rows 4*kg .. 4*kg+3 of its tile
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sred[wave][s][4 * kg + r][l16] = acc[s][r];
+    __syncthreads();
+    const int t = threadIdx.x;
+    if (t >= 256) return;
+    const int r = t >> 4, b = t & 15;
+    if (b >= nb) return;
+    float v = 0.f, u = 0.f;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) { v += sred[w][0][r][b]; if (NS == 2) u += sred[w][NS - 1][r][b]; }
+    if (MODE == GEMV_SILU) {
+        ((bf16_t*)a.y[0])[(int64_t)b * a.R[0] + row0 + r] = f32_to_bf16(v / (1.0f + __expf(-v)) * u);
+    } else if (MODE == GEMV_RESID) {
+        bf16_t* y = (bf16_t*)a.y[which] + (int64_t)b * a.R[which] + row0 + r;
+        *y = f32_to_bf16(bf16_to_f32(*y) + v);
+    } else if (MODE == GEMV_F32) {
+        ((float*)a.y[which])[(int64_t)b * a.R[which] + row0 + r] = v;
+    } else {
+        ((bf16_t*)a.y[which])[(int64_t)b * a.R[which] + row0 + r] = f32_to_bf16(v);
+    }
+}
+
+bool gemv_mfma_supported(const GemvArgs& a, int nb) {
+    if (nb < 1 || nb > 16 || a.gamma || a.K <= 0 || a.K % 256 != 0) return false;
+    if (a.mode != GEMV_STORE && a.mode != GEMV_SILU && a.mode != GEMV_RESID && a.mode != GEMV_F32) return false;
+    for (int i = 0; i < 3; ++i)
+        if (a.R[i] < 0 || a.R[i] % 16 != 0) return false;
+    return true;
+}
+
+hipError_t launch_gemv_mfma(const GemvArgs& a, int nb, hipStream_t s) {
+    const int64_t rows = a.mode == GEMV_SILU ? (int64_t)a.R[0] : (int64_t)a.R[0] + a.R[1] + a.R[2];
+    if (rows == 0) return hipSuccess;
+    const dim3 g((unsigned)(rows / 16)), b(512);
+    switch (a.mode) {
+        case GEMV_STORE: gemv_mfma_kernel<GEMV_STORE><<<g, b, 0, s>>>(a, nb); break;
+        case GEMV_SILU: gemv_mfma_kernel<GEMV_SILU><<<g, b, 0, s>>>(a, nb); break;
+        case GEMV_RESID: gemv_mfma_kernel<GEMV_RESID><<<g, b, 0, s>>>(a, nb); break;
+        case GEMV_F32: gemv_mfma_kernel<GEMV_F32><<<g, b, 0, s>>>(a, nb); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// nb input vectors (1 <= nb <= 16).  bf16 with tile-friendly shapes runs on the matrix cores; otherwise the
+// dot-product kernel, instantiated for 2, 4 and 8 vectors: other counts run as a sum of those (rows of X and Y are
+// contiguous, so a group of vectors is the same call on shifted pointers)
+hipError_t launch_gemv_nb(const GemvArgs& a, int nb, bool bf16, hipStream_t s) {
+    if (nb < 1 || nb > DECODE_MAX_BATCH || a.gamma || a.mode == GEMV_QKV_ROPE) return hipErrorInvalidValue;
+    if (bf16 && nb > 1 && gemv_mfma_supported(a, nb)) return launch_gemv_mfma(a, nb, s);
+    const size_t eb = bf16 ? 2 : 4;
+    int done = 0;
+    while (done < nb) {
+        const int left = nb - done;
+        const int take = left >= 8 ? 8 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
+        GemvArgs g = a;
+        g.x = (const char*)a.x + (size_t)done * a.K * eb;
+        for (int i = 0; i < 3; ++i)
+            if (a.y[i]) g.y[i] = (char*)a.y[i] + (size_t)done * a.R[i] * (a.mode == GEMV_F32 ? 4 : eb);
+        hipError_t e;
+        if (take == 1) e = launch_gemv(g, bf16, s);
+        else if (bf16) e = take == 8 ? launch_gemv_nb_t<bf16_t, 8>(g, s) : take == 4 ? launch_gemv_nb_t<bf16_t, 4>(g, s) : launch_gemv_nb_t<bf16_t, 2>(g, s);
+        else e = take == 8 ? launch_gemv_nb_t<float, 8>(g, s) : take == 4 ? launch_gemv_nb_t<float, 4>(g, s) : launch_gemv_nb_t<float, 2>(g, s);
+        if (e != hipSuccess) return e;
+        done += take;
+    }
+    return hipSuccess;
+}
+
 // ------------------------------------------------------------------- rotary table of one position
 __global__ void decode_rope_row_kernel(int pos, int half, double neg2_over_d_log2base, float2* __restrict__ table) {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -285,15 +534,62 @@ hipError_t launch_decode_rope_append(void* q, const void* k, const void* v, int 
     return hipGetLastError();
 }
 
+// the same for a batch of sequences (blockIdx.y = sequence): q [B, H, d], k / v [B, Hkv, d]; every sequence has its
+// own cache, row and position (by-value descriptor: at most DECODE_MAX_BATCH sequences)
+template <typename T>
+__global__ void decode_rope_append_batched_kernel(T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
+                                                  int H, int Hkv, int d, double neg2_over_d_log2base, DecodeBatch db) {
+    const int half = d / 2;
+    const int b = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int pos = db.pos[b];
+    const int64_t row = db.count[b];
+    if (i == 0) db.cache_pos[b][row] = pos;
+    if (i >= (H + Hkv) * half) return;
+    const int head = i / half, j = i % half;
+    double sn, cs;
+    sincos((double)pos * exp2((double)j * neg2_over_d_log2base), &sn, &cs);
+    const float c = (float)cs, s = (float)sn;
+    if (head < H) {
+        T* p = q + ((int64_t)b * H + head) * d + j;
+        const float x0 = to_f32(p[0]), x1 = to_f32(p[half]);
+        p[0] = from_f32<T>(x0 * c - x1 * s);
+        p[half] = from_f32<T>(x1 * c + x0 * s);
+    } else {
+        const int g = head - H;
+        const T* p = k + ((int64_t)b * Hkv + g) * d + j;
+        const float x0 = to_f32(p[0]), x1 = to_f32(p[half]);
+        T* o = (T*)db.cache_k[b] + (row * Hkv + g) * (int64_t)d + j;
+        o[0] = from_f32<T>(x0 * c - x1 * s);
+        o[half] = from_f32<T>(x1 * c + x0 * s);
+        T* ov = (T*)db.cache_v[b] + (row * Hkv + g) * (int64_t)d + j;
+        const T* pv = v + ((int64_t)b * Hkv + g) * d + j;
+        ov[0] = pv[0];
+        ov[half] = pv[half];
+    }
+}
+
+hipError_t launch_decode_rope_append_batched(void* q, const void* k, const void* v, int H, int Hkv, int d, float base,
+                                             const DecodeBatch& db, bool bf16, hipStream_t s) {
+    if (db.n < 1 || db.n > DECODE_MAX_BATCH) return hipErrorInvalidValue;
+    const int n = (H + Hkv) * (d / 2);
+    const double kk = -2.0 / (double)d * log2((double)base);
+    const dim3 g((unsigned)((n + 255) / 256), (unsigned)db.n), b(256);
+    if (bf16)
+        decode_rope_append_batched_kernel<bf16_t><<<g, b, 0, s>>>((bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, H, Hkv, d, kk, db);
+    else
+        decode_rope_append_batched_kernel<float><<<g, b, 0, s>>>((float*)q, (const float*)k, (const float*)v, H, Hkv, d, kk, db);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------- decode attention
 // partial layout: part[((g * nsplit + split) * GRP_MAX + hg) * (d + 2)] = (max, sum, weighted values[d])
 constexpr int GRP_MAX = 8;
 
 // G: query heads per KV head the register arrays are sized for (>= H / Hkv)
 template <typename T, int D, int G>
-__global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ q, const T* __restrict__ K,
-                                                          const T* __restrict__ V, int64_t M, int H, int Hkv, float scale_log2e,
-                                                          float* __restrict__ part) {
+__device__ __forceinline__ void decode_attn_body(const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V,
+                                                 int64_t M, int H, int Hkv, float scale_log2e, float* __restrict__ part) {
     constexpr int EPC = 16 / (int)sizeof(T);
     constexpr int LPK = D / EPC;          // lanes that hold one key row
     constexpr int KPW = 64 / LPK;         // keys per wavefront step
@@ -412,17 +708,35 @@ __global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ 
     }
 }
 
+template <typename T, int D, int G>
+__global__ void __launch_bounds__(256) decode_attn_kernel(const T* __restrict__ q, const T* __restrict__ K,
+                                                          const T* __restrict__ V, int64_t M, int H, int Hkv, float scale_log2e,
+                                                          float* __restrict__ part) {
+    decode_attn_body<T, D, G>(q, K, V, M, H, Hkv, scale_log2e, part);
+}
+// blockIdx.z = sequence: its query [H, D], its cache (count[b] + 1 pairs: the new pair is already appended) and its
+// share of the partial buffer
+template <typename T, int D, int G>
+__global__ void __launch_bounds__(256) decode_attn_batched_kernel(const T* __restrict__ q, DecodeBatch db, int H, int Hkv,
+                                                                  float scale_log2e, float* __restrict__ part, int64_t part_stride) {
+    const int b = blockIdx.z;
+    decode_attn_body<T, D, G>(q + (int64_t)b * H * D, (const T*)db.cache_k[b], (const T*)db.cache_v[b], db.count[b] + 1, H, Hkv,
+                              scale_log2e, part + (int64_t)b * part_stride);
+}
+
 // out[h, e] = sum over splits of the weighted values / sum of sums.  One workgroup of 1024 threads per
 // query head: thread s < 256 takes split s for the (max, sum) part; the weighted values are summed by
 // 1024 / D thread groups that each walk a strided subset of the splits with independent loads.
 template <typename T>
 __global__ void __launch_bounds__(1024) decode_attn_merge_kernel(const float* __restrict__ part, int nsplit, int H, int Hkv, int D,
-                                                                 T* __restrict__ out) {
+                                                                 T* __restrict__ out, int64_t part_stride) {
     __shared__ float sa[256];
     __shared__ float sw[16], sl[16];
     __shared__ float so[1024];
     const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = H / Hkv, g = h / grp, hg = h % grp;
+    part += (int64_t)blockIdx.y * part_stride;      // blockIdx.y = sequence of a batched step
+    out += (int64_t)blockIdx.y * H * D;
     const float* base = part + ((int64_t)g * nsplit * GRP_MAX + hg) * (D + 2);
     const int64_t stride = (int64_t)GRP_MAX * (D + 2);
     const float m = tid < nsplit ? base[tid * stride] : -INFINITY;       // nsplit <= 256: wavefronts 0-3
@@ -497,7 +811,7 @@ static hipError_t launch_decode_attn_t(const T* q, const T* K, const T* V, int64
 #undef SPTS_DEC_ATTN
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_attn_merge_kernel<T><<<dim3((unsigned)H), dim3(1024), 0, s>>>(part, nsplit, H, Hkv, d, out);
+    decode_attn_merge_kernel<T><<<dim3((unsigned)H), dim3(1024), 0, s>>>(part, nsplit, H, Hkv, d, out, 0);
     return hipGetLastError();
 }
 
@@ -508,6 +822,44 @@ hipError_t launch_decode_attn(const void* q, const void* K, const void* V, int64
         return launch_decode_attn_t<bf16_t>((const bf16_t*)q, (const bf16_t*)K, (const bf16_t*)V, M, H, Hkv, d, part, part_floats,
                                             (bf16_t*)out, s);
     return launch_decode_attn_t<float>((const float*)q, (const float*)K, (const float*)V, M, H, Hkv, d, part, part_floats, (float*)out, s);
+}
+
+// the same for a batch of sequences in one launch (grid z = sequence); every sequence takes the same number of
+// splits, chosen for the longest cache; out [B, H, d]
+template <typename T>
+static hipError_t launch_decode_attn_batched_t(const T* q, const DecodeBatch& db, int H, int Hkv, int d, float* part,
+                                               size_t part_floats, T* out, hipStream_t s) {
+    int64_t mmax = 1;
+    for (int b = 0; b < db.n; ++b) mmax = db.count[b] + 1 > mmax ? db.count[b] + 1 : mmax;
+    const int nsplit = decode_attn_splits(mmax, Hkv, d, part_floats / (size_t)db.n);
+    const int64_t stride = (int64_t)Hkv * nsplit * GRP_MAX * (d + 2);
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
+    const dim3 g((unsigned)nsplit, (unsigned)Hkv, (unsigned)db.n), b(256);
+    const int grp = H / Hkv;
+#define SPTS_DEC_ATTN_B(D_)                                                                                                 \
+    if (grp <= 1) decode_attn_batched_kernel<T, D_, 1><<<g, b, 0, s>>>(q, db, H, Hkv, scale_log2e, part, stride);           \
+    else if (grp <= 2) decode_attn_batched_kernel<T, D_, 2><<<g, b, 0, s>>>(q, db, H, Hkv, scale_log2e, part, stride);      \
+    else if (grp <= 4) decode_attn_batched_kernel<T, D_, 4><<<g, b, 0, s>>>(q, db, H, Hkv, scale_log2e, part, stride);      \
+    else decode_attn_batched_kernel<T, D_, GRP_MAX><<<g, b, 0, s>>>(q, db, H, Hkv, scale_log2e, part, stride);
+    switch (d) {
+        case 128: SPTS_DEC_ATTN_B(128) break;
+        case 64: SPTS_DEC_ATTN_B(64) break;
+        case 32: SPTS_DEC_ATTN_B(32) break;
+        case 16: SPTS_DEC_ATTN_B(16) break;
+        default: return hipErrorInvalidValue;
+    }
+#undef SPTS_DEC_ATTN_B
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    decode_attn_merge_kernel<T><<<dim3((unsigned)H, (unsigned)db.n), dim3(1024), 0, s>>>(part, nsplit, H, Hkv, d, out, stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_attn_batched(const void* q, const DecodeBatch& db, int H, int Hkv, int d, float* part, size_t part_floats,
+                                      void* out, bool bf16, hipStream_t s) {
+    if (db.n < 1 || db.n > DECODE_MAX_BATCH || part_floats / (size_t)db.n < decode_attn_min_scratch_floats(Hkv, d)) return hipErrorInvalidValue;
+    if (bf16) return launch_decode_attn_batched_t<bf16_t>((const bf16_t*)q, db, H, Hkv, d, part, part_floats, (bf16_t*)out, s);
+    return launch_decode_attn_batched_t<float>((const float*)q, db, H, Hkv, d, part, part_floats, (float*)out, s);
 }
 
 // ------------------------------------------------------------------------------ greedy head

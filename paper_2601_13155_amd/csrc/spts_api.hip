@@ -522,6 +522,90 @@ int spts_greedy_token(spts_ctx* c, const void* x, const void* gamma_f, const voi
     return SPTS_OK;
 }
 
+int spts_decode_layer_batched(spts_ctx* c, void* x, const int32_t* pos, int32_t batch, const spts_layer_weights* w,
+                              spts_kv_out* caches) {
+    if (!c || batch < 0 || batch > SPTS_MAX_DECODE_BATCH) return SPTS_EINVAL;
+    if (batch == 0) return SPTS_OK;
+    if (!x || !pos || !w || !caches) return SPTS_EINVAL;
+    if (!w->Wq || !w->Wk || !w->Wv || !w->Wo || !w->gamma1 || !w->Wgate || !w->Wup || !w->Wdown || !w->gamma2) return SPTS_EINVAL;
+    if (!aligned16(x) || !aligned16(w->gamma1) || !aligned16(w->gamma2)) return SPTS_EALIGN;
+    if (batch > c->lim.max_tokens) return SPTS_EWORKSPACE;
+    DecodeBatch db{};
+    db.n = batch;
+    for (int b = 0; b < batch; ++b) {
+        const spts_kv_out& kc = caches[b];
+        if (pos[b] < 0 || kc.count < 0 || kc.count >= kc.capacity || !kc.k || !kc.v || !kc.pos) return SPTS_EINVAL;
+        if (!aligned16(kc.k) || !aligned16(kc.v) || !aligned16(kc.pos)) return SPTS_EALIGN;
+        for (int o = 0; o < b; ++o)
+            if (caches[o].k == kc.k) return SPTS_EINVAL;   // one cache per sequence
+        db.cache_k[b] = kc.k; db.cache_v[b] = kc.v; db.cache_pos[b] = kc.pos; db.count[b] = kc.count; db.pos[b] = pos[b];
+    }
+    const auto& m = c->m;
+    const int QD = m.H * m.d, KV = m.Hkv * m.d;
+    void* xn = c->p<void>(c->off.xn);
+    void* q = c->p<void>(c->off.q);
+    void* kx = c->p<void>(c->off.khat);
+    void* vx = c->p<void>(c->off.vhat);
+    void* att = c->p<void>(c->off.att);
+    void* hbuf = c->p<void>(c->off.big);
+    float* part = c->p<float>(c->off.tmp32);
+    const size_t part_floats = (c->off.qp - c->off.tmp32) / sizeof(float);
+    GemvArgs qkv{}; qkv.mode = GEMV_STORE; qkv.x = xn; qkv.K = m.D;
+    qkv.W[0] = w->Wq; qkv.W[1] = w->Wk; qkv.W[2] = w->Wv; qkv.R[0] = QD; qkv.R[1] = KV; qkv.R[2] = KV;
+    qkv.y[0] = q; qkv.y[1] = kx; qkv.y[2] = vx;
+    GemvArgs o{}; o.mode = GEMV_RESID; o.x = att; o.K = QD; o.W[0] = w->Wo; o.R[0] = m.D; o.y[0] = x;
+    GemvArgs gu{}; gu.mode = GEMV_SILU; gu.x = xn; gu.K = m.D; gu.W[0] = w->Wgate; gu.W[1] = w->Wup; gu.R[0] = m.Dff; gu.y[0] = hbuf;
+    GemvArgs dn{}; dn.mode = GEMV_RESID; dn.x = hbuf; dn.K = m.Dff; dn.W[0] = w->Wdown; dn.R[0] = m.D; dn.y[0] = x;
+    if (!gemv_supported(qkv, c->bf16) || !gemv_supported(o, c->bf16) || !gemv_supported(dn, c->bf16)) return SPTS_ESHAPE;
+    {
+        GemvArgs chk = gu; chk.R[1] = m.Dff;
+        if (!gemv_supported(chk, c->bf16)) return SPTS_ESHAPE;
+    }
+    if (!decode_attn_supported(m.H, m.Hkv, m.d, c->bf16)) return SPTS_ESHAPE;
+    if (part_floats / (size_t)batch < decode_attn_min_scratch_floats(m.Hkv, m.d)) return SPTS_EWORKSPACE;
+    hipStream_t st = c->stream;
+    c->dec_rope_pos = -1;
+    { PHASE(c, PH_DEC_NORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, xn, batch, m.D, c->bf16, st)); }
+    { PHASE(c, PH_DEC_QKV); SPTS_HIP(c, launch_gemv_nb(qkv, batch, c->bf16, st)); }
+    { PHASE(c, PH_DEC_ROPE_APPEND);
+      SPTS_HIP(c, launch_decode_rope_append_batched(q, kx, vx, m.H, m.Hkv, m.d, m.rope_base, db, c->bf16, st)); }
+    { PHASE(c, PH_DEC_ATTN); SPTS_HIP(c, launch_decode_attn_batched(q, db, m.H, m.Hkv, m.d, part, part_floats, att, c->bf16, st)); }
+    { PHASE(c, PH_DEC_O); SPTS_HIP(c, launch_gemv_nb(o, batch, c->bf16, st)); }
+    { PHASE(c, PH_DEC_NORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, m.rms_eps, xn, batch, m.D, c->bf16, st)); }
+    { PHASE(c, PH_DEC_GATE_UP); SPTS_HIP(c, launch_gemv_nb(gu, batch, c->bf16, st)); }
+    { PHASE(c, PH_DEC_DOWN); SPTS_HIP(c, launch_gemv_nb(dn, batch, c->bf16, st)); }
+    for (int b = 0; b < batch; ++b) caches[b].count += 1;
+    return SPTS_OK;
+}
+
+int spts_greedy_token_batched(spts_ctx* c, const void* x, const void* gamma_f, const void* table, int32_t V, int32_t batch,
+                              int32_t* token_out, float* logits_out, void* x_next) {
+    if (!c || batch < 0 || batch > SPTS_MAX_DECODE_BATCH) return SPTS_EINVAL;
+    if (batch == 0) return SPTS_OK;
+    if (!x || !gamma_f || !table || !token_out || V <= 0) return SPTS_EINVAL;
+    if (!aligned16(x) || !aligned16(gamma_f) || !aligned16(table) || (logits_out && !aligned16(logits_out)) ||
+        (x_next && !aligned16(x_next)))
+        return SPTS_EALIGN;
+    const auto& m = c->m;
+    if (batch > c->lim.max_tokens) return SPTS_EWORKSPACE;
+    float* logits = logits_out;
+    if (!logits) {
+        if ((size_t)V * batch * sizeof(float) > c->off.misc - c->off.big) return SPTS_EWORKSPACE;
+        logits = c->p<float>(c->off.big);
+    }
+    void* xn = c->p<void>(c->off.xn);
+    GemvArgs g{}; g.mode = GEMV_F32; g.x = xn; g.K = m.D; g.W[0] = table; g.R[0] = V; g.y[0] = logits;
+    if (!gemv_supported(g, c->bf16)) return SPTS_ESHAPE;
+    const size_t eb = c->bf16 ? 2 : 4;
+    PHASE(c, PH_DEC_HEAD);
+    SPTS_HIP(c, launch_rmsnorm(x, gamma_f, m.rms_eps, xn, batch, m.D, c->bf16, c->stream));
+    SPTS_HIP(c, launch_gemv_nb(g, batch, c->bf16, c->stream));
+    for (int b = 0; b < batch; ++b)
+        SPTS_HIP(c, launch_argmax_row(logits + (size_t)b * V, V, token_out + b, table, m.D,
+                                      x_next ? (char*)x_next + (size_t)b * m.D * eb : nullptr, c->bf16, c->stream));
+    return SPTS_OK;
+}
+
 int spts_select_topk_segmented(spts_ctx* c, const float* scores, const int64_t* seg_offsets, const int64_t* seg_k,
                                const int64_t* out_offsets, int32_t batch, int64_t max_len, int32_t protect_last,
                                int32_t* idx_out) {

@@ -196,6 +196,22 @@ bool decode_attn_supported(int H, int Hkv, int d, bool bf16);
 size_t decode_attn_min_scratch_floats(int Hkv, int d);
 hipError_t launch_decode_attn(const void* q, const void* K, const void* V, int64_t M, int H, int Hkv, int d, float* part,
                               size_t part_floats, void* out, bool bf16, hipStream_t s);
+// A decode step over a few sequences at once: by-value descriptor of their caches (device pointers), the row
+// each appends to (= its current count) and the new token's position.
+constexpr int DECODE_MAX_BATCH = 16;
+struct DecodeBatch {
+    void* cache_k[DECODE_MAX_BATCH]; void* cache_v[DECODE_MAX_BATCH]; int32_t* cache_pos[DECODE_MAX_BATCH];
+    int64_t count[DECODE_MAX_BATCH]; int32_t pos[DECODE_MAX_BATCH]; int32_t n;
+};
+// Y[b, r] = W[r, :] . X[b, :] for nb <= DECODE_MAX_BATCH input vectors (X [nb, K], Y[i] [nb, R[i]] contiguous); modes STORE, SILU,
+// RESID, F32; no fused norm
+hipError_t launch_gemv_nb(const GemvArgs& a, int nb, bool bf16, hipStream_t s);
+// q [n, H, d] rotated in place, k / v [n, Hkv, d] rotated / copied into row count[b] of sequence b's cache
+hipError_t launch_decode_rope_append_batched(void* q, const void* k, const void* v, int H, int Hkv, int d, float base,
+                                             const DecodeBatch& db, bool bf16, hipStream_t s);
+// out [n, H, d]: attention of sequence b's query over its count[b] + 1 cached pairs
+hipError_t launch_decode_attn_batched(const void* q, const DecodeBatch& db, int H, int Hkv, int d, float* part, size_t part_floats,
+                                      void* out, bool bf16, hipStream_t s);
 // token = argmax(logits [V]) with ties to the lowest id; x_next [D] = table[token, :] (skipped when NULL)
 hipError_t launch_argmax_row(const float* logits, int V, int32_t* token, const void* table, int D, void* x_next, bool bf16,
                              hipStream_t s);

@@ -130,6 +130,34 @@ class DecodeRunner:
             self.x.copy_(self.x_next)
 
 
+class BatchedDecodeRunner:
+    """Decode phase for a batch of sequences: per step one spts_decode_layer_batched per layer over the sequences'
+    caches of that layer (caches[b][l]), then spts_greedy_token_batched.  Only enqueues work."""
+
+    def __init__(self, ctx: binding.Context, shape, layers: List[binding.spts_layer_weights], caches: List[List[KVCache]],
+                 gamma_f, table):
+        torch = _torch()
+        self.ctx, self.shape, self.layers, self.caches = ctx, shape, layers, caches
+        self.gamma_f, self.table = gamma_f, table
+        self.batch = len(caches)
+        tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        self.x = torch.zeros((self.batch, shape.D), dtype=tdt, device="cuda")
+        self.x_next = torch.zeros_like(self.x)
+        self.tokens = torch.zeros(max(self.batch, 4), dtype=torch.int32, device="cuda")
+        self.logits = torch.zeros((self.batch, table.shape[0]), dtype=torch.float32, device="cuda")
+
+    def step(self, pos: List[int]):
+        for l, w in enumerate(self.layers):
+            self.ctx.spts_decode_layer_batched(self.x, pos, w, [seq[l].struct for seq in self.caches])
+
+    def generate(self, pos0: List[int], steps: int):
+        for t in range(steps):
+            self.step([p + t for p in pos0])
+            self.ctx.spts_greedy_token_batched(self.x, self.gamma_f, self.table, int(self.table.shape[0]), self.batch,
+                                               self.tokens, self.logits, self.x_next)
+            self.x.copy_(self.x_next)
+
+
 class StackRunner:
     """Runs Alg. 1's outer loop on the GPU: per layer one spts_layer_prefill, at stage ends one
     spts_msdp_compact.  Buffers are allocated once; run() only enqueues work (no host sync)."""

@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(lib):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     declared = set(re.findall(r"\b(spts_[a-z_0-9]+)\s*\(", text))
     assert {"spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_layer_prefill", "spts_msdp_compact",
-            "spts_decode_layer", "spts_greedy_token", "spts_channel_importance", "spts_select_topk_segmented", "spts_select_topk_batched", "spts_layer_prefill_batched", "spts_msdp_compact_batched"} <= declared
+            "spts_decode_layer", "spts_greedy_token", "spts_channel_importance", "spts_select_topk_segmented", "spts_select_topk_batched", "spts_layer_prefill_batched", "spts_msdp_compact_batched", "spts_decode_layer_batched", "spts_greedy_token_batched"} <= declared
     for name in declared:
         assert hasattr(lib, name), name
     assert declared == set(binding.EXPORTS)

@@ -70,6 +70,66 @@ def test_decode_layer_lockstep(torch, dtype, skip):
         assert H.row_rel_err(v2[-1].reshape(1, -1), ref_c.v[-1].reshape(1, -1)) <= tol
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("nseq", [2, 3, 8, 16])
+def test_decode_layer_batched_lockstep(torch, dtype, nseq):
+    """A batch of sequences with caches of different lengths (one batched token-skipped prefill fills them), then two
+    batched decode steps: every sequence's state and appended pair against the oracle's single-sequence decode from
+    the GPU's own input state and cache contents; then the batched greedy head against the oracle per sequence."""
+    shape = _shape(dtype)
+    mdl = H.oracle_model(shape)
+    rnd = H.rnd_for(dtype)
+    tol = H.TOL[dtype]["hidden"]
+    lens = [300, 45, 170, 64, 511, 33, 96, 257, 40, 129, 77, 18, 200, 31, 64, 99][:nseq]
+    P, r = 8, 16
+    w = synth.make_layer(23, 0, shape, r)
+    dw = runtime.upload_layer(w, shape, r)
+    ctx = ctx_for(shape, 4096)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    xs = np.concatenate([synth.hidden_states(300 + b, n, shape.D, dtype) for b, n in enumerate(lens)])
+    ps = np.concatenate([synth.positions(n) for n in lens])
+    ma = [int(0.4 * n) for n in lens]
+    caches = [runtime.KVCache(shape, m + 2) for m in ma]
+    kvs = [c.struct for c in caches]
+    ctx.spts_layer_prefill_batched(runtime.to_device(xs, dtype), torch.from_numpy(ps).cuda(), offs, dw, P, ma, ma, 1, kvs)
+    torch.cuda.synchronize()
+    assert [k.count for k in kvs] == ma
+    new = synth.hidden_states(24, 2 * nseq, shape.D, dtype).reshape(2, nseq, shape.D)
+    for t in range(2):
+        before = [c.host() for c in caches]
+        xt = runtime.to_device(new[t].copy(), dtype)
+        x_in = runtime.to_host(xt).astype(np.float64)
+        pos_t = [n + t for n in lens]
+        ctx.spts_decode_layer_batched(xt, pos_t, dw, kvs)
+        torch.cuda.synchronize()
+        got = runtime.to_host(xt).astype(np.float64)
+        for b in range(nseq):
+            kh, vh, ph = before[b]
+            ref_x, ref_c = orc.decode_layer(x_in[b], pos_t[b], w, mdl, orc.LayerCache(kh, vh, ph), rnd)
+            assert H.row_rel_err(got[b][None, :], ref_x[None, :]) <= tol, (t, b)
+            k2, v2, p2 = caches[b].host()
+            assert k2.shape[0] == kh.shape[0] + 1 and p2[-1] == pos_t[b]
+            assert np.array_equal(k2[:-1], kh) and np.array_equal(v2[:-1], vh) and np.array_equal(p2[:-1], ph)
+            assert H.row_rel_err(k2[-1].reshape(1, -1), ref_c.k[-1].reshape(1, -1)) <= tol
+            assert H.row_rel_err(v2[-1].reshape(1, -1), ref_c.v[-1].reshape(1, -1)) <= tol
+    # greedy head over the batch
+    V = 1000
+    table = synth.vocab_table(7, V, shape.D, dtype)
+    gamma_f = np.ones(shape.D, dtype=np.float32)
+    td, gd = runtime.to_device(table, dtype), runtime.to_device(gamma_f, dtype)
+    toks = torch.zeros(nseq, dtype=torch.int32, device="cuda")
+    logits = torch.zeros((nseq, V), dtype=torch.float32, device="cuda")
+    xnext = torch.zeros_like(xt)
+    ctx.spts_greedy_token_batched(xt, gd, td, V, nseq, toks, logits, xnext)
+    torch.cuda.synchronize()
+    lg, tk = logits.cpu().numpy(), toks.cpu().numpy()
+    for b in range(nseq):
+        ref_tok, ref_logits = orc.greedy_token(got[b], gamma_f, table, mdl, rnd)
+        assert np.max(np.abs(lg[b] - ref_logits)) <= tol * np.max(np.abs(ref_logits))
+        assert tk[b] == int(np.flatnonzero(lg[b] == lg[b].max())[0])        # argmax of the GPU's logits, lowest id
+        assert torch.equal(xnext[b], td[int(tk[b])])
+
+
 def test_decode_rejects_a_full_cache(torch):
     shape = _shape("f32")
     w = synth.make_layer(21, 0, shape, 16)

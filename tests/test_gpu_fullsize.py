@@ -299,6 +299,44 @@ def test_qwen_paper_schedule_layer_lockstep():
     torch.cuda.empty_cache()
 
 
+def test_decode_batched_8b_shaped_layer():
+    """8B-shaped bf16 layer, five sequences: a batched token-skipped prefill fills the caches, then two batched decode
+    steps on the matrix-core GEMV (K = 4096 and 14336: unrolled and tail k-steps); every sequence against the oracle."""
+    import torch
+    wl = synth.WORKLOADS["c1"]
+    shape = wl.shape
+    w, dw = llama_layer()
+    ctx = ctx_for(32768)
+    lens = [1500, 700, 64, 2048, 333]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    xs = np.concatenate([synth.hidden_states(400 + b, n, shape.D, shape.dtype) for b, n in enumerate(lens)])
+    ps = np.concatenate([synth.positions(n) for n in lens])
+    ma = [int(0.4 * n) for n in lens]
+    caches = [runtime.KVCache(shape, m + 2) for m in ma]
+    kvs = [c.struct for c in caches]
+    ctx.spts_layer_prefill_batched(runtime.to_device(xs, shape.dtype), torch.from_numpy(ps).cuda(), offs, dw, 64, ma, ma, 1, kvs)
+    torch.cuda.synchronize()
+    assert [k.count for k in kvs] == ma
+    mdl = H.oracle_model(shape)
+    new = synth.hidden_states(78, 2 * len(lens), shape.D, shape.dtype).reshape(2, len(lens), shape.D)
+    for t in range(2):
+        before = [c.host() for c in caches]
+        xt = runtime.to_device(new[t].copy(), shape.dtype)
+        x_in = runtime.to_host(xt).astype(np.float64)
+        pos_t = [n + t for n in lens]
+        ctx.spts_decode_layer_batched(xt, pos_t, dw, kvs)
+        torch.cuda.synchronize()
+        got = runtime.to_host(xt).astype(np.float64)
+        for b in range(len(lens)):
+            kh, vh, ph = before[b]
+            ref_x, ref_c = orc.decode_layer(x_in[b], pos_t[b], w, mdl, orc.LayerCache(kh, vh, ph), orc.bf16_round)
+            err = H.row_rel_err(got[b][None, :], ref_x[None, :])
+            assert err <= H.TOL["bf16"]["hidden"], (t, b, err)
+            k2, v2, p2 = caches[b].host()
+            assert p2[-1] == pos_t[b] and k2.shape[0] == kh.shape[0] + 1
+            assert H.row_rel_err(k2[-1].reshape(1, -1), ref_c.k[-1].reshape(1, -1)) <= H.TOL["bf16"]["hidden"]
+
+
 def test_decode_8b_shaped_layer_after_skipped_prefill():
     """8B-shaped bf16 layer: token-skipped prefill of 8192 tokens fills the cache with the 3276 active pairs;
     two new tokens then go through spts_decode_layer, each checked against the oracle from the GPU's own
