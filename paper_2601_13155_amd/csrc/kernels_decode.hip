@@ -336,69 +336,110 @@ static hipError_t launch_gemv_nb_t(const GemvArgs& a, hipStream_t s) {
 
 // ------------------------------------------------------------------- the same on the matrix cores (bf16)
 // Y[b, r] = W[r, :] . X[b, :] for up to 16 input vectors with v_mfma_f32_16x16x32_bf16: a weight row is an MFMA
-// operand row, so a lane's 16-byte weight load IS its fragment (row = lane % 16, 8 consecutive k of group lane / 16)
-// and an input vector is an operand column (lanes >= nb feed zeros).  No dot instructions, no lane reductions: the
-// vector ALU only moves the 4 results per lane.  A workgroup of 8 wavefronts owns a strip of 16 rows (a gate strip
-// and the same up strip for the SiLU variant) and splits K eight ways; the eight partial 16x16 tiles meet in LDS.
-// Needs K % 256 == 0 and row counts that are multiples of 16.
+// operand row (row = lane % 16, 8 consecutive k of group lane / 16) and an input vector is an operand column (lanes
+// >= nb feed zeros).  No dot instructions, no lane reductions: the vector ALU only moves the 4 results per lane.
+//
+// The operand layout gives a row only 4 lanes, i.e. 64 bytes per load instruction, and weight streams read as
+// half cache lines by two different instructions run at ~60 % of the rate of whole-line reads (measured: 4.1 against
+// 6.4 TB/s on the 14336 x 4096 gate/up pair).  So the weights (and the input vectors, same shape: 16 rows with row
+// stride K) go through LDS with direct-to-LDS loads whose lanes are laid out for memory, not for the matrix core:
+// one instruction = 8 rows x one whole 128-byte line, two instructions = a 16-row strip x 64 k.  Fragments are then
+// 16-byte LDS reads; the 16-byte chunk c of row r sits at slot c ^ (r >> 1) (the permutation is applied to the
+// global addresses, since the hardware places lane l's 16 bytes at 16 * l), which spreads the 16 rows a fragment
+// read touches over all banks.
+//
+// A workgroup of 4 wavefronts owns a strip of 16 rows (a gate strip and the same up strip for the SiLU variant)
+// and splits K four ways (8 wavefronts with deeper or shallower rings measured the same or slower); every wavefront runs its own ring of DEPTH stages of 64 k (no workgroup barrier in the
+// loop: a wavefront reads only what it loaded itself, after its own vmcnt wait).  The partial 16x16 tiles meet
+// in LDS.  Needs K % 256 == 0 and row counts that are multiples of 16.
 typedef __bf16 mfma_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float mfma_f32x4 __attribute__((ext_vector_type(4)));
 
-template <int MODE>
-__global__ void __launch_bounds__(512) gemv_mfma_kernel(GemvArgs a, int nb) {
-    constexpr int NS = MODE == GEMV_SILU ? 2 : 1;          // strips per workgroup (gate, up)
-    __shared__ float sred[8][NS][16][17];                  // [wavefront][strip][row][token], padded
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+constexpr int GEMV_MFMA_WAVES = 4;
+
+template <int MODE, int XI>
+__global__ void __launch_bounds__(GEMV_MFMA_WAVES * 64) gemv_mfma_kernel(GemvArgs a, int nb) {
+    constexpr int NW = GEMV_MFMA_WAVES;
+    constexpr int NS = MODE == GEMV_SILU ? 2 : 1;          // weight strips per workgroup (gate, up)
+    constexpr int DEPTH = NS == 2 ? 3 : 4;                 // ring stages per wavefront (64 / 72 KB: two workgroups per CU)
+    constexpr int NI = NS * 2 + XI;                        // direct-to-LDS loads per stage
+    constexpr uint32_t STRIP_B = 2048, STAGE_B = (NS + 1) * STRIP_B, WAVE_B = DEPTH * STAGE_B;
+    static_assert((DEPTH - 1) * NI <= 63, "vmcnt field");
+    static_assert(NW * 64 >= 256 && (size_t)NW * WAVE_B >= (size_t)NW * NS * 16 * 17 * 4, "the partial tiles reuse the ring");
+    extern __shared__ __attribute__((aligned(16))) char gsm[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, kg = lane >> 4;
     int64_t row0 = (int64_t)blockIdx.x * 16;
     int which = 0;
-    const bf16_t* wbase[NS];
+    const int nstage = a.K / (NW * 64);
+    const int64_t kw = (int64_t)wave * nstage * 64;         // first k of this wavefront's contiguous share
+    const char* wb[NS];
     if (MODE == GEMV_SILU) {
-        wbase[0] = (const bf16_t*)a.W[0] + (row0 + l16) * a.K;
-        wbase[NS - 1] = (const bf16_t*)a.W[1] + (row0 + l16) * a.K;
+        wb[0] = (const char*)((const bf16_t*)a.W[0] + row0 * a.K + kw);
+        wb[NS - 1] = (const char*)((const bf16_t*)a.W[1] + row0 * a.K + kw);
     } else {
         if (row0 >= a.R[0]) { row0 -= a.R[0]; which = 1; if (row0 >= a.R[1]) { row0 -= a.R[1]; which = 2; } }
-        wbase[0] = (const bf16_t*)a.W[which] + (row0 + l16) * a.K;
+        wb[0] = (const char*)((const bf16_t*)a.W[which] + row0 * a.K + kw);
     }
-    // 32-wide k-steps of this wavefront: a contiguous eighth of the row (interleaving the wavefronts' steps so that
-    // they read neighbouring 64-byte pieces at the same time measured 10 % slower)
-    const int ksteps = a.K / 256;
-    const int64_t k0 = (int64_t)wave * ksteps * 32 + kg * 8;
+    const char* xb = (const char*)((const bf16_t*)a.x + kw);
+    // load lanes: instruction j covers strip rows 8j .. 8j+7, lane -> (row 8j + lane / 8, slot lane % 8)
+    uint32_t voff_w[2], voff_x[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int r = 8 * j + (lane >> 3), chunk = (lane & 7) ^ (r >> 1);
+        const int xr = r < nb ? r : nb - 1;                 // rows beyond the batch: any valid row (their lanes feed zeros)
+        voff_w[j] = (uint32_t)(((int64_t)r * a.K + chunk * 8) * 2);
+        voff_x[j] = (uint32_t)(((int64_t)xr * a.K + chunk * 8) * 2);
+    }
+    const uint32_t ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)gsm + (uint32_t)wave * WAVE_B;
+    auto issue = [&](int st) {                              // stage st -> ring slot st % DEPTH
+        const uint32_t slot = ring + (uint32_t)(st % DEPTH) * STAGE_B;
+        const int64_t koff = (int64_t)st * 128;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) dma16s(voff_w[j], wb[s] + koff, slot + s * STRIP_B + j * 1024);
+#pragma unroll
+        for (int j = 0; j < XI; ++j) dma16s(voff_x[j], xb + koff, slot + NS * STRIP_B + j * 1024);
+    };
+    const int npre = nstage < DEPTH ? nstage : DEPTH;
+    for (int st = 0; st < npre; ++st) issue(st);
+    // fragment reads: lane (row l16, k group kg), half h of the stage -> chunk 4h + kg of its row
+    const char* myring = gsm + (size_t)wave * WAVE_B;
+    uint32_t foff[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) foff[h] = (uint32_t)(l16 * 128 + (((4 * h + kg) ^ (l16 >> 1)) * 16));
     const bool tok = l16 < nb;
-    const bf16_t* xrow = (const bf16_t*)a.x + (int64_t)(tok ? l16 : 0) * a.K + k0;
     mfma_f32x4 acc[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) acc[s] = mfma_f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr int U = 4;                                    // k-steps whose loads are issued together
-    int ks = 0;
-    for (; ks + U <= ksteps; ks += U) {
-        u32x4 wv[U][NS], xv[U];
+    for (int st = 0; st < nstage; ++st) {
+        // stages issued so far: min(nstage, st + DEPTH); all but the DEPTH - 1 youngest must have landed
+        if (st + DEPTH <= nstage) SPTS_WAIT_VMCNT((DEPTH - 1) * NI); else SPTS_WAIT_VMCNT(0);
+        asm volatile("" ::: "memory");
+        const char* slot = myring + (size_t)(st % DEPTH) * STAGE_B;
+        u32x4 wv[NS][2], xv[2];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) wv[s][h] = *reinterpret_cast<const u32x4*>(slot + s * STRIP_B + foff[h]);
+            xv[h] = *reinterpret_cast<const u32x4*>(slot + NS * STRIP_B + foff[h]);
+            if (!tok) xv[h] = u32x4{0u, 0u, 0u, 0u};
+        }
+        // the slot is refilled only after its fragments have arrived in registers
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (st + DEPTH < nstage) issue(st + DEPTH);
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int s = 0; s < NS; ++s)
-                wv[u][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wbase[s] + k0 + (int64_t)(ks + u) * 32));
-            xv[u] = *reinterpret_cast<const u32x4*>(xrow + (int64_t)(ks + u) * 32);
-            if (!tok) xv[u] = u32x4{0u, 0u, 0u, 0u};
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int s = 0; s < NS; ++s)
-                acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(mfma_bf16x8, wv[u][s]),
-                                                                 __builtin_bit_cast(mfma_bf16x8, xv[u]), acc[s], 0, 0, 0);
+                acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(mfma_bf16x8, wv[s][h]),
+                                                                 __builtin_bit_cast(mfma_bf16x8, xv[h]), acc[s], 0, 0, 0);
     }
-    for (; ks < ksteps; ++ks) {
-        u32x4 xv = *reinterpret_cast<const u32x4*>(xrow + (int64_t)ks * 32);
-        if (!tok) xv = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const u32x4 wv = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wbase[s] + k0 + (int64_t)ks * 32));
-            acc[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(mfma_bf16x8, wv), __builtin_bit_cast(mfma_bf16x8, xv),
-                                                             acc[s], 0, 0, 0);
-        }
-    }
-    // lane (token l16, row group kg) holds rows 4*kg .. 4*kg+3 of its tile
+    // every wavefront is done with its ring (nothing in flight: the last stage waited for vmcnt 0); the partial
+    // tiles take its place.  Lane (token l16, row group kg) holds rows 4*kg .. 4*kg+3 of its tile.
+    __syncthreads();
+    float (*sred)[NS][16][17] = reinterpret_cast<float (*)[NS][16][17]>(gsm);
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
@@ -410,7 +451,7 @@ __global__ void __launch_bounds__(512) gemv_mfma_kernel(GemvArgs a, int nb) {
     if (b >= nb) return;
     float v = 0.f, u = 0.f;
 #pragma unroll
-    for (int w = 0; w < 8; ++w) { v += sred[w][0][r][b]; if (NS == 2) u += sred[w][NS - 1][r][b]; }
+    for (int w = 0; w < NW; ++w) { v += sred[w][0][r][b]; if (NS == 2) u += sred[w][NS - 1][r][b]; }
     if (MODE == GEMV_SILU) {
         ((bf16_t*)a.y[0])[(int64_t)b * a.R[0] + row0 + r] = f32_to_bf16(v / (1.0f + __expf(-v)) * u);
     } else if (MODE == GEMV_RESID) {
@@ -428,21 +469,42 @@ bool gemv_mfma_supported(const GemvArgs& a, int nb) {
     if (a.mode != GEMV_STORE && a.mode != GEMV_SILU && a.mode != GEMV_RESID && a.mode != GEMV_F32) return false;
     for (int i = 0; i < 3; ++i)
         if (a.R[i] < 0 || a.R[i] % 16 != 0) return false;
+    // per-lane byte offsets are 32-bit: 16 rows of K elements
+    if ((int64_t)16 * a.K * 2 >= ((int64_t)1 << 32)) return false;
     return true;
 }
 
-hipError_t launch_gemv_mfma(const GemvArgs& a, int nb, hipStream_t s) {
-    const int64_t rows = a.mode == GEMV_SILU ? (int64_t)a.R[0] : (int64_t)a.R[0] + a.R[1] + a.R[2];
+template <int MODE, int XI>
+static hipError_t launch_gemv_mfma_t(const GemvArgs& a, int nb, unsigned grid, hipStream_t s) {
+    constexpr int NS = MODE == GEMV_SILU ? 2 : 1, DEPTH = NS == 2 ? 3 : 4, NW = GEMV_MFMA_WAVES;
+    const size_t lds = (size_t)NW * DEPTH * (NS + 1) * 2048;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<MODE, XI>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    gemv_mfma_kernel<MODE, XI><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nb);
+    return hipGetLastError();
+}
+
+template <int MODE>
+static hipError_t launch_gemv_mfma_m(const GemvArgs& a, int nb, hipStream_t s) {
+    const int64_t rows = MODE == GEMV_SILU ? (int64_t)a.R[0] : (int64_t)a.R[0] + a.R[1] + a.R[2];
     if (rows == 0) return hipSuccess;
-    const dim3 g((unsigned)(rows / 16)), b(512);
+    const unsigned grid = (unsigned)(rows / 16);
+    return nb > 8 ? launch_gemv_mfma_t<MODE, 2>(a, nb, grid, s) : launch_gemv_mfma_t<MODE, 1>(a, nb, grid, s);
+}
+
+hipError_t launch_gemv_mfma(const GemvArgs& a, int nb, hipStream_t s) {
     switch (a.mode) {
-        case GEMV_STORE: gemv_mfma_kernel<GEMV_STORE><<<g, b, 0, s>>>(a, nb); break;
-        case GEMV_SILU: gemv_mfma_kernel<GEMV_SILU><<<g, b, 0, s>>>(a, nb); break;
-        case GEMV_RESID: gemv_mfma_kernel<GEMV_RESID><<<g, b, 0, s>>>(a, nb); break;
-        case GEMV_F32: gemv_mfma_kernel<GEMV_F32><<<g, b, 0, s>>>(a, nb); break;
+        case GEMV_STORE: return launch_gemv_mfma_m<GEMV_STORE>(a, nb, s);
+        case GEMV_SILU: return launch_gemv_mfma_m<GEMV_SILU>(a, nb, s);
+        case GEMV_RESID: return launch_gemv_mfma_m<GEMV_RESID>(a, nb, s);
+        case GEMV_F32: return launch_gemv_mfma_m<GEMV_F32>(a, nb, s);
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 // nb input vectors (1 <= nb <= 16).  bf16 with tile-friendly shapes runs on the matrix cores; otherwise the
@@ -769,11 +831,12 @@ __global__ void __launch_bounds__(1024) decode_attn_merge_kernel(const float* __
     }
 }
 
-// number of key splits: two workgroups per CU (measured best on 4.6K-13K cached pairs: 32 / 64 / 128 /
-// 256 splits of 8 KV heads take 14.6 / 11.7 / 12.8 / 14.3 us), at least 64 keys each, and no more than
-// the scratch buffer (scratch_floats) holds
-int decode_attn_splits(int64_t M, int Hkv, int d, size_t scratch_floats) {
-    int64_t s = 512 / (Hkv > 0 ? Hkv : 1);
+// number of key splits per sequence: two workgroups per CU over the whole launch (measured best on 4.6K-13K cached
+// pairs, one sequence: 32 / 64 / 128 / 256 splits of 8 KV heads take 14.6 / 11.7 / 12.8 / 14.3 us; 8 sequences of
+// 8.3K pairs: 8 / 16 / 32 / 64 splits take 61 / 62 / 65 / 69 us, 4 splits 89 us), at least 64 keys each, and no
+// more than the scratch buffer (scratch_floats, per sequence) holds
+int decode_attn_splits(int64_t M, int Hkv, int d, size_t scratch_floats, int nseq) {
+    int64_t s = 512 / ((int64_t)(Hkv > 0 ? Hkv : 1) * (nseq > 0 ? nseq : 1));
     if (s > (M + 63) / 64) s = (M + 63) / 64;
     const int64_t cap = (int64_t)(scratch_floats / ((size_t)Hkv * GRP_MAX * (d + 2)));
     if (s > cap) s = cap;
@@ -792,7 +855,7 @@ bool decode_attn_supported(int H, int Hkv, int d, bool bf16) {
 template <typename T>
 static hipError_t launch_decode_attn_t(const T* q, const T* K, const T* V, int64_t M, int H, int Hkv, int d, float* part,
                                        size_t part_floats, T* out, hipStream_t s) {
-    const int nsplit = decode_attn_splits(M, Hkv, d, part_floats);
+    const int nsplit = decode_attn_splits(M, Hkv, d, part_floats, 1);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
     const dim3 g((unsigned)nsplit, (unsigned)Hkv), b(256);
     const int grp = H / Hkv;
@@ -831,7 +894,7 @@ static hipError_t launch_decode_attn_batched_t(const T* q, const DecodeBatch& db
                                                size_t part_floats, T* out, hipStream_t s) {
     int64_t mmax = 1;
     for (int b = 0; b < db.n; ++b) mmax = db.count[b] + 1 > mmax ? db.count[b] + 1 : mmax;
-    const int nsplit = decode_attn_splits(mmax, Hkv, d, part_floats / (size_t)db.n);
+    const int nsplit = decode_attn_splits(mmax, Hkv, d, part_floats / (size_t)db.n, db.n);
     const int64_t stride = (int64_t)Hkv * nsplit * GRP_MAX * (d + 2);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
     const dim3 g((unsigned)nsplit, (unsigned)Hkv, (unsigned)db.n), b(256);
