@@ -130,6 +130,77 @@ def test_decode_layer_batched_lockstep(torch, dtype, nseq):
         assert torch.equal(xnext[b], td[int(tk[b])])
 
 
+def _fill_cache(torch, cache, shape, n, seed):
+    """n cached pairs written directly, positions 0..n-1: seeded normal keys scaled by 4 (peaked attention) and values
+    scaled by 8, so that the attention output dominates the layer's output and a misplaced key, value column or
+    dropped tile shows in it (on the oracle alone: two swapped value columns move the output by 3-6 %, permuted keys
+    by 30-40 %, a missing half of the values by 8-20 %, against the 2 % bar)."""
+    rng = np.random.default_rng(seed)
+    k = (4.0 * rng.standard_normal((n, shape.Hkv, shape.d))).astype(np.float32)
+    v = (8.0 * rng.standard_normal((n, shape.Hkv, shape.d))).astype(np.float32)
+    cache.k[:n].copy_(runtime.to_device(k, shape.dtype))
+    cache.v[:n].copy_(runtime.to_device(v, shape.dtype))
+    cache.pos[:n].copy_(torch.arange(n, dtype=torch.int32))
+    cache.struct.count = n
+
+
+_SHARP_SHAPES = {
+    "bf16-d128-g1": synth.ModelShape(D=512, H=4, Hkv=4, d=128, Dff=1024, dtype="bf16"),
+    "bf16-d128-g2": synth.ModelShape(D=512, H=4, Hkv=2, d=128, Dff=1024, dtype="bf16"),
+    "bf16-d128-g4": synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16"),
+    "bf16-d128-g8": synth.ModelShape(D=512, H=8, Hkv=1, d=128, Dff=1024, dtype="bf16"),
+    "bf16-d64": synth.ModelShape(D=256, H=4, Hkv=2, d=64, Dff=688, dtype="bf16"),
+    "f32-tiny": synth.TINY,
+}
+
+
+@pytest.mark.parametrize("name", list(_SHARP_SHAPES))
+def test_decode_attention_sharp_single_and_batched(torch, name):
+    """Decode over caches whose attention output dominates the layer (see _fill_cache), with cache lengths on and
+    around the kernel's step and split edges (0 cached pairs, 31 / 32 / 33 and 63 / 64 / 65 keys with the new pair, one
+    split, many splits): bf16 with head dimension 128 and 1 / 2 / 4 / 8 query heads per KV head, bf16 with head
+    dimension 64, fp32.  One sequence at a time, then the same caches as one batch."""
+    shape = _SHARP_SHAPES[name]
+    dt = shape.dtype
+    mdl = H.oracle_model(shape)
+    rnd = H.rnd_for(dt)
+    tol = H.TOL[dt]["hidden"]
+    w = synth.make_layer(41, 0, shape, 16)
+    dw = runtime.upload_layer(w, shape, 16)
+    ctx = ctx_for(shape, 4096)
+    lens = [0, 30, 31, 32, 63, 64, 65, 700, 2049, 3000]
+    caches = [runtime.KVCache(shape, n + 3) for n in lens]
+    for b, (c, n) in enumerate(zip(caches, lens)):
+        _fill_cache(torch, c, shape, n, 500 + b)
+    new = synth.hidden_states(42, 2 * len(lens), shape.D, dt).reshape(2, len(lens), shape.D)
+
+    def check(b, x_in, got, before, pos):
+        kh, vh, ph = before
+        ref_x, ref_c = orc.decode_layer(x_in, pos, w, mdl, orc.LayerCache(kh, vh, ph), rnd)
+        assert H.row_rel_err(got[None, :], ref_x[None, :]) <= tol, (name, lens[b], H.row_rel_err(got[None, :], ref_x[None, :]))
+        k2, v2, p2 = caches[b].host()
+        assert k2.shape[0] == kh.shape[0] + 1 and p2[-1] == pos
+        assert np.array_equal(k2[:-1], kh) and np.array_equal(v2[:-1], vh)
+        assert H.row_rel_err(k2[-1].reshape(1, -1), ref_c.k[-1].reshape(1, -1)) <= tol
+
+    for b, n in enumerate(lens):
+        before = caches[b].host()
+        xt = runtime.to_device(new[0, b:b + 1].copy(), dt).reshape(-1)
+        x_in = runtime.to_host(xt).astype(np.float64)
+        ctx.spts_decode_layer(xt, n, dw, caches[b].struct)
+        torch.cuda.synchronize()
+        check(b, x_in, runtime.to_host(xt).astype(np.float64), before, n)
+    before = [c.host() for c in caches]
+    xt = runtime.to_device(new[1].copy(), dt)
+    x_in = runtime.to_host(xt).astype(np.float64)
+    pos_t = [n + 1 for n in lens]
+    ctx.spts_decode_layer_batched(xt, pos_t, dw, [c.struct for c in caches])
+    torch.cuda.synchronize()
+    got = runtime.to_host(xt).astype(np.float64)
+    for b in range(len(lens)):
+        check(b, x_in[b], got[b], before[b], pos_t[b])
+
+
 def test_decode_rejects_a_full_cache(torch):
     shape = _shape("f32")
     w = synth.make_layer(21, 0, shape, 16)
