@@ -596,11 +596,14 @@ hipError_t launch_decode_rope_append(void* q, const void* k, const void* v, int 
     return hipGetLastError();
 }
 
-// the same for a batch of sequences (blockIdx.y = sequence): q [B, H, d], k / v [B, Hkv, d]; every sequence has its
-// own cache, row and position (by-value descriptor: at most DECODE_MAX_BATCH sequences)
+// the same for a batch of sequences (blockIdx.y = sequence), from the fp32 sums of the projections: q32 [B, H, d],
+// k32 / v32 [B, Hkv, d] -> q [B, H, d] and the new cache rows, rounded to T once, after the rotation (as the
+// single-sequence GEMV's epilogue does); every sequence has its own cache, row and position (by-value descriptor: at
+// most DECODE_MAX_BATCH sequences)
 template <typename T>
-__global__ void decode_rope_append_batched_kernel(T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
-                                                  int H, int Hkv, int d, double neg2_over_d_log2base, DecodeBatch db) {
+__global__ void decode_rope_append_batched_kernel(const float* __restrict__ q32, const float* __restrict__ k32,
+                                                  const float* __restrict__ v32, T* __restrict__ q, int H, int Hkv, int d,
+                                                  double neg2_over_d_log2base, DecodeBatch db) {
     const int half = d / 2;
     const int b = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -613,34 +616,33 @@ __global__ void decode_rope_append_batched_kernel(T* __restrict__ q, const T* __
     sincos((double)pos * exp2((double)j * neg2_over_d_log2base), &sn, &cs);
     const float c = (float)cs, s = (float)sn;
     if (head < H) {
-        T* p = q + ((int64_t)b * H + head) * d + j;
-        const float x0 = to_f32(p[0]), x1 = to_f32(p[half]);
-        p[0] = from_f32<T>(x0 * c - x1 * s);
-        p[half] = from_f32<T>(x1 * c + x0 * s);
+        const int64_t o = ((int64_t)b * H + head) * d + j;
+        const float x0 = q32[o], x1 = q32[o + half];
+        q[o] = from_f32<T>(x0 * c - x1 * s);
+        q[o + half] = from_f32<T>(x1 * c + x0 * s);
     } else {
         const int g = head - H;
-        const T* p = k + ((int64_t)b * Hkv + g) * d + j;
-        const float x0 = to_f32(p[0]), x1 = to_f32(p[half]);
+        const int64_t i0 = ((int64_t)b * Hkv + g) * d + j;
+        const float x0 = k32[i0], x1 = k32[i0 + half];
         T* o = (T*)db.cache_k[b] + (row * Hkv + g) * (int64_t)d + j;
         o[0] = from_f32<T>(x0 * c - x1 * s);
         o[half] = from_f32<T>(x1 * c + x0 * s);
         T* ov = (T*)db.cache_v[b] + (row * Hkv + g) * (int64_t)d + j;
-        const T* pv = v + ((int64_t)b * Hkv + g) * d + j;
-        ov[0] = pv[0];
-        ov[half] = pv[half];
+        ov[0] = from_f32<T>(v32[i0]);
+        ov[half] = from_f32<T>(v32[i0 + half]);
     }
 }
 
-hipError_t launch_decode_rope_append_batched(void* q, const void* k, const void* v, int H, int Hkv, int d, float base,
-                                             const DecodeBatch& db, bool bf16, hipStream_t s) {
+hipError_t launch_decode_rope_append_batched(const float* q32, const float* k32, const float* v32, void* q, int H, int Hkv, int d,
+                                             float base, const DecodeBatch& db, bool bf16, hipStream_t s) {
     if (db.n < 1 || db.n > DECODE_MAX_BATCH) return hipErrorInvalidValue;
     const int n = (H + Hkv) * (d / 2);
     const double kk = -2.0 / (double)d * log2((double)base);
     const dim3 g((unsigned)((n + 255) / 256), (unsigned)db.n), b(256);
     if (bf16)
-        decode_rope_append_batched_kernel<bf16_t><<<g, b, 0, s>>>((bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, H, Hkv, d, kk, db);
+        decode_rope_append_batched_kernel<bf16_t><<<g, b, 0, s>>>(q32, k32, v32, (bf16_t*)q, H, Hkv, d, kk, db);
     else
-        decode_rope_append_batched_kernel<float><<<g, b, 0, s>>>((float*)q, (const float*)k, (const float*)v, H, Hkv, d, kk, db);
+        decode_rope_append_batched_kernel<float><<<g, b, 0, s>>>(q32, k32, v32, (float*)q, H, Hkv, d, kk, db);
     return hipGetLastError();
 }
 

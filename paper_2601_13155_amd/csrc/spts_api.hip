@@ -544,15 +544,17 @@ int spts_decode_layer_batched(spts_ctx* c, void* x, const int32_t* pos, int32_t 
     const int QD = m.H * m.d, KV = m.Hkv * m.d;
     void* xn = c->p<void>(c->off.xn);
     void* q = c->p<void>(c->off.q);
-    void* kx = c->p<void>(c->off.khat);
-    void* vx = c->p<void>(c->off.vhat);
     void* att = c->p<void>(c->off.att);
     void* hbuf = c->p<void>(c->off.big);
     float* part = c->p<float>(c->off.tmp32);
     const size_t part_floats = (c->off.qp - c->off.tmp32) / sizeof(float);
-    GemvArgs qkv{}; qkv.mode = GEMV_STORE; qkv.x = xn; qkv.K = m.D;
+    // the projections leave fp32 sums (in the FFN's hidden buffer, free until gate/up); the rotary kernel rounds once
+    float* q32 = c->p<float>(c->off.big);
+    float* k32 = q32 + (size_t)batch * QD;
+    float* v32 = k32 + (size_t)batch * KV;
+    GemvArgs qkv{}; qkv.mode = GEMV_F32; qkv.x = xn; qkv.K = m.D;
     qkv.W[0] = w->Wq; qkv.W[1] = w->Wk; qkv.W[2] = w->Wv; qkv.R[0] = QD; qkv.R[1] = KV; qkv.R[2] = KV;
-    qkv.y[0] = q; qkv.y[1] = kx; qkv.y[2] = vx;
+    qkv.y[0] = q32; qkv.y[1] = k32; qkv.y[2] = v32;
     GemvArgs o{}; o.mode = GEMV_RESID; o.x = att; o.K = QD; o.W[0] = w->Wo; o.R[0] = m.D; o.y[0] = x;
     GemvArgs gu{}; gu.mode = GEMV_SILU; gu.x = xn; gu.K = m.D; gu.W[0] = w->Wgate; gu.W[1] = w->Wup; gu.R[0] = m.Dff; gu.y[0] = hbuf;
     GemvArgs dn{}; dn.mode = GEMV_RESID; dn.x = hbuf; dn.K = m.Dff; dn.W[0] = w->Wdown; dn.R[0] = m.D; dn.y[0] = x;
@@ -568,7 +570,7 @@ int spts_decode_layer_batched(spts_ctx* c, void* x, const int32_t* pos, int32_t 
     { PHASE(c, PH_DEC_NORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, xn, batch, m.D, c->bf16, st)); }
     { PHASE(c, PH_DEC_QKV); SPTS_HIP(c, launch_gemv_nb(qkv, batch, c->bf16, st)); }
     { PHASE(c, PH_DEC_ROPE_APPEND);
-      SPTS_HIP(c, launch_decode_rope_append_batched(q, kx, vx, m.H, m.Hkv, m.d, m.rope_base, db, c->bf16, st)); }
+      SPTS_HIP(c, launch_decode_rope_append_batched(q32, k32, v32, q, m.H, m.Hkv, m.d, m.rope_base, db, c->bf16, st)); }
     { PHASE(c, PH_DEC_ATTN); SPTS_HIP(c, launch_decode_attn_batched(q, db, m.H, m.Hkv, m.d, part, part_floats, att, c->bf16, st)); }
     { PHASE(c, PH_DEC_O); SPTS_HIP(c, launch_gemv_nb(o, batch, c->bf16, st)); }
     { PHASE(c, PH_DEC_NORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma2, m.rms_eps, xn, batch, m.D, c->bf16, st)); }

@@ -206,9 +206,10 @@ struct DecodeBatch {
 // Y[b, r] = W[r, :] . X[b, :] for nb <= DECODE_MAX_BATCH input vectors (X [nb, K], Y[i] [nb, R[i]] contiguous); modes STORE, SILU,
 // RESID, F32; no fused norm
 hipError_t launch_gemv_nb(const GemvArgs& a, int nb, bool bf16, hipStream_t s);
-// q [n, H, d] rotated in place, k / v [n, Hkv, d] rotated / copied into row count[b] of sequence b's cache
-hipError_t launch_decode_rope_append_batched(void* q, const void* k, const void* v, int H, int Hkv, int d, float base,
-                                             const DecodeBatch& db, bool bf16, hipStream_t s);
+// fp32 projection sums q32 [n, H, d], k32 / v32 [n, Hkv, d] -> q [n, H, d] rotated, k rotated / v copied into row count[b] of
+// sequence b's cache; one rounding to the element type, after the rotation
+hipError_t launch_decode_rope_append_batched(const float* q32, const float* k32, const float* v32, void* q, int H, int Hkv, int d,
+                                             float base, const DecodeBatch& db, bool bf16, hipStream_t s);
 // out [n, H, d]: attention of sequence b's query over its count[b] + 1 cached pairs
 hipError_t launch_decode_attn_batched(const void* q, const DecodeBatch& db, int H, int Hkv, int d, float* part, size_t part_floats,
                                       void* out, bool bf16, hipStream_t s);
