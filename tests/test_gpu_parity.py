@@ -272,6 +272,33 @@ def test_layer_modes_on_matrix_core_kernels(torch, name, shape, N, P, r):
     assert dense["kv_count"] == N
 
 
+@pytest.mark.parametrize("name,shape,N,P,r", [
+    ("d128", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 64, 256),
+    ("d64", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16"), 1100, 16, 256),
+    ("tiny_f32", synth.TINY, 301, 32, 16),
+], ids=["d128", "d64", "tiny_f32"])
+def test_layer_with_peaked_dominant_attention(torch, name, shape, N, P, r):
+    """The same layer calls with Wk scaled by 4 and Wv by 8: the softmax concentrates on a few keys and the attention
+    output dominates the residual stream, so a misplaced key, value column, mask edge or rounding point in the
+    attention path moves the layer output by percents instead of averaging out over hundreds of keys (the probe scores
+    sharpen in the same way).  Dense branch, skip branch, and active queries against all keys (kv_mode = 1)."""
+    ctx = ctx_for(shape, 2048)
+    w = dict(synth.make_layer(8, 0, shape, r))
+    w["Wk"] = (4.0 * np.asarray(w["Wk"], dtype=np.float32)).astype(np.float32)
+    w["Wv"] = (8.0 * np.asarray(w["Wv"], dtype=np.float32)).astype(np.float32)
+    x = synth.hidden_states(8, N, shape.D, shape.dtype)
+    pos = (synth.positions(N) * 2 + 1).astype(np.int32)
+    dw = runtime.upload_layer(w, shape, r)
+    mdl = H.oracle_model(shape)
+    ma, mf = int(0.3 * N), int(0.45 * N)
+    dense = runtime.run_layer(ctx, x, pos, dw, shape, skip=0, probe_len=P, m_attn=0, m_ffn=0)
+    H.lockstep_layer(dense, x, pos, w, mdl, orc.LayerCfg(0, P, N, N, 1, 0), shape.dtype)
+    skip = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=ma, m_ffn=mf)
+    H.lockstep_layer(skip, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 0), shape.dtype)
+    kv1 = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=ma, m_ffn=mf, kv_mode=1)
+    H.lockstep_layer(kv1, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 1), shape.dtype)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_layer_dense_keepall_keepzero_and_modes(torch, dtype):
     shape = synth.TINY if dtype == "f32" else synth.ModelShape(D=256, H=4, Hkv=2, d=64, Dff=688, dtype="bf16")
