@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's)")
     ap.add_argument("--weight-pool", type=int, default=2,
                     help="distinct synthetic weight sets; layers cycle through them (bounds set-up time)")
+    ap.add_argument("--row-major-weights", action="store_true",
+                    help="do not upload the slab-major weight copies (the prefill GEMMs then read the row-major matrices)")
     ap.add_argument("--dense-steps", type=int, default=1, help="timed steps of the dense (skip=0) prefill; 0 = skip it")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096, help="0 = no cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket phases with events in the timed region")
@@ -140,7 +142,7 @@ def main():
     host_sets, dev_sets = [], []
     for i in range(pool):
         w = synth.make_layer(wl.seed, i, shape, wl.r, wl.dlow, wl.r_pad)
-        dev_sets.append(runtime.upload_layer(w, shape, wl.proxy_r))
+        dev_sets.append(runtime.upload_layer(w, shape, wl.proxy_r, pack=not args.row_major_weights))
         host_sets.append(w if i == 0 else None)
         log(f"[setup] weight set {i + 1}/{pool} ready ({time.perf_counter() - t_setup:.1f} s)")
     layers = [dev_sets[l % pool] for l in range(wl.layers)]

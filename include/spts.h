@@ -76,6 +76,11 @@ typedef struct {
     const void *Ug, *Vg, *Uu, *Vu, *Ud, *Vd;
     int32_t r;    /* proxy rank                         */
     int32_t Dlow; /* proxy inner dimension (<= Dff)     */
+    /* Optional slab-major copies of the projection / FFN matrices made by spts_pack_slab32 (NULL = none; bf16 only).
+     * The prefill calls read a matrix through its copy where their matrix-core GEMM takes it (same arithmetic, same
+     * results; the copy only changes which bytes a load instruction fetches together); the decode calls and the fp32
+     * path always read the row-major originals, which must be given in any case.  Wgate_s and Wup_s go together. */
+    const void *Wq_s, *Wk_s, *Wv_s, *Wo_s, *Wgate_s, *Wup_s, *Wdown_s;
 } spts_layer_weights;
 
 /* Per-layer control (Alg. 1: skip flag, budgets M_fixed; Sec. 3.4). */
@@ -101,6 +106,14 @@ typedef struct {
 } spts_kv_out;
 
 typedef struct spts_ctx spts_ctx;
+
+/* Slab-major copy of a row-major matrix W [rows, K] of 2-byte elements (bf16): out[(s * rows + r) * 32 + j] =
+ * W[r * K + 32 * s + j], i.e. the 32 columns of K slab s of consecutive rows lie next to each other (64 bytes per row).
+ * A GEMM load instruction then moves 16 rows of a slab as 1 KB of whole cache lines instead of 64-byte halves of 16
+ * lines (a layout choice of this library, not part of the method; Sec. 3.2 / 3.3 define the products it serves).
+ * W and out are device pointers, 16-byte aligned, rows * K elements each, not overlapping; K % 32 == 0.
+ * SPTS_EINVAL / SPTS_EALIGN / SPTS_ESHAPE on bad arguments; the copy is enqueued on the context's stream. */
+int spts_pack_slab32(spts_ctx *ctx, const void *W, int64_t rows, int64_t K, void *out);
 
 /* Bytes of device workspace a context needs to serve calls with N <= max_tokens,
  * probe_len <= max_probe, r <= max_r, Dlow <= max_dlow.  0 on invalid arguments. */

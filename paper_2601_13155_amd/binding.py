@@ -22,6 +22,7 @@ EXPORTS = (
     "spts_workspace_bytes", "spts_create", "spts_destroy", "spts_strerror", "spts_last_hip_error", "spts_uses_mfma",
     "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_select_topk_segmented", "spts_layer_prefill", "spts_layer_prefill_batched", "spts_msdp_compact", "spts_msdp_compact_batched",
     "spts_decode_layer", "spts_decode_layer_batched", "spts_greedy_token", "spts_greedy_token_batched", "spts_channel_importance",
+    "spts_pack_slab32",
     "spts_profile_begin", "spts_profile_end", "spts_profile_count", "spts_profile_get",
 )
 
@@ -33,7 +34,8 @@ class spts_model_desc(C.Structure):
 
 class spts_layer_weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("Wq", "Wk", "Wv", "Wo", "gamma1", "Wgate", "Wup", "Wdown", "gamma2",
-                                           "Ug", "Vg", "Uu", "Vu", "Ud", "Vd")] + [("r", C.c_int32), ("Dlow", C.c_int32)]
+                                           "Ug", "Vg", "Uu", "Vu", "Ud", "Vd")] + [("r", C.c_int32), ("Dlow", C.c_int32)] + \
+               [(n, C.c_void_p) for n in ("Wq_s", "Wk_s", "Wv_s", "Wo_s", "Wgate_s", "Wup_s", "Wdown_s")]
 
 
 class spts_layer_cfg(C.Structure):
@@ -100,6 +102,8 @@ def load() -> C.CDLL:
     lib.spts_greedy_token.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
     lib.spts_channel_importance.restype = C.c_int
     lib.spts_channel_importance.argtypes = [vp, vp, i64, C.POINTER(spts_layer_weights), i64, vp]
+    lib.spts_pack_slab32.restype = C.c_int
+    lib.spts_pack_slab32.argtypes = [vp, vp, i64, i64, vp]
     lib.spts_profile_begin.restype = C.c_int
     lib.spts_profile_begin.argtypes = [vp]
     lib.spts_profile_end.restype = C.c_int
@@ -140,9 +144,9 @@ def model_desc(shape) -> spts_model_desc:
 def layer_weights(tensors: dict, r: int = 0, Dlow: int = 0) -> spts_layer_weights:
     """tensors: name -> device tensor in the ABI layout ([d_out, d_in]); missing names become NULL."""
     w = spts_layer_weights()
-    for name, _ in spts_layer_weights._fields_[:15]:
-        t = tensors.get(name)
-        setattr(w, name, _ptr(t))
+    for name, typ in spts_layer_weights._fields_:
+        if typ is C.c_void_p:
+            setattr(w, name, _ptr(tensors.get(name)))
     w.r, w.Dlow = int(r), int(Dlow)
     w._keepalive = tensors  # keep the device tensors referenced as long as the struct lives
     return w
@@ -267,6 +271,9 @@ class Context:
     def spts_channel_importance(self, x_cal, T: int, w: spts_layer_weights, k: int, importance_out):
         _check(load().spts_channel_importance(self.handle, _ptr(x_cal), T, C.byref(w), k, _ptr(importance_out)),
                "spts_channel_importance")
+
+    def spts_pack_slab32(self, W, rows: int, K: int, out):
+        _check(load().spts_pack_slab32(self.handle, _ptr(W), rows, K, _ptr(out)), "spts_pack_slab32")
 
     def spts_msdp_compact(self, x_in, pos_in, s_mha, N, N_next, protect_last, x_out, pos_out, map_new2old,
                           map_old2new=None):

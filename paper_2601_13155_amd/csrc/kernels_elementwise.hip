@@ -299,4 +299,22 @@ hipError_t launch_transpose_pad(const void* v, void* vt, int64_t M, int C, int64
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- slab-major copy of a row-major matrix
+// out[(s * rows + r) * 32 + j] = W[r * K + 32 * s + j] (2-byte elements, K % 32 == 0): the 32 columns of K slab s of
+// consecutive rows lie next to each other, 64 bytes per row.  One thread per 16-byte chunk.
+__global__ void __launch_bounds__(256) pack_slab32_kernel(const u32x4* __restrict__ W, int64_t rows, int64_t chunks_per_row,
+                                                          u32x4* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= rows * chunks_per_row) return;
+    const int64_t r = i / chunks_per_row, c = i % chunks_per_row;
+    out[((c >> 2) * rows + r) * 4 + (c & 3)] = W[i];
+}
+
+hipError_t launch_pack_slab32(const void* W, int64_t rows, int64_t K, void* out, hipStream_t s) {
+    if (rows <= 0 || K <= 0 || K % 32 != 0) return hipErrorInvalidValue;
+    const int64_t n = rows * (K / 8);
+    pack_slab32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>((const u32x4*)W, rows, K / 8, (u32x4*)out);
+    return hipGetLastError();
+}
+
 }  // namespace spts

@@ -147,16 +147,21 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     // 32-bit per-lane byte offset that never changes: no vector instructions for addresses in the loop.
     // Bases: A rows from row0 on (or the whole gather source when rows come through an index list, whose
     // byte size must then fit 32 bits); the B rows this wavefront moves.
+    // Slab-major operands (32-wide slabs): a row of a slab is 64 bytes and consecutive rows are adjacent, so the row
+    // pitch is 64 bytes and one slab further on is rows * 64 bytes.
+    const bool a_slab = BK == 32 && a.a_slab, b_slab = BK == 32 && a.b_slab;
+    const int64_t a_pitch = a_slab ? 64 : a.lda * 2, b_pitch = b_slab ? 64 : a.ldb * 2;      // bytes between rows
+    const int64_t a_kstep = a_slab ? a.M * 64 : BK * 2, b_kstep = b_slab ? a.b_rows * 64 : BK * 2;   // bytes per slab
     uint32_t oa[LPO], ob[LPO];
-    const char* abase = (const char*)a.A + (a.a_idx ? (int64_t)0 : row0 * a.lda * 2);
-    const char* a1base = DUAL_A ? (const char*)a.A1 + (a.a_idx ? (int64_t)0 : row0 * a.lda * 2) : abase;
+    const char* abase = (const char*)a.A + (a.a_idx ? (int64_t)0 : row0 * a_pitch);
+    const char* a1base = DUAL_A ? (const char*)a.A1 + (a.a_idx ? (int64_t)0 : row0 * a_pitch) : abase;
     const char* bbase;
     {
         const int rw = wave * LROWS;   // first B tile row of this wavefront
-        if (DUAL) bbase = rw < 128 ? (const char*)a.B0 + (int64_t)(col0 + rw) * a.ldb * 2
-                                   : (const char*)a.B1 + (int64_t)(col0 + rw - 128) * a.ldb * 2;
-        else if (a.B1 && col0 >= a.N / 2) bbase = (const char*)a.B1 + (int64_t)(col0 - a.N / 2 + rw) * a.ldb * 2;
-        else bbase = (const char*)a.B0 + (int64_t)(col0 + rw) * a.ldb * 2;
+        if (DUAL) bbase = rw < 128 ? (const char*)a.B0 + (int64_t)(col0 + rw) * b_pitch
+                                   : (const char*)a.B1 + (int64_t)(col0 + rw - 128) * b_pitch;
+        else if (a.B1 && col0 >= a.N / 2) bbase = (const char*)a.B1 + (int64_t)(col0 - a.N / 2 + rw) * b_pitch;
+        else bbase = (const char*)a.B0 + (int64_t)(col0 + rw) * b_pitch;
     }
 #pragma unroll
     for (int q = 0; q < LPO; ++q) {
@@ -166,8 +171,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
         int64_t grow = row0 + r;
         if (grow >= a.M) grow = a.M - 1;  // clamp: duplicates of the last row are never stored
         const int64_t srow = a.a_idx ? (int64_t)a.a_idx[grow] : grow - row0;
-        oa[q] = (uint32_t)((srow * a.lda + c * 8) * 2);
-        ob[q] = (uint32_t)(((int64_t)rl * a.ldb + c * 8) * 2);
+        oa[q] = (uint32_t)(srow * a_pitch + c * 16);
+        ob[q] = (uint32_t)((int64_t)rl * b_pitch + c * 16);
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
     const uint32_t lds_w = lds0 + wave * (LROWS * S::ROW_BYTES);   // this wavefront's rows inside an operand tile
@@ -175,10 +180,10 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
 #define SPTS_DMA_ONE(kt_, u)                                                                   \
     {                                                                                          \
         const uint32_t sb_ = lds_w + ((kt_) % NST) * STAGE + ((u) / NOPS) * 1024;              \
-        const int ko_ = (kbeg + (kt_)) * BK;                                                   \
-        if ((u) % NOPS == 0) dma16s(oa[(u) / NOPS], abase + ko_ * 2, sb_);                     \
-        else if ((u) % NOPS == 1) dma16s(ob[(u) / NOPS], bbase + ko_ * 2, sb_ + TILE_BYTES);   \
-        else dma16s(oa[(u) / NOPS], a1base + ko_ * 2, sb_ + 2 * TILE_BYTES);                   \
+        const int64_t ks_ = kbeg + (kt_);                                                      \
+        if ((u) % NOPS == 0) dma16s(oa[(u) / NOPS], abase + ks_ * a_kstep, sb_);               \
+        else if ((u) % NOPS == 1) dma16s(ob[(u) / NOPS], bbase + ks_ * b_kstep, sb_ + TILE_BYTES); \
+        else dma16s(oa[(u) / NOPS], a1base + ks_ * a_kstep, sb_ + 2 * TILE_BYTES);             \
     }
 #define SPTS_DMA_SLAB(kt_)                                                                     \
     { _Pragma("unroll") for (int u_ = 0; u_ < PER; ++u_) SPTS_DMA_ONE(kt_, u_) }
@@ -488,6 +493,10 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     if (a.M <= 0 || a.N <= 0 || a.N % ncols != 0) return false;
     if (a.K < 32 || a.K % 32 != 0) return false;
     if (a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
+    // slab-major operands: served by the 32-wide-slab instantiations; A not gathered, B one matrix (two for SiLU)
+    if ((a.a_slab || a.b_slab) && a.epi != EPI_SILU_MUL && a.epi != EPI_RESIDUAL && a.epi != EPI_STORE && a.epi != EPI_ROPE) return false;
+    if (a.a_slab && (a.a_idx || a.A1)) return false;
+    if (a.b_slab && (a.b_rows < a.N || (a.epi == EPI_STORE && a.B1))) return false;
     if (!al16(a.A) || !al16(a.B0) || (a.A1 && !al16(a.A1)) || (dual && !al16(a.B1))) return false;
     if (a.epi != EPI_SUMSQ) {
         if (a.ldc % 8 != 0 || !al16(a.C)) return false;
@@ -630,12 +639,13 @@ int gemm_pick_split(int64_t M, int32_t N, int32_t K, int epi, int32_t* nfull) {
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
     constexpr int NW = SPTS_GEMM_NW;
+    const bool slab = a.a_slab || a.b_slab;   // slab-major operands exist for 32-wide slabs only
     hipError_t e;
     switch (a.epi) {
-        case EPI_STORE: e = (a.K % 64 == 0 ? launch_t<EPI_STORE, 64, false, NW>(a, s) : launch_t<EPI_STORE, 32, false, NW>(a, s)); break;
-        case EPI_RESIDUAL: e = (a.K % 64 == 0 ? launch_t<EPI_RESIDUAL, 64, false, NW>(a, s) : launch_t<EPI_RESIDUAL, 32, false, NW>(a, s)); break;
+        case EPI_STORE: e = (a.K % 64 == 0 && !slab ? launch_t<EPI_STORE, 64, false, NW>(a, s) : launch_t<EPI_STORE, 32, false, NW>(a, s)); break;
+        case EPI_RESIDUAL: e = (a.K % 64 == 0 && !slab ? launch_t<EPI_RESIDUAL, 64, false, NW>(a, s) : launch_t<EPI_RESIDUAL, 32, false, NW>(a, s)); break;
         case EPI_SUMSQ: e = (a.K % 64 == 0 ? launch_t<EPI_SUMSQ, 64, false, NW>(a, s) : launch_t<EPI_SUMSQ, 32, false, NW>(a, s)); break;
-        case EPI_ROPE: e = (a.K % 64 == 0 ? launch_t<EPI_ROPE, 64, false, NW>(a, s) : launch_t<EPI_ROPE, 32, false, NW>(a, s)); break;
+        case EPI_ROPE: e = (a.K % 64 == 0 && !slab ? launch_t<EPI_ROPE, 64, false, NW>(a, s) : launch_t<EPI_ROPE, 32, false, NW>(a, s)); break;
         case EPI_SILU_MUL:
             if (a.A1) e = launch_t<EPI_SILU_MUL, 32, true, NW>(a, s);
             else e = launch_t<EPI_SILU_MUL, 32, false, NW>(a, s);   // 4 stages of 32 measured 2 % faster here than 2 of 64

@@ -166,11 +166,23 @@ GemmArgs gemm_args(const void* A, int64_t lda, const int32_t* a_idx, const void*
     return g;
 }
 
-// out[rows, heads*d] = rotary(A * B^T); table row of output row i is (tidx ? tidx[i] : i + row0)
-int run_gemm_rope(spts_ctx* c, GemmArgs g, int heads, const int32_t* tidx, int64_t row0, void* out) {
+// B (one weight matrix, or the gate / up pair) through its slab-major copy when the caller gave one and the
+// matrix-core kernel serves the call with it; otherwise g keeps the row-major pointers
+void prefer_slab(const spts_ctx* c, GemmArgs& g, const void* s0, const void* s1, int64_t rows) {
+    if (!c->bf16 || !s0 || (g.B1 && !s1)) return;
+    GemmArgs t = g;
+    t.B0 = s0; if (g.B1) t.B1 = s1;
+    t.b_slab = 1; t.b_rows = rows;
+    if (gemm_mfma_supported(t)) g = t;
+}
+
+// out[rows, heads*d] = rotary(A * B^T); table row of output row i is (tidx ? tidx[i] : i + row0); b_slab: optional
+// slab-major copy of B (heads*d rows)
+int run_gemm_rope(spts_ctx* c, GemmArgs g, int heads, const int32_t* tidx, int64_t row0, void* out, const void* b_slab = nullptr) {
     const float2* table = c->p<float2>(c->off.rope);
     GemmArgs f = g;
     f.epi = EPI_ROPE; f.C = out; f.rope = table + row0 * (c->m.d / 2); f.rope_idx = tidx; f.head_dim = c->m.d;
+    prefer_slab(c, f, b_slab, nullptr, g.N);
     if (c->bf16 && gemm_mfma_supported(f)) return run_gemm_mfma(c, f);
     g.C = c->p<float>(c->off.tmp32); g.c_is_f32 = 1; g.epi = EPI_STORE;
     SPTS_TRY(run_gemm(c, g));
@@ -194,7 +206,8 @@ int check_weights_proxy(const spts_ctx* c, const spts_layer_weights* w) {
 int check_weights_full(const spts_ctx* c, const spts_layer_weights* w, bool need_proxy) {
     SPTS_TRY(check_weights_attn(w));
     if (!w->Wv || !w->Wo || !w->Wgate || !w->Wup || !w->Wdown || !w->gamma2) return SPTS_EINVAL;
-    const void* ps[] = {w->Wv, w->Wo, w->Wgate, w->Wup, w->Wdown, w->gamma2};
+    const void* ps[] = {w->Wv, w->Wo, w->Wgate, w->Wup, w->Wdown, w->gamma2,
+                        w->Wq_s, w->Wk_s, w->Wv_s, w->Wo_s, w->Wgate_s, w->Wup_s, w->Wdown_s};   // the copies may be NULL
     for (const void* p : ps) if (!aligned16(p)) return SPTS_EALIGN;
     if (need_proxy) SPTS_TRY(check_weights_proxy(c, w));
     return SPTS_OK;
@@ -209,7 +222,7 @@ int probe_scores_rows(spts_ctx* c, int64_t row0, int64_t n, const spts_layer_wei
     const size_t eb = c->bf16 ? 2 : 4;
     const char* xn_probe = c->p<char>(c->off.xn) + (size_t)(row0 + n - P) * m.D * eb;
     GemmArgs gq = gemm_args(xn_probe, m.D, nullptr, w->Wq, m.D, nullptr, QD, P, QD, m.D);
-    { PHASE(c, PH_PROBE_Q); SPTS_TRY(run_gemm_rope(c, gq, m.H, nullptr, row0 + n - P, c->p<void>(c->off.qp))); }
+    { PHASE(c, PH_PROBE_Q); SPTS_TRY(run_gemm_rope(c, gq, m.H, nullptr, row0 + n - P, c->p<void>(c->off.qp), w->Wq_s)); }
     ProbeArgs pa{};
     pa.qp = c->p<void>(c->off.qp); pa.k = k_rows; pa.S = s_out;
     pa.stats = c->p<float>(c->off.probe);
@@ -231,7 +244,7 @@ int probe_attn_impl(spts_ctx* c, const void* x, const int32_t* pos, int64_t N, c
     { PHASE(c, PH_RMSNORM); SPTS_HIP(c, launch_rmsnorm(x, w->gamma1, m.rms_eps, c->p<void>(c->off.xn), N, m.D, c->bf16, c->stream)); }
     const int KV = m.Hkv * m.d;
     GemmArgs gk = gemm_args(c->p<void>(c->off.xn), m.D, nullptr, w->Wk, m.D, nullptr, KV, N, KV, m.D);
-    { PHASE(c, PH_K_PROJ); SPTS_TRY(run_gemm_rope(c, gk, m.Hkv, nullptr, 0, k_out)); }
+    { PHASE(c, PH_K_PROJ); SPTS_TRY(run_gemm_rope(c, gk, m.Hkv, nullptr, 0, k_out, w->Wk_s)); }
     if (!want_scores) return SPTS_OK;
     return probe_scores_rows(c, 0, N, w, P, k_out, s_out);
 }
@@ -608,6 +621,14 @@ int spts_greedy_token_batched(spts_ctx* c, const void* x, const void* gamma_f, c
     return SPTS_OK;
 }
 
+int spts_pack_slab32(spts_ctx* c, const void* W, int64_t rows, int64_t K, void* out) {
+    if (!c || !W || !out || rows <= 0 || K <= 0) return SPTS_EINVAL;
+    if (!aligned16(W) || !aligned16(out)) return SPTS_EALIGN;
+    if (K % 32 != 0) return SPTS_ESHAPE;
+    SPTS_HIP(c, launch_pack_slab32(W, rows, K, out, c->stream));
+    return SPTS_OK;
+}
+
 int spts_select_topk_segmented(spts_ctx* c, const float* scores, const int64_t* seg_offsets, const int64_t* seg_k,
                                const int64_t* out_offsets, int32_t batch, int64_t max_len, int32_t protect_last,
                                int32_t* idx_out) {
@@ -765,7 +786,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         // queries of the active rows (rows gathered through idxA inside the GEMM's A loads)
         GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, Ma, QD, m.D);
         gq.a_rows = N;
-        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q))); }
+        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s)); }
         const int32_t* qpos = pos;
         const int32_t* kpos = pos;
         void* kk = kall;
@@ -792,6 +813,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         const bool amf = c->bf16 && attention_mfma_supported(aa);
         GemmArgs gv = gemm_args(xn, m.D, full_kv ? nullptr : idxA, w->Wv, m.D, vv, KV, Mk, KV, m.D);
         gv.a_rows = N;
+        prefer_slab(c, gv, w->Wv_s, nullptr, KV);
         bool vt_done = false;
         if (amf) {
             // the matrix-core projection writes the transposed copy (keys contiguous) in its epilogue
@@ -812,6 +834,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         // x[T_a] += att * Wo^T
         GemmArgs go = gemm_args(c->p<void>(c->off.att), QD, nullptr, w->Wo, QD, x, m.D, Ma, m.D, QD, EPI_RESIDUAL);
         go.c_idx = idxA;
+        prefer_slab(c, go, w->Wo_s, nullptr, m.D);
         { PHASE(c, PH_O_PROJ); SPTS_TRY(run_gemm(c, go)); }
     }
 
@@ -833,9 +856,11 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
     GemmArgs gh = gemm_args(xn, m.D, idxF, w->Wgate, m.D, c->p<void>(c->off.big), m.Dff, Mf, m.Dff, m.D, EPI_SILU_MUL);
     gh.a_rows = N;
     gh.B1 = w->Wup;
+    prefer_slab(c, gh, w->Wgate_s, w->Wup_s, m.Dff);
     { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
     GemmArgs gd = gemm_args(c->p<void>(c->off.big), m.Dff, nullptr, w->Wdown, m.Dff, x, m.D, Mf, m.D, m.Dff, EPI_RESIDUAL);
     gd.c_idx = idxF;
+    prefer_slab(c, gd, w->Wdown_s, nullptr, m.D);
     { PHASE(c, PH_FFN_DOWN); SPTS_TRY(run_gemm(c, gd)); }
     return SPTS_OK;
 }
@@ -917,7 +942,7 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
     if (MaT > 0) {
         GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, MaT, QD, m.D);
         gq.a_rows = N;
-        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q))); }
+        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s)); }
         const int32_t* posA = pos;
         const char* khat = (const char*)kall;
         char* vhat = c->p<char>(c->off.vhat);
@@ -930,6 +955,7 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
         }
         GemmArgs gv = gemm_args(xn, m.D, idxA, w->Wv, m.D, vhat, KV, MaT, KV, m.D);
         gv.a_rows = N;
+        prefer_slab(c, gv, w->Wv_s, nullptr, KV);
         { PHASE(c, PH_V_PROJ); SPTS_TRY(run_gemm(c, gv)); }
         for (int b = 0; b < batch; ++b) {
             if (ma[b] == 0) continue;
@@ -957,6 +983,7 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
         }
         GemmArgs go = gemm_args(c->p<void>(c->off.att), QD, nullptr, w->Wo, QD, x, m.D, MaT, m.D, QD, EPI_RESIDUAL);
         go.c_idx = idxA;
+        prefer_slab(c, go, w->Wo_s, nullptr, m.D);
         { PHASE(c, PH_O_PROJ); SPTS_TRY(run_gemm(c, go)); }
     }
 
@@ -975,9 +1002,11 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
     GemmArgs gh = gemm_args(xn, m.D, idxF, w->Wgate, m.D, c->p<void>(c->off.big), m.Dff, MfT, m.Dff, m.D, EPI_SILU_MUL);
     gh.a_rows = N;
     gh.B1 = w->Wup;
+    prefer_slab(c, gh, w->Wgate_s, w->Wup_s, m.Dff);
     { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
     GemmArgs gd = gemm_args(c->p<void>(c->off.big), m.Dff, nullptr, w->Wdown, m.Dff, x, m.D, MfT, m.D, m.Dff, EPI_RESIDUAL);
     gd.c_idx = idxF;
+    prefer_slab(c, gd, w->Wdown_s, nullptr, m.D);
     { PHASE(c, PH_FFN_DOWN); SPTS_TRY(run_gemm(c, gd)); }
     return SPTS_OK;
 }

@@ -88,6 +88,10 @@ struct GemmArgs {
     // the last, partly filled round of tiles into a full round of short work units.
     // ksplit <= 1 disables it (nfull is then ignored).
     int32_t ksplit; int32_t nfull; float* part32;
+    // slab-major operands (matrix-core path, 32-wide K slabs only): A stored [K/32][M][32], B0 / B1 stored [K/32][b_rows][32]
+    // (pack_slab32 of the row-major matrix), so that the 16 rows a load instruction moves are 1 KB of whole cache lines
+    // instead of 64-byte halves of 16 lines.  a_slab excludes a_idx (the packed copy is already gathered).
+    int32_t a_slab; int32_t b_slab; int64_t b_rows;
 };
 // Split plan for a GEMM of this shape on a 256-CU device: returns ksplit (1 = do not split) and
 // sets *nfull; needs (tiles - nfull) * ksplit * 65536 floats of part32.
@@ -101,6 +105,8 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s);
 int gemm_sumsq_blocks(int32_t N, bool mfma);
 
 // ------------------------------------------------------------------ elementwise / data movement
+// slab-major copy of a row-major [rows, K] matrix of 2-byte elements: out[(s * rows + r) * 32 + j] = W[r * K + 32 * s + j]
+hipError_t launch_pack_slab32(const void* W, int64_t rows, int64_t K, void* out, hipStream_t s);
 hipError_t launch_rope_table(const int32_t* pos, int64_t N, int d, float base, float2* table, hipStream_t s);
 hipError_t launch_rmsnorm(const void* x, const void* gamma, float eps, void* out, int64_t N, int D, bool bf16, hipStream_t s);
 // out[n, h, :] = rotary(in_f32[n, h, :]) with table row (idx ? idx[n] : n + row0)

@@ -34,10 +34,25 @@ def make_context(shape, max_tokens: int, max_probe: int, max_r: int, max_dlow: i
     return binding.Context(shape, max_tokens, max_probe, max_r, max_dlow)
 
 
-def upload_layer(w: Dict[str, np.ndarray], shape, r: int) -> binding.spts_layer_weights:
-    """Weights in the paper's orientation (synth.make_layer) -> device struct in the ABI layout."""
+SLAB_PACKED = ("Wq", "Wk", "Wv", "Wo", "Wgate", "Wup", "Wdown")
+
+
+def pack_slab32(a: np.ndarray) -> np.ndarray:
+    """Host-side slab-major copy of a row-major [rows, K] matrix (K % 32 == 0): element (s * rows + r) * 32 + j of the
+    result is a[r, 32 * s + j]; same shape and dtype, the layout spts_pack_slab32 writes on the device."""
+    rows, K = a.shape
+    return np.ascontiguousarray(a.reshape(rows, K // 32, 32).transpose(1, 0, 2)).reshape(rows, K)
+
+
+def upload_layer(w: Dict[str, np.ndarray], shape, r: int, pack: bool = True) -> binding.spts_layer_weights:
+    """Weights in the paper's orientation (synth.make_layer) -> device struct in the ABI layout.  pack (bf16 only): the
+    projection and FFN matrices also get the slab-major copies that the prefill GEMMs prefer."""
     abi = synth.to_abi_layout(w)
     dev = {k: to_device(v, shape.dtype) for k, v in abi.items()}
+    if pack and shape.dtype == "bf16":
+        for name in SLAB_PACKED:
+            if name in abi and abi[name].shape[1] % 32 == 0:
+                dev[name + "_s"] = to_device(pack_slab32(np.asarray(abi[name])), shape.dtype)
     dlow = int(abi["Vd"].shape[1]) if "Vd" in abi else 0
     return binding.layer_weights(dev, r=r if "Ug" in abi else 0, Dlow=dlow)
 

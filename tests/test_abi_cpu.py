@@ -100,3 +100,17 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libspts.so")
     with pytest.raises(RuntimeError):
         binding.load()
+
+
+def test_host_slab_packing_layout():
+    """runtime.pack_slab32 (the layout spts_pack_slab32 documents): element (s * rows + r) * 32 + j = a[r, 32 s + j]."""
+    import numpy as np
+    from paper_2601_13155_amd import runtime
+    rows, K = 5, 96
+    a = np.arange(rows * K, dtype=np.float32).reshape(rows, K)
+    p = runtime.pack_slab32(a)
+    assert p.shape == a.shape
+    flat = p.reshape(-1)
+    for r in range(rows):
+        for k in range(K):
+            assert flat[((k // 32) * rows + r) * 32 + k % 32] == a[r, k]

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from oracle import spts_oracle as orc
-from paper_2601_13155_amd import runtime, synth
+from paper_2601_13155_amd import binding, runtime, synth
 from tests import helpers as H
 
 pytestmark = pytest.mark.gpu
@@ -297,6 +297,57 @@ def test_layer_with_peaked_dominant_attention(torch, name, shape, N, P, r):
     H.lockstep_layer(skip, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 0), shape.dtype)
     kv1 = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=ma, m_ffn=mf, kv_mode=1)
     H.lockstep_layer(kv1, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 1), shape.dtype)
+
+
+def test_pack_slab32_matches_the_host_layout(torch):
+    """spts_pack_slab32 on the device against the same permutation written with numpy (bit-exact), and its error codes."""
+    ctx = ctx_for(synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 2048)
+    rng = np.random.default_rng(3)
+    for rows, K in ((48, 96), (1, 32), (333, 4096), (1024, 512)):
+        a = rng.standard_normal((rows, K)).astype(np.float32)
+        ad = runtime.to_device(a, "bf16")
+        out = torch.zeros_like(ad)
+        ctx.spts_pack_slab32(ad, rows, K, out)
+        torch.cuda.synchronize()
+        want = runtime.pack_slab32(runtime.to_host(ad))
+        assert np.array_equal(runtime.to_host(out), want), (rows, K)
+        # the layout itself, element by element on a sample
+        flat = runtime.to_host(out).reshape(-1)
+        src = runtime.to_host(ad)
+        for r_, k_ in ((0, 0), (rows - 1, K - 1), (rows // 2, 33 % K), (rows - 1, 31)):
+            assert flat[((k_ // 32) * rows + r_) * 32 + k_ % 32] == src[r_, k_]
+    ad = runtime.to_device(rng.standard_normal((8, 48)).astype(np.float32), "bf16")
+    with pytest.raises(binding.SptsError):
+        ctx.spts_pack_slab32(ad, 8, 48, torch.zeros_like(ad))          # K % 32 != 0
+    with pytest.raises(binding.SptsError):
+        ctx.spts_pack_slab32(ad, 0, 32, torch.zeros_like(ad))
+
+
+@pytest.mark.parametrize("name,shape,N,P,r", [
+    ("d128", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 64, 256),
+    ("d64", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16"), 1100, 16, 256),
+], ids=["d128", "d64"])
+def test_layer_with_row_major_weights_only(torch, name, shape, N, P, r):
+    """The other tests upload the slab-major weight copies as well (runtime.upload_layer packs by default), so the
+    prefill GEMMs read the weights through them; here the struct carries the row-major matrices alone.  Both paths
+    against the oracle, skip and dense, and against each other (same products in the same k order; only the K shares
+    of split tiles may group differently)."""
+    ctx = ctx_for(shape, 2048)
+    w, x, pos = _mk(shape, N, r, seed=9)
+    mdl = H.oracle_model(shape)
+    ma, mf = int(0.35 * N), int(0.4 * N)
+    outs = {}
+    for pack in (False, True):
+        dw = runtime.upload_layer(w, shape, r, pack=pack)
+        assert bool(dw.Wgate_s) == pack and bool(dw.Wq_s) == pack
+        skip = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=ma, m_ffn=mf, want_kv=True)
+        H.lockstep_layer(skip, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 0), shape.dtype)
+        dense = runtime.run_layer(ctx, x, pos, dw, shape, skip=0, probe_len=P, m_attn=0, m_ffn=0)
+        H.lockstep_layer(dense, x, pos, w, mdl, orc.LayerCfg(0, P, N, N, 1, 0), shape.dtype)
+        outs[pack] = (skip, dense)
+    for a, b in zip(outs[False], outs[True]):
+        assert H.row_rel_err(a["x"], b["x"]) <= H.TOL["bf16"]["hidden"]
+    assert np.array_equal(outs[False][0]["idx_attn"], outs[True][0]["idx_attn"])
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
