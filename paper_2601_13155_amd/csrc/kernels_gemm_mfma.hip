@@ -468,6 +468,23 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     // ---- the staged tile leaves row by row: NCH consecutive lanes write one row's OUT_COLS columns as
     //      16-byte pieces (whole 128-byte lines), rows through the scatter list when there is one
     __syncthreads();
+    if (EPI == EPI_SILU_MUL && a.c_slab) {
+        // slab-major output: slab sl of the tile is 256 rows x 64 bytes, contiguous over the rows; 4 lanes per row
+        constexpr int RPS = NW * 64 / 4;         // rows per pass
+        const int oc4 = tid & 3, r_in = tid >> 2;
+#pragma unroll
+        for (int sl = 0; sl < OUT_COLS / 32; ++sl)
+#pragma unroll
+            for (int p = 0; p < 256 / RPS; ++p) {
+                const int tr = p * RPS + r_in;
+                const int64_t grow = row0 + tr;
+                if (grow < a.M) {
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(smem + tr * ROWB + ((((sl * 4 + oc4) ^ tr) & (NCH - 1)) << 4));
+                    *reinterpret_cast<u32x4*>(Cb + (((int64_t)(col0 >> 5) + sl) * a.M + grow) * 32 + oc4 * 8) = v;
+                }
+            }
+        return;
+    }
     constexpr int RPP = NW * 64 / NCH;           // rows per pass of the workgroup
     const int oc = tid % NCH, orow = tid / NCH;
 #pragma unroll 4
@@ -497,6 +514,7 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     if ((a.a_slab || a.b_slab) && a.epi != EPI_SILU_MUL && a.epi != EPI_RESIDUAL && a.epi != EPI_STORE && a.epi != EPI_ROPE) return false;
     if (a.a_slab && (a.a_idx || a.A1)) return false;
     if (a.b_slab && (a.b_rows < a.N || (a.epi == EPI_STORE && a.B1))) return false;
+    if (a.c_slab && (a.epi != EPI_SILU_MUL || a.c_idx)) return false;
     if (!al16(a.A) || !al16(a.B0) || (a.A1 && !al16(a.A1)) || (dual && !al16(a.B1))) return false;
     if (a.epi != EPI_SUMSQ) {
         if (a.ldc % 8 != 0 || !al16(a.C)) return false;

@@ -176,6 +176,15 @@ void prefer_slab(const spts_ctx* c, GemmArgs& g, const void* s0, const void* s1,
     if (gemm_mfma_supported(t)) g = t;
 }
 
+// The FFN's hidden activations in slab-major layout when both matrix-core GEMMs take it: gate/up writes them that way
+// and down reads its A operand as whole cache lines (the buffer is the library's own, so the layout is free)
+void hidden_slab(const spts_ctx* c, GemmArgs& gate_up, GemmArgs& down) {
+    if (!c->bf16) return;
+    GemmArgs tg = gate_up, td = down;
+    tg.c_slab = 1; td.a_slab = 1;
+    if (gemm_mfma_supported(tg) && gemm_mfma_supported(td)) { gate_up = tg; down = td; }
+}
+
 // out[rows, heads*d] = rotary(A * B^T); table row of output row i is (tidx ? tidx[i] : i + row0); b_slab: optional
 // slab-major copy of B (heads*d rows)
 int run_gemm_rope(spts_ctx* c, GemmArgs g, int heads, const int32_t* tidx, int64_t row0, void* out, const void* b_slab = nullptr) {
@@ -199,7 +208,7 @@ int check_weights_proxy(const spts_ctx* c, const spts_layer_weights* w) {
     if (!w || !w->gamma2 || !w->Ug || !w->Vg || !w->Uu || !w->Vu || !w->Ud || !w->Vd) return SPTS_EINVAL;
     if (w->r <= 0 || w->Dlow <= 0) return SPTS_EINVAL;
     if (w->r > c->lim.max_r || w->Dlow > c->lim.max_dlow) return SPTS_EWORKSPACE;
-    const void* ps[] = {w->gamma2, w->Ug, w->Vg, w->Uu, w->Vu, w->Ud, w->Vd};
+    const void* ps[] = {w->gamma2, w->Ug, w->Vg, w->Uu, w->Vu, w->Ud, w->Vd, w->Vg_s, w->Vu_s, w->Vd_s};   // the copies may be NULL
     for (const void* p : ps) if (!aligned16(p)) return SPTS_EALIGN;
     return SPTS_OK;
 }
@@ -273,9 +282,12 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
     // hp = silu(tg Vg) * (tu Vu)   [N, Dlow]
     GemmArgs g3 = gemm_args(t, 2 * r, nullptr, w->Vg, r, c->p<void>(c->off.big), Dlow, N, Dlow, r, EPI_SILU_MUL);
     g3.B1 = w->Vu; g3.A1 = t + (size_t)r * eb;
-    { PHASE(c, PH_PROXY_MID); SPTS_TRY(run_gemm(c, g3)); }
+    prefer_slab(c, g3, w->Vg_s, w->Vu_s, Dlow);
     // z = hp Vd^T   [N, r]
     GemmArgs g4 = gemm_args(c->p<void>(c->off.big), Dlow, nullptr, w->Vd, Dlow, c->p<void>(c->off.z), r, N, r, Dlow);
+    prefer_slab(c, g4, w->Vd_s, nullptr, r);
+    hidden_slab(c, g3, g4);
+    { PHASE(c, PH_PROXY_MID); SPTS_TRY(run_gemm(c, g3)); }
     { PHASE(c, PH_PROXY_Z); SPTS_TRY(run_gemm(c, g4)); }
     // o = z Ud^T [N, D] is never stored: per-block sums of squares, then the square root
     GemmArgs g5 = gemm_args(c->p<void>(c->off.z), r, nullptr, w->Ud, r, nullptr, 0, N, m.D, r, EPI_SUMSQ);
@@ -857,10 +869,11 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
     gh.a_rows = N;
     gh.B1 = w->Wup;
     prefer_slab(c, gh, w->Wgate_s, w->Wup_s, m.Dff);
-    { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
     GemmArgs gd = gemm_args(c->p<void>(c->off.big), m.Dff, nullptr, w->Wdown, m.Dff, x, m.D, Mf, m.D, m.Dff, EPI_RESIDUAL);
     gd.c_idx = idxF;
     prefer_slab(c, gd, w->Wdown_s, nullptr, m.D);
+    hidden_slab(c, gh, gd);
+    { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
     { PHASE(c, PH_FFN_DOWN); SPTS_TRY(run_gemm(c, gd)); }
     return SPTS_OK;
 }
@@ -1003,10 +1016,11 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
     gh.a_rows = N;
     gh.B1 = w->Wup;
     prefer_slab(c, gh, w->Wgate_s, w->Wup_s, m.Dff);
-    { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
     GemmArgs gd = gemm_args(c->p<void>(c->off.big), m.Dff, nullptr, w->Wdown, m.Dff, x, m.D, MfT, m.D, m.Dff, EPI_RESIDUAL);
     gd.c_idx = idxF;
     prefer_slab(c, gd, w->Wdown_s, nullptr, m.D);
+    hidden_slab(c, gh, gd);
+    { PHASE(c, PH_FFN_GATE_UP); SPTS_TRY(run_gemm(c, gh)); }
     { PHASE(c, PH_FFN_DOWN); SPTS_TRY(run_gemm(c, gd)); }
     return SPTS_OK;
 }
