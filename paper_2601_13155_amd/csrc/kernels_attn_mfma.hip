@@ -312,14 +312,16 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
         float inv = l > 0.f ? 1.0f / l : 0.f;
         int64_t qi = q0w + qb * 32 + l32;
         if (qi < a.Mq) {
-            bf16_t* orow = O + (qi * a.H + h) * (int64_t)D;
+            // row-major: row qi, columns h*D + 32*db + ...; slab-major: slab h*D/32 + db holds 32 columns of every row
+            bf16_t* orow = a.out_slab ? O + ((int64_t)h * (D / 32) * a.Mq + qi) * 32 : O + (qi * a.H + h) * (int64_t)D;
+            const int64_t dstep = a.out_slab ? a.Mq * 32 : 32;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     u32x2 w = {pk2(o[db][qb][4 * q4] * inv, o[db][qb][4 * q4 + 1] * inv),
                                pk2(o[db][qb][4 * q4 + 2] * inv, o[db][qb][4 * q4 + 3] * inv)};
-                    *reinterpret_cast<u32x2*>(orow + db * 32 + 8 * q4 + 4 * lh) = w;
+                    *reinterpret_cast<u32x2*>(orow + db * dstep + 8 * q4 + 4 * lh) = w;
                 }
         }
     }

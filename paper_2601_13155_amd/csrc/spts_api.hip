@@ -838,15 +838,20 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
             if (amf && !vt_done) SPTS_HIP(c, launch_transpose_pad(vv, c->p<void>(c->off.vt), Mk, KV, aa.ldvt, c->bf16, st));
         }
         if (kv) kv->count = Mk;
+        // x[T_a] += att * Wo^T; the attention output (a buffer of the library's own) goes slab-major when the matrix-core
+        // attention writes it and the matrix-core GEMM reads it
+        GemmArgs go = gemm_args(c->p<void>(c->off.att), QD, nullptr, w->Wo, QD, x, m.D, Ma, m.D, QD, EPI_RESIDUAL);
+        go.c_idx = idxA;
+        prefer_slab(c, go, w->Wo_s, nullptr, m.D);
+        if (amf) {
+            GemmArgs t = go; t.a_slab = 1;
+            if (gemm_mfma_supported(t)) { go = t; aa.out_slab = 1; }
+        }
         {
             PHASE(c, PH_ATTENTION);
             if (amf) SPTS_HIP(c, launch_attention_mfma(aa, st));
             else SPTS_HIP(c, launch_attention_generic(aa, c->bf16, st));
         }
-        // x[T_a] += att * Wo^T
-        GemmArgs go = gemm_args(c->p<void>(c->off.att), QD, nullptr, w->Wo, QD, x, m.D, Ma, m.D, QD, EPI_RESIDUAL);
-        go.c_idx = idxA;
-        prefer_slab(c, go, w->Wo_s, nullptr, m.D);
         { PHASE(c, PH_O_PROJ); SPTS_TRY(run_gemm(c, go)); }
     }
 

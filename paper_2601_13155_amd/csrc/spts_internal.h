@@ -149,6 +149,7 @@ struct AttnArgs {
     const int32_t* qpos; const int32_t* kpos;  // ascending absolute positions
     void* out;      // [Mq, H, d]
     int64_t Mq, Mk; int H, Hkv, d;
+    int out_slab;   // matrix-core path only: out written slab-major [H*d/32][Mq][32] (A operand of an a_slab GEMM)
 };
 hipError_t launch_attention_generic(const AttnArgs& a, bool bf16, hipStream_t s);
 bool attention_mfma_supported(const AttnArgs& a);
