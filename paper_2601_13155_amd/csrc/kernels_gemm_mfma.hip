@@ -468,7 +468,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     // ---- the staged tile leaves row by row: NCH consecutive lanes write one row's OUT_COLS columns as
     //      16-byte pieces (whole 128-byte lines), rows through the scatter list when there is one
     __syncthreads();
-    if (EPI == EPI_SILU_MUL && a.c_slab) {
+    if ((EPI == EPI_SILU_MUL || EPI == EPI_STORE) && a.c_slab) {
         // slab-major output: slab sl of the tile is 256 rows x 64 bytes, contiguous over the rows; 4 lanes per row
         constexpr int RPS = NW * 64 / 4;         // rows per pass
         const int oc4 = tid & 3, r_in = tid >> 2;
@@ -512,9 +512,9 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     if (a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
     // slab-major operands: served by the 32-wide-slab instantiations; A not gathered, B one matrix (two for SiLU)
     if ((a.a_slab || a.b_slab) && a.epi != EPI_SILU_MUL && a.epi != EPI_RESIDUAL && a.epi != EPI_STORE && a.epi != EPI_ROPE) return false;
-    if (a.a_slab && (a.a_idx || a.A1)) return false;
+    if (a.a_slab && a.a_idx) return false;
     if (a.b_slab && (a.b_rows < a.N || (a.epi == EPI_STORE && a.B1))) return false;
-    if (a.c_slab && (a.epi != EPI_SILU_MUL || a.c_idx)) return false;
+    if (a.c_slab && ((a.epi != EPI_SILU_MUL && a.epi != EPI_STORE) || a.c_idx || a.Ct)) return false;
     if (!al16(a.A) || !al16(a.B0) || (a.A1 && !al16(a.A1)) || (dual && !al16(a.B1))) return false;
     if (a.epi != EPI_SUMSQ) {
         if (a.ldc % 8 != 0 || !al16(a.C)) return false;
@@ -585,7 +585,10 @@ __global__ void __launch_bounds__(256) splitk_finish_kernel(GemmArgs a, int nM, 
         const f32x4 s = quad(j);
         const int col = col0 + wn * 128 + j * 32 + 4 * lh + 8 * q;
         u32x2 o = {pack_bf16x2(s.x, s.y), pack_bf16x2(s.z, s.w)};
-        if (rok) *reinterpret_cast<u32x2*>(Cb + crow * a.ldc + col) = o;
+        if (rok) {
+            if (a.c_slab) *reinterpret_cast<u32x2*>(Cb + ((int64_t)(col >> 5) * a.M + grow) * 32 + (col & 31)) = o;   // slab-major C
+            else *reinterpret_cast<u32x2*>(Cb + crow * a.ldc + col) = o;
+        }
         if (a.Ct && grow < a.ldct) {
             bf16_t* ct = (bf16_t*)a.Ct;
             const uint16_t e[4] = {(uint16_t)(o.x & 0xffff), (uint16_t)(o.x >> 16), (uint16_t)(o.y & 0xffff), (uint16_t)(o.y >> 16)};

@@ -265,20 +265,6 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
     const int r = w->r, Dlow = w->Dlow;
     const size_t eb = c->bf16 ? 2 : 4;
     char* t = c->p<char>(c->off.t);  // [N, 2r]: columns [0,r) = x Ug, [r,2r) = x Uu
-    {
-        PHASE(c, PH_PROXY_IN);
-        // one launch for both factors when the matrix-core kernel takes it (columns [0,r) from Ug, [r,2r) from Uu)
-        GemmArgs g12 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, 2 * r, m.D);
-        g12.B1 = w->Uu;
-        if (c->bf16 && gemm_mfma_supported(g12)) {
-            SPTS_TRY(run_gemm_mfma(c, g12));
-        } else {
-            GemmArgs g1 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, r, m.D);
-            SPTS_TRY(run_gemm(c, g1));
-            GemmArgs g2 = gemm_args(xn2, m.D, nullptr, w->Uu, m.D, t + (size_t)r * eb, 2 * r, N, r, m.D);
-            SPTS_TRY(run_gemm(c, g2));
-        }
-    }
     // hp = silu(tg Vg) * (tu Vu)   [N, Dlow]
     GemmArgs g3 = gemm_args(t, 2 * r, nullptr, w->Vg, r, c->p<void>(c->off.big), Dlow, N, Dlow, r, EPI_SILU_MUL);
     g3.B1 = w->Vu; g3.A1 = t + (size_t)r * eb;
@@ -287,6 +273,25 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
     GemmArgs g4 = gemm_args(c->p<void>(c->off.big), Dlow, nullptr, w->Vd, Dlow, c->p<void>(c->off.z), r, N, r, Dlow);
     prefer_slab(c, g4, w->Vd_s, nullptr, r);
     hidden_slab(c, g3, g4);
+    {
+        PHASE(c, PH_PROXY_IN);
+        // one launch for both factors when the matrix-core kernel takes it (columns [0,r) from Ug, [r,2r) from Uu)
+        GemmArgs g12 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, 2 * r, m.D);
+        g12.B1 = w->Uu;
+        if (c->bf16 && gemm_mfma_supported(g12)) {
+            // t slab-major between the two launches when both take it: [2r/32][N][32], t_u starts r/32 slabs in
+            GemmArgs s12 = g12, s3 = g3;
+            s12.c_slab = 1;
+            s3.a_slab = 1; s3.A1 = t + (size_t)(r / 32) * (size_t)N * 64;
+            if (r % 32 == 0 && gemm_mfma_supported(s12) && gemm_mfma_supported(s3)) { g12 = s12; g3 = s3; }
+            SPTS_TRY(run_gemm_mfma(c, g12));
+        } else {
+            GemmArgs g1 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, r, m.D);
+            SPTS_TRY(run_gemm(c, g1));
+            GemmArgs g2 = gemm_args(xn2, m.D, nullptr, w->Uu, m.D, t + (size_t)r * eb, 2 * r, N, r, m.D);
+            SPTS_TRY(run_gemm(c, g2));
+        }
+    }
     { PHASE(c, PH_PROXY_MID); SPTS_TRY(run_gemm(c, g3)); }
     { PHASE(c, PH_PROXY_Z); SPTS_TRY(run_gemm(c, g4)); }
     // o = z Ud^T [N, D] is never stored: per-block sums of squares, then the square root

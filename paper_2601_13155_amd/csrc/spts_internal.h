@@ -92,7 +92,8 @@ struct GemmArgs {
     // (pack_slab32 of the row-major matrix), so that the 16 rows a load instruction moves are 1 KB of whole cache lines
     // instead of 64-byte halves of 16 lines.  a_slab excludes a_idx (the packed copy is already gathered).
     int32_t a_slab; int32_t b_slab; int64_t b_rows;
-    int32_t c_slab;   // EPI_SILU_MUL: C written slab-major [N/32][M][32] (the A operand of a following a_slab GEMM); no c_idx
+    int32_t c_slab;   // EPI_SILU_MUL / EPI_STORE: C written slab-major [N/32][M][32] (the A operand of a following a_slab GEMM);
+                      // no c_idx, no Ct
 };
 // Split plan for a GEMM of this shape on a 256-CU device: returns ksplit (1 = do not split) and
 // sets *nfull; needs (tiles - nfull) * ksplit * 65536 floats of part32.
