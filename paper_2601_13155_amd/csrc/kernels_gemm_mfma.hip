@@ -24,6 +24,14 @@
 //  * Fragment reads of the next k-step are issued between the MFMAs of the current one
 //    (sched_group_barrier pins the interleaving); the barrier sits a few MFMAs into the second
 //    k-step so that the matrix pipe stays fed while wavefronts meet.
+//  * Slab-major operands.  With row-major operands and slabs of 32 a load instruction takes 64 bytes of each of 16
+//    rows, so every 128-byte line is requested twice (by the loads of two consecutive slabs) and the kernel is bound
+//    by L2 requests (measured: whole-line loads of the same data are 8-9 % faster, per operand).  An operand stored
+//    [K/32][rows][32] (64 bytes per row and slab, neighbouring rows adjacent) makes the same 16 rows 1 KB of whole
+//    lines; only the addresses differ (row pitch 64 bytes, slab pitch rows * 64 bytes), the LDS image and the order
+//    of the products do not.  B: slab-major weight copies (b_slab); A: activations that another kernel of this library
+//    wrote slab-major (a_slab; the SiLU and store epilogues and the split-K finish write such a C on request, c_slab).
+//    Calls with slab operands run the 32-wide, 4-stage instantiation whatever K is.
 //  * Rows of A may be gathered through an index list (the active-token gather of Eq. (skip) is
 //    folded into the A loads: a row is 2*K contiguous bytes, so nothing is lost in coalescing),
 //    rows of C may be scattered through one (the residual update X[T] += ...).
