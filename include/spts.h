@@ -76,13 +76,13 @@ typedef struct {
     const void *Ug, *Vg, *Uu, *Vu, *Ud, *Vd;
     int32_t r;    /* proxy rank                         */
     int32_t Dlow; /* proxy inner dimension (<= Dff)     */
-    /* Optional slab-major copies of the projection / FFN matrices and of three proxy factors made by spts_pack_slab32 (NULL = none; bf16 only).
+    /* Optional slab-major copies of the projection / FFN matrices and of five proxy factors made by spts_pack_slab32 (NULL = none; bf16 only).
      * The prefill calls read a matrix through its copy where their matrix-core GEMM takes it (same arithmetic, same
      * results; the copy only changes which bytes a load instruction fetches together); the decode calls and the fp32
      * path always read the row-major originals, which must be given in any case.  Wgate_s and Wup_s go together, and
-     * so do Vg_s and Vu_s. */
+     * so do Vg_s and Vu_s, and Ug_s and Uu_s. */
     const void *Wq_s, *Wk_s, *Wv_s, *Wo_s, *Wgate_s, *Wup_s, *Wdown_s;
-    const void *Vg_s, *Vu_s, *Vd_s;
+    const void *Vg_s, *Vu_s, *Vd_s, *Ug_s, *Uu_s;
 } spts_layer_weights;
 
 /* Per-layer control (Alg. 1: skip flag, budgets M_fixed; Sec. 3.4). */

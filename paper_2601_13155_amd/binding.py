@@ -35,7 +35,7 @@ class spts_model_desc(C.Structure):
 class spts_layer_weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("Wq", "Wk", "Wv", "Wo", "gamma1", "Wgate", "Wup", "Wdown", "gamma2",
                                            "Ug", "Vg", "Uu", "Vu", "Ud", "Vd")] + [("r", C.c_int32), ("Dlow", C.c_int32)] + \
-               [(n, C.c_void_p) for n in ("Wq_s", "Wk_s", "Wv_s", "Wo_s", "Wgate_s", "Wup_s", "Wdown_s", "Vg_s", "Vu_s", "Vd_s")]
+               [(n, C.c_void_p) for n in ("Wq_s", "Wk_s", "Wv_s", "Wo_s", "Wgate_s", "Wup_s", "Wdown_s", "Vg_s", "Vu_s", "Vd_s", "Ug_s", "Uu_s")]
 
 
 class spts_layer_cfg(C.Structure):

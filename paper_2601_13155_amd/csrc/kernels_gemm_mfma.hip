@@ -518,10 +518,10 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     if (a.M <= 0 || a.N <= 0 || a.N % ncols != 0) return false;
     if (a.K < 32 || a.K % 32 != 0) return false;
     if (a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
-    // slab-major operands: served by the 32-wide-slab instantiations; A not gathered, B one matrix (two for SiLU)
+    // slab-major operands: served by the 32-wide-slab instantiations; A not gathered
     if ((a.a_slab || a.b_slab) && a.epi != EPI_SILU_MUL && a.epi != EPI_RESIDUAL && a.epi != EPI_STORE && a.epi != EPI_ROPE) return false;
     if (a.a_slab && a.a_idx) return false;
-    if (a.b_slab && (a.b_rows < a.N || (a.epi == EPI_STORE && a.B1))) return false;
+    if (a.b_slab && a.b_rows < (a.epi == EPI_STORE && a.B1 ? a.N / 2 : a.N)) return false;   // rows of each B matrix
     if (a.c_slab && ((a.epi != EPI_SILU_MUL && a.epi != EPI_STORE) || a.c_idx || a.Ct)) return false;
     if (!al16(a.A) || !al16(a.B0) || (a.A1 && !al16(a.A1)) || (dual && !al16(a.B1))) return false;
     if (a.epi != EPI_SUMSQ) {

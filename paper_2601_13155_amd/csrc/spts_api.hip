@@ -208,7 +208,7 @@ int check_weights_proxy(const spts_ctx* c, const spts_layer_weights* w) {
     if (!w || !w->gamma2 || !w->Ug || !w->Vg || !w->Uu || !w->Vu || !w->Ud || !w->Vd) return SPTS_EINVAL;
     if (w->r <= 0 || w->Dlow <= 0) return SPTS_EINVAL;
     if (w->r > c->lim.max_r || w->Dlow > c->lim.max_dlow) return SPTS_EWORKSPACE;
-    const void* ps[] = {w->gamma2, w->Ug, w->Vg, w->Uu, w->Vu, w->Ud, w->Vd, w->Vg_s, w->Vu_s, w->Vd_s};   // the copies may be NULL
+    const void* ps[] = {w->gamma2, w->Ug, w->Vg, w->Uu, w->Vu, w->Ud, w->Vd, w->Vg_s, w->Vu_s, w->Vd_s, w->Ug_s, w->Uu_s};   // the copies may be NULL
     for (const void* p : ps) if (!aligned16(p)) return SPTS_EALIGN;
     return SPTS_OK;
 }
@@ -278,6 +278,7 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
         // one launch for both factors when the matrix-core kernel takes it (columns [0,r) from Ug, [r,2r) from Uu)
         GemmArgs g12 = gemm_args(xn2, m.D, nullptr, w->Ug, m.D, t, 2 * r, N, 2 * r, m.D);
         g12.B1 = w->Uu;
+        prefer_slab(c, g12, w->Ug_s, w->Uu_s, r);
         if (c->bf16 && gemm_mfma_supported(g12)) {
             // t slab-major between the two launches when both take it: [2r/32][N][32], t_u starts r/32 slabs in
             GemmArgs s12 = g12, s3 = g3;

@@ -34,7 +34,7 @@ def make_context(shape, max_tokens: int, max_probe: int, max_r: int, max_dlow: i
     return binding.Context(shape, max_tokens, max_probe, max_r, max_dlow)
 
 
-SLAB_PACKED = ("Wq", "Wk", "Wv", "Wo", "Wgate", "Wup", "Wdown", "Vg", "Vu", "Vd")
+SLAB_PACKED = ("Wq", "Wk", "Wv", "Wo", "Wgate", "Wup", "Wdown", "Vg", "Vu", "Vd", "Ug", "Uu")
 
 
 def pack_slab32(a: np.ndarray) -> np.ndarray:
