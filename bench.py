@@ -503,7 +503,8 @@ def main():
                    "attn_keep": wl.attn_keep, "ffn_keep": wl.ffn_keep, "proxy_rank": wl.r, "proxy_dlow": Dlow,
                    "dense_layers": wl.dense_layers, "stage_budgets": list(wl.stage_budgets), "stage_prune": wl.stage_prune,
                    "stage_end_layers": list(wl.stage_end_layers), "stage_cum_keep": list(wl.stage_cum_keep),
-                   "components": wl.components, "weight_pool": pool, "batch": 1},
+                   "components": wl.components, "weight_pool": pool, "batch": 1,
+                   "weight_layout": "row-major" if args.row_major_weights else "row-major + slab-major copies (spts_pack_slab32)"},
         "algorithmic_tflop_per_step": total_flops / 1e12,
         "achieved_tflops_whole_step": total_flops / (ms * 1e-3) / 1e12,
         "roofline": roofline, "cpu_baseline": cpu, "dense": dense, "phases": phase_out, "topk_batched": topk_batched, "decode": decode, "proxy_builder": builder, "ablation": ablation, "batched_layer": batched,
