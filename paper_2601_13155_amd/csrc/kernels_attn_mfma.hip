@@ -304,25 +304,54 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
     // the slot after the last block of a wavefront that worked through the last tile
     if (n_tiles > 0) SPTS_ATT_BLOCK(2 * n_tiles, sa, sb, pfa, pfb)
 
-    // ---- normalise and store: lane holds 4 consecutive value columns of its query per r/4
+    // ---- normalise and store.  A lane holds 4 consecutive value columns of its query per r/4, i.e. a store from the
+    //      fragment layout would carry 16-byte pieces of 32 rows per instruction; the wavefront's 32 x D tile goes
+    //      through LDS instead (the ring is free once every wavefront is past its last fragment read; a wavefront
+    //      uses its own 32 * D * 2 bytes) and leaves as whole lines.  Chunk c (16 bytes) of row r sits at c ^ (r % NCH).
+    static_assert(QB == 1, "one 32-query block per wavefront");
+    constexpr int NCH = D / 8;                       // 16-byte chunks per row
     bf16_t* O = (bf16_t*)a.out;
+    __syncthreads();
+    char* stg = smem + (size_t)wave * (32 * D * 2);
+    {
+        const float l = l_run[0] + __shfl_xor(l_run[0], 32);
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        float l = l_run[qb] + __shfl_xor(l_run[qb], 32);
-        float inv = l > 0.f ? 1.0f / l : 0.f;
-        int64_t qi = q0w + qb * 32 + l32;
-        if (qi < a.Mq) {
-            // row-major: row qi, columns h*D + 32*db + ...; slab-major: slab h*D/32 + db holds 32 columns of every row
-            bf16_t* orow = a.out_slab ? O + ((int64_t)h * (D / 32) * a.Mq + qi) * 32 : O + (qi * a.H + h) * (int64_t)D;
-            const int64_t dstep = a.out_slab ? a.Mq * 32 : 32;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int q4 = 0; q4 < 4; ++q4) {
+                u32x2 w = {pk2(o[db][0][4 * q4] * inv, o[db][0][4 * q4 + 1] * inv),
+                           pk2(o[db][0][4 * q4 + 2] * inv, o[db][0][4 * q4 + 3] * inv)};
+                *reinterpret_cast<u32x2*>(stg + l32 * (D * 2) + ((((db * 4 + q4) ^ l32) & (NCH - 1)) << 4) + lh * 8) = w;
+            }
+    }
+    __syncthreads();
+    if (a.out_slab) {
+        // slab h*D/32 + sl holds 32 columns of every row: 4 lanes per row, 16 rows = 1 KB contiguous per instruction
+        const int c4 = lane & 3;
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    u32x2 w = {pk2(o[db][qb][4 * q4] * inv, o[db][qb][4 * q4 + 1] * inv),
-                               pk2(o[db][qb][4 * q4 + 2] * inv, o[db][qb][4 * q4 + 3] * inv)};
-                    *reinterpret_cast<u32x2*>(orow + db * dstep + 8 * q4 + 4 * lh) = w;
+        for (int sl = 0; sl < DB; ++sl)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int r = p * 16 + (lane >> 2);
+                const int64_t qi = q0w + r;
+                if (qi < a.Mq) {
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + r * (D * 2) + ((((sl * 4 + c4) ^ r) & (NCH - 1)) << 4));
+                    *reinterpret_cast<u32x4*>(O + (((int64_t)h * DB + sl) * a.Mq + qi) * 32 + c4 * 8) = v;
                 }
+            }
+    } else {
+        // row-major: NCH lanes per row write this head's D columns of it
+        constexpr int RPP = 64 / NCH;                // rows per pass
+        const int c = lane % NCH;
+#pragma unroll
+        for (int p = 0; p < 32 / RPP; ++p) {
+            const int r = p * RPP + lane / NCH;
+            const int64_t qi = q0w + r;
+            if (qi < a.Mq) {
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stg + r * (D * 2) + (((c ^ r) & (NCH - 1)) << 4));
+                *reinterpret_cast<u32x4*>(O + (qi * a.H + h) * (int64_t)D + c * 8) = v;
+            }
         }
     }
 }
