@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E (published)
 # counter runs (FETCH_SIZE, WRITE_SIZE) of this script scaled by the readings of a plain 1 GiB elementwise
 # kernel (--calibrate-copy); the summary with the commands is profiles/c2_ffn_gate_up_hbm_traffic.txt.
 # Counters cannot be read from inside this process, so workloads without a committed counter run report null.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"c2": 3.2980e9}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"c2": 3.3393e9}
 
 
 def log(*a):
