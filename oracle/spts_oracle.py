@@ -48,6 +48,10 @@ composition of torch CPU fp64 routines; keep=1 == dense; keep=0 == identity;
 sum(S) == 1 and the P=1 score against the last row of a brute-force attention
 matrix; full-rank proxy == exact FFN norm; TopK against a stable sort;
 permutation invariance with positions attached; FFN token independence.
+Pins (tests/test_oracle_ltp_pins.py): the layer's LTP decision, TopK of C^FFN * S^MHA with the
+pre-attention score and the post-attention proxy norm, against a torch composition of the attention
+half, a scalar-loop proxy and a Python sort; a constant-C layer (set = TopK of S^MHA) and a flat-S
+layer (set = TopK of C^FFN).
 Numerical values of scores/selected sets on real text are not printed anywhere
 in the paper: parity unpinned for those (only the properties above pin them).
 
