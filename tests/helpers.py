@@ -62,18 +62,39 @@ def count_swaps(idx_gpu, idx_ref, scores_ref, band, protect_last=1):
     return len(diff) // 2
 
 
-def lockstep_layer(gpu, x, pos, w, mdl, cfg, dtype):
+def swap_bound(m, dtype):
+    """Largest number of near-tie swaps a selection of m indices may show: none in fp32, m/50 (at least 1) in bf16."""
+    return 0 if dtype == "f32" else max(1, int(m) // 50)
+
+
+def lockstep_layer(gpu, x, pos, w, mdl, cfg, dtype, rnd=None):
     """Lock-step parity of one layer in a single oracle pass: at each selection point the oracle's own
     set is compared with the GPU's (near-tie swaps counted, anything else fails), then the oracle
     adopts the GPU's set so that the hidden states stay like-for-like.
-    Returns dict(swaps_attn, swaps_ffn, err, ref)."""
-    rnd = rnd_for(dtype)
+
+    Bars: S^MHA element-wise within the score tolerance; the attention set must be the TopK of the GPU's own
+    stored scores (the decision itself is exact), so an index may differ from the oracle's only if its oracle
+    score lies within 2e/(1-e) of the oracle's k-th score, e being the *measured* score error; the FFN set within the score
+    tolerance of the k-th score; at most swap_bound() swaps per selection; hidden states within the tolerance.
+    `rnd` overrides the oracle's rounding hook (default: identity for fp32, bf16 rounding at the store points
+    for bf16; pass orc.identity to compare a bf16 run with the plain fp64 algorithm).
+    Returns dict(swaps_attn, swaps_ffn, err, s_err, ref)."""
+    rnd = rnd_for(dtype) if rnd is None else rnd
     tol = TOL[dtype]
     swaps = {"attn": 0, "ffn": 0}
+    s_err = [0.0]
 
     def adopt(which, gpu_idx):
         def hook(scores, own):
-            swaps[which] = count_swaps(gpu_idx, own, scores, tol["score"], cfg.protect_last)
+            band = tol["score"]
+            if which == "attn":
+                s_err[0] = score_rel_err(gpu["s_mha"], scores)
+                assert s_err[0] <= tol["score"], f"S^MHA out of tolerance: {s_err[0]}"
+                assert np.array_equal(gpu_idx, orc.topk_select(gpu["s_mha"], len(own), cfg.protect_last)), \
+                    "attention set is not the TopK of the GPU's own scores"
+                band = min(band, 2.0 * s_err[0] / (1.0 - s_err[0]) * (1.0 + 1e-6) + 1e-12)
+            swaps[which] = count_swaps(gpu_idx, own, scores, band, cfg.protect_last)
+            assert swaps[which] <= swap_bound(len(own), dtype), f"{which}: {swaps[which]} near-tie swaps of {len(own)}"
             return gpu_idx
         return hook
 
@@ -81,8 +102,6 @@ def lockstep_layer(gpu, x, pos, w, mdl, cfg, dtype):
     if cfg.skip:
         kw = dict(force_idx_attn=adopt("attn", gpu["idx_attn"]), force_idx_ffn=adopt("ffn", gpu["idx_ffn"]))
     ref = orc.layer_prefill(x, pos, w, mdl, cfg, rnd=rnd, score_cast=orc.f32_round, **kw)
-    if cfg.skip:
-        assert score_rel_err(gpu["s_mha"], ref.s_mha) <= tol["score"], "S^MHA out of tolerance"
     err = row_rel_err(gpu["x"], ref.x)
     assert err <= tol["hidden"], f"hidden states: row-relative error {err}"
-    return dict(swaps_attn=swaps["attn"], swaps_ffn=swaps["ffn"], err=err, ref=ref)
+    return dict(swaps_attn=swaps["attn"], swaps_ffn=swaps["ffn"], err=err, s_err=s_err[0], ref=ref)

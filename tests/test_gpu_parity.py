@@ -251,6 +251,30 @@ def test_layer_prefill_lockstep(torch, name, shape, N, P, r, ka, kf):
 @pytest.mark.parametrize("name,shape,N,P,r", [
     ("d128", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 64, 256),
     ("d64", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16"), 1100, 16, 256),
+    ("generic", H.small_shape(dtype="bf16"), 130, 4, 8),
+], ids=["d128", "d64", "generic"])
+def test_bf16_layer_against_the_plain_fp64_algorithm(torch, name, shape, N, P, r):
+    """The bf16 layer against the layer exactly as the paper defines it: the oracle in plain fp64 with NO rounding at
+    any intermediate (rnd = identity); only the inputs are bf16 values.  Same bars as the bf16-faithful runs: scores
+    and hidden states within 2e-2, selections up to counted near-tie swaps; skip branch and dense branch."""
+    ctx = ctx_for(shape, 2048)
+    w, x, pos = _mk(shape, N, r, seed=12)
+    dw = runtime.upload_layer(w, shape, r)
+    mdl = H.oracle_model(shape)
+    ma, mf = int(0.4 * N), int(0.4 * N)
+    skip = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=ma, m_ffn=mf, want_kv=True)
+    res = H.lockstep_layer(skip, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 0), shape.dtype, rnd=orc.identity)
+    print(f"{name} vs plain fp64: swaps attn={res['swaps_attn']} ffn={res['swaps_ffn']} score err={res['s_err']:.2e} hidden err={res['err']:.2e}")
+    tol = H.TOL["bf16"]["hidden"]
+    assert H.row_rel_err(skip["k_cache"].reshape(ma, -1), res["ref"].k_cache.reshape(ma, -1)) <= tol
+    assert H.row_rel_err(skip["v_cache"].reshape(ma, -1), res["ref"].v_cache.reshape(ma, -1)) <= tol
+    dense = runtime.run_layer(ctx, x, pos, dw, shape, skip=0, probe_len=P, m_attn=0, m_ffn=0)
+    H.lockstep_layer(dense, x, pos, w, mdl, orc.LayerCfg(0, P, N, N, 1, 0), shape.dtype, rnd=orc.identity)
+
+
+@pytest.mark.parametrize("name,shape,N,P,r", [
+    ("d128", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 64, 256),
+    ("d64", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16"), 1100, 16, 256),
 ], ids=["d128", "d64"])
 def test_layer_modes_on_matrix_core_kernels(torch, name, shape, N, P, r):
     """The matrix-core attention with separate query / key sets (kv_mode = 1: active queries against the keys
