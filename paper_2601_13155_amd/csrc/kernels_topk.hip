@@ -242,6 +242,191 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
+// One problem spread over the chip (N up to TOPK_MULTI_MAX_N): the same radix select, but every 8-bit
+// pass is its own launch of G workgroups, and no workgroup ever communicates with another one inside
+// a launch: no atomics, no fences, no counters, nothing to clear between calls.  Workgroup g owns the
+// contiguous slice [g * 1024 * KPT, (g + 1) * 1024 * KPT) (keys in registers for the duration of a
+// launch), counts its share of the current digit into a private LDS histogram and stores those 256
+// counters as row g of a table in the scratch.  The NEXT launch starts with every workgroup adding
+// up the G rows for itself (G * 1 KB from L2, sixteen 16-byte loads in flight per lane) and picking
+// the bin -- all workgroups reach the same (prefix, need) because the sums are integers -- before it
+// counts the next digit into the other of two tables.  The fifth launch picks the last digit, turns
+// the last table into its own output offsets (keys above the threshold and keys equal to it in the
+// slices before its own) and writes its piece of the ascending index list.
+struct TopkMultiScratch {
+    int32_t rows[2][TOPK_MULTI_MAX_WG][256];   // histogram rows of the even / odd passes
+    int32_t gt_hi[TOPK_MULTI_MAX_WG];          // last pass: keys of the slice whose decided 24 bits exceed the prefix
+    uint32_t prefix[4]; int32_t need[4];       // state after pass p (written by workgroup 0 of launch p + 1)
+};
+static_assert(sizeof(TopkMultiScratch) <= TOPK_MULTI_SCRATCH_BYTES, "scratch size constant too small");
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// hist[0..256) = column sums of the G rows of `table`; all 1024 lanes take part, ends with a barrier
+__device__ inline void topk_sum_rows(const int32_t (*table)[256], int G, int (*part)[256], int* hist) {
+    const int tid = threadIdx.x;
+    const int c4 = (tid & 63) * 4;
+    i32x4 sum = {0, 0, 0, 0};
+    for (int r = tid >> 6; r < G; r += 16) sum += *(const i32x4*)&table[r][c4];
+    *(i32x4*)&part[tid >> 6][c4] = sum;
+    __syncthreads();
+    if (tid < 256) {
+        int t = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t += part[q][tid];
+        hist[tid] = t;
+    }
+    __syncthreads();
+}
+
+template <int KPT>
+__global__ void __launch_bounds__(TOPK_THREADS) topk_multi_hist_kernel(const float* __restrict__ scores, int N, int k,
+                                                                       int protect_last, TopkMultiScratch* scr, int pass) {
+    __shared__ int hist[256];
+    __shared__ __attribute__((aligned(16))) int part[16][256];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int64_t sh_need;
+    __shared__ int wave_cnt[TOPK_WAVES];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x, G = gridDim.x;
+    const int lo = g * (1024 * KPT) + wave * (64 * KPT);
+    uint32_t keys[KPT];
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int i = lo + 64 * j + lane;
+        keys[j] = i < N ? load_key(scores, i, N, protect_last) : 0u;
+    }
+    // state after the previous pass: the bin choice the previous launch's table implies
+    uint32_t prefix = 0u;
+    int64_t need = k;
+    if (pass > 0) {
+        if (pass > 1) { prefix = scr->prefix[pass - 2]; need = scr->need[pass - 2]; }
+        if (tid == 0) { sh_prefix = prefix; sh_need = need; }
+        topk_sum_rows(scr->rows[(pass - 1) & 1], G, part, hist);
+        if (wave == 0) pick_bin(hist, lane, 24 - 8 * (pass - 1), prefix, need, &sh_prefix, &sh_need);
+        __syncthreads();
+        prefix = sh_prefix;
+        need = sh_need;
+        if (g == 0 && tid == 0) { scr->prefix[pass - 1] = prefix; scr->need[pass - 1] = (int32_t)need; }
+    }
+    const int shift = 24 - 8 * pass;
+    const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    __syncthreads();
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    int cgt = 0;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const bool valid = lo + 64 * j + lane < N;
+        hist_add(hist, valid && (keys[j] & hi_mask) == prefix, (int)((keys[j] >> shift) & 0xFF));
+        if (pass == 3) cgt += (int)__popcll(__ballot(valid && (keys[j] & hi_mask) > prefix));
+    }
+    if (lane == 0) wave_cnt[wave] = cgt;
+    __syncthreads();
+    if (tid < 256) scr->rows[pass & 1][g][tid] = hist[tid];
+    if (tid == 0 && pass == 3) {
+        int t = 0;
+        for (int w = 0; w < TOPK_WAVES; ++w) t += wave_cnt[w];
+        scr->gt_hi[g] = t;
+    }
+}
+
+template <int KPT>
+__global__ void __launch_bounds__(TOPK_THREADS) topk_multi_write_kernel(const float* __restrict__ scores, int N, int protect_last,
+                                                                        const TopkMultiScratch* scr, int32_t* __restrict__ idx_out) {
+    __shared__ int hist[256];
+    __shared__ __attribute__((aligned(16))) int part[16][256];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int64_t sh_need;
+    __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
+    __shared__ int red_gt[TOPK_WAVES], red_eq[TOPK_WAVES];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x, G = gridDim.x;
+    const int lo = g * (1024 * KPT) + wave * (64 * KPT);
+    uint32_t keys[KPT];
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int i = lo + 64 * j + lane;
+        keys[j] = i < N ? load_key(scores, i, N, protect_last) : 0u;
+    }
+    // the last digit: threshold key T and the number of keys equal to T still to be taken
+    const int32_t (*table)[256] = scr->rows[1];
+    {
+        const uint32_t prefix = scr->prefix[2];
+        const int64_t need = scr->need[2];
+        if (tid == 0) { sh_prefix = prefix; sh_need = need; }
+        topk_sum_rows(table, G, part, hist);
+        if (wave == 0) pick_bin(hist, lane, 0, prefix, need, &sh_prefix, &sh_need);
+        __syncthreads();
+    }
+    const uint32_t T = sh_prefix;
+    const int need_eq = (int)sh_need;
+    const int digit = (int)(T & 0xFFu);
+    // keys above T / equal to T in the slices before this one: eight lanes per row of the table, each 32 consecutive
+    // bins (eight 16-byte loads), rows at or beyond g contribute nothing
+    int row_gt = 0, row_eq = 0;
+    {
+        const int r = tid >> 3, sub = tid & 7;
+        if (r < g) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int b = sub * 32 + q * 4;
+                const i32x4 v = *(const i32x4*)&table[r][b];
+                row_gt += (b > digit ? v[0] : 0) + (b + 1 > digit ? v[1] : 0) + (b + 2 > digit ? v[2] : 0) + (b + 3 > digit ? v[3] : 0);
+            }
+            if (sub == 0) { row_gt += scr->gt_hi[r]; row_eq = table[r][digit]; }
+        }
+    }
+    int cgt = 0, ceq = 0;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const bool valid = lo + 64 * j + lane < N;
+        cgt += (int)__popcll(__ballot(valid && keys[j] > T));
+        ceq += (int)__popcll(__ballot(valid && keys[j] == T));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { row_gt += __shfl_xor(row_gt, off); row_eq += __shfl_xor(row_eq, off); }
+    if (lane == 0) { wave_gt[wave] = cgt; wave_eq[wave] = ceq; red_gt[wave] = row_gt; red_eq[wave] = row_eq; }
+    __syncthreads();
+    int gt_before = 0, eq_before = 0;
+    for (int w = 0; w < TOPK_WAVES; ++w) { gt_before += red_gt[w]; eq_before += red_eq[w]; }
+    for (int w = 0; w < wave; ++w) { gt_before += wave_gt[w]; eq_before += wave_eq[w]; }
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int i = lo + 64 * j + lane;
+        const bool valid = i < N;
+        const bool gt = valid && keys[j] > T, eq = valid && keys[j] == T;
+        const uint64_t mgt = __ballot(gt), meq = __ballot(eq);
+        const int my_gt = gt_before + lane_prefix_popc(mgt);
+        const int my_eq = eq_before + lane_prefix_popc(meq);
+        if (gt || (eq && my_eq < need_eq)) idx_out[my_gt + (my_eq < need_eq ? my_eq : need_eq)] = i;
+        gt_before += (int)__popcll(mgt);
+        eq_before += (int)__popcll(meq);
+    }
+}
+
+template <int KPT>
+static hipError_t topk_multi_launch(const float* scores, int N, int k, int protect_last, int32_t* idx_out,
+                                    TopkMultiScratch* scr, hipStream_t s) {
+    const int G = (N + 1024 * KPT - 1) / (1024 * KPT);
+    for (int pass = 0; pass < 4; ++pass)
+        topk_multi_hist_kernel<KPT><<<dim3(G), dim3(TOPK_THREADS), 0, s>>>(scores, N, k, protect_last, scr, pass);
+    topk_multi_write_kernel<KPT><<<dim3(G), dim3(TOPK_THREADS), 0, s>>>(scores, N, protect_last, scr, idx_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_topk_multi(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out, void* scratch,
+                             hipStream_t s) {
+    if (k <= 0 || N <= 0) return hipSuccess;
+    if (N > TOPK_MULTI_MAX_N || k > N || !scratch) return hipErrorInvalidValue;
+    TopkMultiScratch* scr = (TopkMultiScratch*)scratch;
+    // slices of 4096 keys (32 workgroups at N = 131072: every workgroup re-adds all rows of the table, so a small
+    // grid keeps that cheap); longer rows take 8192 so that the grid stays within the table
+    if (N <= (int64_t)TOPK_MULTI_MAX_WG * 4096) return topk_multi_launch<4>(scores, (int)N, (int)k, protect_last, idx_out, scr, s);
+    return topk_multi_launch<8>(scores, (int)N, (int)k, protect_last, idx_out, scr, s);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Mean of the k largest |values| of every row of a [rows, T] matrix (Eq. (channel_importance): the
 // importance of an FFN channel is the mean of the top-rho fraction of its saliencies over the
 // calibration tokens; rows = channels).  Same radix select as above on the keys of |v| (exact

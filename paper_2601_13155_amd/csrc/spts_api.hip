@@ -14,7 +14,7 @@ namespace {
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Workspace {
-    size_t rope, xn, kall, tmp32, qp, probe, S, C, SF, part, idxA, idxF, posA, q, khat, vhat, vt, att, t, z, big, misc, seg;
+    size_t rope, xn, kall, tmp32, qp, probe, S, C, SF, part, idxA, idxF, posA, q, khat, vhat, vt, att, t, z, big, misc, seg, topk;
     size_t total;
 };
 
@@ -51,6 +51,7 @@ Workspace carve(const spts_model_desc& m, const Limits& L) {
     w.big = take(Np * inner * b);
     w.misc = take(4096);
     w.seg = take(3 * (size_t)(SPTS_MAX_BATCH + 1) * sizeof(int64_t));   // segment descriptors of a batched call
+    w.topk = take(TOPK_MULTI_SCRATCH_BYTES);                             // tables of the chip-wide TopK
     w.total = off;
     return w;
 }
@@ -306,6 +307,15 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
     return SPTS_OK;
 }
 
+// TopK of one score row: longer rows are spread over the chip (a launch per radix pass), short ones stay in one workgroup
+int run_topk(spts_ctx* c, const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out) {
+    if (N >= TOPK_MULTI_MIN_N && N <= TOPK_MULTI_MAX_N)
+        SPTS_HIP(c, launch_topk_multi(scores, N, k, protect_last, idx_out, c->p<void>(c->off.topk), c->stream));
+    else
+        SPTS_HIP(c, launch_topk(scores, N, k, protect_last, idx_out, 1, c->stream));
+    return SPTS_OK;
+}
+
 int common_call_checks(const spts_ctx* c, int64_t N) {
     if (!c) return SPTS_EINVAL;
     if (N < 0) return SPTS_EINVAL;
@@ -438,8 +448,7 @@ int spts_select_topk(spts_ctx* c, const float* scores, int64_t N, int64_t k, int
     if (!scores || !idx_out) return SPTS_EINVAL;
     if (!aligned16(scores) || !aligned16(idx_out)) return SPTS_EALIGN;
     PHASE(c, PH_TOPK);
-    SPTS_HIP(c, launch_topk(scores, N, k, protect_last, idx_out, 1, c->stream));
-    return SPTS_OK;
+    return run_topk(c, scores, N, k, protect_last, idx_out);
 }
 
 int spts_select_topk_batched(spts_ctx* c, const float* scores, int64_t N, int64_t k, int32_t protect_last, int32_t batch,
@@ -700,7 +709,7 @@ int spts_msdp_compact(spts_ctx* c, const void* x_in, const int32_t* pos_in, cons
     PHASE(c, PH_COMPACT);
     if (map_old2new) SPTS_HIP(c, launch_fill_i32(map_old2new, -1, N, c->stream));
     if (keep == 0) return SPTS_OK;
-    SPTS_HIP(c, launch_topk(s_mha, N, keep, protect_last, map_new2old, 1, c->stream));
+    SPTS_TRY(run_topk(c, s_mha, N, keep, protect_last, map_new2old));
     const int64_t row_bytes = (int64_t)c->m.D * (c->bf16 ? 2 : 4);
     SPTS_HIP(c, launch_gather_rows(x_in, map_new2old, x_out, keep, row_bytes, c->stream));
     SPTS_HIP(c, launch_gather_i32(pos_in, map_new2old, pos_out, keep, c->stream));
@@ -798,7 +807,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
     if (skip) {
         idxA = idx_attn ? idx_attn : c->p<int32_t>(c->off.idxA);
         PHASE(c, PH_TOPK);
-        SPTS_HIP(c, launch_topk(S, N, Ma, cfg->protect_last, idxA, 1, st));
+        SPTS_TRY(run_topk(c, S, N, Ma, cfg->protect_last, idxA));
     }
     if (Ma > 0) {
         // queries of the active rows (rows gathered through idxA inside the GEMM's A loads)
@@ -874,7 +883,7 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         SPTS_TRY(proxy_scores_impl(c, xn, N, w, S, nullptr, SF));
         idxF = idx_ffn ? idx_ffn : c->p<int32_t>(c->off.idxF);
         PHASE(c, PH_TOPK);
-        SPTS_HIP(c, launch_topk(SF, N, Mf, cfg->protect_last, idxF, 1, st));
+        SPTS_TRY(run_topk(c, SF, N, Mf, cfg->protect_last, idxF));
     }
     GemmArgs gh = gemm_args(xn, m.D, idxF, w->Wgate, m.D, c->p<void>(c->off.big), m.Dff, Mf, m.Dff, m.D, EPI_SILU_MUL);
     gh.a_rows = N;

@@ -140,6 +140,16 @@ struct TopkSegments { const int64_t* offsets; const int64_t* k; const int64_t* o
 hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out,
                        int batch, hipStream_t s, TopkSegments seg = TopkSegments{nullptr, nullptr, nullptr});
 
+// One problem spread over many workgroups (a launch per radix pass + one for the ordered compaction); `scratch`:
+// TOPK_MULTI_SCRATCH_BYTES of device memory, 256-byte aligned, contents irrelevant on entry (every word that is
+// read was written earlier in the same call); calls sharing a scratch must not overlap.  N <= TOPK_MULTI_MAX_N.
+constexpr int TOPK_MULTI_MAX_WG = 128;
+constexpr int64_t TOPK_MULTI_MAX_N = (int64_t)TOPK_MULTI_MAX_WG * 8192;
+constexpr int64_t TOPK_MULTI_MIN_N = 20000;   // shorter rows: one workgroup with the keys in registers is as fast (measured crossover)
+constexpr size_t TOPK_MULTI_SCRATCH_BYTES = 2 * (size_t)TOPK_MULTI_MAX_WG * 256 * 4 + (size_t)TOPK_MULTI_MAX_WG * 4 + 64;
+hipError_t launch_topk_multi(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out, void* scratch,
+                             hipStream_t s);
+
 // ------------------------------------------------------------------ attention
 struct AttnArgs {
     const void* q;  // [Mq, H, d]

@@ -65,6 +65,33 @@ def test_select_topk_bit_exact(torch):
                 if k == 0:
                     assert int(out[0]) == -7
 
+def test_select_topk_chip_wide_bit_exact(torch):
+    """Rows longer than one workgroup's registers take the chip-wide radix select (a launch per pass over up to 128
+    workgroups): lengths around its slice sizes (1, 2, 4 and 8 keys per lane) up to its maximum of 2^20 scores, back
+    to back on one context (the scratch tables are reused from call to call), same adversarial value patterns."""
+    rng = np.random.default_rng(1)
+    shape = synth.ModelShape(D=32, H=1, Hkv=1, d=16, Dff=32, dtype="f32")
+    ctx = runtime.make_context(shape, 1 << 20, 4, 4, 32)
+    for n in (20000, 20001, 32769, 131071, 131073, 262144, 262145, 300001, 524288, 524289, (1 << 20) - 5, 1 << 20):
+        cases = {
+            "uniform": rng.random(n).astype(np.float32),
+            "all_equal": np.full(n, 0.25, dtype=np.float32),
+            "duplicates": rng.integers(0, 3, n).astype(np.float32),
+            "probability_like": ((1.0 + 0.3 * rng.standard_normal(n)).clip(0.05, None) / n).astype(np.float32),
+        }
+        z = rng.random(n).astype(np.float32); z[rng.random(n) < 0.9] = 0.0; z[::5] = -0.0
+        cases["many_signed_zeros"] = z
+        for name, s in cases.items():
+            sd = torch.from_numpy(s).cuda()
+            for k in sorted({1, n // 4, int(0.3 * n), n - 1, n}):
+                for protect in (0, 1):
+                    out = torch.full((k,), -7, dtype=torch.int32, device="cuda")
+                    ctx.spts_select_topk(sd, n, k, protect, out)
+                    assert np.array_equal(out.cpu().numpy(), orc.topk_select(s, k, protect)), (name, n, k, protect)
+    del ctx
+    torch.cuda.empty_cache()
+
+
 
 def test_select_topk_deterministic_and_nested(torch):
     rng = np.random.default_rng(1)
