@@ -153,6 +153,21 @@ int spts_probe_ffn(spts_ctx *ctx, const void *x, int64_t N, const spts_layer_wei
 int spts_select_topk(spts_ctx *ctx, const float *scores, int64_t N, int64_t k, int32_t protect_last,
                      int32_t *idx_out);
 
+/* spts_select_topk for callers that cannot allocate device memory and so cannot give a context its workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): no context, no workspace.
+ * Same selection and same output as spts_select_topk (bit-identical), always through the chip-wide radix select,
+ * whose histogram tables (about 257 KB) live in a file-scope device array of the library: every GPU the library
+ * runs on holds one copy until the process ends.  The call allocates nothing, frees nothing and calls no
+ * allocating routine; its first use on a device looks the array's address up (hipGetSymbolAddress, no allocation).
+ * hip_stream: hipStream_t as void* (NULL = default stream) on the current device; scores [N] and idx_out [k] are
+ * device pointers, 16-byte aligned.  0 <= k <= N <= SPTS_TOPK_STATIC_MAX_N: a longer row is rejected with
+ * SPTS_ESHAPE before anything is launched (SPTS_EINVAL / SPTS_EALIGN / SPTS_EHIP as for the other calls).
+ * All calls on one GPU share that GPU's array: two calls must not overlap in time (issue them on one stream, or
+ * order the streams), otherwise they race on the tables.  Nothing in the array has to be cleared between calls. */
+#define SPTS_TOPK_STATIC_MAX_N 1048576
+int spts_select_topk_static(void *hip_stream, const float *scores, int64_t N, int64_t k, int32_t protect_last,
+                            int32_t *idx_out);
+
 /* TopK over `batch` independent score rows (Sec. 3.2 TopK applied per sequence of a batch):
  * scores [batch, N] row-major, idx_out [batch, k], every row selected and ordered as by
  * spts_select_topk.  0 <= batch <= 65535, N <= the context's max_tokens (as for the single-row

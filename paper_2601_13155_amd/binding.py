@@ -20,7 +20,7 @@ SPTS_F32, SPTS_BF16 = 0, 1
 
 EXPORTS = (
     "spts_workspace_bytes", "spts_create", "spts_destroy", "spts_strerror", "spts_last_hip_error", "spts_uses_mfma",
-    "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_batched", "spts_select_topk_segmented", "spts_layer_prefill", "spts_layer_prefill_batched", "spts_msdp_compact", "spts_msdp_compact_batched",
+    "spts_probe_attn", "spts_probe_ffn", "spts_select_topk", "spts_select_topk_static", "spts_select_topk_batched", "spts_select_topk_segmented", "spts_layer_prefill", "spts_layer_prefill_batched", "spts_msdp_compact", "spts_msdp_compact_batched",
     "spts_decode_layer", "spts_decode_layer_batched", "spts_greedy_token", "spts_greedy_token_batched", "spts_channel_importance",
     "spts_pack_slab32",
     "spts_profile_begin", "spts_profile_end", "spts_profile_count", "spts_profile_get",
@@ -77,6 +77,8 @@ def load() -> C.CDLL:
     lib.spts_probe_ffn.argtypes = [vp, vp, i64, C.POINTER(spts_layer_weights), vp, vp, vp]
     lib.spts_select_topk.restype = C.c_int
     lib.spts_select_topk.argtypes = [vp, vp, i64, i64, i32, vp]
+    lib.spts_select_topk_static.restype = C.c_int
+    lib.spts_select_topk_static.argtypes = [vp, vp, i64, i64, i32, vp]
     lib.spts_select_topk_batched.restype = C.c_int
     lib.spts_select_topk_batched.argtypes = [vp, vp, i64, i64, i32, i32, vp]
     lib.spts_select_topk_segmented.restype = C.c_int
@@ -154,6 +156,15 @@ def layer_weights(tensors: dict, r: int = 0, Dlow: int = 0) -> spts_layer_weight
 
 def spts_workspace_bytes(model: spts_model_desc, max_tokens: int, max_probe: int, max_r: int, max_dlow: int) -> int:
     return int(load().spts_workspace_bytes(C.byref(model), max_tokens, max_probe, max_r, max_dlow))
+
+
+SPTS_TOPK_STATIC_MAX_N = 1048576
+
+
+def spts_select_topk_static(stream, scores, N: int, k: int, protect_last: int, idx_out):
+    """Context-free TopK on the library's own static scratch; stream: a torch stream, a raw hipStream_t or None."""
+    h = getattr(stream, "cuda_stream", stream)
+    _check(load().spts_select_topk_static(h, _ptr(scores), N, k, protect_last, _ptr(idx_out)), "spts_select_topk_static")
 
 
 class Context:

@@ -19,6 +19,8 @@
 // the contiguous slice [64*KPT*w, 64*KPT*(w+1))); longer inputs re-read the scores in every sweep.
 #include "spts_internal.h"
 
+#include <mutex>
+
 namespace spts {
 
 constexpr int TOPK_THREADS = 1024;
@@ -413,6 +415,32 @@ static hipError_t topk_multi_launch(const float* scores, int N, int k, int prote
         topk_multi_hist_kernel<KPT><<<dim3(G), dim3(TOPK_THREADS), 0, s>>>(scores, N, k, protect_last, scr, pass);
     topk_multi_write_kernel<KPT><<<dim3(G), dim3(TOPK_THREADS), 0, s>>>(scores, N, protect_last, scr, idx_out);
     return hipGetLastError();
+}
+
+// Scratch of the no-allocation entry point: one array per GPU, in the code object's own device memory.  Nothing in it
+// has to start at zero: every word a call reads was written earlier in the same call.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[TOPK_MULTI_SCRATCH_BYTES];
+
+hipError_t topk_static_scratch(void** out) {
+    // In host code the array's name is only a handle for the runtime: the address a kernel can use comes from
+    // hipGetSymbolAddress, once per device (every GPU holds its own copy at its own address).
+    constexpr int MAX_DEV = 64;
+    static std::mutex mtx;
+    static void* dev_ptr[MAX_DEV] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEV) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mtx);
+    if (!dev_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        dev_ptr[dev] = p;
+    }
+    *out = dev_ptr[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_topk_multi(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out, void* scratch,

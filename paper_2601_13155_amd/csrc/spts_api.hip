@@ -451,6 +451,20 @@ int spts_select_topk(spts_ctx* c, const float* scores, int64_t N, int64_t k, int
     return run_topk(c, scores, N, k, protect_last, idx_out);
 }
 
+static_assert(SPTS_TOPK_STATIC_MAX_N <= TOPK_MULTI_MAX_N, "the static scratch's tables cover the documented maximum");
+
+int spts_select_topk_static(void* hip_stream, const float* scores, int64_t N, int64_t k, int32_t protect_last, int32_t* idx_out) {
+    if (N < 0 || k < 0 || k > N) return SPTS_EINVAL;
+    if (N > SPTS_TOPK_STATIC_MAX_N) return SPTS_ESHAPE;
+    if (k == 0) return SPTS_OK;
+    if (!scores || !idx_out) return SPTS_EINVAL;
+    if (!aligned16(scores) || !aligned16(idx_out)) return SPTS_EALIGN;
+    void* scr = nullptr;
+    if (topk_static_scratch(&scr) != hipSuccess) return SPTS_EHIP;
+    if (launch_topk_multi(scores, N, k, protect_last, idx_out, scr, (hipStream_t)hip_stream) != hipSuccess) return SPTS_EHIP;
+    return SPTS_OK;
+}
+
 int spts_select_topk_batched(spts_ctx* c, const float* scores, int64_t N, int64_t k, int32_t protect_last, int32_t batch,
                              int32_t* idx_out) {
     SPTS_TRY(common_call_checks(c, N));

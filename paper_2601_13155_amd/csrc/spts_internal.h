@@ -147,6 +147,8 @@ constexpr int TOPK_MULTI_MAX_WG = 128;
 constexpr int64_t TOPK_MULTI_MAX_N = (int64_t)TOPK_MULTI_MAX_WG * 8192;
 constexpr int64_t TOPK_MULTI_MIN_N = 20000;   // shorter rows: one workgroup with the keys in registers is as fast (measured crossover)
 constexpr size_t TOPK_MULTI_SCRATCH_BYTES = 2 * (size_t)TOPK_MULTI_MAX_WG * 256 * 4 + (size_t)TOPK_MULTI_MAX_WG * 4 + 64;
+// device address of this GPU's file-scope scratch array of TOPK_MULTI_SCRATCH_BYTES (looked up once per device, then cached)
+hipError_t topk_static_scratch(void** out);
 hipError_t launch_topk_multi(const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out, void* scratch,
                              hipStream_t s);
 
