@@ -22,19 +22,40 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA (published)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E (published)
-# Bytes per launch that the dominant kernel (ffn_gate_up) moves between L2 and the fabric, from two rocprofv3
-# counter runs (FETCH_SIZE, WRITE_SIZE) of this script scaled by the readings of a plain 1 GiB elementwise
-# kernel (--calibrate-copy); the summary with the commands is profiles/c2_ffn_gate_up_hbm_traffic.txt.
-# Counters cannot be read from inside this process, so workloads without a committed counter run report null.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"c2": 3.3393e9}
+# Kernel behind the roofline figure (phase ffn_gate_up of the library's event timer) as rocprofv3 names it.
+DOMINANT_KERNEL = "gemm_mfma_kernel<1, 32, false, 8>"
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "c2_ffn_gate_up_hbm_traffic.txt")
+
+
+def measured_traffic(workload):
+    """Bytes per launch that the dominant kernel moves between L2 and the fabric, read from the committed counter
+    summary (two rocprofv3 --pmc runs of this script, FETCH_SIZE and WRITE_SIZE, scaled by the readings of a plain
+    1 GiB elementwise kernel, --calibrate-copy).  Counters cannot be read inside this process; the summary carries one
+    line `bench-table: workload=<w> kernel="<name>" bytes_per_launch=<b>` per workload it covers.  The figure is used only
+    if that line names this workload AND the kernel timed here; otherwise None."""
+    try:
+        with open(TRAFFIC_SUMMARY) as f:
+            lines = [l.strip() for l in f if l.startswith("bench-table:")]
+    except OSError:
+        return None, None
+    for l in lines:
+        fields = dict(kv.split("=", 1) for kv in __import__("shlex").split(l[len("bench-table:"):]))
+        if fields.get("workload") == workload:
+            assert fields.get("kernel") == DOMINANT_KERNEL, (
+                f"{TRAFFIC_SUMMARY} was measured on {fields.get('kernel')!r}, bench.py times {DOMINANT_KERNEL!r}: regenerate it")
+            return float(fields["bytes_per_launch"]), os.path.relpath(TRAFFIC_SUMMARY, ROOT)
+    return None, None
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(wl, w_host, sample_tokens, layers_equiv):
-    """Times the oracle (as it stands) on one skip layer over a prefix of the workload's input."""
+def cpu_baseline(wl, w_host, sample_tokens):
+    """Times the oracle (as it stands) on one skip layer of the workload at two prefix lengths, n/2 and n tokens, fits
+    t(N) = a*N + b*N^2 through the two timings (projections, proxy and FFN grow with N, the reduced attention with
+    N^2 at a fixed keep ratio) and sums the fit over the candidate counts of the stack's layers (the stage pruning
+    shrinks them): tokens/s = N_0 / sum_l t(N_l), labelled extrapolated."""
     import numpy as np
     from oracle import spts_oracle as orc
     from paper_2601_13155_amd import synth
@@ -43,30 +64,46 @@ def cpu_baseline(wl, w_host, sample_tokens, layers_equiv):
     except Exception:
         threadpool_info = None
     shape = wl.shape
-    n = min(sample_tokens, wl.N)
-    x = synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype)[:n]
-    pos = synth.positions(n)
     mdl = orc.Model(shape.D, shape.H, shape.Hkv, shape.d, shape.Dff, shape.rms_eps, shape.rope_base)
-    first_skip = next(it for it in wl.layer_plan() if it.get("skip", 1))   # budgets of the first skip layer, scaled to n
+    plan = wl.layer_plan()
+    first_skip = next(it for it in plan if it.get("skip", 1))   # budgets of the first skip layer, scaled to the sample
     ka, kf = first_skip["m_attn"] / first_skip["N"], first_skip["m_ffn"] / first_skip["N"]
-    cfg = orc.LayerCfg(1, min(wl.probe_len, n), int(ka * n), int(kf * n), wl.protect_last, 0)
-    t0 = time.perf_counter()
-    orc.layer_prefill(x, pos, w_host, mdl, cfg, rnd=orc.bf16_round if shape.dtype == "bf16" else orc.identity,
-                      score_cast=orc.f32_round)
-    dt = time.perf_counter() - t0
+    w64 = {k: np.asarray(v, dtype=np.float64) for k, v in w_host.items()}   # conversion is not part of the timing
+    x_all = synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype)
+    n2 = min(sample_tokens, wl.N)
+    n1 = max(n2 // 2, min(wl.probe_len, n2))
+    secs = {}
+    for n in sorted({n1, n2}):
+        cfg = orc.LayerCfg(1, min(wl.probe_len, n), int(ka * n), int(kf * n), wl.protect_last, 0)
+        t0 = time.perf_counter()
+        orc.layer_prefill(x_all[:n], synth.positions(n), w64, mdl, cfg,
+                          rnd=orc.bf16_round if shape.dtype == "bf16" else orc.identity, score_cast=orc.f32_round)
+        secs[n] = time.perf_counter() - t0
+    if n1 != n2:
+        bq = (secs[n2] / n2 - secs[n1] / n1) / (n2 - n1)
+        bq = max(bq, 0.0)
+        al = secs[n2] / n2 - bq * n2
+    else:
+        al, bq = secs[n2] / n2, 0.0
+    t_stack = sum(al * it["N"] + bq * it["N"] ** 2 for it in plan)
     threads = None
     if threadpool_info is not None:
         ths = [p.get("num_threads") for p in threadpool_info() if p.get("user_api") == "blas"]
         threads = max(ths) if ths else None
     if threads is None:
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    try:
+        allowed = len(os.sched_getaffinity(0))
+    except AttributeError:
+        allowed = os.cpu_count()
     return {
-        "value": n / (dt * layers_equiv), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-        "sample": (f"oracle.layer_prefill (numpy fp64, bf16-faithful rounding) on ONE skip layer over the first {n} "
-                   f"tokens of the workload input (keep {ka:.3f}/{kf:.3f}, P={min(wl.probe_len, n)}, r={wl.r}): "
-                   f"{dt:.2f} s; tokens/s extrapolated as {n} / ({dt:.2f} s x {layers_equiv} layers), i.e. ignoring "
-                   f"both the MSDP shrink and the growth of attention cost with length"),
-        "seconds_one_layer": dt,
+        "value": wl.N / t_stack, "unit": "tokens/s", "cores": int(threads), "nproc": int(os.cpu_count() or 0),
+        "cpus_allowed": int(allowed), "kind": "oracle",
+        "sample": (f"oracle.layer_prefill (numpy fp64, bf16-faithful rounding) on ONE skip layer over the first {n1} and the first "
+                   f"{n2} tokens of the workload input (keep {ka:.3f}/{kf:.3f}, P={wl.probe_len}, r={wl.r}): {secs[n1]:.2f} s and "
+                   f"{secs[n2]:.2f} s; t(N) = {al:.3e}*N + {bq:.3e}*N^2 fitted through both and summed over the {len(plan)} "
+                   f"layers' candidate counts (extrapolated: {t_stack:.0f} s for the stack)"),
+        "seconds_per_sample": {str(k): v for k, v in secs.items()}, "seconds_stack_extrapolated": t_stack,
     }
 
 
@@ -90,7 +127,8 @@ def main():
     ap.add_argument("--row-major-weights", action="store_true",
                     help="do not upload the slab-major weight copies (the prefill GEMMs then read the row-major matrices)")
     ap.add_argument("--dense-steps", type=int, default=1, help="timed steps of the dense (skip=0) prefill; 0 = skip it")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=4096, help="0 = no cpu_baseline leg")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192,
+                    help="the oracle is timed on one layer over the first n/2 and the first n tokens (0 = no cpu_baseline leg)")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket phases with events in the timed region")
     ap.add_argument("--topk-batch", type=int, default=2048,
                     help="rows of the batched TopK micro-benchmark (rows x 131072 fp32 scores; 0 = skip it)")
@@ -104,6 +142,9 @@ def main():
     ap.add_argument("--batch-seqs", type=int, default=4,
                     help="sequences of the batched-layer leg (one skip layer over that many sequences of 8192 tokens, "
                          "as one spts_layer_prefill_batched call and as single calls; 0 = skip it)")
+    ap.add_argument("--builder-channels", action="store_true",
+                    help="p32 / q32: the proxy's Dlow channels are chosen on the GPU (spts_channel_importance + spts_select_topk "
+                         "on synthetic calibration rows) instead of a seeded random subset")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first launch a plain elementwise kernel (dst = src + 1 over 2^28 floats: reads 1 GiB, writes 1 GiB) "
                          "three times; under a counter-collecting profiler its FETCH_SIZE / WRITE_SIZE readings give the "
@@ -140,15 +181,24 @@ def main():
     t_setup = time.perf_counter()
     pool = max(1, min(args.weight_pool, wl.layers))
     host_sets, dev_sets = [], []
+    ctx = runtime.make_context(shape, wl.N, wl.probe_len, wl.proxy_r, Dlow)
     for i in range(pool):
-        w = synth.make_layer(wl.seed, i, shape, wl.r, wl.dlow, wl.r_pad)
+        channels = None
+        if args.builder_channels and wl.dlow:
+            # Sec. 3.3 on the GPU: channel scores over synthetic calibration rows (rho = 0.2), C = TopK(I, Dlow); the
+            # SVD of the sliced matrices is harness set-up
+            dw0 = runtime.upload_layer(synth.layer_weights(wl.seed, i, shape), shape, 0, pack=False)
+            T = min(args.builder_tokens or 2048, wl.N)
+            channels, _ = runtime.select_proxy_channels(ctx, dw0, shape, synth.calibration_states(wl.seed + i, T, shape.D, shape.dtype),
+                                                        max(1, int(0.2 * T)), wl.dlow)
+            del dw0
+        w = synth.make_layer(wl.seed, i, shape, wl.r, wl.dlow, wl.r_pad, channels=channels)
         dev_sets.append(runtime.upload_layer(w, shape, wl.proxy_r, pack=not args.row_major_weights))
         host_sets.append(w if i == 0 else None)
         log(f"[setup] weight set {i + 1}/{pool} ready ({time.perf_counter() - t_setup:.1f} s)")
     layers = [dev_sets[l % pool] for l in range(wl.layers)]
     x0 = runtime.to_device(synth.hidden_states(wl.seed, wl.N, shape.D, shape.dtype), shape.dtype)
     pos0 = torch.from_numpy(synth.positions(wl.N)).cuda()
-    ctx = runtime.make_context(shape, wl.N, wl.probe_len, wl.proxy_r, Dlow)
     assert ctx.uses_mfma(), "matrix-core kernels are not serving this workload"
     runner = runtime.StackRunner(ctx, shape, layers, plan, wl.probe_len, wl.protect_last, skip=1)
     log(f"[setup] done in {time.perf_counter() - t_setup:.1f} s; workload {wl.name}: N={wl.N}, layers={wl.layers}")
@@ -206,9 +256,11 @@ def main():
             phase_out[name] = {"ms_per_step": tot_ms / args.steps, "launches_per_step": n / args.steps}
         gu_ms = phases["ffn_gate_up"][0] / args.steps
         achieved = gate_up_flops / (gu_ms * 1e-3) / 1e12
-        roofline = {"kernel": "gemm_mfma_kernel<EPI_SILU_MUL> (ffn_gate_up)", "bound": "mfma", "achieved": achieved,
+        traffic, traffic_src = (None, None) if (args.layers or args.length or args.row_major_weights) else measured_traffic(wl.name)
+        roofline = {"kernel": f"spts::{DOMINANT_KERNEL} (ffn_gate_up: SiLU(gate)*up GEMM on the gathered rows)", "bound": "mfma",
+                    "achieved": achieved,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(wl.name) if not args.layers else None,
+                    "traffic": traffic, "traffic_source": traffic_src,
                     "traffic_unit": "bytes per launch (L2 <-> fabric, counter-measured offline)",
                     "flops_per_step": gate_up_flops, "ms_per_step": gu_ms,
                     "launches_per_step": phases["ffn_gate_up"][1] / args.steps}
@@ -489,8 +541,8 @@ def main():
 
     cpu = None
     if args.cpu_sample_tokens > 0:
-        cpu = cpu_baseline(wl, host_sets[0], args.cpu_sample_tokens, wl.layers)
-        log(f"[cpu] oracle layer on {min(args.cpu_sample_tokens, wl.N)} tokens: {cpu['seconds_one_layer']:.2f} s")
+        cpu = cpu_baseline(wl, host_sets[0], args.cpu_sample_tokens)
+        log(f"[cpu] oracle layer timings {cpu['seconds_per_sample']} s -> stack extrapolated {cpu['seconds_stack_extrapolated']:.0f} s")
 
     out = {
         "metric": "SPTS prefill tokens/s (TTFT = ms_per_step) at %dK, %s-shaped, 1 GPU%s" % (
@@ -504,6 +556,7 @@ def main():
                    "dense_layers": wl.dense_layers, "stage_budgets": list(wl.stage_budgets), "stage_prune": wl.stage_prune,
                    "stage_end_layers": list(wl.stage_end_layers), "stage_cum_keep": list(wl.stage_cum_keep),
                    "components": wl.components, "weight_pool": pool, "batch": 1,
+                   "proxy_channels": ("all" if not wl.dlow else "TopK of channel scores computed on the GPU" if args.builder_channels else "seeded random subset"),
                    "weight_layout": "row-major" if args.row_major_weights else "row-major + slab-major copies (spts_pack_slab32)"},
         "algorithmic_tflop_per_step": total_flops / 1e12,
         "achieved_tflops_whole_step": total_flops / (ms * 1e-3) / 1e12,

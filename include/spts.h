@@ -80,7 +80,10 @@ typedef struct {
      * The prefill calls read a matrix through its copy where their matrix-core GEMM takes it (same arithmetic, same
      * results; the copy only changes which bytes a load instruction fetches together); the decode calls and the fp32
      * path always read the row-major originals, which must be given in any case.  Wgate_s and Wup_s go together, and
-     * so do Vg_s and Vu_s, and Ug_s and Uu_s. */
+     * so do Vg_s and Vu_s, and Ug_s and Uu_s.
+     * Contract: X_s must be spts_pack_slab32(X) of the matrix X given in the same struct, made after the last write
+     * to X.  The library cannot tell a stale copy from a fresh one: prefill would then compute with the copy and
+     * decode with the original, silently.  Re-pack whenever X changes. */
     const void *Wq_s, *Wk_s, *Wv_s, *Wo_s, *Wgate_s, *Wup_s, *Wdown_s;
     const void *Vg_s, *Vu_s, *Vd_s, *Ug_s, *Uu_s;
 } spts_layer_weights;
@@ -205,7 +208,10 @@ int spts_layer_prefill(spts_ctx *ctx, void *x, const int32_t *pos, int64_t N,
  * not written, the caches receive every row).  Optional outputs: kv [batch] (one cache per
  * sequence, filled with its active pairs), s_mha [Ntot], idx_attn / idx_ffn: the active sets of the
  * sequences back to back, as ascending row numbers of the batch (sequence b's share starts at
- * sum over b' < b of min(len_b', m_b')). */
+ * sum over b' < b of min(len_b', m_b')).
+ * Like every call, this one only enqueues work and returns: the host arrays are read before it returns (their
+ * values reach the device as kernel arguments, not through a copy of host memory), so they may be freed at once,
+ * and the call may be recorded under stream capture. */
 #define SPTS_MAX_BATCH 1024
 int spts_layer_prefill_batched(spts_ctx *ctx, void *x, const int32_t *pos, const int64_t *seq_offsets,
                                int32_t batch, const spts_layer_weights *w, int32_t skip,

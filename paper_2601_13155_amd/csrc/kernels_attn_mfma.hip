@@ -371,12 +371,9 @@ static hipError_t launch_attn_t(const AttnArgs& a, hipStream_t s) {
     const int total = nQ * a.H;
     const int grid = (total + 7) / 8 * 8;
     const size_t lds = (size_t)AttnLds<D>::STAGE * ATT_NST;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<D, QB, NW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_mfma_kernel<D, QB, NW>), (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
     attn_mfma_kernel<D, QB, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nQ, total, scale_log2e);

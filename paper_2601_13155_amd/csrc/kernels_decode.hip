@@ -478,12 +478,9 @@ template <int MODE, int XI>
 static hipError_t launch_gemv_mfma_t(const GemvArgs& a, int nb, unsigned grid, hipStream_t s) {
     constexpr int NS = MODE == GEMV_SILU ? 2 : 1, DEPTH = NS == 2 ? 3 : 4, NW = GEMV_MFMA_WAVES;
     const size_t lds = (size_t)NW * DEPTH * (NS + 1) * 2048;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<MODE, XI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemv_mfma_kernel<MODE, XI>), (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     gemv_mfma_kernel<MODE, XI><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nb);
     return hipGetLastError();

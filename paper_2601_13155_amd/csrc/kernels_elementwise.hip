@@ -3,9 +3,26 @@
 // one pass over the data.
 #include "spts_internal.h"
 
+#include <mutex>
+#include <set>
+#include <utility>
+
 namespace spts {
 
 static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+hipError_t ensure_dynamic_lds(const void* kernel, int bytes) {
+    static std::mutex mtx;
+    static std::set<std::pair<int, const void*>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mtx);
+    if (done.count({dev, kernel})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.insert({dev, kernel});
+    return e;
+}
 
 // ---------------------------------------------------------------- rotary table
 // table[n, j] = (cos, sin)(pos[n] * base^(-2j/d)), j < d/2.  Angles are formed in fp64 so that
@@ -236,6 +253,25 @@ __global__ void add_segment_base_kernel(int32_t* __restrict__ idx, const int64_t
     }
     idx[i] += (int32_t)seg_offsets[lo];
 }
+// dst[first + i] = chunk.v[i] for i < chunk.n: host integers travel as kernel arguments (captured by value at launch,
+// so the host array may die as soon as the call returns, and nothing is staged or synchronised)
+__global__ void write_i64_kernel(I64Chunk chunk, int64_t* __restrict__ dst, int64_t first) {
+    const int i = threadIdx.x;
+    if (i < chunk.n) dst[first + i] = chunk.v[i];
+}
+
+hipError_t launch_write_i64(const int64_t* host_vals, int64_t n, int64_t* dst, hipStream_t s) {
+    for (int64_t first = 0; first < n; first += I64Chunk::CAP) {
+        I64Chunk c;
+        c.n = (int32_t)(n - first < I64Chunk::CAP ? n - first : I64Chunk::CAP);
+        for (int i = 0; i < c.n; ++i) c.v[i] = host_vals[first + i];
+        write_i64_kernel<<<dim3(1), dim3(I64Chunk::CAP), 0, s>>>(c, dst, first);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_add_segment_base(int32_t* idx, const int64_t* out_offsets, const int64_t* seg_offsets, int nseg, int64_t total,
                                    hipStream_t s) {
     if (total <= 0 || nseg <= 0) return hipSuccess;

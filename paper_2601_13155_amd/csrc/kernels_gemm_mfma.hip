@@ -551,12 +551,9 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     const int nunits = split ? (tiles - nfull) * a.ksplit : 0;
     const int grid = 8 * ((nfull + 7) / 8 + (nunits + 7) / 8);
     const size_t lds = (size_t)Slab<BK>::TILE_BYTES * (DUAL_A ? 3 : 2) * (BK == 64 ? 2 : (DUAL_A ? 3 : 4));
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<EPI, BK, DUAL_A, NW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&gemm_mfma_kernel<EPI, BK, DUAL_A, NW>), (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     gemm_mfma_kernel<EPI, BK, DUAL_A, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nM, nN, nfull, nunits);
     return hipGetLastError();

@@ -767,8 +767,9 @@ int spts_msdp_compact_batched(spts_ctx* c, const void* x_in, const int32_t* pos_
     PHASE(c, PH_COMPACT);
     if (map_old2new) SPTS_HIP(c, launch_fill_i32(map_old2new, -1, N, c->stream));
     if (keep == 0) return SPTS_OK;
+    // the descriptors travel by value as kernel arguments: no staging copy of a host array that dies with this call
     int64_t* seg = c->p<int64_t>(c->off.seg);
-    SPTS_HIP(c, hipMemcpyAsync(seg, desc.data(), desc.size() * sizeof(int64_t), hipMemcpyHostToDevice, c->stream));
+    SPTS_HIP(c, launch_write_i64(desc.data(), (int64_t)desc.size(), seg, c->stream));
     const TopkSegments segs{seg, seg + (batch + 1), seg + 2 * (batch + 1)};
     SPTS_HIP(c, launch_topk(s_mha, max_len, 0, protect_last, map_new2old, batch, c->stream, segs));
     SPTS_HIP(c, launch_add_segment_base(map_new2old, segs.out_offsets, segs.offsets, batch, keep, c->stream));
@@ -963,8 +964,9 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
     auto upload = [&](const std::vector<int64_t>& k, const std::vector<int64_t>& out) -> hipError_t {
         for (int b = 0; b <= batch; ++b) { dOff[b] = seq_offsets[b]; dOut[b] = out[b]; if (b < batch) dKa[b] = k[b]; }
         dKa[batch] = 0;
-        // the descriptors of the previous selection may still be read by work in flight: the copy is stream-ordered
-        return hipMemcpyAsync(seg, desc.data(), desc.size() * sizeof(int64_t), hipMemcpyHostToDevice, st);
+        // the descriptors of the previous selection may still be read by work in flight: the small kernels that write the
+        // new ones (values passed by value as kernel arguments) are stream-ordered behind it
+        return launch_write_i64(desc.data(), (int64_t)desc.size(), seg, st);
     };
     const TopkSegments segs{seg, seg + (batch + 1), seg + 2 * (batch + 1)};
     int64_t max_len = 0;

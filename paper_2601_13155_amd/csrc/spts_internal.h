@@ -59,6 +59,9 @@ __device__ inline void dma16s(uint32_t voff, const void* sbase, uint32_t lds_bas
 // probability fragments come out of the matrix core, so a value fragment is one 16-byte read.
 __host__ __device__ inline int64_t vt_key_slot(int64_t key) { return (key & ~(int64_t)12) | ((key & 4) << 1) | ((key & 8) >> 1); }
 
+// Raises a kernel's dynamic-LDS limit once per (device, kernel); safe to call from several host threads.
+hipError_t ensure_dynamic_lds(const void* kernel, int bytes);
+
 // ------------------------------------------------------------------ GEMM (C = A * B^T)
 enum GemmEpilogue : int {
     EPI_STORE = 0,      // C[row, col] = acc          (T, or fp32 when c_is_f32)
@@ -120,6 +123,10 @@ hipError_t launch_gather_i32(const int32_t* in, const int32_t* idx, int32_t* out
 hipError_t launch_copy_bytes(const void* in, void* out, int64_t bytes, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 hipError_t launch_iota_i32(int32_t* p, int64_t n, hipStream_t s);
+// n host int64 values -> device array dst, in chunks passed by value as kernel arguments (no host staging buffer, no
+// synchronisation, safe under stream capture)
+struct I64Chunk { static constexpr int CAP = 256; int64_t v[CAP]; int32_t n; };
+hipError_t launch_write_i64(const int64_t* host_vals, int64_t n, int64_t* dst, hipStream_t s);
 // idx[i] += seg_offsets[b] for i in [out_offsets[b], out_offsets[b+1]); device descriptor arrays
 hipError_t launch_add_segment_base(int32_t* idx, const int64_t* out_offsets, const int64_t* seg_offsets, int nseg, int64_t total,
                                    hipStream_t s);

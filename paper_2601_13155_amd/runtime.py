@@ -89,6 +89,21 @@ def run_layer(ctx: binding.Context, x: np.ndarray, pos: np.ndarray, dw: binding.
     return out
 
 
+def select_proxy_channels(ctx: binding.Context, dw: binding.spts_layer_weights, shape, x_cal: np.ndarray, k: int, dlow: int):
+    """The data-driven part of the offline proxy construction (Sec. 3.3) on the GPU: channel scores of Eq.
+    (channel_importance) over the calibration rows x_cal [T, D], then C = TopK(I, dlow).  Returns (channel ids
+    ascending [dlow] int32, scores [Dff] fp32) as host arrays; the SVD of the sliced matrices stays in the harness
+    (synth.proxy_factors).  Sequencing of two library calls only."""
+    torch = _torch()
+    T = int(x_cal.shape[0])
+    imp = torch.zeros(shape.Dff, dtype=torch.float32, device="cuda")
+    ctx.spts_channel_importance(to_device(x_cal, shape.dtype), T, dw, int(k), imp)
+    sel = torch.empty(dlow, dtype=torch.int32, device="cuda")
+    ctx.spts_select_topk(imp, shape.Dff, dlow, 0, sel)
+    torch.cuda.synchronize()
+    return sel.cpu().numpy(), imp.cpu().numpy()
+
+
 class KVCache:
     """Device buffers of one layer's cache: k, v [capacity, Hkv, d], pos [capacity]; count lives on the host."""
 

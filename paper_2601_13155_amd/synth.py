@@ -279,9 +279,15 @@ def proxy_factors(weights: Dict[str, np.ndarray], r: int, dtype: str, channels: 
     return out
 
 
-def make_layer(seed: int, layer: int, shape: ModelShape, r: int, dlow: int = 0, r_pad: int = 0) -> Dict[str, np.ndarray]:
+def make_layer(seed: int, layer: int, shape: ModelShape, r: int, dlow: int = 0, r_pad: int = 0,
+               channels: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Weights + proxy factors of one layer.  The proxy keeps all Dff channels (dlow = 0), a seeded random subset of
+    dlow channels, or exactly `channels` (ascending ids, e.g. the set the offline construction of Sec. 3.3 chose)."""
     w = layer_weights(seed, layer, shape)
-    ch = proxy_channels(seed, layer, shape.Dff, dlow) if dlow else None
+    if channels is not None:
+        ch = np.asarray(channels, dtype=np.int64)
+    else:
+        ch = proxy_channels(seed, layer, shape.Dff, dlow) if dlow else None
     w.update(proxy_factors(w, r, shape.dtype, ch, r_pad))
     return w
 

@@ -525,3 +525,39 @@ def test_channel_importance_8b_shaped():
     swaps = H.count_swaps(sel, orc.select_channels(ref, dlow), ref, tol, 0)
     print(f"channel importance: max rel err {err:.3e}, selection swaps {swaps} of {dlow}")
     assert err <= tol
+
+
+def test_paper_proxy_built_on_the_gpu_then_layer_lockstep():
+    """Sec. 3.3 end to end at the 8B shape with the paper's settings: channel scores over 2048 synthetic calibration
+    rows with rho = 0.2, C = TopK(I, 512) on the GPU, rank-192 SVD of W[:, C] (stored zero-padded to 256) in the
+    harness, then a single-row-probe skip layer at N = 8192 with that proxy, lock-step against the oracle, which
+    selects its own channels (sets compared, near ties counted) and continues from the GPU's set."""
+    import torch
+    wl = synth.WORKLOADS["p32"]
+    shape = wl.shape
+    ctx = ctx_for(32768)
+    base = synth.layer_weights(wl.seed, 12, shape)
+    dw0 = runtime.upload_layer(base, shape, 0)
+    T, dlow = 2048, wl.dlow
+    k = int(0.2 * T)
+    xc = synth.calibration_states(wl.seed, T, shape.D, shape.dtype)
+    sel, imp = runtime.select_proxy_channels(ctx, dw0, shape, xc, k, dlow)
+    ref_imp = orc.channel_importance(xc, base["Wgate"], base["Wup"], k, orc.bf16_round)
+    tol = H.TOL["bf16"]["score"]
+    assert np.max(np.abs(imp - ref_imp)) <= tol * np.max(np.abs(ref_imp))
+    assert np.array_equal(sel, orc.select_channels(imp, dlow))
+    swaps = H.count_swaps(sel, orc.select_channels(ref_imp, dlow), ref_imp, tol, 0)
+    assert swaps <= H.swap_bound(dlow, "bf16")
+    del dw0
+    w = _f64(synth.make_layer(wl.seed, 12, shape, wl.r, r_pad=wl.r_pad, channels=sel))
+    assert w["Vg"].shape == (256, 512)
+    dw = runtime.upload_layer(w, shape, wl.proxy_r)
+    N, budget = 8192, 2304
+    x = synth.hidden_states(wl.seed, N, shape.D, shape.dtype)
+    pos = synth.positions(N)
+    gpu = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=1, m_attn=budget, m_ffn=budget, protect_last=1)
+    res = H.lockstep_layer(gpu, x, pos, w, H.oracle_model(shape), orc.LayerCfg(1, 1, budget, budget, 1, 0), shape.dtype)
+    print(f"built proxy: channel swaps {swaps}/{dlow}; layer swaps attn={res['swaps_attn']} ffn={res['swaps_ffn']} hidden err={res['err']:.3e}")
+    del dw
+    torch.cuda.empty_cache()
+

@@ -690,3 +690,38 @@ def test_channel_importance_and_selection(torch, dtype):
         sel = sel.cpu().numpy()
         assert np.array_equal(sel, orc.select_channels(got, dlow))
         H.count_swaps(sel, orc.select_channels(ref, dlow), ref, tol, 0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_proxy_built_from_selected_channels_runs_the_layer(torch, dtype):
+    """The offline construction of Sec. 3.3 end to end: channel scores on a calibration set and C = TopK(I, Dlow) on
+    the GPU (spts_channel_importance, spts_select_topk), the rank-r SVD of W[:, C] in the harness, then a token-skipped
+    layer with that Dlow < Dff proxy.  The oracle does the same through select_channels: the channel sets must agree
+    up to counted near ties, the oracle then builds its factors from the GPU's set and the layer runs lock-step."""
+    if dtype == "f32":
+        shape, N, P, r, dlow, T = synth.TINY, 301, 8, 16, 128, 200
+    else:
+        shape, N, P, r, dlow, T = synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 1, 64, 512, 700
+    base = synth.layer_weights(41, 0, shape)
+    ctx = ctx_for(shape, 2048)
+    dw0 = runtime.upload_layer(base, shape, 0)                      # FFN matrices only: the scores need no proxy
+    xc = synth.calibration_states(41, T, shape.D, dtype)
+    k = max(1, int(0.2 * T))                                        # rho = 0.2
+    sel, imp = runtime.select_proxy_channels(ctx, dw0, shape, xc, k, dlow)
+    ref_imp = orc.channel_importance(xc, base["Wgate"], base["Wup"], k, H.rnd_for(dtype))
+    tol = H.TOL[dtype]["score"]
+    assert np.max(np.abs(imp - ref_imp)) <= tol * np.max(np.abs(ref_imp))
+    assert np.array_equal(sel, orc.select_channels(imp, dlow))
+    swaps = H.count_swaps(sel, orc.select_channels(ref_imp, dlow), ref_imp, tol, 0)
+    assert swaps <= H.swap_bound(dlow, dtype)
+    w = synth.make_layer(41, 0, shape, r, channels=sel)
+    assert w["Vg"].shape == (r, dlow) and w["Vd"].shape == (r, dlow)
+    dw = runtime.upload_layer(w, shape, r)
+    assert dw.Dlow == dlow
+    x = synth.hidden_states(41, N, shape.D, dtype)
+    pos = synth.positions(N)
+    ma, mf = int(0.4 * N), int(0.3 * N)
+    gpu = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=ma, m_ffn=mf)
+    res = H.lockstep_layer(gpu, x, pos, w, H.oracle_model(shape), orc.LayerCfg(1, P, ma, mf, 1, 0), dtype)
+    print(f"{dtype}: channel swaps {swaps}/{dlow}, layer swaps attn={res['swaps_attn']} ffn={res['swaps_ffn']} err={res['err']:.2e}")
+
