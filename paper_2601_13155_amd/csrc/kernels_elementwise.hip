@@ -188,6 +188,56 @@ hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int
     return hipGetLastError();
 }
 
+// Row gather with its bookkeeping in one launch: out[i, :] = in[idx[i], :] and, where wanted, pos_out[i] = pos_in[idx[i]]
+// and old2new[idx[i]] = i.  A workgroup takes 1024 16-byte vectors (8 rows of 2 KB, 2 rows of 8 KB, ...): every lane has
+// four independent loads (64 bytes) in flight before its first store.
+__global__ void __launch_bounds__(256) gather_rows_maps_kernel(const u32x4* __restrict__ in, const int32_t* __restrict__ idx,
+                                                               u32x4* __restrict__ out, int64_t n, int row_vec, int rows_per_wg,
+                                                               const int32_t* __restrict__ pos_in, int32_t* __restrict__ pos_out,
+                                                               int32_t* __restrict__ old2new) {
+    const int64_t row0 = (int64_t)blockIdx.x * rows_per_wg;
+    const int total = rows_per_wg * row_vec;      // vectors of this workgroup (<= 1024, or one row of any length)
+    for (int base = 0; base < total; base += 1024) {
+        u32x4 v[4];
+        int64_t dst[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = base + u * 256 + (int)threadIdx.x;
+            const int r = e / row_vec, c = e - r * row_vec;
+            const int64_t row = row0 + r;
+            dst[u] = -1;
+            if (e < total && row < n) {
+                v[u] = in[(int64_t)idx[row] * row_vec + c];
+                dst[u] = row * row_vec + c;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (dst[u] >= 0) out[dst[u]] = v[u];
+    }
+    if ((int)threadIdx.x < rows_per_wg) {
+        const int64_t row = row0 + threadIdx.x;
+        if (row < n) {
+            const int32_t src = idx[row];
+            if (pos_out) pos_out[row] = pos_in[src];
+            if (old2new) old2new[src] = (int32_t)row;
+        }
+    }
+}
+
+hipError_t launch_gather_rows_maps(const void* in, const int32_t* idx, void* out, int64_t n, int64_t row_bytes,
+                                   const int32_t* pos_in, int32_t* pos_out, int32_t* old2new, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    if (row_bytes % 16 != 0 || row_bytes / 16 > (int64_t)1 << 24) return hipErrorInvalidValue;
+    const int row_vec = (int)(row_bytes / 16);
+    int rows_per_wg = 1024 / row_vec;
+    if (rows_per_wg < 1) rows_per_wg = 1;
+    if (rows_per_wg > 256) rows_per_wg = 256;
+    gather_rows_maps_kernel<<<dim3((unsigned)cdiv(n, rows_per_wg)), dim3(256), 0, s>>>((const u32x4*)in, idx, (u32x4*)out, n, row_vec,
+                                                                                     rows_per_wg, pos_in, pos_out, old2new);
+    return hipGetLastError();
+}
+
 __global__ void gather_i32_kernel(const int32_t* __restrict__ in, const int32_t* __restrict__ idx, int32_t* __restrict__ out, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) out[i] = in[idx[i]];

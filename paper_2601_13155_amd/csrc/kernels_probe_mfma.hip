@@ -38,7 +38,6 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
     using L = ProbeLds<D>;
     constexpr int KS = D / 16;
     __shared__ __attribute__((aligned(16))) char sK[2][L::K_BYTES];
-    __shared__ __attribute__((aligned(16))) float sStat[PASS == 2 ? 128 * RB * 2 : 4];
     __shared__ float sRed[4][PKV];
 
     const int chunk = blockIdx.x, g = blockIdx.y;
@@ -64,8 +63,18 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[rb][ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
     }
+    // pass 2: the lane's 16 rows per block keep their exponent offset in registers: exp2(s * scale - M) / L is taken as
+    // exp2(fma(s, scale, log2(1/L) - M)) (padded rows and empty rows: offset -inf, probability 0)
+    float coff[PASS == 2 ? RB : 1][16];
     if (PASS == 2) {
-        for (int i = tid; i < 128 * RB * 2; i += 256) sStat[i] = stats[(int64_t)g * Rp * 2 + i];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rr = wave * 32 * RB + rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                const float2 st = *reinterpret_cast<const float2*>(stats + ((int64_t)g * Rp + rr) * 2);
+                coff[rb][r] = st.y > 0.f ? __builtin_amdgcn_logf(st.y) - st.x : -INFINITY;
+            }
     }
 
     constexpr int KCH = PKV * L::CPRK / 256;
@@ -153,22 +162,14 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
                     // lane: key = column kb*32 + l32; rows = rb*32 + 8*(r/4) + 4*lh + r%4
                     const int64_t key = key0 + kb * 32 + l32;
 #pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const int rbase = wave * 32 * RB + rb * 32 + 8 * q4 + 4 * lh;
-                        const float4 st0 = *reinterpret_cast<const float4*>(&sStat[2 * rbase]);
-                        const float4 st1 = *reinterpret_cast<const float4*>(&sStat[2 * rbase + 4]);
-                        const float mm[4] = {st0.x, st0.z, st1.x, st1.z};
-                        const float il[4] = {st0.y, st0.w, st1.y, st1.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            float pv = __builtin_amdgcn_exp2f(s[4 * q4 + e] * scale_log2e - mm[e]) * il[e];
-                            if (need_mask) {
-                                const int rr = rbase + e;
-                                const int64_t vl = rr < R ? a.N - a.P + rr / grp : -1;
-                                if (key > vl) pv = 0.f;
-                            }
-                            ksum[kb] += pv;
+                    for (int r = 0; r < 16; ++r) {
+                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2e, coff[rb][r]));
+                        if (need_mask) {
+                            const int rr = wave * 32 * RB + rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                            const int64_t vl = rr < R ? a.N - a.P + rr / grp : -1;
+                            if (key > vl) pv = 0.f;
                         }
+                        ksum[kb] += pv;
                     }
                 }
             }

@@ -307,6 +307,20 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
     return SPTS_OK;
 }
 
+// out[i, :] = in[idx[i], :] with the position gather and the old->new map (each optional) in the same launch when rows
+// are whole 16-byte vectors, else as separate launches
+int gather_rows_maps(spts_ctx* c, const void* in, const int32_t* idx, void* out, int64_t n, int64_t row_bytes,
+                     const int32_t* pos_in, int32_t* pos_out, int32_t* old2new) {
+    if (row_bytes % 16 == 0) {
+        SPTS_HIP(c, launch_gather_rows_maps(in, idx, out, n, row_bytes, pos_in, pos_out, old2new, c->stream));
+        return SPTS_OK;
+    }
+    SPTS_HIP(c, launch_gather_rows(in, idx, out, n, row_bytes, c->stream));
+    if (pos_out) SPTS_HIP(c, launch_gather_i32(pos_in, idx, pos_out, n, c->stream));
+    if (old2new) SPTS_HIP(c, launch_scatter_iota(idx, old2new, n, c->stream));
+    return SPTS_OK;
+}
+
 // TopK of one score row: longer rows are spread over the chip (a launch per radix pass), short ones stay in one workgroup
 int run_topk(spts_ctx* c, const float* scores, int64_t N, int64_t k, int protect_last, int32_t* idx_out) {
     if (N >= TOPK_MULTI_MIN_N && N <= TOPK_MULTI_MAX_N)
@@ -725,10 +739,7 @@ int spts_msdp_compact(spts_ctx* c, const void* x_in, const int32_t* pos_in, cons
     if (keep == 0) return SPTS_OK;
     SPTS_TRY(run_topk(c, s_mha, N, keep, protect_last, map_new2old));
     const int64_t row_bytes = (int64_t)c->m.D * (c->bf16 ? 2 : 4);
-    SPTS_HIP(c, launch_gather_rows(x_in, map_new2old, x_out, keep, row_bytes, c->stream));
-    SPTS_HIP(c, launch_gather_i32(pos_in, map_new2old, pos_out, keep, c->stream));
-    if (map_old2new) SPTS_HIP(c, launch_scatter_iota(map_new2old, map_old2new, keep, c->stream));
-    return SPTS_OK;
+    return gather_rows_maps(c, x_in, map_new2old, x_out, keep, row_bytes, pos_in, pos_out, map_old2new);
 }
 
 int spts_msdp_compact_batched(spts_ctx* c, const void* x_in, const int32_t* pos_in, const float* s_mha,
@@ -774,10 +785,7 @@ int spts_msdp_compact_batched(spts_ctx* c, const void* x_in, const int32_t* pos_
     SPTS_HIP(c, launch_topk(s_mha, max_len, 0, protect_last, map_new2old, batch, c->stream, segs));
     SPTS_HIP(c, launch_add_segment_base(map_new2old, segs.out_offsets, segs.offsets, batch, keep, c->stream));
     const int64_t row_bytes = (int64_t)c->m.D * (c->bf16 ? 2 : 4);
-    SPTS_HIP(c, launch_gather_rows(x_in, map_new2old, x_out, keep, row_bytes, c->stream));
-    SPTS_HIP(c, launch_gather_i32(pos_in, map_new2old, pos_out, keep, c->stream));
-    if (map_old2new) SPTS_HIP(c, launch_scatter_iota(map_new2old, map_old2new, keep, c->stream));
-    return SPTS_OK;
+    return gather_rows_maps(c, x_in, map_new2old, x_out, keep, row_bytes, pos_in, pos_out, map_old2new);
 }
 
 int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, const spts_layer_weights* w,
@@ -834,19 +842,19 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         void* kk = kall;
         void* vv;
         if (skip) {
+            // K-hat = K[T_a] and the active positions, straight into the cache when there is one: one launch
             int32_t* posA = (kv && !full_kv) ? kv->pos : c->p<int32_t>(c->off.posA);
             PHASE(c, PH_GATHER);
-            SPTS_HIP(c, launch_gather_i32(pos, idxA, posA, Ma, st));
+            if (!full_kv) {
+                kk = kv ? kv->k : c->p<void>(c->off.khat);
+                SPTS_TRY(gather_rows_maps(c, kall, idxA, kk, Ma, (int64_t)KV * eb, pos, posA, nullptr));
+                kpos = posA;
+            } else {
+                SPTS_HIP(c, launch_gather_i32(pos, idxA, posA, Ma, st));
+            }
             qpos = posA;
         }
-        if (!full_kv) {
-            kk = kv ? kv->k : c->p<void>(c->off.khat);
-            PHASE(c, PH_GATHER);
-            SPTS_HIP(c, launch_gather_rows(kall, idxA, kk, Ma, (int64_t)KV * eb, st));
-            kpos = qpos;
-        } else if (kv) {
-            SPTS_HIP(c, launch_copy_bytes(pos, kv->pos, N * 4, st));
-        }
+        if (full_kv && kv) SPTS_HIP(c, launch_copy_bytes(pos, kv->pos, N * 4, st));
         vv = kv ? kv->v : c->p<void>(c->off.vhat);
         AttnArgs aa{};
         aa.q = c->p<void>(c->off.q); aa.k = kk; aa.v = vv; aa.qpos = qpos; aa.kpos = kpos; aa.out = c->p<void>(c->off.att);
@@ -997,8 +1005,7 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
         char* vhat = c->p<char>(c->off.vhat);
         if (skip) {
             PHASE(c, PH_GATHER);
-            SPTS_HIP(c, launch_gather_i32(pos, idxA, c->p<int32_t>(c->off.posA), MaT, st));
-            SPTS_HIP(c, launch_gather_rows(kall, idxA, c->p<void>(c->off.khat), MaT, (int64_t)KV * eb, st));
+            SPTS_TRY(gather_rows_maps(c, kall, idxA, c->p<void>(c->off.khat), MaT, (int64_t)KV * eb, pos, c->p<int32_t>(c->off.posA), nullptr));
             posA = c->p<int32_t>(c->off.posA);
             khat = c->p<char>(c->off.khat);
         }

@@ -119,6 +119,10 @@ hipError_t launch_rope_apply(const float* in, const float2* table, const int32_t
                              int64_t n, int heads, int d, bool bf16, hipStream_t s);
 // out[i, :] = in[idx[i], :]   (row_bytes multiple of 4)
 hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n, int64_t row_bytes, hipStream_t s);
+// out[i, :] = in[idx[i], :] (row_bytes multiple of 16) and, in the same launch, pos_out[i] = pos_in[idx[i]] (when pos_out) and
+// old2new[idx[i]] = i (when old2new)
+hipError_t launch_gather_rows_maps(const void* in, const int32_t* idx, void* out, int64_t n, int64_t row_bytes,
+                                   const int32_t* pos_in, int32_t* pos_out, int32_t* old2new, hipStream_t s);
 hipError_t launch_gather_i32(const int32_t* in, const int32_t* idx, int32_t* out, int64_t n, hipStream_t s);
 hipError_t launch_copy_bytes(const void* in, void* out, int64_t bytes, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
