@@ -243,6 +243,128 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restr
     }
 }
 
+// Long rows of a batch (N > 32768, N % 4 == 0, equal rows): one workgroup per row as above, but written for streaming.
+// Every wavefront owns one contiguous slice in all sweeps and reads it as 16-byte loads, four per lane in flight (64 KB per
+// workgroup); histograms are private to the wavefront (16 x 256 counters in LDS, summed before the bin is picked), and the
+// last radix pass leaves what the compaction needs -- per wavefront the keys above the decided prefix and the histogram
+// of the last digit -- so no separate counting sweep is needed: five sweeps over the row instead of six.
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+constexpr int LONG_U = 4;                       // 16-byte loads in flight per lane
+constexpr int LONG_STEP = 64 * 4 * LONG_U;      // scores a wavefront takes per iteration
+
+__global__ void __launch_bounds__(TOPK_THREADS) topk_long_kernel(const float* __restrict__ scores, int64_t N, int64_t k,
+                                                                 int protect_last, int32_t* __restrict__ idx_out) {
+    __shared__ int whist[TOPK_WAVES][256];
+    __shared__ int hist[256];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int64_t sh_need;
+    __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
+    scores += (int64_t)blockIdx.x * N;
+    idx_out += (int64_t)blockIdx.x * k;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = (int)N;
+    const int per_wave = ((n + TOPK_WAVES - 1) / TOPK_WAVES + LONG_STEP - 1) / LONG_STEP * LONG_STEP;
+    const int lo = wave * per_wave;
+    const int hi = lo + per_wave < n ? lo + per_wave : n;   // n % 4 == 0, so a 16-byte load that starts below hi ends below it
+    const uint32_t last_key_at = protect_last ? (uint32_t)(n - 1) : 0xFFFFFFFFu;
+
+    if (tid == 0) { sh_prefix = 0; sh_need = k; }
+    uint32_t prefix = 0;
+    int64_t need = k;
+    int cgt = 0;   // last pass: keys of this wavefront's slice whose decided 24 bits exceed the prefix
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+        for (int i = lane; i < 256; i += 64) whist[wave][i] = 0;
+        __syncthreads();
+        for (int base = lo; base < hi; base += LONG_STEP) {
+            f32x4v v[LONG_U];
+#pragma unroll
+            for (int u = 0; u < LONG_U; ++u) {
+                const int i0 = base + u * 256 + lane * 4;
+                v[u] = i0 < hi ? *reinterpret_cast<const f32x4v*>(scores + i0) : f32x4v{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < LONG_U; ++u) {
+                const int i0 = base + u * 256 + lane * 4;
+                const bool valid = i0 < hi;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    uint32_t key = order_key(v[u][e]);
+                    if ((uint32_t)(i0 + e) == last_key_at) key = 0xFFFFFFFFu;
+                    hist_add(whist[wave], valid && (key & hi_mask) == prefix, (int)((key >> shift) & 0xFF));
+                    if (pass == 3) cgt += (int)__popcll(__ballot(valid && (key & hi_mask) > prefix));
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < 256) {
+            int t = 0;
+#pragma unroll
+            for (int w = 0; w < TOPK_WAVES; ++w) t += whist[w][tid];
+            hist[tid] = t;
+        }
+        __syncthreads();
+        if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
+        __syncthreads();
+        prefix = sh_prefix;
+        need = sh_need;
+    }
+    const uint32_t T = prefix;
+    const int need_eq = (int)need;
+    // this wavefront's keys above T / equal to T, from its own last-digit histogram
+    {
+        const int digit = (int)(T & 0xFFu);
+        int above = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int b = lane * 4 + q;
+            above += b > digit ? whist[wave][b] : 0;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) above += __shfl_xor(above, off);
+        if (lane == 0) { wave_gt[wave] = above + cgt; wave_eq[wave] = whist[wave][digit]; }
+    }
+    __syncthreads();
+    int gt_before = 0, eq_before = 0;
+    for (int w = 0; w < wave; ++w) { gt_before += wave_gt[w]; eq_before += wave_eq[w]; }
+    // ordered compaction of the slice: index order inside an iteration is (load u, lane, element e)
+    for (int base = lo; base < hi; base += LONG_STEP) {
+        f32x4v v[LONG_U];
+#pragma unroll
+        for (int u = 0; u < LONG_U; ++u) {
+            const int i0 = base + u * 256 + lane * 4;
+            v[u] = i0 < hi ? *reinterpret_cast<const f32x4v*>(scores + i0) : f32x4v{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < LONG_U; ++u) {
+            const int i0 = base + u * 256 + lane * 4;
+            const bool valid = i0 < hi;
+            bool gt[4], eq[4];
+            int lower_gt = 0, lower_eq = 0, tot_gt = 0, tot_eq = 0;   // selected keys of lower lanes / of the whole wavefront, this load
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint32_t key = order_key(v[u][e]);
+                if ((uint32_t)(i0 + e) == last_key_at) key = 0xFFFFFFFFu;
+                gt[e] = valid && key > T;
+                eq[e] = valid && key == T;
+                const uint64_t mg = __ballot(gt[e]), me = __ballot(eq[e]);
+                lower_gt += lane_prefix_popc(mg); lower_eq += lane_prefix_popc(me);
+                tot_gt += (int)__popcll(mg); tot_eq += (int)__popcll(me);
+            }
+            int my_gt = gt_before + lower_gt, my_eq = eq_before + lower_eq;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (gt[e] || (eq[e] && my_eq < need_eq)) idx_out[my_gt + (my_eq < need_eq ? my_eq : need_eq)] = i0 + e;
+                my_gt += gt[e] ? 1 : 0;
+                my_eq += eq[e] ? 1 : 0;
+            }
+            gt_before += tot_gt;
+            eq_before += tot_eq;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // One problem spread over the chip (N up to TOPK_MULTI_MAX_N): the same radix select, but every 8-bit
 // pass is its own launch of G workgroups, and no workgroup ever communicates with another one inside
@@ -531,6 +653,7 @@ hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_la
     if (N <= 1024 * 8) topk_reg_kernel<8><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
     else if (N <= 1024 * 16) topk_reg_kernel<16><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
     else if (N <= 1024 * 32) topk_reg_kernel<32><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
+    else if (!seg.offsets && N % 4 == 0 && N < ((int64_t)1 << 30)) topk_long_kernel<<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
     else topk_kernel<<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
     return hipGetLastError();
 }

@@ -294,7 +294,17 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
             SPTS_TRY(run_gemm(c, g2));
         }
     }
-    { PHASE(c, PH_PROXY_MID); SPTS_TRY(run_gemm(c, g3)); }
+    {
+        PHASE(c, PH_PROXY_MID);
+        // hidden layer: the register-stationary kernel when the projection behind it reads the hidden state slab-major
+        // and the factors come with their slab-major copies; else the dual-product GEMM
+        ProxyHiddenArgs ph{};
+        ph.Vg_s = w->Vg_s; ph.Vu_s = w->Vu_s; ph.hp = c->p<void>(c->off.big); ph.N = N; ph.Dlow = Dlow; ph.r = r;
+        if (g3.a_slab) { ph.tg = t; ph.tu = t + (size_t)(r / 32) * (size_t)N * 64; ph.t_row_pitch = 64; ph.t_slab_pitch = N * 64; }
+        else { ph.tg = t; ph.tu = t + (size_t)r * eb; ph.t_row_pitch = (int64_t)2 * r * eb; ph.t_slab_pitch = 64; }
+        if (c->bf16 && g4.a_slab && proxy_hidden_supported(ph)) SPTS_HIP(c, launch_proxy_hidden(ph, c->stream));
+        else SPTS_TRY(run_gemm(c, g3));
+    }
     { PHASE(c, PH_PROXY_Z); SPTS_TRY(run_gemm(c, g4)); }
     // o = z Ud^T [N, D] is never stored: per-block sums of squares, then the square root
     GemmArgs g5 = gemm_args(c->p<void>(c->off.z), r, nullptr, w->Ud, r, nullptr, 0, N, m.D, r, EPI_SUMSQ);

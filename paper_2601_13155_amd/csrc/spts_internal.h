@@ -109,6 +109,19 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s);
 // number of column blocks a EPI_SUMSQ launch writes per row
 int gemm_sumsq_blocks(int32_t N, bool mfma);
 
+// ------------------------------------------------------------------ proxy hidden layer (register-stationary rows)
+// h[n, c] = silu(t_g[n, :] . Vg[c, :]) * (t_u[n, :] . Vu[c, :]) for n < N, c < Dlow, written slab-major [Dlow/32][N][32].
+// t_g / t_u: element (n, k) at base + n * t_row_pitch + (k / 32) * t_slab_pitch + (k % 32) * 2 bytes (covers a row-major
+// [N, 2r] matrix and a slab-major one); Vg_s / Vu_s: slab-major copies [r/32][Dlow][32] of the factors.
+struct ProxyHiddenArgs {
+    const void* tg; const void* tu; int64_t t_row_pitch, t_slab_pitch;
+    const void* Vg_s; const void* Vu_s;
+    void* hp;
+    int64_t N; int32_t Dlow; int32_t r;
+};
+bool proxy_hidden_supported(const ProxyHiddenArgs& a);
+hipError_t launch_proxy_hidden(const ProxyHiddenArgs& a, hipStream_t s);
+
 // ------------------------------------------------------------------ elementwise / data movement
 // slab-major copy of a row-major [rows, K] matrix of 2-byte elements: out[(s * rows + r) * 32 + j] = W[r * K + 32 * s + j]
 hipError_t launch_pack_slab32(const void* W, int64_t rows, int64_t K, void* out, hipStream_t s);

@@ -114,7 +114,8 @@ def test_select_topk_deterministic_and_nested(torch):
 def test_select_topk_batched_rows_match_oracle(torch):
     rng = np.random.default_rng(2)
     ctx = ctx_for(synth.TINY, 131072)
-    for n, batch in ((1000, 7), (8193, 5), (40000, 3)):
+    # 40000, 65540 and 131072 take the streaming long-row kernel (16-byte loads), 40001 the scalar one
+    for n, batch in ((1000, 7), (8193, 5), (40000, 3), (40001, 2), (65540, 3), (131072, 2)):
         s = ((1.0 + 0.3 * rng.standard_normal((batch, n))).clip(0.05, None) / n).astype(np.float32)
         s[1, ::3] = s[1, 0]   # a row with many ties
         sd = torch.from_numpy(s).cuda()
