@@ -234,6 +234,38 @@ def test_probe_attn_and_ffn(torch, name, shape, N, P, r):
     assert torch.equal(f2, cd)
 
 
+@pytest.mark.parametrize("N,dlow", [(1, 0), (31, 0), (257, 0), (1237, 0), (2048, 0), (900, 256), (1500, 512), (3000, 1024)],
+                         ids=lambda v: str(v))
+def test_probe_ffn_hidden_layer_kernel_shapes(torch, N, dlow):
+    """LTP probe with the rank-256 proxy, whose hidden layer runs in the register-stationary kernel: row counts around its
+    32-row wavefronts and 256-row workgroups, channel counts of 8 to 64 tiles (all of Dff, or Dlow < Dff channels), against
+    the oracle; and against the same call with row-major factors only (no slab-major copies: the hidden layer then takes the
+    dual-product GEMM), which must give the same scores to the last bit but for K-split groupings of the projection."""
+    shape = synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0)
+    ctx = ctx_for(shape, 4096)
+    w = synth.make_layer(15, 0, shape, 256, dlow=dlow)
+    x = synth.hidden_states(15, N, shape.D, shape.dtype)
+    mdl = H.oracle_model(shape)
+    tol = H.TOL["bf16"]["score"]
+    s_mha = np.random.default_rng(N).random(N).astype(np.float32)
+    xd = runtime.to_device(x, shape.dtype)
+    sd = torch.from_numpy(s_mha).cuda()
+    outs = []
+    for pack in (True, False):
+        dw = runtime.upload_layer(w, shape, 256, pack=pack)
+        assert dw.Dlow == (dlow or shape.Dff) and bool(dw.Vg_s) == pack
+        cd = torch.full((N,), -1.0, dtype=torch.float32, device="cuda")
+        fd = torch.full((N,), -1.0, dtype=torch.float32, device="cuda")
+        ctx.spts_probe_ffn(xd, N, dw, sd, cd, fd)
+        torch.cuda.synchronize()
+        outs.append((cd.cpu().numpy(), fd.cpu().numpy()))
+    c_ref, f_ref = orc.probe_ffn(x, w, mdl, s_mha, orc.bf16_round)
+    for c_got, f_got in outs:
+        assert H.score_rel_err(c_got, c_ref) <= tol, H.score_rel_err(c_got, c_ref)
+        assert H.score_rel_err(f_got, f_ref) <= tol
+    assert H.score_rel_err(outs[0][0], outs[1][0]) <= 1e-2
+
+
 # ------------------------------------------------------------------------------------------ layer
 LAYER_CASES = [
     # name, shape, N, P, r, keep_attn, keep_ffn
