@@ -29,8 +29,9 @@
 //    is rescaled only when some lane's running maximum moved.
 //  * Key tiles beyond the last visible position are never visited; tiles that are entirely visible
 //    to a wavefront skip the mask; a wavefront whose queries see nothing of a tile skips its work.
-//  * Work ids are laid out (kv head, query tile descending, head in group) and split contiguously
-//    over the 8 XCDs: the heads that share a KV head run on the same XCD's L2, longest tiles first.
+//  * Work items are laid out (kv head, query tile descending, head in group) and split over the 8 XCDs so that the heads
+//    that share a KV head run on the same XCD's L2, longest tiles first: contiguously when there are at least 8 kv heads,
+//    dealt out in turn to the XCDs of a head's group when there are fewer (so that every XCD gets long and short tiles).
 #include "spts_internal.h"
 
 namespace spts {
@@ -61,7 +62,7 @@ template <int D> struct AttnLds {
 __device__ inline uint32_t pk2(float a, float b) { return cvt_pk_bf16(a, b); }
 
 template <int D, int QB, int NW>
-__global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, int total, float scale_log2e) {
+__global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, int total, int xpg, float scale_log2e) {
     using L = AttnLds<D>;
     constexpr int BQ = NW * QB * 32;
     constexpr int KS = D / 16;   // k-steps of the QK^T product
@@ -78,13 +79,27 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
     static_assert(QB == 1 && (NSTEP == 16 || NSTEP == 8), "the pipeline slot is written for one 32-query block per wavefront");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    const int per = (total + 7) / 8;
-    const int id = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
-    if (id >= total) return;
+    // Work item = (kv head g, query tile, head hg of the group), the items of a kv head ordered longest tile first.
+    // Workgroup b runs on XCD b % 8 as that XCD's (b / 8)-th workgroup.  With at least 8 kv heads every XCD takes a
+    // contiguous range of items (whole kv heads when Hkv % 8 == 0).  With fewer kv heads (xpg = 8 / Hkv XCDs per head) a
+    // contiguous range would give one XCD of the group the long tiles and another the short ones (a causal tile's work
+    // grows with its index), so the items of a head are dealt out to its XCDs in turn.
     const int grp = a.H / a.Hkv;
-    const int hg = id % grp;
-    const int qtile = nQ - 1 - (id / grp) % nQ;
-    const int g = id / (grp * nQ);
+    int g, item;
+    if (xpg > 1) {
+        const int xcd = (int)(blockIdx.x % 8), pos = (int)(blockIdx.x / 8);
+        g = xcd / xpg;
+        item = pos * xpg + xcd % xpg;
+        if (item >= nQ * grp) return;
+    } else {
+        const int per = (total + 7) / 8;
+        const int id = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
+        if (id >= total) return;
+        g = id / (grp * nQ);
+        item = id % (grp * nQ);
+    }
+    const int hg = item % grp;
+    const int qtile = nQ - 1 - item / grp;
     const int h = g * grp + hg;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -369,14 +384,17 @@ static hipError_t launch_attn_t(const AttnArgs& a, hipStream_t s) {
     constexpr int BQ = NW * QB * 32;
     const int nQ = (int)((a.Mq + BQ - 1) / BQ);
     const int total = nQ * a.H;
-    const int grid = (total + 7) / 8 * 8;
+    // XCDs per kv head when the kv heads are fewer than the XCDs and divide them; 1 = contiguous split of all items
+    const int xpg = (a.Hkv < 8 && 8 % a.Hkv == 0) ? 8 / a.Hkv : 1;
+    const int grp = a.H / a.Hkv;
+    const int grid = xpg > 1 ? 8 * ((nQ * grp + xpg - 1) / xpg) : (total + 7) / 8 * 8;
     const size_t lds = (size_t)AttnLds<D>::STAGE * ATT_NST;
     {
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_mfma_kernel<D, QB, NW>), (int)lds);
         if (e != hipSuccess) return e;
     }
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-    attn_mfma_kernel<D, QB, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nQ, total, scale_log2e);
+    attn_mfma_kernel<D, QB, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nQ, total, xpg, scale_log2e);
     return hipGetLastError();
 }
 
