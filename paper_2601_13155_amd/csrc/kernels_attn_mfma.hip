@@ -7,14 +7,15 @@
 //
 // Layout of the computation (gfx950, wave64, MFMA 32x32x16 bf16):
 //  * S^T = K Q^T is computed instead of S: the MFMA result then has one query per lane column, so
-//    the row maximum / row sum of the online softmax are in-lane reductions plus one exchange with
-//    lane^32, and the probabilities already sit in the operand layout of the second product.
+//    the row sum of the softmax is an in-lane reduction plus one exchange with lane^32 at the end,
+//    and the probabilities already sit in the operand layout of the second product.
 //  * O^T += V^T P^T takes V^T tiles (keys contiguous) as the A operand.  The value projection
 //    writes that transposed copy with the keys of every 16-group in the order the probability
 //    fragments come out of the matrix core (vt_key_slot), so a value fragment is one 16-byte read.
 //  * One workgroup = 8 wavefronts x 32 queries of one head (256 queries): two wavefronts per SIMD, so
 //    one wavefront's softmax arithmetic and LDS latencies hide behind the other's MFMAs (4 wavefronts
-//    x 64 queries halve the LDS traffic but leave every LDS round trip exposed: 540 vs 820 TFLOP/s).
+//    x 64 queries halve the LDS traffic but leave every LDS round trip exposed: 540 vs 820 TFLOP/s with the
+//    earlier softmax).
 //    K / V^T tiles of 64 keys travel global memory -> LDS directly (global_load_lds_dwordx4, swizzle
 //    applied on the global side) into a ring of 5 stages (all 160 KB): tile t+3 is in flight while the
 //    keys of tiles t and t+1 and the values of tiles t-1 and t are multiplied; one barrier per tile.
@@ -24,9 +25,14 @@
 //    of the softmax.  A wavefront issues in order, so vector instructions only run in the shadow of an
 //    MFMA when they sit right behind it in the instruction stream (measured on this chip: a 1:1 mix of
 //    MFMA time and vector time takes 0.75 of their sum when interleaved, their sum when not).
-//    The softmax scale is folded into the exponent's FMA, probabilities are packed with the hardware
-//    bf16 converter, the row maximum crosses the two lane halves with v_permlane32_swap, the accumulator
-//    is rescaled only when some lane's running maximum moved.
+//    With the textbook online softmax (scale folded into an FMA, running maximum per block, rescale when it moved)
+//    the vector ALU was as busy as the matrix pipe (57 % / 56 % of the cycles, counters) and the two overlapped for
+//    only half of that; the softmax here is cut to one exponential per logit and one conversion + one dot product
+//    per pair (see the slot below): q arrives pre-scaled, the MFMA starts from minus a reference maximum that
+//    moves only when a block overflows it by a wide margin, the row sum is a bf16 dot product with (1, 1).
+//    816 -> ~970 TFLOP/s at 13107 x 13107, 32 heads.  What is left is issue-bound rather than bound by one unit:
+//    timing variants without the softmax, without the fragment reads, without the tile loads or without the barrier
+//    each gain 4-12 %, and all of them together reach 1450 TFLOP/s (MFMAs only, at the clock the chip then holds).
 //  * Key tiles beyond the last visible position are never visited; tiles that are entirely visible
 //    to a wavefront skip the mask; a wavefront whose queries see nothing of a tile skips its work.
 //  * Work items are laid out (kv head, query tile descending, head in group) and split over the 8 XCDs so that the heads
@@ -38,9 +44,12 @@ namespace spts {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BKV = 64;
 constexpr int ATT_NST = 5;
+constexpr float ATT_TAU = 8.0f;        // a query's reference maximum moves to a block's maximum that is this far above it (log2 units)
+constexpr float ATT_SUM_MAX = 4096.0f; // a lane asks for the check when its 16 probabilities of a block sum to more (16 * 2^ATT_TAU)
 
 template <int D> struct AttnLds {
     static constexpr int K_BYTES = BKV * D * 2;
@@ -62,7 +71,7 @@ template <int D> struct AttnLds {
 __device__ inline uint32_t pk2(float a, float b) { return cvt_pk_bf16(a, b); }
 
 template <int D, int QB, int NW>
-__global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, int total, int xpg, float scale_log2e) {
+__global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, int total, int xpg, float qmul) {
     using L = AttnLds<D>;
     constexpr int BQ = NW * QB * 32;
     constexpr int KS = D / 16;   // k-steps of the QK^T product
@@ -71,7 +80,6 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
     constexpr int V_LOADS = L::template v_loads<NW>();
     constexpr int PER = K_LOADS + V_LOADS;
     constexpr int NSTEP = KS + 2 * DB;   // MFMAs per pipeline slot: QK^T of one block + PV of another
-    constexpr int NA = NSTEP / 8;
 #ifndef SPTS_ATT_FD
 #define SPTS_ATT_FD 3
 #endif
@@ -141,6 +149,17 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
         const bf16_t* qr = Q + (qi * a.H + h) * (int64_t)D + 8 * lh;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
+        // q normally arrives carrying log2(e)/sqrt(d) (qmul == 1); otherwise the rest of the factor is folded in here
+        if (qmul != 1.0f) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                u32x4 raw = __builtin_bit_cast(u32x4, qf[qb][ks]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    raw[j] = pk2(__uint_as_float(raw[j] << 16) * qmul, __uint_as_float(raw[j] & 0xffff0000u) * qmul);
+                qf[qb][ks] = __builtin_bit_cast(bf16x8, raw);
+            }
+        }
     }
 
     // ---- direct-to-LDS tile loads.  Wavefront w moves K rows [64/NW*w, 64/NW*(w+1)) and V^T rows
@@ -148,31 +167,41 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
     const bf16_t* Kg = (const bf16_t*)a.k;
     const bf16_t* Vt = (const bf16_t*)a.vt;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    // A lane's byte offset from the tile's first key (K) / first key column of the kv head's V^T rows is the same for
+    // every tile; the tile's base is wavefront-uniform and advances in scalar registers.
     int krow[K_LOADS], kchunk[K_LOADS];
-    const bf16_t* vptr[V_LOADS];
+    uint32_t koffv[K_LOADS], voffv[V_LOADS];
 #pragma unroll
     for (int q = 0; q < K_LOADS; ++q) {
         krow[q] = wave * (BKV / NW) + q * L::K_ROWS_PER_LOAD + lane / L::CPRK;
         kchunk[q] = (lane % L::CPRK) ^ L::kswz(krow[q]);
+        koffv[q] = (uint32_t)((krow[q] * a.Hkv * D + kchunk[q] * 8) * 2);
     }
 #pragma unroll
     for (int q = 0; q < V_LOADS; ++q) {
         const int row = wave * (D / NW) + q * 8 + (lane >> 3);
         const int c = (lane & 7) ^ L::vswz(row);
-        vptr[q] = Vt + ((int64_t)g * D + row) * a.ldvt + c * 8;
+        voffv[q] = (uint32_t)(((int64_t)row * a.ldvt + c * 8) * 2);   // < 2^32: checked on the host
     }
+    const bf16_t* Vg = Vt + (int64_t)g * D * a.ldvt;
 #define SPTS_ATT_DMA(t_)                                                                                   \
     {                                                                                                      \
         const int64_t key0_ = (int64_t)(t_) * BKV;                                                         \
         const uint32_t sb_ = lds0 + ((t_) % ATT_NST) * L::STAGE;                                           \
-        _Pragma("unroll") for (int q = 0; q < K_LOADS; ++q) {                                              \
-            int64_t key_ = key0_ + krow[q];                                                                \
-            if (key_ >= a.Mk) key_ = a.Mk - 1;                                                             \
-            dma16(Kg + (key_ * a.Hkv + g) * (int64_t)D + kchunk[q] * 8,                                    \
-                  sb_ + wave * (BKV / NW * 2 * D) + q * 1024);                                             \
+        if (key0_ + BKV <= a.Mk) {                                                                         \
+            const bf16_t* kb_ = Kg + (key0_ * a.Hkv + g) * (int64_t)D;                                     \
+            _Pragma("unroll") for (int q = 0; q < K_LOADS; ++q)                                            \
+                dma16s(koffv[q], kb_, sb_ + wave * (BKV / NW * 2 * D) + q * 1024);                         \
+        } else {   /* last, partial tile: rows past the end re-read the last key (masked later) */         \
+            _Pragma("unroll") for (int q = 0; q < K_LOADS; ++q) {                                          \
+                int64_t key_ = key0_ + krow[q];                                                            \
+                if (key_ >= a.Mk) key_ = a.Mk - 1;                                                         \
+                dma16(Kg + (key_ * a.Hkv + g) * (int64_t)D + kchunk[q] * 8,                                \
+                      sb_ + wave * (BKV / NW * 2 * D) + q * 1024);                                         \
+            }                                                                                              \
         }                                                                                                  \
         _Pragma("unroll") for (int q = 0; q < V_LOADS; ++q)                                                \
-            dma16(vptr[q] + key0_, sb_ + L::K_BYTES + wave * (D / NW * BKV * 2) + q * 1024);               \
+            dma16s(voffv[q], Vg + key0_, sb_ + L::K_BYTES + wave * (D / NW * BKV * 2) + q * 1024);         \
     }
 
     f32x16 o[DB][QB];
@@ -182,9 +211,12 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[db][qb][r] = 0.f;
-    float m_run[QB], l_run[QB];
+    float l_run[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+    for (int qb = 0; qb < QB; ++qb) l_run[qb] = 0.f;
+    // minus the reference maximum of the lane's query, 16 times: the C operand that starts a block's S^T product, so the
+    // logits leave the matrix core already relative to it
+    f32x16 cinit = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     f32x16 sa[QB], sb[QB];   // S^T of two consecutive 32-key blocks (one being produced, one in the softmax)
     bf16x8 pfa[QB][2], pfb[QB][2];   // probabilities of two consecutive blocks (one being produced, one multiplied)
 #pragma unroll
@@ -196,6 +228,7 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
             pfb[qb][hf] = __builtin_bit_cast(bf16x8, z_);
         }
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
     // S^T block: 32 keys (block kb_ of the tile in `stage_`) x QB*32 queries
 #define SPTS_ATT_QK(SDST, stage_, kb_)                                                                     \
@@ -224,19 +257,34 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
     // block b_.  The matrix pipe and the vector ALU work side by side only when a wavefront offers both
     // kinds of work at once (it issues in order: behind a run of MFMAs it can only wait for the pipe), so
     // the slot is written as NSTEP steps of one MFMA + one fragment read (FD steps ahead) + a share of
-    // the softmax, fenced off from each other for the scheduler:
-    //   steps [0, NA)   running maximum over the lane's 16 logits       (NA = NSTEP/8)
-    //   step  NA        exchange with lane^32, new maximum, exponent offset
-    //   next NSTEP/2    the 16 exponentials and their sum
-    //   next NSTEP/4    packing to bf16 operand fragments
-    // The accumulator is rescaled after the PV product of block b_-1 (it then holds the blocks <= b_-1
-    // relative to the old maximum).  Slot 0 multiplies an all-zero block -1; the slot after a wavefront's
-    // last block (live_ false) only multiplies that block's probabilities: its QK^T product and softmax
-    // run on stale data and leave the running maximum and sum untouched.
+    // the softmax, fenced off from each other for the scheduler.
+    // The vector ALU is the scarcer unit here (counters: both units busy ~57 % of the time with the classic online
+    // softmax), so the softmax is kept to the instructions that cannot be avoided -- per logit one exponential, per
+    // pair of logits one conversion and one dot product with (1, 1) for the row sum:
+    //  * q carries log2(e)/sqrt(d) and every S^T product starts from minus the query's reference maximum (cinit): the
+    //    MFMA delivers the exponent itself.
+    //  * No maximum is taken in the common path.  The reference is the maximum of block 0 and afterwards moves only
+    //    when a lane's sum of 16 probabilities exceeds ATT_SUM_MAX (some logit is then more than ATT_TAU above the
+    //    reference; an overflowed exponential makes the sum infinite and is caught the same way).  The softmax does not
+    //    depend on the reference, and probabilities up to ATT_SUM_MAX are far inside the range of the fp32 sums and
+    //    the bf16 operands.
+    //  * A move is the rare path, taken by the whole wavefront when any lane asks: block maximum per query, the
+    //    block's logits shifted and its probabilities recomputed, the accumulator and the row sum (blocks < b_, whose
+    //    MFMAs were issued above) rescaled, the S^T of block b_+1 (started from the old reference) shifted and cinit
+    //    refreshed.
+    // Slot 0 multiplies an all-zero block -1; the slot after a wavefront's last block (live_ false) only multiplies
+    // that block's probabilities: its QK^T product and softmax run on stale data and leave the reference and the row
+    // sum untouched.
 #define SPTS_ATT_FRAG(s_)                                                                                  \
     ((s_) < KS ? *reinterpret_cast<const bf16x8*>(sQ_ + L::koff(kbq_ * 32 + l32, 2 * ((s_) % KS) + lh))    \
                : *reinterpret_cast<const bf16x8*>(sP_ + L::voff((((s_) - KS) % DB) * 32 + l32,             \
                                                               2 * (2 * kbp_ + ((s_) - KS) / DB) + lh)))
+#define SPTS_ATT_PAIR(c_)                                                                                  \
+    {                                                                                                      \
+        const uint32_t w_ = pk2(p_[2 * (c_)], p_[2 * (c_) + 1]);   /* a scalar: bit_cast of a vector element reads element 0 */ \
+        pk_[(c_) >> 2][(c_) & 3] = w_;                                                                     \
+        sum_ = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w_), ones2, sum_, false);        \
+    }
 #define SPTS_ATT_BLOCK(b_, SC, SN, PC, PP)                                                                 \
     if ((b_) <= nbw) {                                                                                     \
         const bool live_ = (b_) < nbw;                                                                     \
@@ -247,50 +295,49 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
         const int kbq_ = bn_ & 1, kbp_ = bp_ & 1;                                                          \
         bf16x8 fr_[FD + 1];                                                                                \
         _Pragma("unroll") for (int i_ = 0; i_ < FD; ++i_) fr_[i_] = SPTS_ATT_FRAG(i_);                     \
-        float mx_ = -INFINITY, p_[16], sum_ = 0.f, msc_ = 0.f, m_new_ = 0.f, m_use_ = 0.f;                 \
-        const float m_old_ = m_run[0];                                                                     \
+        float p_[16], sum_ = 0.f;                                                                          \
         u32x4 pk_[2];                                                                                      \
         _Pragma("unroll") for (int i_ = 0; i_ < NSTEP; ++i_) {                                             \
             if (i_ + FD < NSTEP) fr_[(i_ + FD) % (FD + 1)] = SPTS_ATT_FRAG(i_ + FD);                       \
             if (i_ < KS)                                                                                   \
-                SN[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr_[i_ % (FD + 1)], qf[0][i_ % KS], i_ == 0 ? zero16 : SN[0], 0, 0, 0); \
+                SN[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr_[i_ % (FD + 1)], qf[0][i_ % KS], i_ == 0 ? cinit : SN[0], 0, 0, 0); \
             else                                                                                           \
                 o[(i_ - KS) % DB][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr_[i_ % (FD + 1)], PP[0][(i_ - KS) / DB], \
                                                                                o[(i_ - KS) % DB][0], 0, 0, 0); \
-            if (i_ < NA) {                                                                                 \
-                _Pragma("unroll") for (int r = i_ * (16 / NA); r < (i_ + 1) * (16 / NA); ++r) mx_ = fmaxf(mx_, SC[0][r]); \
-            } else if (i_ == NA) {                                                                         \
-                const auto sw_ = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx_), __float_as_uint(mx_), false, false); \
-                mx_ = fmaxf(__uint_as_float(sw_[0]), __uint_as_float(sw_[1]));                             \
-                m_new_ = live_ ? fmaxf(m_old_, mx_) : m_old_;                                              \
-                m_use_ = (m_new_ == -INFINITY) ? 0.f : m_new_;                                             \
-                msc_ = m_use_ * scale_log2e;                                                               \
-            } else if (i_ < NA + 1 + NSTEP / 2) {                                                          \
-                constexpr int EPS_ = 32 / NSTEP;   /* exponentials per step */                             \
-                _Pragma("unroll") for (int e = (i_ - NA - 1) * EPS_; e < (i_ - NA) * EPS_; ++e) {          \
-                    p_[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(SC[0][e], scale_log2e, -msc_));          \
-                    sum_ += p_[e];                                                                         \
-                }                                                                                          \
-            } else if (i_ < NA + 1 + NSTEP / 2 + NSTEP / 4) {                                              \
-                constexpr int CPS_ = 32 / NSTEP;   /* packed pairs per step */                             \
-                _Pragma("unroll") for (int c = (i_ - NA - 1 - NSTEP / 2) * CPS_; c < (i_ - NA - NSTEP / 2) * CPS_; ++c) \
-                    pk_[c >> 2][c & 3] = pk2(p_[2 * c], p_[2 * c + 1]);                                    \
-            }                                                                                              \
+            constexpr int EPS_ = 16 / NSTEP;   /* exponentials per step: 1 or 2 */                         \
+            _Pragma("unroll") for (int e = i_ * EPS_; e < (i_ + 1) * EPS_; ++e) p_[e] = __builtin_amdgcn_exp2f(SC[0][e]); \
+            if (EPS_ == 2) SPTS_ATT_PAIR(i_)                                                               \
+            else if (i_ & 1) SPTS_ATT_PAIR(i_ >> 1)                                                        \
             __builtin_amdgcn_sched_barrier(0);                                                             \
+        }                                                                                                  \
+        /* a use of the probabilities in this basic block: without it the exponentials are sunk past */   \
+        /* the branch below, out of reach of the MFMAs they are meant to overlap                      */   \
+        asm volatile("" ::"v"(pk_[0]), "v"(pk_[1]), "v"(sum_));                                            \
+        const bool ask_ = live_ && ((b_) == 0 || !(sum_ <= ATT_SUM_MAX));                                  \
+        if (__ballot(ask_) != 0) {                                                                         \
+            asm volatile("");   /* keeps this a branch */                                                  \
+            float mx_ = -INFINITY;                                                                         \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) mx_ = fmaxf(mx_, SC[0][r]);                     \
+            const auto sw_ = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx_), __float_as_uint(mx_), false, false); \
+            mx_ = fmaxf(__uint_as_float(sw_[0]), __uint_as_float(sw_[1]));                                 \
+            const bool need_ = live_ && mx_ > ((b_) == 0 ? -INFINITY : ATT_TAU);                           \
+            const float pend_ = need_ ? mx_ : 0.f;                                                         \
+            sum_ = 0.f;                                                                                    \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                               \
+                SC[0][r] -= pend_;                                                                         \
+                p_[r] = __builtin_amdgcn_exp2f(SC[0][r]);                                                  \
+            }                                                                                              \
+            _Pragma("unroll") for (int c = 0; c < 8; ++c) SPTS_ATT_PAIR(c)                                 \
+            if ((b_) > 0) {   /* in slot 0 both are still zero, and 2^-pend_ may not be finite */           \
+                const float alpha_ = __builtin_amdgcn_exp2f(-pend_);                                       \
+                l_run[0] *= alpha_;                                                                        \
+                _Pragma("unroll") for (int db = 0; db < DB; ++db)                                          \
+                    _Pragma("unroll") for (int r = 0; r < 16; ++r) o[db][0][r] *= alpha_;                  \
+            }                                                                                              \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) { SN[0][r] -= pend_; cinit[r] -= pend_; }       \
         }                                                                                                  \
         PC[0][0] = __builtin_bit_cast(bf16x8, pk_[0]);                                                     \
         PC[0][1] = __builtin_bit_cast(bf16x8, pk_[1]);                                                     \
-        /* a use of the probabilities in this basic block: without it the exponentials are sunk past */   \
-        /* the rescale branch below, out of reach of the MFMAs they are meant to overlap             */   \
-        asm volatile("" ::"v"(PC[0][0]), "v"(PC[0][1]), "v"(sum_));                                        \
-        m_run[0] = m_new_;                                                                                 \
-        /* rescale (only when some lane's maximum moved) and accumulate the row sums */                    \
-        if (__ballot(m_new_ != m_old_) != 0) {                                                             \
-            const float alpha_ = __builtin_amdgcn_exp2f((m_old_ - m_use_) * scale_log2e);                  \
-            l_run[0] *= alpha_;                                                                            \
-            _Pragma("unroll") for (int db = 0; db < DB; ++db)                                              \
-                _Pragma("unroll") for (int r = 0; r < 16; ++r) o[db][0][r] *= alpha_;                      \
-        }                                                                                                  \
         l_run[0] += live_ ? sum_ : 0.f;                                                                    \
     }
 
@@ -371,10 +418,13 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(AttnArgs a, int nQ, 
     }
 }
 
+float attention_mfma_q_scale(int d) { return 1.4426950408889634f / sqrtf((float)d); }
+
 bool attention_mfma_supported(const AttnArgs& a) {
     if (a.d != 128 && a.d != 64) return false;
     if (a.Mq <= 0 || a.Mk <= 0 || a.H % a.Hkv != 0) return false;
     if (!a.vt || a.ldvt % BKV != 0 || a.ldvt < (a.Mk + BKV - 1) / BKV * BKV) return false;
+    if (a.ldvt * (int64_t)a.d * 2 >= ((int64_t)1 << 32)) return false;   // a lane's offset inside a kv head's V^T rows is 32-bit
     auto al = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
     return al(a.q) && al(a.k) && al(a.vt) && al(a.out);
 }
@@ -393,8 +443,9 @@ static hipError_t launch_attn_t(const AttnArgs& a, hipStream_t s) {
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_mfma_kernel<D, QB, NW>), (int)lds);
         if (e != hipSuccess) return e;
     }
-    const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-    attn_mfma_kernel<D, QB, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nQ, total, xpg, scale_log2e);
+    const float want = attention_mfma_q_scale(D);
+    const float qmul = (a.q_scale != 0.f) ? want / a.q_scale : want;   // exactly 1 when the producer applied `want`
+    attn_mfma_kernel<D, QB, NW><<<dim3(grid), dim3(NW * 64), lds, s>>>(a, nQ, total, xpg, qmul);
     return hipGetLastError();
 }
 

@@ -135,7 +135,7 @@ hipError_t launch_rmsnorm(const void* x, const void* gamma, float eps, void* out
 template <typename T>
 __global__ void rope_apply_kernel(const float* __restrict__ in, const float2* __restrict__ table,
                                   const int32_t* __restrict__ idx, int64_t row0, T* __restrict__ out, int64_t n,
-                                  int heads, int d) {
+                                  int heads, int d, float scale) {
     int half = d >> 1;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t total = n * heads * half;
@@ -148,17 +148,17 @@ __global__ void rope_apply_kernel(const float* __restrict__ in, const float2* __
     float2 cs = table[trow * half + j];
     int64_t base = (row * heads + h) * (int64_t)d;
     float a = in[base + j], b = in[base + j + half];
-    out[base + j] = from_f32<T>(a * cs.x - b * cs.y);
-    out[base + j + half] = from_f32<T>(b * cs.x + a * cs.y);
+    out[base + j] = from_f32<T>((a * cs.x - b * cs.y) * scale);
+    out[base + j + half] = from_f32<T>((b * cs.x + a * cs.y) * scale);
 }
 
 hipError_t launch_rope_apply(const float* in, const float2* table, const int32_t* idx, int64_t row0, void* out,
-                             int64_t n, int heads, int d, bool bf16, hipStream_t s) {
+                             int64_t n, int heads, int d, bool bf16, hipStream_t s, float scale) {
     if (n == 0) return hipSuccess;
     int64_t total = n * heads * (d / 2);
     dim3 g((unsigned)cdiv(total, 256)), b(256);
-    if (bf16) rope_apply_kernel<bf16_t><<<g, b, 0, s>>>(in, table, idx, row0, (bf16_t*)out, n, heads, d);
-    else rope_apply_kernel<float><<<g, b, 0, s>>>(in, table, idx, row0, (float*)out, n, heads, d);
+    if (bf16) rope_apply_kernel<bf16_t><<<g, b, 0, s>>>(in, table, idx, row0, (bf16_t*)out, n, heads, d, scale);
+    else rope_apply_kernel<float><<<g, b, 0, s>>>(in, table, idx, row0, (float*)out, n, heads, d, scale);
     return hipGetLastError();
 }
 

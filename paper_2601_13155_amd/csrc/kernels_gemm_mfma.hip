@@ -423,6 +423,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
                 const int64_t trow = a.rope_idx ? (int64_t)a.rope_idx[growc] : growc;
                 const int half = a.head_dim >> 1;
                 const float2* tab = a.rope + trow * half;
+                const float rs = a.rope_scale != 0.f ? a.rope_scale : 1.f;
                 if (half == 64) {
                     // wavefront = one head of 128 columns: blocks (0,2) and (1,3) are d/2 apart
 #pragma unroll
@@ -436,8 +437,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
                             for (int t = 0; t < 4; ++t) {
                                 float2 cs = tab[jj + 8 * q + t];
                                 float x1 = acc[i][j][4 * q + t], x2 = acc[i][j + 2][4 * q + t];
-                                lo[t] = x1 * cs.x - x2 * cs.y;
-                                hi[t] = x2 * cs.x + x1 * cs.y;
+                                lo[t] = (x1 * cs.x - x2 * cs.y) * rs;
+                                hi[t] = (x2 * cs.x + x1 * cs.y) * rs;
                             }
                             uint2 o1, o2;
                             o1.x = pack_bf16x2(lo[0], lo[1]); o1.y = pack_bf16x2(lo[2], lo[3]);
@@ -459,8 +460,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
                             for (int t = 0; t < 4; ++t) {
                                 float2 cs = tab[jj + 8 * q + t];
                                 float x1 = acc[i][2 * hh][4 * q + t], x2 = acc[i][2 * hh + 1][4 * q + t];
-                                lo[t] = x1 * cs.x - x2 * cs.y;
-                                hi[t] = x2 * cs.x + x1 * cs.y;
+                                lo[t] = (x1 * cs.x - x2 * cs.y) * rs;
+                                hi[t] = (x2 * cs.x + x1 * cs.y) * rs;
                             }
                             uint2 o1, o2;
                             o1.x = pack_bf16x2(lo[0], lo[1]); o1.y = pack_bf16x2(lo[2], lo[3]);
@@ -619,12 +620,13 @@ __global__ void __launch_bounds__(256) splitk_finish_kernel(GemmArgs a, int nM, 
         const f32x4 x1 = quad(j1), x2 = quad(j2);
         const int64_t trow = a.rope_idx ? (int64_t)a.rope_idx[grow] : grow;
         const float2* tab = a.rope + trow * half + jj;
+        const float rs = a.rope_scale != 0.f ? a.rope_scale : 1.f;
         float lo[4], hi[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const float2 cs = tab[t];
-            lo[t] = x1[t] * cs.x - x2[t] * cs.y;
-            hi[t] = x2[t] * cs.x + x1[t] * cs.y;
+            lo[t] = (x1[t] * cs.x - x2[t] * cs.y) * rs;
+            hi[t] = (x2[t] * cs.x + x1[t] * cs.y) * rs;
         }
         const int col = col0 + wn * 128 + (half == 64 ? 0 : (j >> 1) * 64) + jj;
         u32x2 o1 = {pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3])};

@@ -186,17 +186,19 @@ void hidden_slab(const spts_ctx* c, GemmArgs& gate_up, GemmArgs& down) {
     if (gemm_mfma_supported(tg) && gemm_mfma_supported(td)) { gate_up = tg; down = td; }
 }
 
-// out[rows, heads*d] = rotary(A * B^T); table row of output row i is (tidx ? tidx[i] : i + row0); b_slab: optional
-// slab-major copy of B (heads*d rows)
-int run_gemm_rope(spts_ctx* c, GemmArgs g, int heads, const int32_t* tidx, int64_t row0, void* out, const void* b_slab = nullptr) {
+// out[rows, heads*d] = out_scale * rotary(A * B^T); table row of output row i is (tidx ? tidx[i] : i + row0); b_slab:
+// optional slab-major copy of B (heads*d rows)
+int run_gemm_rope(spts_ctx* c, GemmArgs g, int heads, const int32_t* tidx, int64_t row0, void* out, const void* b_slab = nullptr,
+                  float out_scale = 1.0f) {
     const float2* table = c->p<float2>(c->off.rope);
     GemmArgs f = g;
     f.epi = EPI_ROPE; f.C = out; f.rope = table + row0 * (c->m.d / 2); f.rope_idx = tidx; f.head_dim = c->m.d;
+    f.rope_scale = out_scale;
     prefer_slab(c, f, b_slab, nullptr, g.N);
     if (c->bf16 && gemm_mfma_supported(f)) return run_gemm_mfma(c, f);
     g.C = c->p<float>(c->off.tmp32); g.c_is_f32 = 1; g.epi = EPI_STORE;
     SPTS_TRY(run_gemm(c, g));
-    SPTS_HIP(c, launch_rope_apply(c->p<float>(c->off.tmp32), table, tidx, row0, out, g.M, heads, c->m.d, c->bf16, c->stream));
+    SPTS_HIP(c, launch_rope_apply(c->p<float>(c->off.tmp32), table, tidx, row0, out, g.M, heads, c->m.d, c->bf16, c->stream, out_scale));
     return SPTS_OK;
 }
 
@@ -843,10 +845,6 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         SPTS_TRY(run_topk(c, S, N, Ma, cfg->protect_last, idxA));
     }
     if (Ma > 0) {
-        // queries of the active rows (rows gathered through idxA inside the GEMM's A loads)
-        GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, Ma, QD, m.D);
-        gq.a_rows = N;
-        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s)); }
         const int32_t* qpos = pos;
         const int32_t* kpos = pos;
         void* kk = kall;
@@ -871,6 +869,12 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         aa.Mq = Ma; aa.Mk = Mk; aa.H = m.H; aa.Hkv = m.Hkv; aa.d = m.d;
         aa.ldvt = (Mk + 255) / 256 * 256; aa.vt = c->p<void>(c->off.vt);
         const bool amf = c->bf16 && attention_mfma_supported(aa);
+        // queries of the active rows (rows gathered through idxA inside the GEMM's A loads); for the matrix-core
+        // attention they leave the projection already multiplied by log2(e)/sqrt(d), before their one rounding
+        if (amf) aa.q_scale = attention_mfma_q_scale(m.d);
+        GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, Ma, QD, m.D);
+        gq.a_rows = N;
+        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s, amf ? aa.q_scale : 1.0f)); }
         GemmArgs gv = gemm_args(xn, m.D, full_kv ? nullptr : idxA, w->Wv, m.D, vv, KV, Mk, KV, m.D);
         gv.a_rows = N;
         prefer_slab(c, gv, w->Wv_s, nullptr, KV);
@@ -1007,9 +1011,6 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
         SPTS_HIP(c, launch_add_segment_base(idxA, segs.out_offsets, segs.offsets, batch, MaT, st));
     }
     if (MaT > 0) {
-        GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, MaT, QD, m.D);
-        gq.a_rows = N;
-        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s)); }
         const int32_t* posA = pos;
         const char* khat = (const char*)kall;
         char* vhat = c->p<char>(c->off.vhat);
@@ -1019,12 +1020,7 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
             posA = c->p<int32_t>(c->off.posA);
             khat = c->p<char>(c->off.khat);
         }
-        GemmArgs gv = gemm_args(xn, m.D, idxA, w->Wv, m.D, vhat, KV, MaT, KV, m.D);
-        gv.a_rows = N;
-        prefer_slab(c, gv, w->Wv_s, nullptr, KV);
-        { PHASE(c, PH_V_PROJ); SPTS_TRY(run_gemm(c, gv)); }
-        for (int b = 0; b < batch; ++b) {
-            if (ma[b] == 0) continue;
+        auto attn_args = [&](int b) {
             AttnArgs aa{};
             aa.q = c->p<char>(c->off.q) + (size_t)oa[b] * QD * eb;
             aa.k = khat + (size_t)oa[b] * KV * eb; aa.v = vhat + (size_t)oa[b] * KV * eb;
@@ -1032,7 +1028,25 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
             aa.out = c->p<char>(c->off.att) + (size_t)oa[b] * QD * eb;
             aa.Mq = ma[b]; aa.Mk = ma[b]; aa.H = m.H; aa.Hkv = m.Hkv; aa.d = m.d;
             aa.ldvt = (ma[b] + 255) / 256 * 256; aa.vt = c->p<void>(c->off.vt);
-            const bool amf = c->bf16 && attention_mfma_supported(aa);
+            return aa;
+        };
+        // the queries carry the matrix-core attention's factor only when every sequence takes that kernel
+        bool amf_all = c->bf16;
+        for (int b = 0; amf_all && b < batch; ++b)
+            if (ma[b] > 0) amf_all = attention_mfma_supported(attn_args(b));
+        const float q_scale = amf_all ? attention_mfma_q_scale(m.d) : 1.0f;
+        GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, MaT, QD, m.D);
+        gq.a_rows = N;
+        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s, q_scale)); }
+        GemmArgs gv = gemm_args(xn, m.D, idxA, w->Wv, m.D, vhat, KV, MaT, KV, m.D);
+        gv.a_rows = N;
+        prefer_slab(c, gv, w->Wv_s, nullptr, KV);
+        { PHASE(c, PH_V_PROJ); SPTS_TRY(run_gemm(c, gv)); }
+        for (int b = 0; b < batch; ++b) {
+            if (ma[b] == 0) continue;
+            AttnArgs aa = attn_args(b);
+            const bool amf = amf_all;
+            if (amf) aa.q_scale = q_scale;
             PHASE(c, PH_ATTENTION);
             if (amf) {
                 SPTS_HIP(c, launch_transpose_pad(aa.v, c->p<void>(c->off.vt), ma[b], KV, aa.ldvt, c->bf16, st));

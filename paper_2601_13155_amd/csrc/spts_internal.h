@@ -81,6 +81,7 @@ struct GemmArgs {
     float* part; int32_t part_ld;                       // EPI_SUMSQ partial sums [M, part_ld]
     const float2* rope; int32_t head_dim;               // EPI_ROPE: cos/sin table [rows, head_dim/2]
     const int32_t* rope_idx;                            // table row = rope_idx ? rope_idx[row] : row
+    float rope_scale;                                   // EPI_ROPE: the rotated values are multiplied by this before rounding (0 = 1)
     int64_t M; int32_t N; int32_t K;
     int32_t epi; int32_t c_is_f32;
     // tail split-K (matrix-core path; EPI_STORE / EPI_RESIDUAL / EPI_ROPE): the first `nfull` tiles (in
@@ -127,9 +128,9 @@ hipError_t launch_proxy_hidden(const ProxyHiddenArgs& a, hipStream_t s);
 hipError_t launch_pack_slab32(const void* W, int64_t rows, int64_t K, void* out, hipStream_t s);
 hipError_t launch_rope_table(const int32_t* pos, int64_t N, int d, float base, float2* table, hipStream_t s);
 hipError_t launch_rmsnorm(const void* x, const void* gamma, float eps, void* out, int64_t N, int D, bool bf16, hipStream_t s);
-// out[n, h, :] = rotary(in_f32[n, h, :]) with table row (idx ? idx[n] : n + row0)
+// out[n, h, :] = scale * rotary(in_f32[n, h, :]) with table row (idx ? idx[n] : n + row0)
 hipError_t launch_rope_apply(const float* in, const float2* table, const int32_t* idx, int64_t row0, void* out,
-                             int64_t n, int heads, int d, bool bf16, hipStream_t s);
+                             int64_t n, int heads, int d, bool bf16, hipStream_t s, float scale = 1.0f);
 // out[i, :] = in[idx[i], :]   (row_bytes multiple of 4)
 hipError_t launch_gather_rows(const void* in, const int32_t* idx, void* out, int64_t n, int64_t row_bytes, hipStream_t s);
 // out[i, :] = in[idx[i], :] (row_bytes multiple of 16) and, in the same launch, pos_out[i] = pos_in[idx[i]] (when pos_out) and
@@ -187,7 +188,11 @@ struct AttnArgs {
     void* out;      // [Mq, H, d]
     int64_t Mq, Mk; int H, Hkv, d;
     int out_slab;   // matrix-core path only: out written slab-major [H*d/32][Mq][32] (A operand of an a_slab GEMM)
+    float q_scale;  // matrix-core path only: factor the producer of q already folded into it (0 or 1 = none); the kernel
+                    // folds in the rest of attention_mfma_q_scale(d), at the price of a second bf16 rounding of q
 };
+// log2(e) / sqrt(d): with q carrying this factor the matrix-core kernel's logits are exponents of 2 as they leave the MFMA
+float attention_mfma_q_scale(int d);
 hipError_t launch_attention_generic(const AttnArgs& a, bool bf16, hipStream_t s);
 bool attention_mfma_supported(const AttnArgs& a);
 hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t s);

@@ -67,7 +67,7 @@ def swap_bound(m, dtype):
     return 0 if dtype == "f32" else max(1, int(m) // 50)
 
 
-def lockstep_layer(gpu, x, pos, w, mdl, cfg, dtype, rnd=None):
+def lockstep_layer(gpu, x, pos, w, mdl, cfg, dtype, rnd=None, hidden_tol=None):
     """Lock-step parity of one layer in a single oracle pass: at each selection point the oracle's own
     set is compared with the GPU's (near-tie swaps counted, anything else fails), then the oracle
     adopts the GPU's set so that the hidden states stay like-for-like.
@@ -77,7 +77,8 @@ def lockstep_layer(gpu, x, pos, w, mdl, cfg, dtype, rnd=None):
     score lies within 2e/(1-e) of the oracle's k-th score, e being the *measured* score error; the FFN set within the score
     tolerance of the k-th score; at most swap_bound() swaps per selection; hidden states within the tolerance.
     `rnd` overrides the oracle's rounding hook (default: identity for fp32, bf16 rounding at the store points
-    for bf16; pass orc.identity to compare a bf16 run with the plain fp64 algorithm).
+    for bf16; pass orc.identity to compare a bf16 run with the plain fp64 algorithm).  `hidden_tol` replaces the
+    hidden-state tolerance (a test that widens it says why).
     Returns dict(swaps_attn, swaps_ffn, err, s_err, ref)."""
     rnd = rnd_for(dtype) if rnd is None else rnd
     tol = TOL[dtype]
@@ -103,5 +104,5 @@ def lockstep_layer(gpu, x, pos, w, mdl, cfg, dtype, rnd=None):
         kw = dict(force_idx_attn=adopt("attn", gpu["idx_attn"]), force_idx_ffn=adopt("ffn", gpu["idx_ffn"]))
     ref = orc.layer_prefill(x, pos, w, mdl, cfg, rnd=rnd, score_cast=orc.f32_round, **kw)
     err = row_rel_err(gpu["x"], ref.x)
-    assert err <= tol["hidden"], f"hidden states: row-relative error {err}"
+    assert err <= (tol["hidden"] if hidden_tol is None else hidden_tol), f"hidden states: row-relative error {err}"
     return dict(swaps_attn=swaps["attn"], swaps_ffn=swaps["ffn"], err=err, s_err=s_err[0], ref=ref)

@@ -383,6 +383,34 @@ def test_layer_with_peaked_dominant_attention(torch, name, shape, N, P, r):
     H.lockstep_layer(kv1, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 1), shape.dtype)
 
 
+def test_attention_under_steep_logits(torch):
+    """Wk scaled by 16 and by 160: logits spread over tens to hundreds of log2 units, so a query's reference maximum
+    in the matrix-core attention moves many times along the keys (and at 160 an exponential taken against a stale
+    reference overflows before the move is noticed).  A move that forgets to rescale the accumulator, the row sum or
+    the next block's logits is an error of order one, or a NaN.  bf16 rounding of q and k perturbs a logit in
+    proportion to its size, so the bar is wider than the usual 2e-2: 8e-2 at 16 (measured 3.5e-2), and at 160, where
+    the softmax is one-hot on keys that bf16 can no longer rank, only finiteness and a bounded output."""
+    shape = synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0)
+    N, P, r = 1500, 64, 256
+    ctx = ctx_for(shape, 2048)
+    x = synth.hidden_states(8, N, shape.D, shape.dtype)
+    pos = (synth.positions(N) * 2 + 1).astype(np.int32)
+    mdl = H.oracle_model(shape)
+    for f in (16.0, 160.0):
+        w = dict(synth.make_layer(8, 0, shape, r))
+        w["Wk"] = (f * np.asarray(w["Wk"], dtype=np.float32)).astype(np.float32)
+        w["Wv"] = (8.0 * np.asarray(w["Wv"], dtype=np.float32)).astype(np.float32)
+        dw = runtime.upload_layer(w, shape, r)
+        dense = runtime.run_layer(ctx, x, pos, dw, shape, skip=0, probe_len=P, m_attn=0, m_ffn=0)
+        got = np.asarray(dense["x"], dtype=np.float64)
+        assert np.isfinite(got).all()
+        if f == 16.0:
+            H.lockstep_layer(dense, x, pos, w, mdl, orc.LayerCfg(0, P, N, N, 1, 0), shape.dtype, hidden_tol=8e-2)
+        else:
+            ref = orc.layer_prefill(x, pos, w, mdl, orc.LayerCfg(0, P, N, N, 1, 0), rnd=H.rnd_for(shape.dtype)).x
+            assert H.row_rel_err(got, ref) <= 0.5
+
+
 def test_pack_slab32_matches_the_host_layout(torch):
     """spts_pack_slab32 on the device against the same permutation written with numpy (bit-exact), and its error codes."""
     ctx = ctx_for(synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 2048)
