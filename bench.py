@@ -77,7 +77,7 @@ def cpu_baseline(wl, w_host, sample_tokens):
         cfg = orc.LayerCfg(1, min(wl.probe_len, n), int(ka * n), int(kf * n), wl.protect_last, 0)
         t0 = time.perf_counter()
         orc.layer_prefill(x_all[:n], synth.positions(n), w64, mdl, cfg,
-                          rnd=orc.bf16_round if shape.dtype == "bf16" else orc.identity, score_cast=orc.f32_round)
+                          rnd=orc.bf16_prefill if shape.dtype == "bf16" else orc.identity, score_cast=orc.f32_round)
         secs[n] = time.perf_counter() - t0
     if n1 != n2:
         bq = (secs[n2] / n2 - secs[n1] / n1) / (n2 - n1)

@@ -40,8 +40,9 @@ Readings taken where the paper is silent (each shared with the HIP path):
 
 ``rnd`` hooks: ``identity`` gives the plain fp64 algorithm; ``bf16_round``
 rounds at the points where a bf16 implementation stores a tensor (the
-"bf16-faithful" mode used to tighten parity bands).  Accumulation is fp64 in
-both modes.
+"bf16-faithful" mode used to tighten parity bands); ``bf16_prefill`` is the same
+for a prefill that stores its queries with the softmax factor folded in.
+Accumulation is fp64 in all modes.
 
 Pins (tests/test_oracle_pins.py): dense block against an independent
 composition of torch CPU fp64 routines; keep=1 == dense; keep=0 == identity;
@@ -101,6 +102,16 @@ def f32_round(a: Array) -> Array:
     return np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
 
 
+def bf16_prefill(a: Array) -> Array:
+    """``bf16_round`` for a bf16 prefill that stores its queries (probe window and active rows) already multiplied
+    by the softmax factor log2(e)/sqrt(d): the mark below makes ``project_queries`` round q * factor instead of q for
+    the prefill calls, which moves a bf16 rounding point and nothing else (with ``identity`` nothing changes)."""
+    return bf16_round(a)
+
+
+bf16_prefill.prefill_queries_scaled = True
+
+
 @dataclass
 class Model:
     D: int
@@ -158,10 +169,15 @@ def project_keys(xn: Array, pos: Array, Wk: Array, mdl: Model, rnd=identity) -> 
     return rnd(rope(k, pos, mdl.rope_base))
 
 
-def project_queries(xn_rows: Array, pos_rows: Array, Wq: Array, mdl: Model, rnd=identity) -> Array:
+def project_queries(xn_rows: Array, pos_rows: Array, Wq: Array, mdl: Model, rnd=identity, prefill: bool = False) -> Array:
+    """Q = rope(Xn W_Q) for the given rows -> [n, H, d].  ``prefill`` with a hook marked ``prefill_queries_scaled``:
+    the value that is rounded is q * log2(e)/sqrt(d) (the factor as an fp32 number); the queries returned are still q."""
     n = xn_rows.shape[0]
-    q = (xn_rows @ np.asarray(Wq, dtype=np.float64)).reshape(n, mdl.H, mdl.d)
-    return rnd(rope(q, pos_rows, mdl.rope_base))
+    q = rope((xn_rows @ np.asarray(Wq, dtype=np.float64)).reshape(n, mdl.H, mdl.d), pos_rows, mdl.rope_base)
+    if prefill and getattr(rnd, "prefill_queries_scaled", False):
+        c = float(np.float32(np.float32(1.4426950408889634) / np.sqrt(np.float32(mdl.d))))
+        return rnd(q * c) / c
+    return rnd(q)
 
 
 def probe_scores(qp: Array, k: Array, mdl: Model) -> Array:
@@ -257,7 +273,7 @@ def probe_attn(x: Array, pos: Array, w: Dict[str, Array], mdl: Model, probe_len:
     P = int(probe_len)
     xn = rnd(rmsnorm(x, w["gamma1"], mdl.rms_eps))
     k = project_keys(xn, pos, w["Wk"], mdl, rnd)
-    qp = project_queries(xn[N - P:], np.asarray(pos)[N - P:], w["Wq"], mdl, rnd)
+    qp = project_queries(xn[N - P:], np.asarray(pos)[N - P:], w["Wq"], mdl, rnd, prefill=True)
     return k, probe_scores(qp, k, mdl)
 
 
@@ -320,7 +336,7 @@ def layer_prefill(x: Array, pos: Array, w: Dict[str, Array], mdl: Model, cfg: La
     k_all = project_keys(xn, pos, w["Wk"], mdl, rnd)
     if cfg.skip:
         P = int(cfg.probe_len)
-        qp = project_queries(xn[N - P:], pos[N - P:], w["Wq"], mdl, rnd)
+        qp = project_queries(xn[N - P:], pos[N - P:], w["Wq"], mdl, rnd, prefill=True)
         S = score_cast(probe_scores(qp, k_all, mdl))
         out.s_mha = S
         Ma = min(N, int(cfg.m_attn))
@@ -335,7 +351,7 @@ def layer_prefill(x: Array, pos: Array, w: Dict[str, Array], mdl: Model, cfg: La
     out.idx_attn = Ta
     if Ta.size > 0:
         xa = xn[Ta]
-        q = project_queries(xa, pos[Ta], w["Wq"], mdl, rnd)
+        q = project_queries(xa, pos[Ta], w["Wq"], mdl, rnd, prefill=True)
         if cfg.skip and cfg.kv_mode == 1:
             kk = k_all
             vv = rnd((xn @ f64(w["Wv"])).reshape(N, mdl.Hkv, mdl.d))

@@ -21,7 +21,7 @@ __global__ void __launch_bounds__(64) attention_generic_kernel(AttnArgs a) {
     const T* q = (const T*)a.q + (i * a.H + h) * (int64_t)d;
     const T* K = (const T*)a.k;
     const T* V = (const T*)a.v;
-    const float scale = 1.0f / sqrtf((float)d);
+    const float scale = 1.0f / sqrtf((float)d) / (a.q_scale != 0.f ? a.q_scale : 1.0f);   // q may arrive pre-scaled
     for (int j = lane; j < d; j += 64) qs[j] = to_f32(q[j]);
     __syncthreads();
     const int qp = a.qpos[i];
@@ -89,7 +89,7 @@ __global__ void __launch_bounds__(256) probe_stats_generic_kernel(ProbeArgs a) {
     const int d = a.d;
     const T* q = (const T*)a.qp + ((int64_t)p * a.H + h) * d;
     const T* K = (const T*)a.k;
-    const float scale = 1.0f / sqrtf((float)d);
+    const float scale = 1.0f / sqrtf((float)d) / (a.q_scale != 0.f ? a.q_scale : 1.0f);   // q may arrive pre-scaled
     for (int j = threadIdx.x; j < d; j += 256) qs[j] = to_f32(q[j]);
     __syncthreads();
     const int64_t nvis = a.N - a.P + p + 1;  // candidates 0 .. N-P+p
@@ -129,7 +129,7 @@ __global__ void __launch_bounds__(256) probe_accum_generic_kernel(ProbeArgs a) {
     const int d = a.d;
     const T* K = (const T*)a.k;
     const T* Q = (const T*)a.qp;
-    const float scale = 1.0f / sqrtf((float)d);
+    const float scale = 1.0f / sqrtf((float)d) / (a.q_scale != 0.f ? a.q_scale : 1.0f);   // q may arrive pre-scaled
     const int grp = a.H / a.Hkv;
     float acc = 0.f;
     for (int p = 0; p < a.P; ++p) {

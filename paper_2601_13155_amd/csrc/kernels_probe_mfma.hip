@@ -33,7 +33,7 @@ template <int D> struct ProbeLds {
 
 // stats_part: [nchunks][Hkv][Rp][2]; stats: [Hkv][Rp][2] (M, 1/L); part: [Hkv][Np]
 template <int D, int RB, int PASS>
-__global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, int64_t Np, float scale_log2e,
+__global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, int64_t Np, float qmul,
                                                          float* __restrict__ stats_part, const float* __restrict__ stats) {
     using L = ProbeLds<D>;
     constexpr int KS = D / 16;
@@ -62,10 +62,23 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
         const bf16_t* qr = Q + ((int64_t)p * a.H + g * grp + hg) * D + 8 * lh;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[rb][ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
+        // qp normally arrives carrying log2(e)/sqrt(d) (qmul == 1): the logits leave the matrix core as exponents of 2;
+        // otherwise the rest of the factor is folded in here (a second bf16 rounding)
+        if (qmul != 1.0f) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                u32x4 raw = __builtin_bit_cast(u32x4, qf[rb][ks]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    raw[j] = cvt_pk_bf16(__uint_as_float(raw[j] << 16) * qmul, __uint_as_float(raw[j] & 0xffff0000u) * qmul);
+                qf[rb][ks] = __builtin_bit_cast(bf16x8, raw);
+            }
+        }
     }
-    // pass 2: the lane's 16 rows per block keep their exponent offset in registers: exp2(s * scale - M) / L is taken as
-    // exp2(fma(s, scale, log2(1/L) - M)) (padded rows and empty rows: offset -inf, probability 0)
-    float coff[PASS == 2 ? RB : 1][16];
+    // pass 2: the lane's 16 rows per block keep their exponent offset log2(1/L) - M in registers, laid out as the C operand
+    // that starts a block's product: the MFMA then delivers log2 of the probability itself (padded rows and empty rows:
+    // offset -inf, probability 0)
+    f32x16 coff[PASS == 2 ? RB : 1];
     if (PASS == 2) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
@@ -126,7 +139,7 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        float v = s[kb][r] * scale_log2e;
+                        float v = s[kb][r];
                         if (need_mask) {
                             int64_t key = key0 + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
                             if (key > vis_last[rb]) v = -INFINITY;
@@ -151,9 +164,7 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
             for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb) {
-                    f32x16 s;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+                    f32x16 s = coff[rb];
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
                         bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + L::koff(kb * 32 + l32, 2 * ks + lh));
@@ -163,7 +174,7 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
                     const int64_t key = key0 + kb * 32 + l32;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2e, coff[rb][r]));
+                        float pv = __builtin_amdgcn_exp2f(s[r]);
                         if (need_mask) {
                             const int rr = wave * 32 * RB + rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
                             const int64_t vl = rr < R ? a.N - a.P + rr / grp : -1;
@@ -268,11 +279,12 @@ static hipError_t launch_probe_t(const ProbeArgs& a, int Rp, hipStream_t s) {
     float* part = stats + (size_t)a.Hkv * Rp * 2;
     ProbeArgs b = a;
     b.partial = part;
-    const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+    const float want = attention_mfma_q_scale(D);
+    const float qmul = (a.q_scale != 0.f) ? want / a.q_scale : want;   // exactly 1 when the producer applied `want`
     dim3 grid(nchunks, a.Hkv), block(256);
-    probe_mfma_kernel<D, RB, 1><<<grid, block, 0, s>>>(b, Rp, Np, scale_log2e, stats_part, nullptr);
+    probe_mfma_kernel<D, RB, 1><<<grid, block, 0, s>>>(b, Rp, Np, qmul, stats_part, nullptr);
     probe_combine_kernel<<<dim3((a.Hkv * Rp + 3) / 4), block, 0, s>>>(stats_part, stats, nchunks, a.Hkv, Rp, R);
-    probe_mfma_kernel<D, RB, 2><<<grid, block, 0, s>>>(b, Rp, Np, scale_log2e, nullptr, stats);
+    probe_mfma_kernel<D, RB, 2><<<grid, block, 0, s>>>(b, Rp, Np, qmul, nullptr, stats);
     probe_final_kernel<<<dim3((unsigned)((a.N + 255) / 256)), block, 0, s>>>(part, a.S, a.N, Np, a.Hkv, 1.0f / (float)(a.P * a.H));
     return hipGetLastError();
 }

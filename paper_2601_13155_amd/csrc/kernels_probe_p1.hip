@@ -146,7 +146,7 @@ static hipError_t launch_probe_p1_t(const ProbeArgs& a, float* scratch, hipStrea
     float* logit = scratch;
     float* stats_part = logit + (size_t)a.H * Np;
     float* stats = stats_part + (size_t)nchunks * a.H * 2;
-    const float scale_log2e = 1.4426950408889634f / sqrtf((float)a.d);
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)a.d) / (a.q_scale != 0.f ? a.q_scale : 1.0f);   // qp may arrive pre-scaled
     const dim3 g((unsigned)nchunks, (unsigned)a.Hkv), b(256);
     const T* q = (const T*)a.qp;
     const T* K = (const T*)a.k;

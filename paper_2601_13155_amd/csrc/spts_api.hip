@@ -186,6 +186,10 @@ void hidden_slab(const spts_ctx* c, GemmArgs& gate_up, GemmArgs& down) {
     if (gemm_mfma_supported(tg) && gemm_mfma_supported(td)) { gate_up = tg; down = td; }
 }
 
+// Factor the prefill folds into the queries it stores (probe window and active rows): in bf16 log2(e)/sqrt(d), applied
+// to the fp32 accumulators before their one rounding; in fp32 none.
+float query_store_scale(const spts_ctx* c) { return c->bf16 ? attention_mfma_q_scale(c->m.d) : 1.0f; }
+
 // out[rows, heads*d] = out_scale * rotary(A * B^T); table row of output row i is (tidx ? tidx[i] : i + row0); b_slab:
 // optional slab-major copy of B (heads*d rows)
 int run_gemm_rope(spts_ctx* c, GemmArgs g, int heads, const int32_t* tidx, int64_t row0, void* out, const void* b_slab = nullptr,
@@ -233,16 +237,21 @@ int probe_scores_rows(spts_ctx* c, int64_t row0, int64_t n, const spts_layer_wei
     const int QD = m.H * m.d;
     const size_t eb = c->bf16 ? 2 : 4;
     const char* xn_probe = c->p<char>(c->off.xn) + (size_t)(row0 + n - P) * m.D * eb;
-    GemmArgs gq = gemm_args(xn_probe, m.D, nullptr, w->Wq, m.D, nullptr, QD, P, QD, m.D);
-    { PHASE(c, PH_PROBE_Q); SPTS_TRY(run_gemm_rope(c, gq, m.H, nullptr, row0 + n - P, c->p<void>(c->off.qp), w->Wq_s)); }
     ProbeArgs pa{};
     pa.qp = c->p<void>(c->off.qp); pa.k = k_rows; pa.S = s_out;
     pa.stats = c->p<float>(c->off.probe);
     pa.partial = c->p<float>(c->off.probe) + (2 * (size_t)P * m.H + 64);
     pa.N = n; pa.P = P; pa.H = m.H; pa.Hkv = m.Hkv; pa.d = m.d;
+    const bool p1 = probe_p1_supported(pa);
+    const bool pmf = !p1 && c->bf16 && probe_mfma_supported(pa);
+    // bf16: the queries leave the projection already multiplied by log2(e)/sqrt(d), before their one rounding (the
+    // matrix-core kernels then get exponents of 2 straight from the MFMA; the other kernels divide their scale by it)
+    pa.q_scale = query_store_scale(c);
+    GemmArgs gq = gemm_args(xn_probe, m.D, nullptr, w->Wq, m.D, nullptr, QD, P, QD, m.D);
+    { PHASE(c, PH_PROBE_Q); SPTS_TRY(run_gemm_rope(c, gq, m.H, nullptr, row0 + n - P, c->p<void>(c->off.qp), w->Wq_s, pa.q_scale)); }
     PHASE(c, PH_PROBE_ATTN);
-    if (probe_p1_supported(pa)) SPTS_HIP(c, launch_probe_p1(pa, c->p<float>(c->off.probe), c->bf16, c->stream));
-    else if (c->bf16 && probe_mfma_supported(pa)) SPTS_HIP(c, launch_probe_mfma(pa, c->stream));
+    if (p1) SPTS_HIP(c, launch_probe_p1(pa, c->p<float>(c->off.probe), c->bf16, c->stream));
+    else if (pmf) SPTS_HIP(c, launch_probe_mfma(pa, c->stream));
     else SPTS_HIP(c, launch_probe_generic(pa, c->bf16, c->stream));
     return SPTS_OK;
 }
@@ -869,12 +878,12 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         aa.Mq = Ma; aa.Mk = Mk; aa.H = m.H; aa.Hkv = m.Hkv; aa.d = m.d;
         aa.ldvt = (Mk + 255) / 256 * 256; aa.vt = c->p<void>(c->off.vt);
         const bool amf = c->bf16 && attention_mfma_supported(aa);
-        // queries of the active rows (rows gathered through idxA inside the GEMM's A loads); for the matrix-core
-        // attention they leave the projection already multiplied by log2(e)/sqrt(d), before their one rounding
-        if (amf) aa.q_scale = attention_mfma_q_scale(m.d);
+        // queries of the active rows (rows gathered through idxA inside the GEMM's A loads), stored with the factor of
+        // query_store_scale()
+        aa.q_scale = query_store_scale(c);
         GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, Ma, QD, m.D);
         gq.a_rows = N;
-        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s, amf ? aa.q_scale : 1.0f)); }
+        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s, aa.q_scale)); }
         GemmArgs gv = gemm_args(xn, m.D, full_kv ? nullptr : idxA, w->Wv, m.D, vv, KV, Mk, KV, m.D);
         gv.a_rows = N;
         prefer_slab(c, gv, w->Wv_s, nullptr, KV);
@@ -1030,11 +1039,7 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
             aa.ldvt = (ma[b] + 255) / 256 * 256; aa.vt = c->p<void>(c->off.vt);
             return aa;
         };
-        // the queries carry the matrix-core attention's factor only when every sequence takes that kernel
-        bool amf_all = c->bf16;
-        for (int b = 0; amf_all && b < batch; ++b)
-            if (ma[b] > 0) amf_all = attention_mfma_supported(attn_args(b));
-        const float q_scale = amf_all ? attention_mfma_q_scale(m.d) : 1.0f;
+        const float q_scale = query_store_scale(c);
         GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, MaT, QD, m.D);
         gq.a_rows = N;
         { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s, q_scale)); }
@@ -1045,8 +1050,8 @@ int spts_layer_prefill_batched(spts_ctx* c, void* x, const int32_t* pos, const i
         for (int b = 0; b < batch; ++b) {
             if (ma[b] == 0) continue;
             AttnArgs aa = attn_args(b);
-            const bool amf = amf_all;
-            if (amf) aa.q_scale = q_scale;
+            aa.q_scale = q_scale;
+            const bool amf = c->bf16 && attention_mfma_supported(aa);
             PHASE(c, PH_ATTENTION);
             if (amf) {
                 SPTS_HIP(c, launch_transpose_pad(aa.v, c->p<void>(c->off.vt), ma[b], KV, aa.ldvt, c->bf16, st));

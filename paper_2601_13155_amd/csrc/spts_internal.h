@@ -188,8 +188,8 @@ struct AttnArgs {
     void* out;      // [Mq, H, d]
     int64_t Mq, Mk; int H, Hkv, d;
     int out_slab;   // matrix-core path only: out written slab-major [H*d/32][Mq][32] (A operand of an a_slab GEMM)
-    float q_scale;  // matrix-core path only: factor the producer of q already folded into it (0 or 1 = none); the kernel
-                    // folds in the rest of attention_mfma_q_scale(d), at the price of a second bf16 rounding of q
+    float q_scale;  // factor the producer of q already folded into it (0 or 1 = none).  The matrix-core kernel wants
+                    // attention_mfma_q_scale(d) and folds in what is missing, at the price of a second bf16 rounding of q
 };
 // log2(e) / sqrt(d): with q carrying this factor the matrix-core kernel's logits are exponents of 2 as they leave the MFMA
 float attention_mfma_q_scale(int d);
@@ -201,6 +201,7 @@ hipError_t launch_attention_mfma(const AttnArgs& a, hipStream_t s);
 struct ProbeArgs {
     const void* qp; const void* k; float* S; float* stats; float* partial;
     int64_t N; int P, H, Hkv, d;
+    float q_scale;   // factor the producer of qp already folded into it (0 or 1 = none), as for AttnArgs
 };
 hipError_t launch_probe_generic(const ProbeArgs& a, bool bf16, hipStream_t s);
 bool probe_mfma_supported(const ProbeArgs& a);

@@ -85,14 +85,14 @@ def _sampled_layer_check(x_in, pos, w, shape, cfg, gpu, n_samples, seed):
     Checks S^MHA everywhere, the attention selection (swap-counted), and the output hidden state of sampled
     rows (active in attention and/or FFN) one by one.  Returns (swaps, score error, hidden error, rows, S)."""
     mdl = H.oracle_model(shape)
-    rnd = orc.bf16_round
+    rnd = orc.bf16_prefill
     tol = H.TOL["bf16"]
     N = x_in.shape[0]
     f64 = lambda a: np.asarray(a, dtype=np.float64)
     xn = _rows_parallel(lambda lo, hi: rnd(orc.rmsnorm(x_in[lo:hi], w["gamma1"], mdl.rms_eps)), N)
     K = _rows_parallel(lambda lo, hi: orc.project_keys(xn[lo:hi], pos[lo:hi], w["Wk"], mdl, rnd), N)
     P = cfg.probe_len
-    qp = orc.project_queries(xn[N - P:], pos[N - P:], w["Wq"], mdl, rnd)
+    qp = orc.project_queries(xn[N - P:], pos[N - P:], w["Wq"], mdl, rnd, prefill=True)
     S = orc.f32_round(orc.probe_scores(qp, K, mdl))
     s_err = H.score_rel_err(gpu["s_mha"], S)
     assert s_err <= tol["score"], f"S^MHA: {s_err}"
@@ -110,7 +110,7 @@ def _sampled_layer_check(x_in, pos, w, shape, cfg, gpu, n_samples, seed):
     x_new = {}
     for i in pick:
         row = int(Ta[i])
-        q = orc.project_queries(xn[row:row + 1], pos[row:row + 1], w["Wq"], mdl, rnd)
+        q = orc.project_queries(xn[row:row + 1], pos[row:row + 1], w["Wq"], mdl, rnd, prefill=True)
         att = rnd(orc.causal_attention(q, Kh[: i + 1], Vh[: i + 1], pos[row:row + 1], pos[Ta[: i + 1]], mdl))
         o = att.reshape(1, -1) @ f64(w["Wo"])
         x_new[row] = rnd(f64(x_in[row]) + o[0])
@@ -140,7 +140,7 @@ def _ffn_selection_check(ctx, dw, w, shape, x_in_dev, pos_dev, cfg, idx_attn, id
     with near-tie swaps counted in the band the measured score error implies.  Returns (swaps, c_err, sf_err)."""
     import torch
     mdl = H.oracle_model(shape)
-    rnd = orc.bf16_round
+    rnd = orc.bf16_prefill
     tol = H.TOL["bf16"]["score"]
     N = int(x_in_dev.shape[0])
     Ma, Mf = min(N, cfg.m_attn), min(N, cfg.m_ffn)

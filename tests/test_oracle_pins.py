@@ -373,3 +373,27 @@ def test_bf16_round_hook_matches_torch_bfloat16():
     assert np.array_equal(synth.round_to_bf16(a.astype(np.float32)).astype(np.float64), ref)
     bits = synth.bf16_bits(synth.round_to_bf16(a.astype(np.float32)))
     assert np.array_equal(synth.bf16_bits_to_f32(bits).astype(np.float64), ref)
+
+
+def test_prefill_query_hook_moves_one_rounding_point_only():
+    """bf16_prefill: the prefill's queries are rounded after the factor log2(e)/sqrt(d) is folded in (torch bfloat16
+    as the independent rounding), the decode's queries and every other tensor as with bf16_round, and the plain
+    algorithm (identity) does not know the factor at all."""
+    shape = small_shape()
+    mdl = oracle_model(shape)
+    w = synth.make_layer(5, 0, shape, 8)
+    xn = synth.hidden_states(5, 9, shape.D)
+    pos = synth.positions(9) * 3 + 2
+    q = orc.project_queries(xn, pos, w["Wq"], mdl)                      # fp64, no rounding
+    c = np.float32(np.float32(1.4426950408889634) / np.sqrt(np.float32(mdl.d)))
+    want = torch.from_numpy((q * float(c)).astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy() / float(c)
+    got = orc.project_queries(xn, pos, w["Wq"], mdl, orc.bf16_prefill, prefill=True)
+    assert np.array_equal(got, want)
+    plain = torch.from_numpy(q.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert not np.array_equal(got, plain)                               # the point really moved
+    assert np.array_equal(orc.project_queries(xn, pos, w["Wq"], mdl, orc.bf16_prefill), plain)            # decode call
+    assert np.array_equal(orc.project_queries(xn, pos, w["Wq"], mdl, orc.bf16_round, prefill=True), plain)
+    assert np.array_equal(orc.project_queries(xn, pos, w["Wq"], mdl, orc.identity, prefill=True), q)
+    assert np.array_equal(orc.bf16_prefill(q), orc.bf16_round(q))
+    # relative to the exact queries both roundings are within half a bf16 ulp (2^-9)
+    assert np.max(np.abs(got - q) / np.maximum(np.abs(q), 1e-300)) <= 2.0 ** -8
