@@ -86,6 +86,14 @@ typedef struct {
      * decode with the original, silently.  Re-pack whenever X changes. */
     const void *Wq_s, *Wk_s, *Wv_s, *Wo_s, *Wgate_s, *Wup_s, *Wdown_s;
     const void *Vg_s, *Vu_s, *Vd_s, *Ug_s, *Uu_s;
+    /* Non-zero: the caller states that the columns of Ud are orthonormal, as a truncated SVD of W_down with the singular
+     * values folded into Vd leaves them (all-zero columns of a zero-padded rank are fine when the matching rows of Vd
+     * are zero too).  The norm of the proxy's output, C^FFN = || z Ud^T ||_2 (Eq. (ffn_transformation)), then equals
+     * || z ||_2 and the library takes it from z without evaluating the output projection.  In exact arithmetic the two
+     * are the same number; with factors rounded to bf16 they differ by the orthogonality defect of the rounded Ud
+     * (below 1e-3 relative at D = 4096, r = 256).  The library does not check the statement: with a Ud that is not
+     * orthonormal the scores are those of a different proxy.  0 = evaluate || z Ud^T ||_2 as written. */
+    int32_t Ud_orthonormal;
 } spts_layer_weights;
 
 /* Per-layer control (Alg. 1: skip flag, budgets M_fixed; Sec. 3.4). */

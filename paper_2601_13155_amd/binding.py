@@ -35,7 +35,8 @@ class spts_model_desc(C.Structure):
 class spts_layer_weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("Wq", "Wk", "Wv", "Wo", "gamma1", "Wgate", "Wup", "Wdown", "gamma2",
                                            "Ug", "Vg", "Uu", "Vu", "Ud", "Vd")] + [("r", C.c_int32), ("Dlow", C.c_int32)] + \
-               [(n, C.c_void_p) for n in ("Wq_s", "Wk_s", "Wv_s", "Wo_s", "Wgate_s", "Wup_s", "Wdown_s", "Vg_s", "Vu_s", "Vd_s", "Ug_s", "Uu_s")]
+               [(n, C.c_void_p) for n in ("Wq_s", "Wk_s", "Wv_s", "Wo_s", "Wgate_s", "Wup_s", "Wdown_s", "Vg_s", "Vu_s", "Vd_s", "Ug_s", "Uu_s")] + \
+               [("Ud_orthonormal", C.c_int32)]
 
 
 class spts_layer_cfg(C.Structure):
@@ -143,13 +144,15 @@ def model_desc(shape) -> spts_model_desc:
                            SPTS_BF16 if shape.dtype == "bf16" else SPTS_F32)
 
 
-def layer_weights(tensors: dict, r: int = 0, Dlow: int = 0) -> spts_layer_weights:
-    """tensors: name -> device tensor in the ABI layout ([d_out, d_in]); missing names become NULL."""
+def layer_weights(tensors: dict, r: int = 0, Dlow: int = 0, ud_orthonormal: bool = False) -> spts_layer_weights:
+    """tensors: name -> device tensor in the ABI layout ([d_out, d_in]); missing names become NULL.
+    ud_orthonormal: the caller's statement that Ud has orthonormal columns (see spts_layer_weights in spts.h)."""
     w = spts_layer_weights()
     for name, typ in spts_layer_weights._fields_:
         if typ is C.c_void_p:
             setattr(w, name, _ptr(tensors.get(name)))
     w.r, w.Dlow = int(r), int(Dlow)
+    w.Ud_orthonormal = 1 if ud_orthonormal else 0
     w._keepalive = tensors  # keep the device tensors referenced as long as the struct lives
     return w
 

@@ -357,6 +357,48 @@ hipError_t launch_finish_ffn_scores(const float* part, int nparts, const float* 
     return hipGetLastError();
 }
 
+// C[n] = || z[n, :] ||_2 (and S^FFN = C * S^MHA): the proxy's output norm when U_down has orthonormal columns.  One
+// wavefront per row, lane l takes elements l, l + 64, ...; a fixed shuffle tree (deterministic).
+template <typename T>
+__global__ void __launch_bounds__(256) row_norm_scores_kernel(const T* __restrict__ z, int r, const float* __restrict__ s_mha,
+                                                              float* __restrict__ c_ffn, float* __restrict__ s_ffn, int64_t N) {
+    const int lane = threadIdx.x & 63;
+    const int64_t n = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;
+    const T* row = z + n * (int64_t)r;
+    float acc = 0.f;
+    if (r % 4 == 0) {   // rows are then whole groups of four elements, aligned to their size (z is 16-byte aligned)
+        for (int j = lane * 4; j < r; j += 256) {
+            float v[4];
+            if (sizeof(T) == 2) {
+                const uint2 raw = *reinterpret_cast<const uint2*>(row + j);
+                v[0] = __uint_as_float(raw.x << 16); v[1] = __uint_as_float(raw.x & 0xffff0000u);
+                v[2] = __uint_as_float(raw.y << 16); v[3] = __uint_as_float(raw.y & 0xffff0000u);
+            } else {
+                const float4 raw = *reinterpret_cast<const float4*>(row + j);
+                v[0] = raw.x; v[1] = raw.y; v[2] = raw.z; v[3] = raw.w;
+            }
+            acc += v[0] * v[0]; acc += v[1] * v[1]; acc += v[2] * v[2]; acc += v[3] * v[3];
+        }
+    } else {
+        for (int j = lane; j < r; j += 64) { const float v = to_f32(row[j]); acc += v * v; }
+    }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if (lane == 0) {
+        const float c = sqrtf(acc);
+        if (c_ffn) c_ffn[n] = c;
+        if (s_ffn) s_ffn[n] = s_mha ? c * s_mha[n] : c;
+    }
+}
+hipError_t launch_row_norm_scores(const void* z, int r, bool bf16, const float* s_mha, float* c_ffn, float* s_ffn, int64_t N,
+                                  hipStream_t s) {
+    if (N == 0) return hipSuccess;
+    dim3 g((unsigned)cdiv(N, 4)), b(256);
+    if (bf16) row_norm_scores_kernel<bf16_t><<<g, b, 0, s>>>((const bf16_t*)z, r, s_mha, c_ffn, s_ffn, N);
+    else row_norm_scores_kernel<float><<<g, b, 0, s>>>((const float*)z, r, s_mha, c_ffn, s_ffn, N);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- transpose with zero padding
 // v [M, C] -> vt [C, ldvt] (keys in vt_key_slot order); 32x32 tiles through LDS so both sides are coalesced.
 template <typename T>

@@ -317,6 +317,13 @@ int proxy_scores_impl(spts_ctx* c, const void* xn2, int64_t N, const spts_layer_
         else SPTS_TRY(run_gemm(c, g3));
     }
     { PHASE(c, PH_PROXY_Z); SPTS_TRY(run_gemm(c, g4)); }
+    if (w->Ud_orthonormal) {
+        // ||z Ud^T|| = ||z|| when the columns of Ud are orthonormal (what a truncated SVD with Sigma folded into V
+        // gives): the output projection is not evaluated at all
+        PHASE(c, PH_PROXY_OUT);
+        SPTS_HIP(c, launch_row_norm_scores(c->p<void>(c->off.z), r, c->bf16, s_mha, c_ffn, s_ffn, N, c->stream));
+        return SPTS_OK;
+    }
     // o = z Ud^T [N, D] is never stored: per-block sums of squares, then the square root
     GemmArgs g5 = gemm_args(c->p<void>(c->off.z), r, nullptr, w->Ud, r, nullptr, 0, N, m.D, r, EPI_SUMSQ);
     bool mf = c->bf16 && gemm_mfma_supported(g5);

@@ -153,6 +153,9 @@ hipError_t launch_scatter_iota(const int32_t* idx, int32_t* old2new, int64_t n, 
 // c = sqrt(sum_j part[n, j]); s_ffn = c * (s_mha ? s_mha[n] : 1)
 hipError_t launch_finish_ffn_scores(const float* part, int nparts, const float* s_mha, float* c_ffn, float* s_ffn,
                                     int64_t N, hipStream_t s);
+// c_ffn[n] = ||z[n, :]||_2, s_ffn[n] = c_ffn[n] * s_mha[n] (s_mha may be null); z [N, r] row-major
+hipError_t launch_row_norm_scores(const void* z, int r, bool bf16, const float* s_mha, float* c_ffn, float* s_ffn, int64_t N,
+                                  hipStream_t s);
 // vt[c, vt_key_slot(i)] = v[i, c]  (v [M, C] -> vt [C, ldvt]); keys i in [M, ldvt) are zero-filled
 hipError_t launch_transpose_pad(const void* v, void* vt, int64_t M, int C, int64_t ldvt, bool bf16, hipStream_t s);
 

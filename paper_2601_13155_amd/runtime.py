@@ -44,9 +44,26 @@ def pack_slab32(a: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(a.reshape(rows, K // 32, 32).transpose(1, 0, 2)).reshape(rows, K)
 
 
-def upload_layer(w: Dict[str, np.ndarray], shape, r: int, pack: bool = True) -> binding.spts_layer_weights:
+def ud_columns_orthonormal(Ud: np.ndarray, Vd: np.ndarray, tol: float = 1e-2) -> bool:
+    """True when U_down [D, r] has orthonormal columns up to `tol` (what a truncated SVD with Sigma folded into V gives,
+    also after rounding to bf16), all-zero columns of a zero-padded rank allowed if the matching rows of Vd are zero."""
+    U = np.asarray(Ud, dtype=np.float64)
+    G = U.T @ U
+    d = np.diag(G).copy()
+    zero = d == 0.0
+    if np.any(np.abs(d[~zero] - 1.0) > tol) or np.max(np.abs(G - np.diag(d)), initial=0.0) > tol:
+        return False
+    return not zero.any() or not np.any(np.asarray(Vd)[zero])
+
+
+def upload_layer(w: Dict[str, np.ndarray], shape, r: int, pack: bool = True,
+                 ud_orthonormal: Optional[bool] = None) -> binding.spts_layer_weights:
     """Weights in the paper's orientation (synth.make_layer) -> device struct in the ABI layout.  pack (bf16 only): the
-    projection and FFN matrices also get the slab-major copies that the prefill GEMMs prefer."""
+    projection and FFN matrices also get the slab-major copies that the prefill GEMMs prefer.  ud_orthonormal: whether to
+    tell the library that U_down has orthonormal columns (it then takes the proxy's output norm from z alone); None =
+    check the matrix here."""
+    if ud_orthonormal is None:
+        ud_orthonormal = "Ud" in w and "Vd" in w and ud_columns_orthonormal(w["Ud"], w["Vd"])
     abi = synth.to_abi_layout(w)
     dev = {k: to_device(v, shape.dtype) for k, v in abi.items()}
     if pack and shape.dtype == "bf16":
@@ -54,7 +71,7 @@ def upload_layer(w: Dict[str, np.ndarray], shape, r: int, pack: bool = True) -> 
             if name in abi and abi[name].shape[1] % 32 == 0:
                 dev[name + "_s"] = to_device(pack_slab32(np.asarray(abi[name])), shape.dtype)
     dlow = int(abi["Vd"].shape[1]) if "Vd" in abi else 0
-    return binding.layer_weights(dev, r=r if "Ug" in abi else 0, Dlow=dlow)
+    return binding.layer_weights(dev, r=r if "Ug" in abi else 0, Dlow=dlow, ud_orthonormal=bool(ud_orthonormal))
 
 
 def run_layer(ctx: binding.Context, x: np.ndarray, pos: np.ndarray, dw: binding.spts_layer_weights, shape, *, skip: int,

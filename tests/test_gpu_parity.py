@@ -234,6 +234,52 @@ def test_probe_attn_and_ffn(torch, name, shape, N, P, r):
     assert torch.equal(f2, cd)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_probe_ffn_output_norm_with_and_without_the_orthonormality_statement(torch, dtype):
+    """C^FFN = ||z Ud^T|| as written, and as ||z|| when the caller states that Ud has orthonormal columns (SVD-built
+    factors; upload_layer checks the matrix and makes the statement by default): both against the oracle, which always
+    evaluates the output projection, and against each other.  Then a Ud that is NOT orthonormal (columns rescaled and
+    mixed): the upload must not make the statement, and the general path must match the oracle; forcing the statement
+    on it gives the scores of a different proxy (the test shows the difference is large, i.e. the check matters)."""
+    shape = synth.ModelShape(D=512, H=8, Hkv=2, d=64, Dff=1024, dtype=dtype)
+    N, r = 777, 64
+    ctx = ctx_for(shape, 2048, max_r=r)
+    w = dict(synth.make_layer(31, 0, shape, r))
+    x = synth.hidden_states(31, N, shape.D, shape.dtype)
+    mdl = H.oracle_model(shape)
+    tol = H.TOL[dtype]["score"]
+    xd = runtime.to_device(x, shape.dtype)
+
+    def scores(dw):
+        cd = torch.full((N,), -1.0, dtype=torch.float32, device="cuda")
+        fd = torch.full((N,), -1.0, dtype=torch.float32, device="cuda")
+        ctx.spts_probe_ffn(xd, N, dw, None, cd, fd)
+        torch.cuda.synchronize()
+        assert torch.equal(cd, fd)          # no S^MHA given: S^FFN = C^FFN
+        return cd.cpu().numpy().astype(np.float64)
+
+    assert runtime.ud_columns_orthonormal(w["Ud"], w["Vd"])
+    auto = runtime.upload_layer(w, shape, r)
+    assert auto.Ud_orthonormal == 1
+    c_ref, _ = orc.probe_ffn(x, w, mdl, None, H.rnd_for(dtype))
+    c_fast = scores(auto)
+    c_full = scores(runtime.upload_layer(w, shape, r, ud_orthonormal=False))
+    assert H.score_rel_err(c_fast, c_ref) <= tol and H.score_rel_err(c_full, c_ref) <= tol
+    assert H.score_rel_err(c_fast, c_full) <= (3e-3 if dtype == "bf16" else 1e-5)
+    # a proxy whose Ud is not orthonormal
+    rng = np.random.default_rng(3)
+    mix = np.eye(r) + 0.3 * rng.standard_normal((r, r))
+    w2 = dict(w)
+    w2["Ud"] = synth.storage_round((np.asarray(w["Ud"], dtype=np.float64) @ mix).astype(np.float32), dtype)
+    assert not runtime.ud_columns_orthonormal(w2["Ud"], w2["Vd"])
+    dw2 = runtime.upload_layer(w2, shape, r)
+    assert dw2.Ud_orthonormal == 0
+    c_ref2, _ = orc.probe_ffn(x, w2, mdl, None, H.rnd_for(dtype))
+    assert H.score_rel_err(scores(dw2), c_ref2) <= tol
+    forced = scores(runtime.upload_layer(w2, shape, r, ud_orthonormal=True))
+    assert H.score_rel_err(forced, c_ref2) > 0.1
+
+
 @pytest.mark.parametrize("N,dlow", [(1, 0), (31, 0), (257, 0), (1237, 0), (2048, 0), (900, 256), (1500, 512), (3000, 1024)],
                          ids=lambda v: str(v))
 def test_probe_ffn_hidden_layer_kernel_shapes(torch, N, dlow):

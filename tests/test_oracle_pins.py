@@ -397,3 +397,26 @@ def test_prefill_query_hook_moves_one_rounding_point_only():
     assert np.array_equal(orc.bf16_prefill(q), orc.bf16_round(q))
     # relative to the exact queries both roundings are within half a bf16 ulp (2^-9)
     assert np.max(np.abs(got - q) / np.maximum(np.abs(q), 1e-300)) <= 2.0 ** -8
+
+
+def test_output_norm_of_an_orthonormal_projection_is_the_norm_of_z():
+    """Eq. (ffn_transformation) with U_down from a truncated SVD (orthonormal columns, Sigma in V): ||z U_d^T|| = ||z||,
+    also for a rank zero-padded with zero columns of U_d and zero rows of V_d; not for a U_d with mixed columns.  The
+    check a caller runs before stating orthonormality (runtime.ud_columns_orthonormal) agrees on all three."""
+    from paper_2601_13155_amd import runtime
+    shape = small_shape()
+    mdl = oracle_model(shape)
+    xn2 = synth.hidden_states(12, 23, shape.D)
+    for r, r_pad in ((8, 0), (6, 8)):
+        w = synth.make_layer(12, 0, shape, r, r_pad=r_pad)
+        f = lambda k: np.asarray(w[k], dtype=np.float64)
+        z = (orc.silu(xn2 @ f("Ug") @ f("Vg")) * (xn2 @ f("Uu") @ f("Vu"))) @ f("Vd").T
+        assert np.allclose(orc.transformation_scores(xn2, w), np.linalg.norm(z, axis=1), rtol=1e-6)
+        assert runtime.ud_columns_orthonormal(w["Ud"], w["Vd"])
+    w2 = dict(w)
+    w2["Ud"] = f("Ud") @ (np.eye(f("Ud").shape[1]) + 0.3 * np.random.default_rng(0).standard_normal((f("Ud").shape[1],) * 2))
+    assert not runtime.ud_columns_orthonormal(w2["Ud"], w2["Vd"])
+    assert not np.allclose(orc.transformation_scores(xn2, w2), np.linalg.norm(z, axis=1), rtol=1e-2)
+    w3 = dict(w)   # zero-padded columns whose Vd rows are NOT zero: z has components the projection drops
+    w3["Vd"] = f("Vd") + 0.1
+    assert not runtime.ud_columns_orthonormal(w3["Ud"], w3["Vd"])
