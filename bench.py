@@ -268,6 +268,7 @@ def main():
         phase_flops = {"k_proj": flops_by["k_proj"], "probe_q": flops_by["probe_q"], "probe_attn": flops_by["probe_attn"],
                        "attention": flops_by["attention"], "o_proj": flops_by["o_proj"],
                        "ffn_gate_up": gate_up_flops, "ffn_down": flops_by["ffn"] / 3.0,
+                       "qv_proj": flops_by["qv_proj"],
                        "q_proj": flops_by["qv_proj"] * shape.H / (shape.H + shape.Hkv),
                        "v_proj": flops_by["qv_proj"] * shape.Hkv / (shape.H + shape.Hkv)}
         proxy_ms = sum(phase_out[k]["ms_per_step"] for k in ("proxy_in", "proxy_mid", "proxy_z", "proxy_out") if k in phase_out)

@@ -108,7 +108,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     constexpr int WROWS = 32 * MI;                // output rows per wavefront
     constexpr int LROWS = 256 / NW;               // operand tile rows each wavefront loads
     constexpr bool DUAL = (EPI == EPI_SILU_MUL);
-    constexpr bool CAN_SPLIT = (EPI == EPI_STORE || EPI == EPI_RESIDUAL || EPI == EPI_ROPE);
+    constexpr bool SEG = (EPI == EPI_ROPE_STORE);   // two products side by side: rotary columns, then stored columns
+    constexpr bool CAN_SPLIT = (EPI == EPI_STORE || EPI == EPI_RESIDUAL || EPI == EPI_ROPE || SEG);
     constexpr int TILE_BYTES = S::TILE_BYTES;
     constexpr int NOPS = DUAL_A ? 3 : 2;          // operand tiles per stage (A, B[, A1])
     constexpr int NST = BK == 64 ? 2 : (DUAL_A ? 3 : 4);   // LDS ring stages
@@ -159,7 +160,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     // pitch is 64 bytes and one slab further on is rows * 64 bytes.
     const bool a_slab = BK == 32 && a.a_slab, b_slab = BK == 32 && a.b_slab;
     const int64_t a_pitch = a_slab ? 64 : a.lda * 2, b_pitch = b_slab ? 64 : a.ldb * 2;      // bytes between rows
-    const int64_t a_kstep = a_slab ? a.M * 64 : BK * 2, b_kstep = b_slab ? a.b_rows * 64 : BK * 2;   // bytes per slab
+    const bool second = SEG && col0 >= a.n_split;   // this tile belongs to the second product (B1 -> C2)
+    const int64_t a_kstep = a_slab ? a.M * 64 : BK * 2;                                              // bytes per slab
+    const int64_t b_kstep = b_slab ? (second ? a.b_rows1 : a.b_rows) * 64 : BK * 2;
     uint32_t oa[LPO], ob[LPO];
     const char* abase = (const char*)a.A + (a.a_idx ? (int64_t)0 : row0 * a_pitch);
     const char* a1base = DUAL_A ? (const char*)a.A1 + (a.a_idx ? (int64_t)0 : row0 * a_pitch) : abase;
@@ -168,6 +171,8 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
         const int rw = wave * LROWS;   // first B tile row of this wavefront
         if (DUAL) bbase = rw < 128 ? (const char*)a.B0 + (int64_t)(col0 + rw) * b_pitch
                                    : (const char*)a.B1 + (int64_t)(col0 + rw - 128) * b_pitch;
+        else if (SEG) bbase = second ? (const char*)a.B1 + (int64_t)(col0 - a.n_split + rw) * b_pitch
+                                     : (const char*)a.B0 + (int64_t)(col0 + rw) * b_pitch;
         else if (a.B1 && col0 >= a.N / 2) bbase = (const char*)a.B1 + (int64_t)(col0 - a.N / 2 + rw) * b_pitch;
         else bbase = (const char*)a.B0 + (int64_t)(col0 + rw) * b_pitch;
     }
@@ -357,6 +362,9 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
     // fragment write (32 rows, same chunk) and the row-wise reads are both spread over all banks.
     constexpr int NCH = OUT_COLS / 8;            // 16-byte chunks per staged row
     constexpr int ROWB = OUT_COLS * 2;           // bytes per staged row
+    const int colshift = second ? a.n_split : 0; // the second product's outputs count their columns from n_split
+    if (second) Cb = (bf16_t*)a.C2;
+    const int64_t ldo = second ? a.ldc2 : a.ldc;
     auto stage = [&](int tr, int tc, uint2 o) {
         *reinterpret_cast<uint2*>(smem + tr * ROWB + ((((tc >> 3) ^ tr) & (NCH - 1)) << 4) + ((tc & 4) << 1)) = o;
     };
@@ -367,16 +375,16 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
         const bool rok = grow < a.M;
         const int64_t growc = rok ? grow : a.M - 1;
         const int64_t crow = a.c_idx ? (int64_t)a.c_idx[growc] : growc;
-        if (EPI == EPI_STORE) {
+        if (EPI == EPI_STORE || (SEG && second)) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int cb = col0 + wn * 128 + j * 32 + 4 * lh;
+                const int cb = col0 - colshift + wn * 128 + j * 32 + 4 * lh;   // column of this product's output
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     uint2 o;
                     o.x = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
                     o.y = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                    stage(tr, cb - col0 + 8 * q, o);
+                    stage(tr, cb - (col0 - colshift) + 8 * q, o);
                     if (a.Ct && grow < a.ldct) {
                         bf16_t* ct = (bf16_t*)a.Ct;
                         const uint16_t e[4] = {(uint16_t)(o.x & 0xffff), (uint16_t)(o.x >> 16), (uint16_t)(o.y & 0xffff), (uint16_t)(o.y >> 16)};
@@ -418,7 +426,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
                     }
                 }
             }
-        } else if (EPI == EPI_ROPE) {
+        } else if (EPI == EPI_ROPE || SEG) {
             {
                 const int64_t trow = a.rope_idx ? (int64_t)a.rope_idx[growc] : growc;
                 const int half = a.head_dim >> 1;
@@ -503,7 +511,7 @@ __global__ void __launch_bounds__(NW * 64) gemm_mfma_kernel(GemmArgs a, int nM, 
         if (grow < a.M) {
             const int64_t crow = a.c_idx ? (int64_t)a.c_idx[grow] : grow;
             const u32x4 v = *reinterpret_cast<const u32x4*>(smem + tr * ROWB + (((oc ^ tr) & (NCH - 1)) << 4));
-            *reinterpret_cast<u32x4*>(Cb + crow * a.ldc + col0 + oc * 8) = v;
+            *reinterpret_cast<u32x4*>(Cb + crow * ldo + (col0 - colshift) + oc * 8) = v;
         }
     }
 }
@@ -520,19 +528,25 @@ bool gemm_mfma_supported(const GemmArgs& a) {
     if (a.K < 32 || a.K % 32 != 0) return false;
     if (a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
     // slab-major operands: served by the 32-wide-slab instantiations; A not gathered
-    if ((a.a_slab || a.b_slab) && a.epi != EPI_SILU_MUL && a.epi != EPI_RESIDUAL && a.epi != EPI_STORE && a.epi != EPI_ROPE) return false;
+    const bool seg = a.epi == EPI_ROPE_STORE;
+    if ((a.a_slab || a.b_slab) && a.epi != EPI_SILU_MUL && a.epi != EPI_RESIDUAL && a.epi != EPI_STORE && a.epi != EPI_ROPE && !seg) return false;
+    if (seg) {
+        if (a.n_split <= 0 || a.n_split >= a.N || a.n_split % 256 != 0 || a.c_idx || a.c_slab) return false;
+        if (!a.B1 || !al16(a.B1) || !a.C2 || !al16(a.C2) || a.ldc2 % 8 != 0) return false;
+        if (a.b_slab && (a.b_rows < a.n_split || a.b_rows1 < a.N - a.n_split)) return false;
+    }
     if (a.a_slab && a.a_idx) return false;
-    if (a.b_slab && a.b_rows < (a.epi == EPI_STORE && a.B1 ? a.N / 2 : a.N)) return false;   // rows of each B matrix
+    if (a.b_slab && !seg && a.b_rows < (a.epi == EPI_STORE && a.B1 ? a.N / 2 : a.N)) return false;   // rows of each B matrix
     if (a.c_slab && ((a.epi != EPI_SILU_MUL && a.epi != EPI_STORE) || a.c_idx || a.Ct)) return false;
     if (!al16(a.A) || !al16(a.B0) || (a.A1 && !al16(a.A1)) || (dual && !al16(a.B1))) return false;
     if (a.epi != EPI_SUMSQ) {
         if (a.ldc % 8 != 0 || !al16(a.C)) return false;
     }
-    if (a.epi == EPI_ROPE && a.head_dim != 128 && a.head_dim != 64) return false;
-    if (a.Ct && a.epi != EPI_STORE) return false;
+    if ((a.epi == EPI_ROPE || seg) && a.head_dim != 128 && a.head_dim != 64) return false;
+    if (a.Ct && a.epi != EPI_STORE && !seg) return false;
     if (a.epi == EPI_STORE && a.B1 && (a.N % 512 != 0 || !al16(a.B1))) return false;
     if (a.ksplit > 1) {
-        if (!a.part32 || !al16(a.part32) || (a.epi != EPI_STORE && a.epi != EPI_RESIDUAL && a.epi != EPI_ROPE)) return false;
+        if (!a.part32 || !al16(a.part32) || (a.epi != EPI_STORE && a.epi != EPI_RESIDUAL && a.epi != EPI_ROPE && !seg)) return false;
         if (a.K / 64 < a.ksplit || a.nfull < 0 || a.nfull > (a.M + BM - 1) / BM * (a.N / 256)) return false;
     }
     if (a.M > (int64_t)1 << 30) return false;
@@ -587,13 +601,20 @@ __global__ void __launch_bounds__(256) splitk_finish_kernel(GemmArgs a, int nM, 
     const int64_t growc = rok ? grow : a.M - 1;
     const int64_t crow = a.c_idx ? (int64_t)a.c_idx[growc] : growc;
     bf16_t* Cb = (bf16_t*)a.C;
-    if (a.epi == EPI_STORE) {
+    // two products in one launch: a tile is either a rotary tile of the first or a stored tile of the second
+    int epi = a.epi, colshift = 0;
+    int64_t ldo = a.ldc;
+    if (epi == EPI_ROPE_STORE) {
+        if (col0 >= a.n_split) { epi = EPI_STORE; colshift = a.n_split; Cb = (bf16_t*)a.C2; ldo = a.ldc2; }
+        else epi = EPI_ROPE;
+    }
+    if (epi == EPI_STORE) {
         const f32x4 s = quad(j);
-        const int col = col0 + wn * 128 + j * 32 + 4 * lh + 8 * q;
+        const int col = col0 - colshift + wn * 128 + j * 32 + 4 * lh + 8 * q;
         u32x2 o = {pack_bf16x2(s.x, s.y), pack_bf16x2(s.z, s.w)};
         if (rok) {
             if (a.c_slab) *reinterpret_cast<u32x2*>(Cb + ((int64_t)(col >> 5) * a.M + grow) * 32 + (col & 31)) = o;   // slab-major C
-            else *reinterpret_cast<u32x2*>(Cb + crow * a.ldc + col) = o;
+            else *reinterpret_cast<u32x2*>(Cb + crow * ldo + col) = o;
         }
         if (a.Ct && grow < a.ldct) {
             bf16_t* ct = (bf16_t*)a.Ct;
@@ -601,7 +622,7 @@ __global__ void __launch_bounds__(256) splitk_finish_kernel(GemmArgs a, int nM, 
 #pragma unroll
             for (int t = 0; t < 4; ++t) ct[(int64_t)(col + t) * a.ldct + vt_key_slot(grow)].v = e[t];
         }
-    } else if (a.epi == EPI_RESIDUAL) {
+    } else if (epi == EPI_RESIDUAL) {
         if (!rok) return;
         const f32x4 s = quad(j);
         const int col = col0 + wn * 128 + j * 32 + 4 * lh + 8 * q;
@@ -642,7 +663,7 @@ __global__ void __launch_bounds__(256) splitk_finish_kernel(GemmArgs a, int nM, 
 // and read back) plus one more launch when split ks ways.
 int gemm_pick_split(int64_t M, int32_t N, int32_t K, int epi, int32_t* nfull) {
     *nfull = 0;
-    if (epi != EPI_STORE && epi != EPI_RESIDUAL && epi != EPI_ROPE) return 1;
+    if (epi != EPI_STORE && epi != EPI_RESIDUAL && epi != EPI_ROPE && epi != EPI_ROPE_STORE) return 1;
     if (N % 256 != 0 || M <= 0) return 1;
     const int64_t tiles = ((M + BM - 1) / BM) * (N / 256);
     const int rem = (int)(tiles % 256);
@@ -674,6 +695,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t s) {
         case EPI_RESIDUAL: e = (a.K % 64 == 0 && !slab ? launch_t<EPI_RESIDUAL, 64, false, NW>(a, s) : launch_t<EPI_RESIDUAL, 32, false, NW>(a, s)); break;
         case EPI_SUMSQ: e = (a.K % 64 == 0 ? launch_t<EPI_SUMSQ, 64, false, NW>(a, s) : launch_t<EPI_SUMSQ, 32, false, NW>(a, s)); break;
         case EPI_ROPE: e = (a.K % 64 == 0 && !slab ? launch_t<EPI_ROPE, 64, false, NW>(a, s) : launch_t<EPI_ROPE, 32, false, NW>(a, s)); break;
+        case EPI_ROPE_STORE: e = (a.K % 64 == 0 && !slab ? launch_t<EPI_ROPE_STORE, 64, false, NW>(a, s) : launch_t<EPI_ROPE_STORE, 32, false, NW>(a, s)); break;
         case EPI_SILU_MUL:
             if (a.A1) e = launch_t<EPI_SILU_MUL, 32, true, NW>(a, s);
             else e = launch_t<EPI_SILU_MUL, 32, false, NW>(a, s);   // 4 stages of 32 measured 2 % faster here than 2 of 64

@@ -94,14 +94,14 @@ enum PhaseId {
     PH_ROPE_TABLE = 0, PH_RMSNORM, PH_K_PROJ, PH_PROBE_Q, PH_PROBE_ATTN, PH_TOPK, PH_GATHER, PH_Q_PROJ, PH_V_PROJ,
     PH_ATTENTION, PH_O_PROJ, PH_PROXY_IN, PH_PROXY_MID, PH_PROXY_Z, PH_PROXY_OUT, PH_FFN_GATE_UP, PH_FFN_DOWN,
     PH_COMPACT, PH_DEC_NORM, PH_DEC_QKV, PH_DEC_ROPE_APPEND, PH_DEC_ATTN, PH_DEC_O, PH_DEC_GATE_UP, PH_DEC_DOWN, PH_DEC_HEAD,
-    PH_BUILD_SALIENCY, PH_BUILD_TOPMEAN,
+    PH_BUILD_SALIENCY, PH_BUILD_TOPMEAN, PH_QV_PROJ,
     PH_COUNT
 };
 static const char* const kPhaseNames[PH_COUNT] = {
     "rope_table", "rmsnorm", "k_proj", "probe_q", "probe_attn", "topk", "gather", "q_proj", "v_proj",
     "attention", "o_proj", "proxy_in", "proxy_mid", "proxy_z", "proxy_out", "ffn_gate_up", "ffn_down", "compact",
     "dec_rmsnorm", "dec_qkv", "dec_rope_append", "dec_attention", "dec_o_proj", "dec_gate_up", "dec_down", "dec_head",
-    "build_saliency", "build_topmean"};
+    "build_saliency", "build_topmean", "qv_proj"};
 
 // Brackets the launches issued during its lifetime with two events when profiling is on.
 struct PhaseScope {
@@ -169,11 +169,11 @@ GemmArgs gemm_args(const void* A, int64_t lda, const int32_t* a_idx, const void*
 
 // B (one weight matrix, or the gate / up pair) through its slab-major copy when the caller gave one and the
 // matrix-core kernel serves the call with it; otherwise g keeps the row-major pointers
-void prefer_slab(const spts_ctx* c, GemmArgs& g, const void* s0, const void* s1, int64_t rows) {
+void prefer_slab(const spts_ctx* c, GemmArgs& g, const void* s0, const void* s1, int64_t rows, int64_t rows1 = 0) {
     if (!c->bf16 || !s0 || (g.B1 && !s1)) return;
     GemmArgs t = g;
     t.B0 = s0; if (g.B1) t.B1 = s1;
-    t.b_slab = 1; t.b_rows = rows;
+    t.b_slab = 1; t.b_rows = rows; t.b_rows1 = rows1;
     if (gemm_mfma_supported(t)) g = t;
 }
 
@@ -890,17 +890,34 @@ int spts_layer_prefill(spts_ctx* c, void* x, const int32_t* pos, int64_t N, cons
         aa.q_scale = query_store_scale(c);
         GemmArgs gq = gemm_args(xn, m.D, idxA, w->Wq, m.D, nullptr, QD, Ma, QD, m.D);
         gq.a_rows = N;
-        { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s, aa.q_scale)); }
         GemmArgs gv = gemm_args(xn, m.D, full_kv ? nullptr : idxA, w->Wv, m.D, vv, KV, Mk, KV, m.D);
         gv.a_rows = N;
-        prefer_slab(c, gv, w->Wv_s, nullptr, KV);
-        bool vt_done = false;
-        if (amf) {
-            // the matrix-core projection writes the transposed copy (keys contiguous) in its epilogue
-            GemmArgs gvt = gv; gvt.Ct = c->p<void>(c->off.vt); gvt.ldct = aa.ldvt;
-            if (gemm_mfma_supported(gvt)) { gv = gvt; vt_done = true; }
+        // Queries and values of the same rows (active queries against their own keys, or the dense branch) leave one
+        // launch when the matrix-core kernels take everything: columns [0, H*d) rotary queries, [H*d, H*d + Hkv*d)
+        // values with their transposed copy.  One grid of (H + Hkv) * d / 256 column tiles instead of two, one tail.
+        bool merged = false;
+        if (amf && Mk == Ma && gv.a_idx == gq.a_idx) {
+            GemmArgs f = gq;
+            f.epi = EPI_ROPE_STORE; f.N = QD + KV; f.n_split = QD; f.B1 = w->Wv;
+            f.C = c->p<void>(c->off.q); f.ldc = QD; f.C2 = vv; f.ldc2 = KV;
+            f.rope = c->p<float2>(c->off.rope); f.rope_idx = idxA; f.head_dim = m.d; f.rope_scale = aa.q_scale;
+            f.Ct = c->p<void>(c->off.vt); f.ldct = aa.ldvt;
+            prefer_slab(c, f, w->Wq_s, w->Wv_s, QD, KV);
+            if (gemm_mfma_supported(f)) {
+                PHASE(c, PH_QV_PROJ);
+                SPTS_TRY(run_gemm_mfma(c, f));
+                merged = true;
+            }
         }
-        {
+        if (!merged) {
+            { PHASE(c, PH_Q_PROJ); SPTS_TRY(run_gemm_rope(c, gq, m.H, idxA, 0, c->p<void>(c->off.q), w->Wq_s, aa.q_scale)); }
+            prefer_slab(c, gv, w->Wv_s, nullptr, KV);
+            bool vt_done = false;
+            if (amf) {
+                // the matrix-core projection writes the transposed copy (keys contiguous) in its epilogue
+                GemmArgs gvt = gv; gvt.Ct = c->p<void>(c->off.vt); gvt.ldct = aa.ldvt;
+                if (gemm_mfma_supported(gvt)) { gv = gvt; vt_done = true; }
+            }
             PHASE(c, PH_V_PROJ);
             SPTS_TRY(run_gemm(c, gv));
             if (amf && !vt_done) SPTS_HIP(c, launch_transpose_pad(vv, c->p<void>(c->off.vt), Mk, KV, aa.ldvt, c->bf16, st));

@@ -69,6 +69,8 @@ enum GemmEpilogue : int {
     EPI_RESIDUAL = 2,   // C[crow, col] = C[crow, col] + acc   (crow = c_idx ? c_idx[row] : row)
     EPI_SUMSQ = 3,      // part[row, col_block] = sum over the block's columns of acc^2
     EPI_ROPE = 4,       // C[row, col] = rotary(acc) with table row (rope_idx ? rope_idx[row] : row); MFMA path only
+    EPI_ROPE_STORE = 5, // two products of the same A rows in one launch (MFMA path only): columns [0, n_split) = A * B0^T
+                        // with the rotary epilogue -> C; columns [n_split, N) = A * B1^T stored plainly -> C2 (and Ct)
 };
 
 struct GemmArgs {
@@ -82,6 +84,8 @@ struct GemmArgs {
     const float2* rope; int32_t head_dim;               // EPI_ROPE: cos/sin table [rows, head_dim/2]
     const int32_t* rope_idx;                            // table row = rope_idx ? rope_idx[row] : row
     float rope_scale;                                   // EPI_ROPE: the rotated values are multiplied by this before rounding (0 = 1)
+    int32_t n_split; void* C2; int64_t ldc2;            // EPI_ROPE_STORE: first column of the second product, its output [M, N - n_split]
+    int64_t b_rows1;                                    // EPI_ROPE_STORE with b_slab: rows of the slab-major B1 (b_rows: of B0)
     int64_t M; int32_t N; int32_t K;
     int32_t epi; int32_t c_is_f32;
     // tail split-K (matrix-core path; EPI_STORE / EPI_RESIDUAL / EPI_ROPE): the first `nfull` tiles (in
