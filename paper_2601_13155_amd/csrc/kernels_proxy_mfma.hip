@@ -116,7 +116,7 @@ __global__ void __launch_bounds__(PH_WAVES * 64) proxy_hidden_kernel(ProxyHidden
     f32x16 Ga = zero16, Ua = zero16, Gb = zero16, Ub = zero16;
 
     // One tile: 2*KS MFMAs into (GC, UC) from the ring stage of tile tl_, interleaved with the arithmetic of the previous
-    // tile's accumulators (GP, UP), whose packed result leaves through the staging buffer at the end.
+    // tile's accumulators (GP, UP), whose packed result is stored at the end (two 16-byte pieces per lane).
     constexpr int FD = 3;   // fragment reads run FD k-steps ahead (2 and 4 measure the same)
 #define SPTS_PH_FRAG(X_, ks_) (*reinterpret_cast<const bf16x8*>(sT_ + (X_) * MAT_BYTES + ((ks_) >> 1) * 2048 + foff[(ks_) & 1]))
 #define SPTS_PH_TILE(tl_, GC, UC, GP, UP)                                                                      \
