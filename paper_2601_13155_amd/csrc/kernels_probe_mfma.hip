@@ -33,7 +33,7 @@ template <int D> struct ProbeLds {
 
 // stats_part: [nchunks][Hkv][Rp][2]; stats: [Hkv][Rp][2] (M, 1/L); part: [Hkv][Np]
 template <int D, int RB, int PASS>
-__global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, int64_t Np, float qmul,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((PASS == 2 && RB <= 2) ? 2 : 1, 8))) probe_mfma_kernel(ProbeArgs a, int Rp, int64_t Np, float qmul,
                                                          float* __restrict__ stats_part, const float* __restrict__ stats) {
     using L = ProbeLds<D>;
     constexpr int KS = D / 16;
@@ -79,6 +79,9 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
     // that starts a block's product: the MFMA then delivers log2 of the probability itself (padded rows and empty rows:
     // offset -inf, probability 0)
     f32x16 coff[PASS == 2 ? RB : 1];
+    // ... and, for the tiles that reach into the probe window, (window row p of the register's probe row) + 1, two per
+    // register: candidate N - P + j is hidden from the row when j >= p + 1 (0 for padded rows, whose offset is -inf anyway)
+    uint32_t pvis[PASS == 2 ? RB : 1][8];
     if (PASS == 2) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
@@ -87,6 +90,8 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
                 const int rr = wave * 32 * RB + rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
                 const float2 st = *reinterpret_cast<const float2*>(stats + ((int64_t)g * Rp + rr) * 2);
                 coff[rb][r] = st.y > 0.f ? __builtin_amdgcn_logf(st.y) - st.x : -INFINITY;
+                const uint32_t enc = rr < R ? (uint32_t)(rr / grp + 1) : 0u;
+                if (r & 1) pvis[rb][r >> 1] |= enc << 16; else pvis[rb][r >> 1] = enc;
             }
     }
 
@@ -171,17 +176,15 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(ProbeArgs a, int Rp, in
                         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf, s, 0, 0, 0);
                     }
                     // lane: key = column kb*32 + l32; rows = rb*32 + 8*(r/4) + 4*lh + r%4
-                    const int64_t key = key0 + kb * 32 + l32;
+                    const int krel = (int)(key0 + kb * 32 + l32 - (a.N - a.P));   // position inside the probe window (< 0: before it)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         float pv = __builtin_amdgcn_exp2f(s[r]);
-                        if (need_mask) {
-                            const int rr = wave * 32 * RB + rb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                            const int64_t vl = rr < R ? a.N - a.P + rr / grp : -1;
-                            if (key > vl) pv = 0.f;
-                        }
+                        if (need_mask && krel >= (int)((pvis[rb][r >> 1] >> (16 * (r & 1))) & 0xffffu)) pv = 0.f;
                         ksum[kb] += pv;
                     }
+                    // one block at a time: interleaved, the blocks' accumulators and exponentials do not fit the registers
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
 #pragma unroll
