@@ -32,13 +32,16 @@ template <int D> struct ProbeLds {
 };
 
 // stats_part: [nchunks][Hkv][Rp][2]; stats: [Hkv][Rp][2] (M, 1/L); part: [Hkv][Np]
-template <int D, int RB, int PASS>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((PASS == 2 && RB <= 2) ? 2 : 1, 8))) probe_mfma_kernel(ProbeArgs a, int Rp, int64_t Np, float qmul,
+// NWV wavefronts per workgroup, 32 * RB probe rows each.  Two wavefronts per SIMD are asked of the register allocator
+// where the rows fit (RB <= 2; left alone it used 270 registers for pass 2 and ran one).
+template <int D, int RB, int PASS, int NWV>
+__global__ void __launch_bounds__(64 * NWV) __attribute__((amdgpu_waves_per_eu((PASS == 2 && RB <= 2) ? 2 : 1, 8))) probe_mfma_kernel(ProbeArgs a, int Rp, int64_t Np, float qmul,
                                                          float* __restrict__ stats_part, const float* __restrict__ stats) {
     using L = ProbeLds<D>;
     constexpr int KS = D / 16;
     __shared__ __attribute__((aligned(16))) char sK[2][L::K_BYTES];
-    __shared__ float sRed[4][PKV];
+    constexpr int NT = 64 * NWV;
+    __shared__ float sRed[NWV][PKV];
 
     const int chunk = blockIdx.x, g = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -95,21 +98,22 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((PASS 
             }
     }
 
-    constexpr int KCH = PKV * L::CPRK / 256;
+    constexpr int KCH = PKV * L::CPRK / NT;
+    static_assert(KCH >= 1, "a key tile gives every thread at least one 16-byte chunk");
     const int kc = tid % L::CPRK, kr = tid / L::CPRK;
     const bf16_t* Kg = (const bf16_t*)a.k;
     u32x4 rk[KCH];
     auto load_tile = [&](int t) {
 #pragma unroll
         for (int i = 0; i < KCH; ++i) {
-            int64_t key = key_begin + (int64_t)t * PKV + kr + (256 / L::CPRK) * i;
+            int64_t key = key_begin + (int64_t)t * PKV + kr + (NT / L::CPRK) * i;
             if (key >= a.N) key = a.N - 1;
             rk[i] = *reinterpret_cast<const u32x4*>(Kg + (key * a.Hkv + g) * (int64_t)D + kc * 8);
         }
     };
     auto store_tile = [&](int stage) {
 #pragma unroll
-        for (int i = 0; i < KCH; ++i) *reinterpret_cast<u32x4*>(sK[stage] + L::koff(kr + (256 / L::CPRK) * i, kc)) = rk[i];
+        for (int i = 0; i < KCH; ++i) *reinterpret_cast<u32x4*>(sK[stage] + L::koff(kr + (NT / L::CPRK) * i, kc)) = rk[i];
     };
 
     float m_run[RB], l_run[RB];
@@ -195,7 +199,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((PASS 
             __syncthreads();
             if (tid < PKV) {
                 int64_t key = key0 + tid;
-                if (key < a.N) a.partial[(int64_t)g * Np + key] = sRed[0][tid] + sRed[1][tid] + sRed[2][tid] + sRed[3][tid];
+                if (key < a.N) {
+                    float tot = sRed[0][tid];
+#pragma unroll
+                    for (int wv = 1; wv < NWV; ++wv) tot += sRed[wv][tid];   // fixed order
+                    a.partial[(int64_t)g * Np + key] = tot;
+                }
             }
         }
         if (t + 1 < n_tiles) store_tile((t + 1) & 1);
@@ -272,7 +281,7 @@ bool probe_mfma_supported(const ProbeArgs& a) {
     return al(a.qp) && al(a.k);
 }
 
-template <int D, int RB>
+template <int D, int RB, int NWV = 4>
 static hipError_t launch_probe_t(const ProbeArgs& a, int Rp, hipStream_t s) {
     const int64_t Np = (a.N + 255) / 256 * 256;
     const int nchunks = (int)((a.N + CHUNK - 1) / CHUNK);
@@ -284,10 +293,10 @@ static hipError_t launch_probe_t(const ProbeArgs& a, int Rp, hipStream_t s) {
     b.partial = part;
     const float want = attention_mfma_q_scale(D);
     const float qmul = (a.q_scale != 0.f) ? want / a.q_scale : want;   // exactly 1 when the producer applied `want`
-    dim3 grid(nchunks, a.Hkv), block(256);
-    probe_mfma_kernel<D, RB, 1><<<grid, block, 0, s>>>(b, Rp, Np, qmul, stats_part, nullptr);
+    dim3 grid(nchunks, a.Hkv), block(256), pblock(64 * NWV);
+    probe_mfma_kernel<D, RB, 1, NWV><<<grid, pblock, 0, s>>>(b, Rp, Np, qmul, stats_part, nullptr);
     probe_combine_kernel<<<dim3((a.Hkv * Rp + 3) / 4), block, 0, s>>>(stats_part, stats, nchunks, a.Hkv, Rp, R);
-    probe_mfma_kernel<D, RB, 2><<<grid, block, 0, s>>>(b, Rp, Np, qmul, nullptr, stats);
+    probe_mfma_kernel<D, RB, 2, NWV><<<grid, pblock, 0, s>>>(b, Rp, Np, qmul, nullptr, stats);
     probe_final_kernel<<<dim3((unsigned)((a.N + 255) / 256)), block, 0, s>>>(part, a.S, a.N, Np, a.Hkv, 1.0f / (float)(a.P * a.H));
     return hipGetLastError();
 }
@@ -299,12 +308,12 @@ hipError_t launch_probe_mfma(const ProbeArgs& a, hipStream_t s) {
         if (rb == 1) return launch_probe_t<128, 1>(a, Rp, s);
         if (rb == 2) return launch_probe_t<128, 2>(a, Rp, s);
         if (rb == 3) return launch_probe_t<128, 3>(a, Rp, s);
-        return launch_probe_t<128, 4>(a, Rp, s);
+        return launch_probe_t<128, 2, 8>(a, Rp, s);   // 512 rows: 8 wavefronts x 64 rows keep two wavefronts per SIMD
     }
     if (rb == 1) return launch_probe_t<64, 1>(a, Rp, s);
     if (rb == 2) return launch_probe_t<64, 2>(a, Rp, s);
     if (rb == 3) return launch_probe_t<64, 3>(a, Rp, s);
-    return launch_probe_t<64, 4>(a, Rp, s);
+    return launch_probe_t<64, 2, 8>(a, Rp, s);
 }
 
 }  // namespace spts

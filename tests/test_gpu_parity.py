@@ -200,6 +200,9 @@ PROBE_CASES = [
     ("bf16_d128_ragged", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0), 1111, 33, 64),
     ("bf16_all_mfma", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 64, 256),
     ("bf16_d64_mfma", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16"), 1100, 16, 256),
+    # 512 probe rows per kv head (8 wavefronts x 64 rows), d = 128 and d = 64
+    ("bf16_rows512", synth.ModelShape(D=1024, H=8, Hkv=2, d=128, Dff=2048, dtype="bf16", rope_base=500000.0), 1500, 128, 256),
+    ("bf16_rows512_d64", synth.ModelShape(D=512, H=8, Hkv=2, d=64, Dff=1024, dtype="bf16"), 1237, 128, 256),
 ]
 
 
