@@ -432,6 +432,34 @@ def test_layer_with_peaked_dominant_attention(torch, name, shape, N, P, r):
     H.lockstep_layer(kv1, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 1), shape.dtype)
 
 
+@pytest.mark.parametrize("name,shape", [
+    ("d128_g4", synth.ModelShape(D=512, H=8, Hkv=2, d=128, Dff=1024, dtype="bf16", rope_base=500000.0)),
+    ("d64_g2", synth.ModelShape(D=512, H=8, Hkv=4, d=64, Dff=1024, dtype="bf16")),
+    ("d128_g1", synth.ModelShape(D=512, H=4, Hkv=4, d=128, Dff=1024, dtype="bf16")),
+], ids=["d128_g4", "d64_g2", "d128_g1"])
+def test_matrix_core_layer_at_edge_sizes(torch, name, shape):
+    """Sequence lengths and attention budgets around the matrix-core kernels' blocks: one token, one 32-key block and
+    one key more, one 64-key tile and one more, the 64 / 128 / 256 queries a workgroup takes per head (4, 2 or 1 heads
+    of a kv-head group share a workgroup) and one more.  Dense branch and a skip layer with a tiny and a ragged
+    attention budget, each lock-step against the oracle."""
+    r = 64
+    ctx = ctx_for(shape, 1024, max_probe=64, max_r=r)
+    assert ctx.uses_mfma()
+    mdl = H.oracle_model(shape)
+    w = synth.make_layer(44, 0, shape, r)
+    dw = runtime.upload_layer(w, shape, r)
+    for N in (1, 2, 33, 64, 65, 129, 257, 300):
+        x = synth.hidden_states(44 + N, N, shape.D, shape.dtype)
+        pos = (synth.positions(N) * 3 + 5).astype(np.int32)
+        P = min(8, N)
+        dense = runtime.run_layer(ctx, x, pos, dw, shape, skip=0, probe_len=P, m_attn=0, m_ffn=0)
+        H.lockstep_layer(dense, x, pos, w, mdl, orc.LayerCfg(0, P, N, N, 1, 0), shape.dtype)
+        for ma in sorted({1, min(N, 33), max(1, (2 * N) // 3)}):
+            mf = max(1, N // 2)
+            skip = runtime.run_layer(ctx, x, pos, dw, shape, skip=1, probe_len=P, m_attn=ma, m_ffn=mf)
+            H.lockstep_layer(skip, x, pos, w, mdl, orc.LayerCfg(1, P, ma, mf, 1, 0), shape.dtype)
+
+
 def test_attention_under_steep_logits(torch):
     """Wk scaled by 16 and by 160: logits spread over tens to hundreds of log2 units, so a query's reference maximum
     in the matrix-core attention moves many times along the keys (and at 160 an exponential taken against a stale
