@@ -483,7 +483,7 @@ def main():
         tbytes = tb * (4.0 * tn + 4.0 * tk)
         topk_batched = {"rows": tb, "N": tn, "k": tk, "ms": tms, "gbs": tbytes / (tms * 1e-3) / 1e9,
                         "hbm_frac": tbytes / (tms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                        "note": "algorithmic bytes (scores once + indices) / time; the kernel sweeps the scores five times (first sweep from HBM, the others from the memory-side cache)"}
+                        "note": "algorithmic bytes (scores once + indices) / time; the kernel sweeps the scores three times (first sweep from HBM, the others from the memory-side cache)"}
         del sc, ti, tctx
 
     # ---- one skip layer over a batch of sequences: one batched call against one call per sequence

@@ -245,20 +245,33 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restr
 
 // Long rows of a batch (N > 32768, N % 4 == 0, equal rows): one workgroup per row as above, but written for streaming.
 // Every wavefront owns one contiguous slice in all sweeps and reads it as 16-byte loads, four per lane in flight (64 KB per
-// workgroup); histograms are private to the wavefront (16 x 256 counters in LDS, summed before the bin is picked), and the
-// last radix pass leaves what the compaction needs -- per wavefront the keys above the decided prefix and the histogram
-// of the last digit -- so no separate counting sweep is needed: five sweeps over the row instead of six.
+// workgroup).
+// Three sweeps over the row in the usual case: (1) an 8192-bin histogram of the keys' top 13 bits (sign, exponent, four
+// mantissa bits) finds the bin of the k-th largest key; (2) every wavefront copies the low 19 bits of its keys of that bin
+// into its own LDS region and counts the keys of higher bins -- scores of one layer spread over several octaves, so the
+// bin (4.4 % wide in value) holds a few percent of the row --, the remaining 19 bits are then resolved by three radix passes
+// over LDS, which also leave each wavefront's (greater, equal) counts; (3) the ordered compaction.  If a wavefront's
+// keys of the bin do not fit its region (heavily tied scores), the kernel falls back to four 8-bit passes over the row with
+// histograms private to the wavefront, six sweeps in all; both routes end in the same exact (threshold, rank) pair.
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 constexpr int LONG_U = 4;                       // 16-byte loads in flight per lane
 constexpr int LONG_STEP = 64 * 4 * LONG_U;      // scores a wavefront takes per iteration
+constexpr int LONG_BINS = 8192;                 // histogram of the top 13 key bits
+constexpr int LONG_LOW = 19;                    // key bits below them
+constexpr int LONG_CW = 768;                    // keys of the threshold bin a wavefront can hold in LDS (of its ~N/16)
+constexpr int LONG_LDS_BYTES = LONG_BINS * 4 + TOPK_WAVES * LONG_CW * 4;   // histogram + the wavefronts' regions: 80 KB, two workgroups per CU
 
 __global__ void __launch_bounds__(TOPK_THREADS) topk_long_kernel(const float* __restrict__ scores, int64_t N, int64_t k,
                                                                  int protect_last, int32_t* __restrict__ idx_out) {
-    __shared__ int whist[TOPK_WAVES][256];
+    extern __shared__ __attribute__((aligned(16))) char lsm[];
+    int* h12 = reinterpret_cast<int*>(lsm);                                                       // [LONG_BINS]
+    uint32_t (*cand)[LONG_CW] = reinterpret_cast<uint32_t (*)[LONG_CW]>(lsm + LONG_BINS * 4);     // [TOPK_WAVES][LONG_CW]
+    int (*whist)[256] = reinterpret_cast<int (*)[256]>(lsm + LONG_BINS * 4);                      // fallback only, same bytes
     __shared__ int hist[256];
     __shared__ uint32_t sh_prefix;
     __shared__ int64_t sh_need;
-    __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
+    __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES], wave_tot[TOPK_WAVES];
+    __shared__ int sh_b12, sh_over;
     scores += (int64_t)blockIdx.x * N;
     idx_out += (int64_t)blockIdx.x * k;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -268,52 +281,136 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_long_kernel(const float* __
     const int hi = lo + per_wave < n ? lo + per_wave : n;   // n % 4 == 0, so a 16-byte load that starts below hi ends below it
     const uint32_t last_key_at = protect_last ? (uint32_t)(n - 1) : 0xFFFFFFFFu;
 
-    if (tid == 0) { sh_prefix = 0; sh_need = k; }
-    uint32_t prefix = 0;
-    int64_t need = k;
-    int cgt = 0;   // last pass: keys of this wavefront's slice whose decided 24 bits exceed the prefix
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        for (int i = lane; i < 256; i += 64) whist[wave][i] = 0;
-        __syncthreads();
-        for (int base = lo; base < hi; base += LONG_STEP) {
-            f32x4v v[LONG_U];
-#pragma unroll
-            for (int u = 0; u < LONG_U; ++u) {
-                const int i0 = base + u * 256 + lane * 4;
-                v[u] = i0 < hi ? *reinterpret_cast<const f32x4v*>(scores + i0) : f32x4v{0.f, 0.f, 0.f, 0.f};
-            }
-#pragma unroll
-            for (int u = 0; u < LONG_U; ++u) {
-                const int i0 = base + u * 256 + lane * 4;
-                const bool valid = i0 < hi;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    uint32_t key = order_key(v[u][e]);
-                    if ((uint32_t)(i0 + e) == last_key_at) key = 0xFFFFFFFFu;
-                    hist_add(whist[wave], valid && (key & hi_mask) == prefix, (int)((key >> shift) & 0xFF));
-                    if (pass == 3) cgt += (int)__popcll(__ballot(valid && (key & hi_mask) > prefix));
-                }
-            }
-        }
-        __syncthreads();
-        if (tid < 256) {
-            int t = 0;
-#pragma unroll
-            for (int w = 0; w < TOPK_WAVES; ++w) t += whist[w][tid];
-            hist[tid] = t;
-        }
-        __syncthreads();
-        if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
-        __syncthreads();
-        prefix = sh_prefix;
-        need = sh_need;
+    // one iteration of a sweep over the wavefront's slice: the keys of load u, element e (index i0 + e) go to BODY
+#define SPTS_LONG_SWEEP(BODY)                                                                              \
+    for (int base = lo; base < hi; base += LONG_STEP) {                                                    \
+        f32x4v v[LONG_U];                                                                                  \
+        _Pragma("unroll") for (int u = 0; u < LONG_U; ++u) {                                               \
+            const int i0 = base + u * 256 + lane * 4;                                                      \
+            v[u] = i0 < hi ? *reinterpret_cast<const f32x4v*>(scores + i0) : f32x4v{0.f, 0.f, 0.f, 0.f};   \
+        }                                                                                                  \
+        _Pragma("unroll") for (int u = 0; u < LONG_U; ++u) {                                               \
+            const int i0 = base + u * 256 + lane * 4;                                                      \
+            const bool valid = i0 < hi;                                                                    \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                \
+                uint32_t key = order_key(v[u][e]);                                                         \
+                if ((uint32_t)(i0 + e) == last_key_at) key = 0xFFFFFFFFu;                                  \
+                BODY                                                                                       \
+            }                                                                                              \
+        }                                                                                                  \
     }
-    const uint32_t T = prefix;
-    const int need_eq = (int)need;
-    // this wavefront's keys above T / equal to T, from its own last-digit histogram
+
+    uint32_t T = 0;
+    int need_eq = 0;
+    // ---- sweep 1: top 13 bits
+    for (int i = tid; i < LONG_BINS; i += TOPK_THREADS) h12[i] = 0;
+    if (tid == 0) { sh_over = 0; sh_b12 = 0; sh_need = k; }
+    __syncthreads();
+    SPTS_LONG_SWEEP({ hist_add(h12, valid, (int)(key >> LONG_LOW)); })
+    __syncthreads();
     {
+        // bins in descending order, eight per lane: the bin whose cumulative count reaches k, and the rank inside it
+        constexpr int BPT = LONG_BINS / TOPK_THREADS;
+        int c[BPT], tot = 0;
+#pragma unroll
+        for (int q = 0; q < BPT; ++q) { c[q] = h12[LONG_BINS - 1 - BPT * tid - q]; tot += c[q]; }
+        int incl = tot;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int64_t excl = incl - tot;
+        for (int w = 0; w < wave; ++w) excl += wave_tot[w];
+        if (excl < k && k <= excl + tot) {
+            int64_t rem = k - excl;
+            int q = 0;
+#pragma unroll
+            for (int t = 0; t < BPT - 1; ++t)
+                if (q == t && rem > c[t]) { rem -= c[t]; q = t + 1; }
+            sh_b12 = LONG_BINS - 1 - BPT * tid - q;
+            sh_need = rem;
+        }
+        __syncthreads();
+    }
+    const uint32_t b12 = (uint32_t)sh_b12;
+    int64_t need = sh_need;
+    // ---- sweep 2: the wavefront's keys of that bin into its LDS region (low 20 bits), keys of higher bins counted
+    int cnt = 0, cgt = 0;
+    SPTS_LONG_SWEEP({
+        const uint32_t top = key >> LONG_LOW;
+        cgt += (int)__popcll(__ballot(valid && top > b12));
+        const bool in = valid && top == b12;
+        const uint64_t m = __ballot(in);
+        const int at = cnt + lane_prefix_popc(m);
+        if (in && at < LONG_CW) cand[wave][at] = key & ((1u << LONG_LOW) - 1u);
+        cnt += (int)__popcll(m);
+    })
+    if (lane == 0 && cnt > LONG_CW) sh_over = 1;
+    __syncthreads();
+    if (sh_over == 0) {
+        // ---- the remaining 19 bits from LDS: 8 + 8 + 3
+        uint32_t prefix = 0;
+        const int cnt64 = (cnt + 63) & ~63;
+#pragma unroll
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass == 0 ? 11 : pass == 1 ? 3 : 0;
+            const uint32_t dmask = pass == 2 ? 0x7u : 0xFFu;
+            const uint32_t hi_mask = pass == 0 ? 0u : pass == 1 ? 0x7F800u : 0x7FFF8u;
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            for (int j = lane; j < cnt64; j += 64) {
+                const uint32_t c = j < cnt ? cand[wave][j] : 0u;
+                hist_add(hist, j < cnt && (c & hi_mask) == prefix, (int)((c >> shift) & dmask));
+            }
+            __syncthreads();
+            if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
+            __syncthreads();
+            prefix = sh_prefix;
+            need = sh_need;
+        }
+        T = (b12 << LONG_LOW) | prefix;
+        need_eq = (int)need;
+        int g = 0, e = 0;
+        for (int j = lane; j < cnt64; j += 64) {
+            const uint32_t c = j < cnt ? cand[wave][j] : 0u;
+            g += (int)__popcll(__ballot(j < cnt && c > prefix));
+            e += (int)__popcll(__ballot(j < cnt && c == prefix));
+        }
+        if (lane == 0) { wave_gt[wave] = cgt + g; wave_eq[wave] = e; }
+    } else {
+        // ---- fallback: four 8-bit passes over the row
+        __syncthreads();   // every wavefront has read sh_over before the regions are reused as histograms
+        if (tid == 0) { sh_prefix = 0; sh_need = k; }
+        uint32_t prefix = 0;
+        need = k;
+        cgt = 0;   // last pass: keys of this wavefront's slice whose decided 24 bits exceed the prefix
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+            for (int i = lane; i < 256; i += 64) whist[wave][i] = 0;
+            __syncthreads();
+            SPTS_LONG_SWEEP({
+                hist_add(whist[wave], valid && (key & hi_mask) == prefix, (int)((key >> shift) & 0xFF));
+                if (pass == 3) cgt += (int)__popcll(__ballot(valid && (key & hi_mask) > prefix));
+            })
+            __syncthreads();
+            if (tid < 256) {
+                int t = 0;
+#pragma unroll
+                for (int w = 0; w < TOPK_WAVES; ++w) t += whist[w][tid];
+                hist[tid] = t;
+            }
+            __syncthreads();
+            if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
+            __syncthreads();
+            prefix = sh_prefix;
+            need = sh_need;
+        }
+        T = prefix;
+        need_eq = (int)need;
+        // this wavefront's keys above T / equal to T, from its own last-digit histogram
         const int digit = (int)(T & 0xFFu);
         int above = 0;
 #pragma unroll
@@ -653,7 +750,11 @@ hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_la
     if (N <= 1024 * 8) topk_reg_kernel<8><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
     else if (N <= 1024 * 16) topk_reg_kernel<16><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
     else if (N <= 1024 * 32) topk_reg_kernel<32><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
-    else if (!seg.offsets && N % 4 == 0 && N < ((int64_t)1 << 30)) topk_long_kernel<<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out);
+    else if (!seg.offsets && N % 4 == 0 && N < ((int64_t)1 << 30)) {
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&topk_long_kernel), LONG_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        topk_long_kernel<<<g, b, LONG_LDS_BYTES, s>>>(scores, N, k, protect_last, idx_out);
+    }
     else topk_kernel<<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
     return hipGetLastError();
 }

@@ -117,7 +117,11 @@ def test_select_topk_batched_rows_match_oracle(torch):
     # 40000, 65540 and 131072 take the streaming long-row kernel (16-byte loads), 40001 the scalar one
     for n, batch in ((1000, 7), (8193, 5), (40000, 3), (40001, 2), (65540, 3), (131072, 2)):
         s = ((1.0 + 0.3 * rng.standard_normal((batch, n))).clip(0.05, None) / n).astype(np.float32)
-        s[1, ::3] = s[1, 0]   # a row with many ties
+        s[1, ::3] = s[1, 0]   # a row with many ties (long rows: more than a wavefront's LDS region holds -> the sweep fallback)
+        s[0] = (np.exp(2.0 * rng.standard_normal(n)) / n).astype(np.float32)   # scores over many octaves (sparse histogram bins)
+        if batch > 2:
+            s[2, : n // 2] = s[2, 0]   # two values only: both routes of the long-row kernel meet ties at the threshold
+            s[2, n // 2:] = s[2, n - 1]
         sd = torch.from_numpy(s).cuda()
         for k in (1, int(0.4 * n), n):
             out = torch.full((batch, k), -7, dtype=torch.int32, device="cuda")
