@@ -82,15 +82,95 @@ __device__ inline void pick_bin(const int* hist, int lane, int shift, uint32_t p
     }
 }
 
+// ---- the threshold bin resolved in LDS (used by the register-resident and the long-row kernels) -------------------
+// A first histogram over the keys' top 13 bits (sign, exponent, four mantissa bits: a bin is 4.4 % wide in value) finds the
+// bin of the k-th largest key; every wavefront then copies the low 19 bits of ITS keys of that bin into its own LDS
+// region, and three radix passes over those few keys (8 + 8 + 3 bits) give the exact threshold, the number of keys equal
+// to it that are still wanted, and each wavefront's (greater, equal) counts.  A wavefront whose share of the bin does not
+// fit its region (heavily tied scores) makes the caller fall back to 8-bit passes over all keys.
+constexpr int T13_BINS = 8192;
+constexpr int T13_LOW = 19;
+constexpr int T13_CW = 768;                                              // keys per wavefront region
+constexpr int T13_LDS_BYTES = T13_BINS * 4 + TOPK_WAVES * T13_CW * 4;    // 80 KB: two workgroups per CU
+
+// all 1024 lanes: from the 8192-bin histogram the bin that holds the k-th largest key (-> *sh_bin) and the rank wanted
+// inside it (-> *sh_need); ends with a barrier
+__device__ inline void t13_pick(const int* h13, int64_t k, int* wave_tot, int* sh_bin, int64_t* sh_need) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int BPT = T13_BINS / TOPK_THREADS;   // bins per lane, descending
+    int c[BPT], tot = 0;
+#pragma unroll
+    for (int q = 0; q < BPT; ++q) { c[q] = h13[T13_BINS - 1 - BPT * tid - q]; tot += c[q]; }
+    int incl = tot;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int64_t excl = incl - tot;
+    for (int w = 0; w < wave; ++w) excl += wave_tot[w];
+    if (excl < k && k <= excl + tot) {
+        int64_t rem = k - excl;
+        int q = 0;
+#pragma unroll
+        for (int t = 0; t < BPT - 1; ++t)
+            if (q == t && rem > c[t]) { rem -= c[t]; q = t + 1; }
+        *sh_bin = T13_BINS - 1 - BPT * tid - q;
+        *sh_need = rem;
+    }
+    __syncthreads();
+}
+
+// all 1024 lanes: cand[0 .. cnt) = low 19 bits of this wavefront's keys of the bin, `need` = rank wanted inside the bin.
+// Returns the low 19 bits of the threshold; *need_eq = keys equal to it still wanted; *g / *e = this wavefront's
+// candidates above / equal to it.
+__device__ inline uint32_t t13_resolve(const uint32_t* cand, int cnt, int64_t need, int* hist, uint32_t* sh_prefix,
+                                       int64_t* sh_need, int* need_eq, int* g, int* e) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t prefix = 0;
+    const int cnt64 = (cnt + 63) & ~63;
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 11 : pass == 1 ? 3 : 0;
+        const uint32_t dmask = pass == 2 ? 0x7u : 0xFFu;
+        const uint32_t hi_mask = pass == 0 ? 0u : pass == 1 ? 0x7F800u : 0x7FFF8u;
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int j = lane; j < cnt64; j += 64) {
+            const uint32_t c = j < cnt ? cand[j] : 0u;
+            hist_add(hist, j < cnt && (c & hi_mask) == prefix, (int)((c >> shift) & dmask));
+        }
+        __syncthreads();
+        if (wave == 0) pick_bin(hist, lane, shift, prefix, need, sh_prefix, sh_need);
+        __syncthreads();
+        prefix = *sh_prefix;
+        need = *sh_need;
+    }
+    *need_eq = (int)need;
+    int gg = 0, ee = 0;
+    for (int j = lane; j < cnt64; j += 64) {
+        const uint32_t c = j < cnt ? cand[j] : 0u;
+        gg += (int)__popcll(__ballot(j < cnt && c > prefix));
+        ee += (int)__popcll(__ballot(j < cnt && c == prefix));
+    }
+    *g = gg; *e = ee;
+    return prefix;
+}
+
 // Register-resident variant: N <= 1024 * KPT.  Lane keeps keys[j] = key of element lo + 64*j + lane,
 // lo = 64*KPT*wave; slots at or beyond N hold key 0 and are never written out.
 template <int KPT>
 __global__ void __launch_bounds__(TOPK_THREADS) topk_reg_kernel(const float* __restrict__ scores, int64_t N, int64_t k,
                                                                 int protect_last, int32_t* __restrict__ idx_out, TopkSegments seg) {
+    extern __shared__ __attribute__((aligned(16))) char lsm[];
+    int* h13 = reinterpret_cast<int*>(lsm);                                                   // [T13_BINS]
+    uint32_t (*cand)[T13_CW] = reinterpret_cast<uint32_t (*)[T13_CW]>(lsm + T13_BINS * 4);   // [TOPK_WAVES][T13_CW]
     __shared__ int hist[256];
     __shared__ uint32_t sh_prefix;
     __shared__ int64_t sh_need;
-    __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES];
+    __shared__ int wave_gt[TOPK_WAVES], wave_eq[TOPK_WAVES], wave_tot[TOPK_WAVES];
+    __shared__ int sh_bin, sh_over;
 
     // one independent problem per workgroup: equal rows, or the segment the descriptors give it
     if (seg.offsets) {
@@ -116,36 +196,69 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_reg_kernel(const float* __r
         keys[j] = i < N ? load_key(scores, i, N, protect_last) : 0u;
     }
 
-    if (tid == 0) { sh_prefix = 0; sh_need = k; }
-    uint32_t prefix = 0;
-    int64_t need = k;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
+    // one pass over the keys for their top 13 bits, the rest of the threshold from the bin's keys in LDS
+    uint32_t T = 0;
+    int need_eq = 0;
+    for (int i = tid; i < T13_BINS; i += TOPK_THREADS) h13[i] = 0;
+    if (tid == 0) { sh_over = 0; sh_bin = 0; sh_need = k; }
+    __syncthreads();
 #pragma unroll
-        for (int j = 0; j < KPT; ++j) {
-            const bool valid = lo + 64 * j + lane < N;
-            hist_add(hist, valid && (keys[j] & hi_mask) == prefix, (int)((keys[j] >> shift) & 0xFF));
-        }
-        __syncthreads();
-        if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
-        __syncthreads();
-        prefix = sh_prefix;
-        need = sh_need;
-    }
-    const uint32_t T = prefix;
-    const int need_eq = (int)need;
-
-    int cgt = 0, ceq = 0;
+    for (int j = 0; j < KPT; ++j) hist_add(h13, lo + 64 * j + lane < N, (int)(keys[j] >> T13_LOW));
+    __syncthreads();
+    t13_pick(h13, k, wave_tot, &sh_bin, &sh_need);
+    const uint32_t bin = (uint32_t)sh_bin;
+    int cnt = 0, cgt = 0;
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
         const bool valid = lo + 64 * j + lane < N;
-        cgt += (int)__popcll(__ballot(valid && keys[j] > T));
-        ceq += (int)__popcll(__ballot(valid && keys[j] == T));
+        const uint32_t top = keys[j] >> T13_LOW;
+        cgt += (int)__popcll(__ballot(valid && top > bin));
+        const bool in = valid && top == bin;
+        const uint64_t m = __ballot(in);
+        const int at = cnt + lane_prefix_popc(m);
+        if (in && at < T13_CW) cand[wave][at] = keys[j] & ((1u << T13_LOW) - 1u);
+        cnt += (int)__popcll(m);
     }
-    if (lane == 0) { wave_gt[wave] = cgt; wave_eq[wave] = ceq; }
+    if (lane == 0 && cnt > T13_CW) sh_over = 1;
+    __syncthreads();
+    if (sh_over == 0) {
+        int g, e;
+        const uint32_t low = t13_resolve(cand[wave], cnt, sh_need, hist, &sh_prefix, &sh_need, &need_eq, &g, &e);
+        T = (bin << T13_LOW) | low;
+        if (lane == 0) { wave_gt[wave] = cgt + g; wave_eq[wave] = e; }
+    } else {
+        // heavily tied keys: four 8-bit passes over the registers
+        if (tid == 0) { sh_prefix = 0; sh_need = k; }
+        uint32_t prefix = 0;
+        int64_t need = k;
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < KPT; ++j) {
+                const bool valid = lo + 64 * j + lane < N;
+                hist_add(hist, valid && (keys[j] & hi_mask) == prefix, (int)((keys[j] >> shift) & 0xFF));
+            }
+            __syncthreads();
+            if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
+            __syncthreads();
+            prefix = sh_prefix;
+            need = sh_need;
+        }
+        T = prefix;
+        need_eq = (int)need;
+        int ceq = 0;
+        cgt = 0;
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const bool valid = lo + 64 * j + lane < N;
+            cgt += (int)__popcll(__ballot(valid && keys[j] > T));
+            ceq += (int)__popcll(__ballot(valid && keys[j] == T));
+        }
+        if (lane == 0) { wave_gt[wave] = cgt; wave_eq[wave] = ceq; }
+    }
     __syncthreads();
     int gt_before = 0, eq_before = 0;
     for (int w = 0; w < wave; ++w) { gt_before += wave_gt[w]; eq_before += wave_eq[w]; }
@@ -256,17 +369,13 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_kernel(const float* __restr
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 constexpr int LONG_U = 4;                       // 16-byte loads in flight per lane
 constexpr int LONG_STEP = 64 * 4 * LONG_U;      // scores a wavefront takes per iteration
-constexpr int LONG_BINS = 8192;                 // histogram of the top 13 key bits
-constexpr int LONG_LOW = 19;                    // key bits below them
-constexpr int LONG_CW = 768;                    // keys of the threshold bin a wavefront can hold in LDS (of its ~N/16)
-constexpr int LONG_LDS_BYTES = LONG_BINS * 4 + TOPK_WAVES * LONG_CW * 4;   // histogram + the wavefronts' regions: 80 KB, two workgroups per CU
 
 __global__ void __launch_bounds__(TOPK_THREADS) topk_long_kernel(const float* __restrict__ scores, int64_t N, int64_t k,
                                                                  int protect_last, int32_t* __restrict__ idx_out) {
     extern __shared__ __attribute__((aligned(16))) char lsm[];
-    int* h12 = reinterpret_cast<int*>(lsm);                                                       // [LONG_BINS]
-    uint32_t (*cand)[LONG_CW] = reinterpret_cast<uint32_t (*)[LONG_CW]>(lsm + LONG_BINS * 4);     // [TOPK_WAVES][LONG_CW]
-    int (*whist)[256] = reinterpret_cast<int (*)[256]>(lsm + LONG_BINS * 4);                      // fallback only, same bytes
+    int* h13 = reinterpret_cast<int*>(lsm);                                                     // [T13_BINS]
+    uint32_t (*cand)[T13_CW] = reinterpret_cast<uint32_t (*)[T13_CW]>(lsm + T13_BINS * 4);     // [TOPK_WAVES][T13_CW]
+    int (*whist)[256] = reinterpret_cast<int (*)[256]>(lsm + T13_BINS * 4);                     // fallback only, same bytes
     __shared__ int hist[256];
     __shared__ uint32_t sh_prefix;
     __shared__ int64_t sh_need;
@@ -303,81 +412,31 @@ __global__ void __launch_bounds__(TOPK_THREADS) topk_long_kernel(const float* __
     uint32_t T = 0;
     int need_eq = 0;
     // ---- sweep 1: top 13 bits
-    for (int i = tid; i < LONG_BINS; i += TOPK_THREADS) h12[i] = 0;
+    for (int i = tid; i < T13_BINS; i += TOPK_THREADS) h13[i] = 0;
     if (tid == 0) { sh_over = 0; sh_b12 = 0; sh_need = k; }
     __syncthreads();
-    SPTS_LONG_SWEEP({ hist_add(h12, valid, (int)(key >> LONG_LOW)); })
+    SPTS_LONG_SWEEP({ hist_add(h13, valid, (int)(key >> T13_LOW)); })
     __syncthreads();
-    {
-        // bins in descending order, eight per lane: the bin whose cumulative count reaches k, and the rank inside it
-        constexpr int BPT = LONG_BINS / TOPK_THREADS;
-        int c[BPT], tot = 0;
-#pragma unroll
-        for (int q = 0; q < BPT; ++q) { c[q] = h12[LONG_BINS - 1 - BPT * tid - q]; tot += c[q]; }
-        int incl = tot;
-        for (int off = 1; off < 64; off <<= 1) {
-            const int o = __shfl_up(incl, off);
-            if (lane >= off) incl += o;
-        }
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        int64_t excl = incl - tot;
-        for (int w = 0; w < wave; ++w) excl += wave_tot[w];
-        if (excl < k && k <= excl + tot) {
-            int64_t rem = k - excl;
-            int q = 0;
-#pragma unroll
-            for (int t = 0; t < BPT - 1; ++t)
-                if (q == t && rem > c[t]) { rem -= c[t]; q = t + 1; }
-            sh_b12 = LONG_BINS - 1 - BPT * tid - q;
-            sh_need = rem;
-        }
-        __syncthreads();
-    }
+    t13_pick(h13, k, wave_tot, &sh_b12, &sh_need);
     const uint32_t b12 = (uint32_t)sh_b12;
     int64_t need = sh_need;
-    // ---- sweep 2: the wavefront's keys of that bin into its LDS region (low 20 bits), keys of higher bins counted
+    // ---- sweep 2: the wavefront's keys of that bin into its LDS region (low 19 bits), keys of higher bins counted
     int cnt = 0, cgt = 0;
     SPTS_LONG_SWEEP({
-        const uint32_t top = key >> LONG_LOW;
+        const uint32_t top = key >> T13_LOW;
         cgt += (int)__popcll(__ballot(valid && top > b12));
         const bool in = valid && top == b12;
         const uint64_t m = __ballot(in);
         const int at = cnt + lane_prefix_popc(m);
-        if (in && at < LONG_CW) cand[wave][at] = key & ((1u << LONG_LOW) - 1u);
+        if (in && at < T13_CW) cand[wave][at] = key & ((1u << T13_LOW) - 1u);
         cnt += (int)__popcll(m);
     })
-    if (lane == 0 && cnt > LONG_CW) sh_over = 1;
+    if (lane == 0 && cnt > T13_CW) sh_over = 1;
     __syncthreads();
     if (sh_over == 0) {
-        // ---- the remaining 19 bits from LDS: 8 + 8 + 3
-        uint32_t prefix = 0;
-        const int cnt64 = (cnt + 63) & ~63;
-#pragma unroll
-        for (int pass = 0; pass < 3; ++pass) {
-            const int shift = pass == 0 ? 11 : pass == 1 ? 3 : 0;
-            const uint32_t dmask = pass == 2 ? 0x7u : 0xFFu;
-            const uint32_t hi_mask = pass == 0 ? 0u : pass == 1 ? 0x7F800u : 0x7FFF8u;
-            if (tid < 256) hist[tid] = 0;
-            __syncthreads();
-            for (int j = lane; j < cnt64; j += 64) {
-                const uint32_t c = j < cnt ? cand[wave][j] : 0u;
-                hist_add(hist, j < cnt && (c & hi_mask) == prefix, (int)((c >> shift) & dmask));
-            }
-            __syncthreads();
-            if (wave == 0) pick_bin(hist, lane, shift, prefix, need, &sh_prefix, &sh_need);
-            __syncthreads();
-            prefix = sh_prefix;
-            need = sh_need;
-        }
-        T = (b12 << LONG_LOW) | prefix;
-        need_eq = (int)need;
-        int g = 0, e = 0;
-        for (int j = lane; j < cnt64; j += 64) {
-            const uint32_t c = j < cnt ? cand[wave][j] : 0u;
-            g += (int)__popcll(__ballot(j < cnt && c > prefix));
-            e += (int)__popcll(__ballot(j < cnt && c == prefix));
-        }
+        int g, e;
+        const uint32_t low = t13_resolve(cand[wave], cnt, need, hist, &sh_prefix, &sh_need, &need_eq, &g, &e);
+        T = (b12 << T13_LOW) | low;
         if (lane == 0) { wave_gt[wave] = cgt + g; wave_eq[wave] = e; }
     } else {
         // ---- fallback: four 8-bit passes over the row
@@ -747,13 +806,23 @@ hipError_t launch_topk(const float* scores, int64_t N, int64_t k, int protect_la
     // with segments N is the longest segment (it picks the kernel variant) and k is ignored
     if ((k <= 0 && !seg.offsets) || N <= 0 || batch <= 0) return hipSuccess;
     const dim3 g((unsigned)batch), b(TOPK_THREADS);
-    if (N <= 1024 * 8) topk_reg_kernel<8><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
-    else if (N <= 1024 * 16) topk_reg_kernel<16><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
-    else if (N <= 1024 * 32) topk_reg_kernel<32><<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
+    if (N <= 1024 * 32) {
+        hipError_t e;
+        if (N <= 1024 * 8) {
+            if ((e = ensure_dynamic_lds(reinterpret_cast<const void*>(&topk_reg_kernel<8>), T13_LDS_BYTES)) != hipSuccess) return e;
+            topk_reg_kernel<8><<<g, b, T13_LDS_BYTES, s>>>(scores, N, k, protect_last, idx_out, seg);
+        } else if (N <= 1024 * 16) {
+            if ((e = ensure_dynamic_lds(reinterpret_cast<const void*>(&topk_reg_kernel<16>), T13_LDS_BYTES)) != hipSuccess) return e;
+            topk_reg_kernel<16><<<g, b, T13_LDS_BYTES, s>>>(scores, N, k, protect_last, idx_out, seg);
+        } else {
+            if ((e = ensure_dynamic_lds(reinterpret_cast<const void*>(&topk_reg_kernel<32>), T13_LDS_BYTES)) != hipSuccess) return e;
+            topk_reg_kernel<32><<<g, b, T13_LDS_BYTES, s>>>(scores, N, k, protect_last, idx_out, seg);
+        }
+    }
     else if (!seg.offsets && N % 4 == 0 && N < ((int64_t)1 << 30)) {
-        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&topk_long_kernel), LONG_LDS_BYTES);
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&topk_long_kernel), T13_LDS_BYTES);
         if (e != hipSuccess) return e;
-        topk_long_kernel<<<g, b, LONG_LDS_BYTES, s>>>(scores, N, k, protect_last, idx_out);
+        topk_long_kernel<<<g, b, T13_LDS_BYTES, s>>>(scores, N, k, protect_last, idx_out);
     }
     else topk_kernel<<<g, b, 0, s>>>(scores, N, k, protect_last, idx_out, seg);
     return hipGetLastError();
