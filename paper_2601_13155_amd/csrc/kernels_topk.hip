@@ -17,6 +17,10 @@
 //      out[gt_before + min(eq_before, need_eq)].
 // Up to 32768 scores the keys are read once and stay in registers (KPT per lane, wavefront w holding
 // the contiguous slice [64*KPT*w, 64*KPT*(w+1))); longer inputs re-read the scores in every sweep.
+// Shortcut for step 1 (register-resident and long-row kernels): one pass builds an 8192-bin histogram
+// of the top 13 key bits, the keys of the bin that holds the k-th largest go to LDS and the remaining
+// 19 bits are resolved there; the four 8-bit passes over all keys remain as the route for rows whose
+// threshold bin does not fit (heavily tied scores).  Both routes yield the same exact threshold.
 #include "spts_internal.h"
 
 #include <mutex>
